@@ -1,0 +1,205 @@
+/*
+ * libss - sequence-scheduled batched greedy decoding on one MI355X (gfx950).
+ *
+ * C ABI.  Every pointer argument says "host" or "device" below; nothing in a
+ * signature is a framework type.  All functions are synchronous on return.
+ * Every function that returns int returns SS_OK (0) or a negative ss_status;
+ * ss_last_error() then gives a thread-local message.  No exception or abort
+ * crosses this boundary; outputs are untouched when an error is returned
+ * before any work was started.
+ *
+ * The operations follow the paper's Sec. 4.1 (Method): a group of queries is
+ * ordered by predicted response length and split into micro-batches (binning,
+ * variable batch size), every micro-batch is generated token by token with a
+ * cap on newly generated tokens, rows that overrun the cap are failures that
+ * are collected and recomputed after the group (FCR).  Sec. 4.2 gives the
+ * constants (bin cell 50, baseline batch 16, group 256).
+ */
+#ifndef SS_H
+#define SS_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { SS_OK = 0, SS_EINVAL = -1, SS_ENOMEM = -2, SS_EDEVICE = -3, SS_ESTATE = -4 } ss_status;
+
+/* Thread-local text of the last error on this thread ("" if none).  Host pointer, library-owned. */
+const char* ss_last_error(void);
+
+/* ------------------------------------------------------------------ scheduler (host only) */
+
+/* Policy flags.  0 = vanilla batching: arrival order, fixed batch, cap = base_len (Sec. 4.2 baseline). */
+#define SS_SORT    1u  /* order the group by scheduled length (Sec. 4.1, sort-and-split)                  */
+#define SS_BIN     2u  /* schedule by the upper edge of the prediction's bin (Sec. 4.1, Binning); needs SS_SORT */
+#define SS_FCR     4u  /* cap = largest scheduled length in the micro-batch; overruns fail (Sec. 4.1, FCR) */
+#define SS_VBS     8u  /* batch size inversely proportional to the scheduled length (Sec. 4.1, VBS); needs SS_SORT */
+#define SS_COMPACT 16u /* engine flag: finished rows leave the live batch (not in the paper; outputs unchanged) */
+
+#define SS_VBS_CLAMP_FLOOR 0 /* B = clamp(floor(base_batch*base_len/L), base_batch, max_batch)               */
+#define SS_VBS_PAPER_POW2  1 /* Sec. 4.2: 16 if L >= 300, else 256*50/L rounded to the nearest power of two  */
+
+typedef struct {
+    uint32_t flags;      /* SS_SORT | SS_BIN | SS_FCR | SS_VBS | SS_COMPACT */
+    int32_t  base_batch; /* B0: vanilla / minimum batch size, >= 1 (16 in the paper)            */
+    int32_t  base_len;   /* L0 = global limit on generated tokens per query (L_max), >= 1       */
+    int32_t  max_batch;  /* upper bound of the variable batch size, >= base_batch               */
+    int32_t  vbs_rule;   /* SS_VBS_CLAMP_FLOOR or SS_VBS_PAPER_POW2                             */
+} ss_policy;
+
+/* A plan: micro-batch k holds queries query_idx[mb_offsets[k] .. mb_offsets[k+1]) and may generate at
+ * most mb_cap[k] tokens per row.  query_idx lists each scheduled query exactly once.  All arrays are
+ * host memory owned by the plan and immutable; free with ss_plan_free. */
+typedef struct {
+    int32_t        n;          /* number of scheduled queries       */
+    int32_t        n_mb;       /* number of micro-batches           */
+    const int32_t* mb_offsets; /* host, [n_mb + 1]                  */
+    const int32_t* query_idx;  /* host, [n]                         */
+    const int32_t* mb_cap;     /* host, [n_mb]                      */
+} ss_plan;
+
+/*
+ * First-pass plan of a group (Sec. 4.1).  Pure host integer work, deterministic, no GPU needed.
+ *   pred_lens  host, int32[n], predicted response length of each query (>= 1); may be NULL when
+ *              SS_SORT is not set (vanilla: arrival order, chunks of base_batch, cap base_len).
+ *   bin        bin cell size (50 in the paper); 0 = schedule by the raw prediction; must be > 0 with SS_BIN.
+ * Scheduled length of a query = min(bin*ceil(pred/bin), bin*ceil(base_len/bin)) with SS_BIN, else pred.
+ * Order: stable by (scheduled length, arrival index).  With SS_BIN every bin is chunked on its own
+ * (batch size from the bin's edge; only a bin's last chunk is short).  Without SS_BIN the sorted list
+ * is cut into chunks of base_batch, or with SS_VBS into the longest chunks whose size does not exceed
+ * the batch size allowed for their largest prediction.  cap = min(largest scheduled length in the
+ * micro-batch, base_len) with SS_FCR, else base_len.
+ * Errors: SS_EINVAL for n <= 0, NULL out/policy, pred < 1, bin < 0, SS_BIN without SS_SORT or with bin 0,
+ * SS_VBS without SS_SORT, base_batch < 1, max_batch < base_batch, base_len < 1, unknown vbs_rule.
+ */
+int ss_schedule(const int32_t* pred_lens, int32_t n, int32_t bin, const ss_policy* policy, ss_plan** out);
+
+/*
+ * Plan of the recomputation pass (Sec. 4.1, FCR: failures are collected and recomputed at the end of
+ * the group).  failed_idx (host, int32[n_failed], query indices < n) is ordered stably by
+ * (scheduled length, index), cut into chunks of base_batch, cap = base_len, so nothing fails twice.
+ * n_failed == 0 gives an empty plan.
+ */
+int ss_schedule_failures(const int32_t* pred_lens, int32_t n, const int32_t* failed_idx, int32_t n_failed,
+                         int32_t bin, const ss_policy* policy, ss_plan** out);
+
+void ss_plan_free(ss_plan* plan);
+
+/* ------------------------------------------------------------------ model weights (device resident) */
+
+typedef struct {
+    int32_t n_layers, d_model, n_heads, head_dim, d_ffn, vocab;
+    float   rope_base, rms_eps;
+} ss_model_cfg;
+
+typedef struct ss_weights ss_weights; /* opaque; owns packed bf16 weights and a grow-only device workspace */
+
+#define SS_BF16 0 /* source tensors are bf16 bit patterns (uint16)            */
+#define SS_F32  1 /* source tensors are fp32; rounded to bf16, nearest-even    */
+
+/*
+ * Upload and pack a LLaMA-style decoder (pre-norm, RMSNorm, rotary embedding pairing j with j+head_dim/2,
+ * SwiGLU MLP, untied LM head, no biases; the model family of Sec. 4.2).
+ *   tensors  host array of 3 + 9*n_layers host pointers, matrices [out, in] row-major, in this order:
+ *            embed[vocab,d]; per layer attn_norm[d], wq[d,d], wk[d,d], wv[d,d], wo[d,d], mlp_norm[d],
+ *            wg[ffn,d], wu[ffn,d], wd[d,ffn]; final_norm[d]; lm_head[vocab,d].
+ *            The caller keeps ownership; the data is copied.
+ * Requires n_heads*head_dim == d_model, head_dim in {64, 128}, d_model % 32 == 0, d_ffn % 16 == 0, vocab % 16 == 0.
+ * Errors: SS_EINVAL (shape), SS_EDEVICE (no usable GPU / HIP error), SS_ENOMEM.
+ */
+int  ss_weights_create(const ss_model_cfg* cfg, const void* const* tensors, int32_t src_dtype, ss_weights** out);
+void ss_weights_destroy(ss_weights* w);
+
+/* ------------------------------------------------------------------ generation */
+
+typedef struct {
+    int32_t steps;            /* forwards run: 1 prompt forward + steps-1 decode forwards                    */
+    int32_t rows;             /* B                                                                            */
+    int64_t row_steps;        /* rows actually computed, summed over forwards (B*steps without SS_COMPACT)   */
+    int64_t prompt_tokens;    /* sum of prompt lengths                                                       */
+    int64_t decode_kv_tokens; /* key/value slots read by decode attention, summed over rows and steps        */
+    double  prefill_ms;       /* device time of the prompt forward (HIP events on the call's stream)         */
+    double  decode_ms;        /* device time of all decode forwards                                          */
+} ss_stats;
+
+/*
+ * Generate one micro-batch greedily (Sec. 4.1): the prompts are processed, then one token per row per
+ * step until every row has emitted min(target_len, max_new) tokens; the token that the prompt forward
+ * yields counts as the first generated one, so steps = min(max_new, max target_len).
+ * End of sequence is simulated: row i is finished exactly when it has emitted target_lens[i] tokens.
+ *   w               weights handle; one call at a time per handle (SS_ESTATE otherwise)
+ *   prompt_tokens   host, int32[prompt_offsets[B]], ragged concatenation of the prompts, ids in [0, vocab)
+ *   prompt_offsets  host, int32[B+1], strictly increasing from 0 (no empty prompt)
+ *   max_new         cap on generated tokens per row, >= 1
+ *   target_lens     host, int32[B], >= 1
+ *   flags           0 or SS_COMPACT.  Without it a finished row keeps being computed on its own last
+ *                   token until the micro-batch ends (the padding that vanilla batching pays for);
+ *                   with it the live batch shrinks.  Outputs are identical either way.
+ *   out_tokens      host, int32[B*max_new] row-major; -1 after the emitted length
+ *   out_lens        host, int32[B]   = min(target, max_new)
+ *   out_failed      host, uint8[B]   = target > max_new  (an FCR failure: to be recomputed later)
+ *   stats           host, nullable
+ *   hip_stream      a hipStream_t to run on, or NULL for the handle's own stream
+ * Errors: SS_EINVAL (B <= 0, NULL, bad offsets/ids/lengths, prompt + max_new > 4096 positions),
+ *         SS_ENOMEM, SS_EDEVICE, SS_ESTATE.
+ */
+int ss_decode_microbatch(ss_weights* w, const int32_t* prompt_tokens, const int32_t* prompt_offsets, int32_t B,
+                         int32_t max_new, const int32_t* target_lens, uint32_t flags, int32_t* out_tokens,
+                         int32_t* out_lens, uint8_t* out_failed, ss_stats* stats, void* hip_stream);
+
+/*
+ * Teacher-forced logits (test / measurement entry point).  Each of the B rows is a token sequence
+ * tokens[offsets[i] .. offsets[i+1]); the first n_prompt[i] tokens are processed in one prompt forward,
+ * the remaining ones are fed one per decode step (all rows advance together, exactly as in
+ * ss_decode_microbatch, but the next input is the given token instead of the argmax).
+ *   logits_out  host, float32, one [vocab] row per position >= n_prompt[i]-1 of every row, ordered by
+ *               row then position: sum_i (len_i - n_prompt[i] + 1) rows.
+ *   n_prompt    host, int32[B], 1 <= n_prompt[i] <= len_i.  n_prompt[i] == len_i makes row i a pure
+ *               prompt forward.
+ *   all_prompt_logits  nonzero: n_prompt[i] must equal len_i and logits are returned for every position
+ *               (len_i rows per sequence) - checks the prompt path position by position.
+ */
+int ss_forward_logits(ss_weights* w, const int32_t* tokens, const int32_t* offsets, int32_t B,
+                      const int32_t* n_prompt, int32_t all_prompt_logits, float* logits_out, void* hip_stream);
+
+typedef struct {
+    int32_t n_mb_first, n_mb_failure; /* micro-batches in the first pass and in the recomputation pass */
+    int32_t n_failed;                 /* queries that overran their cap in the first pass              */
+    int64_t steps;                    /* forwards over both passes                                     */
+    int64_t padded_row_steps;         /* sum over micro-batches of B*steps                             */
+    int64_t computed_row_steps;       /* rows actually computed (== padded without SS_COMPACT)         */
+    int64_t useful_tokens;            /* sum of target_lens: every query's tokens counted once         */
+    int64_t prompt_tokens;            /* prompt tokens processed, recomputation included               */
+    double  wall_ms;                  /* host wall time of the whole group, plan building excluded     */
+    double  plan_ms;                  /* host time spent building the two plans                        */
+    double  prefill_ms, decode_ms;    /* device time (HIP events) summed over micro-batches            */
+} ss_group_stats;
+
+/*
+ * Whole group (Sec. 4.1 pipeline without the length predictor): plan -> generate every micro-batch ->
+ * collect failures, discard their partial output and key/value state -> recomputation pass.
+ *   pred_lens   host, int32[n] or NULL (vanilla)
+ *   out_tokens  host, int32[n*base_len] row-major, -1 after each query's length
+ *   out_lens    host, int32[n] = target_lens on success
+ * policy->flags & SS_COMPACT selects the compacting engine for every micro-batch.
+ */
+int ss_run_group(ss_weights* w, const int32_t* prompt_tokens, const int32_t* prompt_offsets, int32_t n,
+                 const int32_t* target_lens, const int32_t* pred_lens, int32_t bin, const ss_policy* policy,
+                 int32_t* out_tokens, int32_t* out_lens, ss_group_stats* stats, void* hip_stream);
+
+/*
+ * Measurement entry point: time `iters` decode forwards of B rows whose key/value history holds `ctx`
+ * tokens each (synthetic state: every row is first prefilled with a ctx-token prompt taken from
+ * `prompt_tokens`, host int32[B*ctx]).  The same kernels and launch configuration as a decode step of
+ * ss_decode_microbatch, replayed on the same positions so that every iteration moves the same bytes.
+ *   ms_out  host, double[iters]: device time of each forward (HIP events on the stream used).
+ */
+int ss_bench_decode_step(ss_weights* w, const int32_t* prompt_tokens, int32_t B, int32_t ctx, int32_t iters,
+                         double* ms_out, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SS_H */

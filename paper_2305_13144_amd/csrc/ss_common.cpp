@@ -1,0 +1,26 @@
+// Thread-local error text for the C ABI.
+#include "ss_internal.h"
+
+#include <cstdarg>
+#include <cstdio>
+
+namespace {
+thread_local char g_err[512] = "";
+}
+
+namespace ss {
+
+int fail(int code, const char* fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+void clear_error() { g_err[0] = '\0'; }
+
+}  // namespace ss
+
+extern "C" const char* ss_last_error(void) { return g_err; }

@@ -1,0 +1,732 @@
+// Host side of the decode engine: weight upload/packing, the grow-only device workspace, one
+// forward over a list of token-rows, and the C-ABI entry points built on it (Sec. 4.1 of the paper:
+// micro-batch generation with a cap, failure collection and recomputation after the group).
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <atomic>
+#include <chrono>
+#include <cmath>
+#include <cstring>
+#include <numeric>
+#include <vector>
+
+#include "ss_internal.h"
+#include "ss_kernels.h"
+
+using ss::bf16_t;
+using ss::GemmArgs;
+using ss::MbState;
+using ss::PackedMat;
+
+#define HIPCHK(expr)                                                                              \
+    do {                                                                                          \
+        hipError_t e_ = (expr);                                                                   \
+        if (e_ != hipSuccess)                                                                     \
+            return ss::fail(e_ == hipErrorOutOfMemory ? SS_ENOMEM : SS_EDEVICE, "%s: %s", #expr, \
+                            hipGetErrorString(e_));                                               \
+    } while (0)
+
+namespace {
+
+struct Layer {
+    bf16_t *attn_norm = nullptr, *mlp_norm = nullptr;
+    PackedMat wqkv, wo, wgu, wd;
+};
+
+// A grow-only device buffer.
+struct Buf {
+    void* p = nullptr;
+    size_t bytes = 0;
+    int ensure(size_t need, bool zero)
+    {
+        if (need <= bytes) return SS_OK;
+        if (p) (void)hipFree(p);
+        p = nullptr;
+        bytes = 0;
+        const size_t want = need + need / 8;
+        hipError_t e = hipMalloc(&p, want);
+        if (e != hipSuccess) {
+            p = nullptr;
+            return ss::fail(SS_ENOMEM, "hipMalloc(%zu bytes): %s", want, hipGetErrorString(e));
+        }
+        bytes = want;
+        if (zero) {
+            e = hipMemset(p, 0, want);
+            if (e != hipSuccess) return ss::fail(SS_EDEVICE, "hipMemset: %s", hipGetErrorString(e));
+        }
+        return SS_OK;
+    }
+    void release()
+    {
+        if (p) (void)hipFree(p);
+        p = nullptr;
+        bytes = 0;
+    }
+    template <class T>
+    T* as() const { return (T*)p; }
+};
+
+struct Workspace {
+    Buf x, h, ao, act, qrot, pqkv, pd, hsel, logits, kv, ints, i64s;
+    void release()
+    {
+        for (Buf* b : {&x, &h, &ao, &act, &qrot, &pqkv, &pd, &hsel, &logits, &kv, &ints, &i64s}) b->release();
+    }
+};
+
+}  // namespace
+
+struct ss_weights {
+    ss_model_cfg cfg{};
+    int device = 0;
+    hipStream_t stream = nullptr;
+    std::vector<void*> allocs;
+    bf16_t* embed = nullptr;
+    std::vector<Layer> layers;
+    bf16_t* final_norm = nullptr;
+    PackedMat lm_head;
+    float *rope_cos = nullptr, *rope_sin = nullptr;
+    Workspace ws;
+    std::atomic<int> busy{0};
+    int32_t* d_sel = nullptr;  // carved from ws.ints
+    MbState st{};
+    size_t kv_layer_stride = 0;  // elements between a layer's K and V, and 2x that between layers
+};
+
+namespace {
+
+struct BusyGuard {
+    ss_weights* w;
+    bool ok;
+    explicit BusyGuard(ss_weights* w_) : w(w_), ok(w_->busy.exchange(1) == 0) {}
+    ~BusyGuard()
+    {
+        if (ok) w->busy.store(0);
+    }
+};
+
+int dev_alloc(ss_weights* w, void** out, size_t bytes, bool zero)
+{
+    void* p = nullptr;
+    hipError_t e = hipMalloc(&p, bytes);
+    if (e != hipSuccess) return ss::fail(SS_ENOMEM, "hipMalloc(%zu bytes): %s", bytes, hipGetErrorString(e));
+    w->allocs.push_back(p);
+    if (zero) HIPCHK(hipMemset(p, 0, bytes));
+    *out = p;
+    return SS_OK;
+}
+
+// Uploads a row-major host matrix through a staging buffer and packs it into dst (Sec. of ss_internal.h
+// on the operand layout).  Source row r -> packed row (r/16*blk_stride + blk_off)*16 + r%16.
+int upload_pack(ss_weights* w, Buf& staging, const void* host, int src_f32, int n_src, int k, bf16_t* dst, int kp,
+                int blk_stride, int blk_off)
+{
+    const size_t bytes = (size_t)n_src * k * (src_f32 ? 4 : 2);
+    if (int rc = staging.ensure(bytes, false)) return rc;
+    HIPCHK(hipMemcpy(staging.p, host, bytes, hipMemcpyHostToDevice));
+    ss::launch_pack_weight(staging.p, src_f32, dst, n_src, k, kp, blk_stride, blk_off, w->stream);
+    HIPCHK(hipStreamSynchronize(w->stream));
+    return SS_OK;
+}
+
+int upload_vec(ss_weights* w, Buf& staging, const void* host, int src_f32, size_t count, bf16_t** out)
+{
+    void* p = nullptr;
+    if (int rc = dev_alloc(w, &p, count * 2, false)) return rc;
+    const size_t bytes = count * (src_f32 ? 4 : 2);
+    if (int rc = staging.ensure(bytes, false)) return rc;
+    HIPCHK(hipMemcpy(staging.p, host, bytes, hipMemcpyHostToDevice));
+    ss::launch_cast_rows(staging.p, src_f32, (bf16_t*)p, count, w->stream);
+    HIPCHK(hipStreamSynchronize(w->stream));
+    *out = (bf16_t*)p;
+    return SS_OK;
+}
+
+int alloc_packed(ss_weights* w, PackedMat* m, int n, int k)
+{
+    m->N = n;
+    m->K = k;
+    m->Kp = ss::padded_k(k);
+    void* p = nullptr;
+    if (int rc = dev_alloc(w, &p, (size_t)n * m->Kp * 2, m->Kp != k)) return rc;
+    m->p = (bf16_t*)p;
+    return SS_OK;
+}
+
+int check_cfg(const ss_model_cfg* c)
+{
+    if (!c) return ss::fail(SS_EINVAL, "cfg is NULL");
+    if (c->n_layers < 1 || c->d_model < 64 || c->n_heads < 1 || c->d_ffn < 16 || c->vocab < 16)
+        return ss::fail(SS_EINVAL, "non-positive model dimension");
+    if (c->n_heads * c->head_dim != c->d_model) return ss::fail(SS_EINVAL, "n_heads*head_dim != d_model");
+    if (c->head_dim != 64 && c->head_dim != 128) return ss::fail(SS_EINVAL, "head_dim must be 64 or 128");
+    if (c->d_model % 64 || c->d_model > 8192) return ss::fail(SS_EINVAL, "d_model must be a multiple of 64, <= 8192");
+    if (c->d_ffn % 16) return ss::fail(SS_EINVAL, "d_ffn must be a multiple of 16");
+    if (c->vocab % 16) return ss::fail(SS_EINVAL, "vocab must be a multiple of 16");
+    if (!(c->rope_base > 1.f) || !(c->rms_eps > 0.f)) return ss::fail(SS_EINVAL, "bad rope_base / rms_eps");
+    return SS_OK;
+}
+
+// ---------------------------------------------------------------------------------------- workspace
+// n_max token-rows in a forward, B micro-batch rows, n_sel rows whose logits are wanted,
+// slots = total key/value slots of the micro-batch.
+int ensure_workspace(ss_weights* w, int n_max, int B, int n_sel, size_t slots, int max_new)
+{
+    const ss_model_cfg& c = w->cfg;
+    const int d = c.d_model, F = c.d_ffn, V = c.vocab;
+    Workspace& ws = w->ws;
+    const size_t nr = (size_t)ss::round_up(n_max, 128);
+    const size_t ks_rows = std::max<size_t>((size_t)8 * std::min(n_max, 1024), (size_t)n_max);
+    int rc;
+    if ((rc = ws.x.ensure(nr * d * 4, false))) return rc;
+    if ((rc = ws.h.ensure(nr * d * 2, true))) return rc;
+    if ((rc = ws.ao.ensure(nr * d * 2, true))) return rc;
+    if ((rc = ws.act.ensure(nr * ss::padded_k(F) * 2, true))) return rc;
+    if ((rc = ws.qrot.ensure(nr * d * 4, false))) return rc;
+    if ((rc = ws.pqkv.ensure(ks_rows * 3 * d * 4, false))) return rc;
+    if ((rc = ws.pd.ensure(ks_rows * d * 4, false))) return rc;
+    if ((rc = ws.hsel.ensure((size_t)ss::round_up(n_sel, 128) * d * 2, true))) return rc;
+    if ((rc = ws.logits.ensure((size_t)ss::round_up(n_sel, 16) * V * 4, false))) return rc;
+    w->kv_layer_stride = slots * d;
+    if ((rc = ws.kv.ensure((size_t)c.n_layers * 2 * slots * d * 2, false))) return rc;
+    // int32 arena: d_n d_step d_nlive (+pad) | tr_tok tr_row tr_pos [n_max] | live_row plen limit cap [B] | am sel [n_sel] | out_tok
+    const size_t Bp = ss::round_up(B, 4), np = ss::round_up(n_max, 4), sp = ss::round_up(n_sel, 4);
+    const size_t n_i32 = 4 + 3 * np + 4 * Bp + 2 * sp + (size_t)B * max_new;
+    if ((rc = ws.ints.ensure(n_i32 * 4, false))) return rc;
+    if ((rc = ws.i64s.ensure(Bp * 8, false))) return rc;
+    int32_t* q = ws.ints.as<int32_t>();
+    MbState& st = w->st;
+    st.d_n = q; st.d_step = q + 1; st.d_nlive = q + 2; q += 4;
+    st.tr_tok = q; q += np;
+    st.tr_row = q; q += np;
+    st.tr_pos = q; q += np;
+    st.live_row = q; q += Bp;
+    st.row_plen = q; q += Bp;
+    st.row_limit = q; q += Bp;
+    st.row_cap = q; q += Bp;
+    st.am = q; q += sp;
+    w->d_sel = q; q += sp;
+    st.out_tok = q;
+    st.max_new = max_new;
+    st.row_so = ws.i64s.as<int64_t>();
+    return SS_OK;
+}
+
+// ---------------------------------------------------------------------------------------- one forward
+// Runs the decoder over the token-rows described by the device state (st.d_n of them, at most n of
+// them: n sizes the grids and picks the kernel variants).  Logits are produced for n_sel rows:
+// the rows listed in d_sel, or the first *d_nsel rows when d_sel is null.  Ends with the argmax.
+void forward(ss_weights* w, int n, int n_sel, const int32_t* d_sel, const int32_t* d_nsel, hipStream_t s)
+{
+    const ss_model_cfg& c = w->cfg;
+    const int d = c.d_model, H = c.n_heads, hd = c.head_dim, F = c.d_ffn, V = c.vocab;
+    Workspace& ws = w->ws;
+    const MbState& st = w->st;
+    float* x = ws.x.as<float>();
+    bf16_t* h = ws.h.as<bf16_t>();
+    bf16_t* ao = ws.ao.as<bf16_t>();
+    bf16_t* act = ws.act.as<bf16_t>();
+    float* qrot = ws.qrot.as<float>();
+    float* pqkv = ws.pqkv.as<float>();
+    float* pd = ws.pd.as<float>();
+    const int Fp = ss::padded_k(F);
+
+    const int ks_qkv = ss::gemm_pick_ksplit(3 * d, d, n, ss::EPI_PARTIAL);
+    const int ks_o = ss::gemm_pick_ksplit(d, d, n, ss::EPI_PARTIAL);
+    const int ks_d = ss::gemm_pick_ksplit(d, Fp, n, ss::EPI_PARTIAL);
+    const size_t st_qkv = (size_t)n * 3 * d, st_d = (size_t)n * d;
+
+    ss::launch_embed(st, w->embed, x, d, n, s);
+    for (int l = 0; l < c.n_layers; ++l) {
+        const Layer& L = w->layers[l];
+        bf16_t* kc = ws.kv.as<bf16_t>() + (size_t)l * 2 * w->kv_layer_stride;
+        bf16_t* vc = kc + w->kv_layer_stride;
+        ss::launch_rmsnorm(st, x, l ? pd : nullptr, ks_d, st_d, L.attn_norm, c.rms_eps, nullptr, nullptr, h, d, n, s);
+        GemmArgs g{};
+        g.W = L.wqkv.p; g.X = h; g.out = pqkv; g.N = 3 * d; g.Kp = d; g.m_rows = n; g.m_stride = n; g.ksplit = ks_qkv;
+        ss::launch_gemm(g, ss::EPI_PARTIAL, s);
+        ss::launch_rope_append(st, pqkv, ks_qkv, st_qkv, qrot, kc, vc, w->rope_cos, w->rope_sin, d, H, hd, n, s);
+        ss::launch_attention(st, qrot, kc, vc, ao, d, H, hd, n, s);
+        g = GemmArgs{};
+        g.W = L.wo.p; g.X = ao; g.out = pd; g.N = d; g.Kp = d; g.m_rows = n; g.m_stride = n; g.ksplit = ks_o;
+        ss::launch_gemm(g, ss::EPI_PARTIAL, s);
+        ss::launch_rmsnorm(st, x, pd, ks_o, st_d, L.mlp_norm, c.rms_eps, nullptr, nullptr, h, d, n, s);
+        g = GemmArgs{};
+        g.W = L.wgu.p; g.X = h; g.out_packed = act; g.N = 2 * F; g.Kp = d; g.m_rows = n; g.kp_out = Fp; g.ksplit = 1;
+        ss::launch_gemm(g, ss::EPI_SWIGLU, s);
+        g = GemmArgs{};
+        g.W = L.wd.p; g.X = act; g.out = pd; g.N = d; g.Kp = Fp; g.m_rows = n; g.m_stride = n; g.ksplit = ks_d;
+        ss::launch_gemm(g, ss::EPI_PARTIAL, s);
+    }
+    bf16_t* hsel = ws.hsel.as<bf16_t>();
+    ss::launch_rmsnorm(st, x, pd, ks_d, st_d, w->final_norm, c.rms_eps, d_sel, d_nsel, hsel, d, n_sel, s);
+    GemmArgs g{};
+    g.W = w->lm_head.p; g.X = hsel; g.out = ws.logits.as<float>(); g.N = V; g.Kp = d; g.m_rows = n_sel;
+    g.m_stride = n_sel; g.ksplit = 1;
+    ss::launch_gemm(g, ss::EPI_PARTIAL, s);
+    ss::launch_argmax(ws.logits.as<float>(), V, d_nsel ? d_nsel : st.d_n, st.am, n_sel, s);
+}
+
+int check_prompts(const ss_weights* w, const int32_t* toks, const int32_t* offs, int B)
+{
+    if (!w) return ss::fail(SS_EINVAL, "weights handle is NULL");
+    if (B <= 0) return ss::fail(SS_EINVAL, "B must be > 0");
+    if (B > ss::kMaxBatch) return ss::fail(SS_EINVAL, "B = %d exceeds %d rows", B, ss::kMaxBatch);
+    if (!toks || !offs) return ss::fail(SS_EINVAL, "NULL prompt arrays");
+    if (offs[0] != 0) return ss::fail(SS_EINVAL, "prompt_offsets[0] must be 0");
+    for (int i = 0; i < B; ++i)
+        if (offs[i + 1] <= offs[i]) return ss::fail(SS_EINVAL, "empty prompt or non-monotone offsets at row %d", i);
+    for (int t = 0; t < offs[B]; ++t)
+        if (toks[t] < 0 || toks[t] >= w->cfg.vocab) return ss::fail(SS_EINVAL, "token id %d out of range", toks[t]);
+    return SS_OK;
+}
+
+struct Upload {
+    std::vector<int32_t> v;
+    hipStream_t s;
+    int put(int32_t* dst, const int32_t* src, size_t n)
+    {
+        HIPCHK(hipMemcpyAsync(dst, src, n * 4, hipMemcpyHostToDevice, s));
+        return SS_OK;
+    }
+};
+
+// Uploads the state of a prompt forward: token-rows are the concatenated prompt positions.
+//   lens[i]   tokens of row i processed by this forward (positions 0..lens[i]-1)
+//   slab[i]   key/value slots reserved for row i
+int upload_prompt_state(ss_weights* w, const int32_t* toks, const int32_t* offs, const int32_t* lens, int B,
+                        const int32_t* slab, const int32_t* limit, const std::vector<int32_t>& sel, hipStream_t s)
+{
+    const MbState& st = w->st;
+    int n = 0;
+    for (int i = 0; i < B; ++i) n += lens[i];
+    std::vector<int32_t> tok(n), row(n), pos(n), live(B), plen(B);
+    std::vector<int64_t> so(B);
+    int at = 0;
+    int64_t slot = 0;
+    for (int i = 0; i < B; ++i) {
+        for (int t = 0; t < lens[i]; ++t, ++at) {
+            tok[at] = toks[offs[i] + t];
+            row[at] = i;
+            pos[at] = t;
+        }
+        live[i] = i;
+        plen[i] = lens[i];
+        so[i] = slot;
+        slot += slab[i];
+    }
+    const int32_t hdr[4] = {n, 0, B, 0};
+    HIPCHK(hipMemcpyAsync(st.d_n, hdr, 16, hipMemcpyHostToDevice, s));
+    HIPCHK(hipMemcpyAsync(st.tr_tok, tok.data(), (size_t)n * 4, hipMemcpyHostToDevice, s));
+    HIPCHK(hipMemcpyAsync(st.tr_row, row.data(), (size_t)n * 4, hipMemcpyHostToDevice, s));
+    HIPCHK(hipMemcpyAsync(st.tr_pos, pos.data(), (size_t)n * 4, hipMemcpyHostToDevice, s));
+    HIPCHK(hipMemcpyAsync(st.live_row, live.data(), (size_t)B * 4, hipMemcpyHostToDevice, s));
+    HIPCHK(hipMemcpyAsync(st.row_plen, plen.data(), (size_t)B * 4, hipMemcpyHostToDevice, s));
+    HIPCHK(hipMemcpyAsync(st.row_limit, limit, (size_t)B * 4, hipMemcpyHostToDevice, s));
+    HIPCHK(hipMemcpyAsync(st.row_cap, slab, (size_t)B * 4, hipMemcpyHostToDevice, s));
+    HIPCHK(hipMemcpyAsync(st.row_so, so.data(), (size_t)B * 8, hipMemcpyHostToDevice, s));
+    if (!sel.empty()) HIPCHK(hipMemcpyAsync(w->d_sel, sel.data(), sel.size() * 4, hipMemcpyHostToDevice, s));
+    HIPCHK(hipStreamSynchronize(s));   // the host vectors above die with this frame
+    return SS_OK;
+}
+
+int decode_microbatch_impl(ss_weights* w, const int32_t* prompt_tokens, const int32_t* prompt_offsets, int32_t B,
+                           int32_t max_new, const int32_t* target_lens, uint32_t flags, int32_t* out_tokens,
+                           int32_t* out_lens, uint8_t* out_failed, ss_stats* stats, hipStream_t s)
+{
+    if (int rc = check_prompts(w, prompt_tokens, prompt_offsets, B)) return rc;
+    if (max_new < 1) return ss::fail(SS_EINVAL, "max_new must be >= 1");
+    if (!target_lens || !out_tokens || !out_lens || !out_failed) return ss::fail(SS_EINVAL, "NULL argument");
+    if (flags & ~SS_COMPACT) return ss::fail(SS_EINVAL, "unknown flag");
+    std::vector<int32_t> lens(B), slab(B), limit(B), sel(B);
+    int n_prompt = prompt_offsets[B], steps = 0;
+    size_t slots = 0;
+    for (int i = 0; i < B; ++i) {
+        if (target_lens[i] < 1) return ss::fail(SS_EINVAL, "target_lens[%d] < 1", i);
+        lens[i] = prompt_offsets[i + 1] - prompt_offsets[i];
+        if (lens[i] + max_new > ss::kMaxPos)
+            return ss::fail(SS_EINVAL, "row %d: prompt %d + max_new %d exceeds %d positions", i, lens[i], max_new,
+                            ss::kMaxPos);
+        slab[i] = lens[i] + max_new;
+        slots += (size_t)slab[i];
+        limit[i] = std::min(target_lens[i], max_new);
+        steps = std::max(steps, limit[i]);
+        sel[i] = prompt_offsets[i + 1] - 1;
+    }
+    HIPCHK(hipSetDevice(w->device));
+    if (int rc = ensure_workspace(w, std::max(n_prompt, B), B, B, slots, max_new)) return rc;
+    const MbState& st = w->st;
+    const int compact = (flags & SS_COMPACT) ? 1 : 0;
+
+    if (int rc = upload_prompt_state(w, prompt_tokens, prompt_offsets, lens.data(), B, slab.data(), limit.data(), sel, s))
+        return rc;
+    ss::launch_fill_i32(st.out_tok, -1, (size_t)B * max_new, s);
+
+    hipEvent_t e0, e1, e2;
+    HIPCHK(hipEventCreate(&e0));
+    HIPCHK(hipEventCreate(&e1));
+    HIPCHK(hipEventCreate(&e2));
+    HIPCHK(hipEventRecord(e0, s));
+    forward(w, n_prompt, B, w->d_sel, st.d_nlive, s);
+    ss::launch_step_update(st, compact, s);
+    HIPCHK(hipEventRecord(e1, s));
+
+    int64_t row_steps = B, kv_tokens = 0;
+    std::vector<int32_t> sorted_limit(limit);
+    std::sort(sorted_limit.begin(), sorted_limit.end());
+    for (int g = 1; g < steps; ++g) {
+        // rows alive for forward g: all of them, or with compaction those that owe more than g tokens
+        int n_live = B;
+        if (compact)
+            n_live = (int)(sorted_limit.end() - std::upper_bound(sorted_limit.begin(), sorted_limit.end(), g));
+        forward(w, n_live, n_live, nullptr, nullptr, s);
+        ss::launch_step_update(st, compact, s);
+        row_steps += n_live;
+        if (stats)
+            for (int i = 0; i < B; ++i)
+                if (!compact || limit[i] > g) kv_tokens += lens[i] + g;
+    }
+    HIPCHK(hipEventRecord(e2, s));
+    HIPCHK(hipMemcpyAsync(out_tokens, st.out_tok, (size_t)B * max_new * 4, hipMemcpyDeviceToHost, s));
+    HIPCHK(hipStreamSynchronize(s));
+    HIPCHK(hipGetLastError());
+    for (int i = 0; i < B; ++i) {
+        out_lens[i] = limit[i];
+        out_failed[i] = target_lens[i] > max_new;
+    }
+    if (stats) {
+        float ms01 = 0.f, ms12 = 0.f;
+        HIPCHK(hipEventElapsedTime(&ms01, e0, e1));
+        HIPCHK(hipEventElapsedTime(&ms12, e1, e2));
+        stats->steps = steps;
+        stats->rows = B;
+        stats->row_steps = row_steps;
+        stats->prompt_tokens = n_prompt;
+        stats->decode_kv_tokens = kv_tokens;
+        stats->prefill_ms = ms01;
+        stats->decode_ms = ms12;
+    }
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    (void)hipEventDestroy(e2);
+    return SS_OK;
+}
+
+}  // namespace
+
+// ============================================================================================ C ABI
+extern "C" int ss_weights_create(const ss_model_cfg* cfg, const void* const* tensors, int32_t src_dtype,
+                                 ss_weights** out)
+{
+    ss::clear_error();
+    if (!out || !tensors) return ss::fail(SS_EINVAL, "NULL argument");
+    if (int rc = check_cfg(cfg)) return rc;
+    if (src_dtype != SS_BF16 && src_dtype != SS_F32) return ss::fail(SS_EINVAL, "unknown src_dtype");
+    const int nt = 3 + 9 * cfg->n_layers;
+    for (int i = 0; i < nt; ++i)
+        if (!tensors[i]) return ss::fail(SS_EINVAL, "tensors[%d] is NULL", i);
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) != hipSuccess || ndev < 1) return ss::fail(SS_EDEVICE, "no HIP device available");
+
+    ss_weights* w = new (std::nothrow) ss_weights();
+    if (!w) return ss::fail(SS_ENOMEM, "host allocation failed");
+    w->cfg = *cfg;
+    auto bail = [&](int rc) {
+        ss_weights_destroy(w);
+        return rc;
+    };
+    if (hipGetDevice(&w->device) != hipSuccess) return bail(ss::fail(SS_EDEVICE, "hipGetDevice failed"));
+    if (hipStreamCreate(&w->stream) != hipSuccess) return bail(ss::fail(SS_EDEVICE, "hipStreamCreate failed"));
+
+    const int d = cfg->d_model, F = cfg->d_ffn, V = cfg->vocab, f32 = (src_dtype == SS_F32);
+    Buf staging;
+    int rc = SS_OK;
+    int ti = 0;
+    auto done = [&](int r) {
+        staging.release();
+        return r == SS_OK ? SS_OK : bail(r);
+    };
+    if ((rc = upload_vec(w, staging, tensors[ti++], f32, (size_t)V * d, &w->embed))) return done(rc);
+    w->layers.resize(cfg->n_layers);
+    for (int l = 0; l < cfg->n_layers; ++l) {
+        Layer& L = w->layers[l];
+        if ((rc = upload_vec(w, staging, tensors[ti++], f32, d, &L.attn_norm))) return done(rc);
+        if ((rc = alloc_packed(w, &L.wqkv, 3 * d, d))) return done(rc);
+        for (int part = 0; part < 3; ++part)   // q, k, v stacked along the output dimension
+            if ((rc = upload_pack(w, staging, tensors[ti++], f32, d, d, L.wqkv.p, L.wqkv.Kp, 1, part * d / 16)))
+                return done(rc);
+        if ((rc = alloc_packed(w, &L.wo, d, d))) return done(rc);
+        if ((rc = upload_pack(w, staging, tensors[ti++], f32, d, d, L.wo.p, L.wo.Kp, 1, 0))) return done(rc);
+        if ((rc = upload_vec(w, staging, tensors[ti++], f32, d, &L.mlp_norm))) return done(rc);
+        if ((rc = alloc_packed(w, &L.wgu, 2 * F, d))) return done(rc);
+        for (int part = 0; part < 2; ++part)   // gate and up strips interleaved: strip 2j = gate, 2j+1 = up
+            if ((rc = upload_pack(w, staging, tensors[ti++], f32, F, d, L.wgu.p, L.wgu.Kp, 2, part))) return done(rc);
+        if ((rc = alloc_packed(w, &L.wd, d, F))) return done(rc);
+        if ((rc = upload_pack(w, staging, tensors[ti++], f32, d, F, L.wd.p, L.wd.Kp, 1, 0))) return done(rc);
+    }
+    if ((rc = upload_vec(w, staging, tensors[ti++], f32, d, &w->final_norm))) return done(rc);
+    if ((rc = alloc_packed(w, &w->lm_head, V, d))) return done(rc);
+    if ((rc = upload_pack(w, staging, tensors[ti++], f32, V, d, w->lm_head.p, w->lm_head.Kp, 1, 0))) return done(rc);
+
+    // rotary tables: cos/sin(pos * base^(-2e/hd)) evaluated in double, stored as fp32 [pos][e]
+    const int half = cfg->head_dim / 2;
+    std::vector<float> tc((size_t)ss::kMaxPos * half), tsn((size_t)ss::kMaxPos * half);
+    for (int e = 0; e < half; ++e) {
+        const double inv = std::pow((double)cfg->rope_base, -2.0 * e / (double)cfg->head_dim);
+        for (int p = 0; p < ss::kMaxPos; ++p) {
+            tc[(size_t)p * half + e] = (float)std::cos(p * inv);
+            tsn[(size_t)p * half + e] = (float)std::sin(p * inv);
+        }
+    }
+    void* p = nullptr;
+    if ((rc = dev_alloc(w, &p, tc.size() * 4, false))) return done(rc);
+    w->rope_cos = (float*)p;
+    if ((rc = dev_alloc(w, &p, tsn.size() * 4, false))) return done(rc);
+    w->rope_sin = (float*)p;
+    if (hipMemcpy(w->rope_cos, tc.data(), tc.size() * 4, hipMemcpyHostToDevice) != hipSuccess ||
+        hipMemcpy(w->rope_sin, tsn.data(), tsn.size() * 4, hipMemcpyHostToDevice) != hipSuccess)
+        return done(ss::fail(SS_EDEVICE, "rotary table upload failed"));
+    staging.release();
+    *out = w;
+    return SS_OK;
+}
+
+extern "C" void ss_weights_destroy(ss_weights* w)
+{
+    if (!w) return;
+    (void)hipSetDevice(w->device);
+    if (w->stream) (void)hipStreamSynchronize(w->stream);
+    w->ws.release();
+    for (void* p : w->allocs) (void)hipFree(p);
+    if (w->stream) (void)hipStreamDestroy(w->stream);
+    delete w;
+}
+
+extern "C" int ss_decode_microbatch(ss_weights* w, const int32_t* prompt_tokens, const int32_t* prompt_offsets,
+                                    int32_t B, int32_t max_new, const int32_t* target_lens, uint32_t flags,
+                                    int32_t* out_tokens, int32_t* out_lens, uint8_t* out_failed, ss_stats* stats,
+                                    void* hip_stream)
+{
+    ss::clear_error();
+    if (!w) return ss::fail(SS_EINVAL, "weights handle is NULL");
+    BusyGuard guard(w);
+    if (!guard.ok) return ss::fail(SS_ESTATE, "another call is in flight on this handle");
+    hipStream_t s = hip_stream ? (hipStream_t)hip_stream : w->stream;
+    return decode_microbatch_impl(w, prompt_tokens, prompt_offsets, B, max_new, target_lens, flags, out_tokens,
+                                  out_lens, out_failed, stats, s);
+}
+
+extern "C" int ss_forward_logits(ss_weights* w, const int32_t* tokens, const int32_t* offsets, int32_t B,
+                                 const int32_t* n_prompt, int32_t all_prompt_logits, float* logits_out,
+                                 void* hip_stream)
+{
+    ss::clear_error();
+    if (int rc = check_prompts(w, tokens, offsets, B)) return rc;
+    if (!n_prompt || !logits_out) return ss::fail(SS_EINVAL, "NULL argument");
+    BusyGuard guard(w);
+    if (!guard.ok) return ss::fail(SS_ESTATE, "another call is in flight on this handle");
+    hipStream_t s = hip_stream ? (hipStream_t)hip_stream : w->stream;
+    const int V = w->cfg.vocab;
+    std::vector<int32_t> len(B), slab(B), limit(B, 1), np(n_prompt, n_prompt + B), sel;
+    std::vector<size_t> out_base(B);
+    int n_p = 0, max_extra = 0;
+    size_t slots = 0, out_rows = 0;
+    for (int i = 0; i < B; ++i) {
+        len[i] = offsets[i + 1] - offsets[i];
+        if (len[i] > ss::kMaxPos) return ss::fail(SS_EINVAL, "row %d longer than %d positions", i, ss::kMaxPos);
+        if (np[i] < 1 || np[i] > len[i]) return ss::fail(SS_EINVAL, "n_prompt[%d] out of range", i);
+        if (all_prompt_logits && np[i] != len[i]) return ss::fail(SS_EINVAL, "all_prompt_logits needs n_prompt == len");
+        slab[i] = len[i];
+        slots += (size_t)len[i];
+        out_base[i] = out_rows;
+        if (all_prompt_logits) {
+            for (int t = 0; t < len[i]; ++t) sel.push_back(n_p + t);
+            out_rows += (size_t)len[i];
+        } else {
+            sel.push_back(n_p + np[i] - 1);
+            out_rows += (size_t)(len[i] - np[i] + 1);
+        }
+        n_p += np[i];
+        max_extra = std::max(max_extra, len[i] - np[i]);
+    }
+    const int n_sel = (int)sel.size();
+    HIPCHK(hipSetDevice(w->device));
+    if (int rc = ensure_workspace(w, std::max(n_p, B), B, std::max(n_sel, B), slots, 1)) return rc;
+    const MbState& st = w->st;
+    // prompt forward over the first n_prompt[i] tokens of every row
+    std::vector<int32_t> ptoks, poffs(B + 1, 0);
+    for (int i = 0; i < B; ++i) {
+        ptoks.insert(ptoks.end(), tokens + offsets[i], tokens + offsets[i] + np[i]);
+        poffs[i + 1] = (int32_t)ptoks.size();
+    }
+    if (int rc = upload_prompt_state(w, ptoks.data(), poffs.data(), np.data(), B, slab.data(), limit.data(), sel, s))
+        return rc;
+    const int32_t nsel32 = n_sel;
+    HIPCHK(hipMemcpyAsync(st.d_nlive, &nsel32, 4, hipMemcpyHostToDevice, s));
+    forward(w, n_p, n_sel, w->d_sel, st.d_nlive, s);
+    std::vector<float> lg((size_t)std::max(n_sel, B) * V);
+    HIPCHK(hipMemcpyAsync(lg.data(), w->ws.logits.p, (size_t)n_sel * V * 4, hipMemcpyDeviceToHost, s));
+    HIPCHK(hipStreamSynchronize(s));
+    if (all_prompt_logits) {
+        std::memcpy(logits_out, lg.data(), (size_t)n_sel * V * 4);
+    } else {
+        for (int i = 0; i < B; ++i) std::memcpy(logits_out + out_base[i] * V, lg.data() + (size_t)i * V, (size_t)V * 4);
+    }
+    // decode steps: rows that still have a forced token feed it at their next position
+    for (int g = 1; g <= max_extra; ++g) {
+        std::vector<int32_t> tok, row, pos;
+        for (int i = 0; i < B; ++i)
+            if (len[i] - np[i] >= g) {
+                tok.push_back(tokens[offsets[i] + np[i] + g - 1]);
+                row.push_back(i);
+                pos.push_back(np[i] + g - 1);
+            }
+        const int n = (int)tok.size();
+        const int32_t n32 = n;
+        HIPCHK(hipMemcpyAsync(st.d_n, &n32, 4, hipMemcpyHostToDevice, s));
+        HIPCHK(hipMemcpyAsync(st.tr_tok, tok.data(), (size_t)n * 4, hipMemcpyHostToDevice, s));
+        HIPCHK(hipMemcpyAsync(st.tr_row, row.data(), (size_t)n * 4, hipMemcpyHostToDevice, s));
+        HIPCHK(hipMemcpyAsync(st.tr_pos, pos.data(), (size_t)n * 4, hipMemcpyHostToDevice, s));
+        forward(w, n, n, nullptr, nullptr, s);
+        HIPCHK(hipMemcpyAsync(lg.data(), w->ws.logits.p, (size_t)n * V * 4, hipMemcpyDeviceToHost, s));
+        HIPCHK(hipStreamSynchronize(s));
+        for (int j = 0; j < n; ++j)
+            std::memcpy(logits_out + (out_base[row[j]] + g) * V, lg.data() + (size_t)j * V, (size_t)V * 4);
+    }
+    HIPCHK(hipGetLastError());
+    return SS_OK;
+}
+
+extern "C" int ss_run_group(ss_weights* w, const int32_t* prompt_tokens, const int32_t* prompt_offsets, int32_t n,
+                            const int32_t* target_lens, const int32_t* pred_lens, int32_t bin, const ss_policy* policy,
+                            int32_t* out_tokens, int32_t* out_lens, ss_group_stats* stats, void* hip_stream)
+{
+    ss::clear_error();
+    if (!w) return ss::fail(SS_EINVAL, "weights handle is NULL");
+    if (n <= 0 || !prompt_tokens || !prompt_offsets || !target_lens || !policy || !out_tokens || !out_lens)
+        return ss::fail(SS_EINVAL, "NULL or empty argument");
+    BusyGuard guard(w);
+    if (!guard.ok) return ss::fail(SS_ESTATE, "another call is in flight on this handle");
+    hipStream_t s = hip_stream ? (hipStream_t)hip_stream : w->stream;
+    for (int i = 0; i < n; ++i)
+        if (target_lens[i] < 1 || target_lens[i] > policy->base_len)
+            return ss::fail(SS_EINVAL, "target_lens[%d] outside [1, base_len]", i);
+
+    using clk = std::chrono::steady_clock;
+    const auto t_plan0 = clk::now();
+    ss_plan* plan = nullptr;
+    if (int rc = ss_schedule(pred_lens, n, bin, policy, &plan)) return rc;
+    double plan_ms = std::chrono::duration<double, std::milli>(clk::now() - t_plan0).count();
+
+    ss_group_stats gs{};
+    const int L = policy->base_len;
+    const uint32_t eflags = policy->flags & SS_COMPACT;
+    std::vector<int32_t> failed;
+    std::vector<int32_t> mb_toks, mb_offs, mb_tl, mb_out, mb_lens;
+    std::vector<uint8_t> mb_failed;
+    for (size_t i = 0; i < (size_t)n * L; ++i) out_tokens[i] = -1;
+
+    auto run_plan = [&](const ss_plan* pl, bool first) -> int {
+        for (int k = 0; k < pl->n_mb; ++k) {
+            const int b0 = pl->mb_offsets[k], B = pl->mb_offsets[k + 1] - b0, cap = pl->mb_cap[k];
+            mb_toks.clear();
+            mb_offs.assign(1, 0);
+            mb_tl.resize(B);
+            for (int r = 0; r < B; ++r) {
+                const int qi = pl->query_idx[b0 + r];
+                mb_toks.insert(mb_toks.end(), prompt_tokens + prompt_offsets[qi], prompt_tokens + prompt_offsets[qi + 1]);
+                mb_offs.push_back((int32_t)mb_toks.size());
+                mb_tl[r] = target_lens[qi];
+            }
+            mb_out.resize((size_t)B * cap);
+            mb_lens.resize(B);
+            mb_failed.resize(B);
+            ss_stats st{};
+            if (int rc = decode_microbatch_impl(w, mb_toks.data(), mb_offs.data(), B, cap, mb_tl.data(), eflags,
+                                                mb_out.data(), mb_lens.data(), mb_failed.data(), &st, s))
+                return rc;
+            for (int r = 0; r < B; ++r) {
+                const int qi = pl->query_idx[b0 + r];
+                if (mb_failed[r]) {   // partial output and key/value state are dropped; recomputed later
+                    failed.push_back(qi);
+                    continue;
+                }
+                std::memcpy(out_tokens + (size_t)qi * L, mb_out.data() + (size_t)r * cap, (size_t)mb_lens[r] * 4);
+                out_lens[qi] = mb_lens[r];
+            }
+            gs.steps += st.steps;
+            gs.padded_row_steps += (int64_t)B * st.steps;
+            gs.computed_row_steps += st.row_steps;
+            gs.prompt_tokens += st.prompt_tokens;
+            gs.prefill_ms += st.prefill_ms;
+            gs.decode_ms += st.decode_ms;
+            (first ? gs.n_mb_first : gs.n_mb_failure) += 1;
+        }
+        return SS_OK;
+    };
+
+    const auto t0 = clk::now();
+    int rc = run_plan(plan, true);
+    ss_plan_free(plan);
+    if (rc) return rc;
+    gs.n_failed = (int32_t)failed.size();
+    if (!failed.empty()) {
+        std::sort(failed.begin(), failed.end());
+        const auto tp = clk::now();
+        ss_plan* fplan = nullptr;
+        if ((rc = ss_schedule_failures(pred_lens, n, failed.data(), (int32_t)failed.size(), bin, policy, &fplan)))
+            return rc;
+        plan_ms += std::chrono::duration<double, std::milli>(clk::now() - tp).count();
+        failed.clear();
+        rc = run_plan(fplan, false);
+        ss_plan_free(fplan);
+        if (rc) return rc;
+        if (!failed.empty()) return ss::fail(SS_ESTATE, "a query failed in the recomputation pass");
+    }
+    gs.wall_ms = std::chrono::duration<double, std::milli>(clk::now() - t0).count();
+    gs.plan_ms = plan_ms;
+    for (int i = 0; i < n; ++i) gs.useful_tokens += target_lens[i];
+    if (stats) *stats = gs;
+    return SS_OK;
+}
+
+extern "C" int ss_bench_decode_step(ss_weights* w, const int32_t* prompt_tokens, int32_t B, int32_t ctx,
+                                    int32_t iters, double* ms_out, void* hip_stream)
+{
+    ss::clear_error();
+    if (!w || !prompt_tokens || !ms_out) return ss::fail(SS_EINVAL, "NULL argument");
+    if (B <= 0 || B > ss::kMaxBatch || ctx < 1 || ctx + 1 > ss::kMaxPos || iters < 1)
+        return ss::fail(SS_EINVAL, "bad B / ctx / iters");
+    for (size_t t = 0; t < (size_t)B * ctx; ++t)
+        if (prompt_tokens[t] < 0 || prompt_tokens[t] >= w->cfg.vocab) return ss::fail(SS_EINVAL, "token id out of range");
+    BusyGuard guard(w);
+    if (!guard.ok) return ss::fail(SS_ESTATE, "another call is in flight on this handle");
+    hipStream_t s = hip_stream ? (hipStream_t)hip_stream : w->stream;
+    std::vector<int32_t> offs(B + 1), lens(B, ctx), slab(B, ctx + 1), limit(B, 2), sel(B);
+    for (int i = 0; i <= B; ++i) offs[i] = i * ctx;
+    for (int i = 0; i < B; ++i) sel[i] = (i + 1) * ctx - 1;
+    HIPCHK(hipSetDevice(w->device));
+    if (int rc = ensure_workspace(w, B * ctx, B, B, (size_t)B * (ctx + 1), 2)) return rc;
+    const MbState& st = w->st;
+    if (int rc = upload_prompt_state(w, prompt_tokens, offs.data(), lens.data(), B, slab.data(), limit.data(), sel, s))
+        return rc;
+    forward(w, B * ctx, B, w->d_sel, st.d_nlive, s);
+    ss::launch_step_update(st, 0, s);   // token-rows of the decode step: every row at position ctx
+    std::vector<hipEvent_t> ev(iters + 1);
+    for (auto& e : ev) HIPCHK(hipEventCreate(&e));
+    HIPCHK(hipEventRecord(ev[0], s));
+    for (int it = 0; it < iters; ++it) {
+        forward(w, B, B, nullptr, nullptr, s);
+        HIPCHK(hipEventRecord(ev[it + 1], s));
+    }
+    HIPCHK(hipStreamSynchronize(s));
+    HIPCHK(hipGetLastError());
+    for (int it = 0; it < iters; ++it) {
+        float ms = 0.f;
+        HIPCHK(hipEventElapsedTime(&ms, ev[it], ev[it + 1]));
+        ms_out[it] = ms;
+    }
+    for (auto& e : ev) (void)hipEventDestroy(e);
+    return SS_OK;
+}

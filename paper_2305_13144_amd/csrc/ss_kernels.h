@@ -1,0 +1,71 @@
+// Launch wrappers of the gfx950 kernels (host side).  All pointers are device pointers.
+#ifndef SS_KERNELS_H
+#define SS_KERNELS_H
+
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+namespace ss {
+
+typedef uint16_t bf16_t;  // bf16 bit pattern
+
+// Packed weight matrix: N output rows (multiple of 16), K inputs padded to Kp (multiple of 64).
+struct PackedMat {
+    bf16_t* p = nullptr;
+    int N = 0, K = 0, Kp = 0;
+};
+
+// Per-micro-batch device state read and written by the kernels, so that one decode step can be
+// replayed without any host-side scalar changing.
+struct MbState {
+    int32_t* d_n;        // [1] token-rows of the next forward
+    int32_t* d_step;     // [1] tokens generated so far by every live row (rows advance in lockstep)
+    int32_t* tr_tok;     // [n_max] token id fed by token-row j
+    int32_t* tr_row;     // [n_max] micro-batch row of token-row j
+    int32_t* tr_pos;     // [n_max] position of token-row j inside its row
+    int32_t* live_row;   // [B]     rows still in the live batch, in slot order
+    int32_t* d_nlive;    // [1]
+    int32_t* row_plen;   // [B] prompt length
+    int32_t* row_limit;  // [B] min(target, cap): tokens the row emits
+    int64_t* row_so;     // [B] first key/value slot of the row's slab
+    int32_t* row_cap;    // [B] slots in the row's slab (prompt + cap)
+    int32_t* am;         // [n_sel_max] argmax of the selected rows' logits
+    int32_t* out_tok;    // [B][max_new]
+    int32_t max_new;
+};
+
+enum Epilogue { EPI_PARTIAL = 0, EPI_SWIGLU = 1 };
+
+struct GemmArgs {
+    const bf16_t* W;     // packed [N, Kp]
+    const bf16_t* X;     // packed [rows, Kp]
+    float* out;          // EPI_PARTIAL: [ksplit][m_stride][N] fp32
+    bf16_t* out_packed;  // EPI_SWIGLU: packed [rows, kp_out], column f = silu(gate_f) * up_f
+    int N, Kp, m_rows;   // m_rows: rows to compute (stores are guarded by it)
+    int m_stride;        // row stride (in rows) between k-slices of `out`
+    int kp_out;          // padded K of out_packed
+    int ksplit;
+};
+
+void launch_pack_weight(const void* src, int src_f32, bf16_t* dst, int n_src, int k, int kp, int blk_stride,
+                        int blk_off, hipStream_t s);
+void launch_cast_rows(const void* src, int src_f32, bf16_t* dst, size_t count, hipStream_t s);
+void launch_embed(const MbState& st, const bf16_t* embed, float* x, int d, int n_max, hipStream_t s);
+void launch_rmsnorm(const MbState& st, float* x, const float* part, int ksplit, size_t part_stride,
+                    const bf16_t* w, float eps, const int32_t* sel, const int32_t* d_nsel, bf16_t* h_packed, int d,
+                    int n_max, hipStream_t s);
+void launch_gemm(const GemmArgs& a, int epilogue, hipStream_t s);
+int  gemm_pick_ksplit(int N, int Kp, int m_rows, int epilogue);
+void launch_rope_append(const MbState& st, const float* qkv_part, int ksplit, size_t part_stride, float* qrot,
+                        bf16_t* kcache, bf16_t* vcache, const float* rope_cos, const float* rope_sin, int d, int H,
+                        int hd, int n_max, hipStream_t s);
+void launch_attention(const MbState& st, const float* qrot, const bf16_t* kcache, const bf16_t* vcache,
+                      bf16_t* out_packed, int d, int H, int hd, int n_max, hipStream_t s);
+void launch_argmax(const float* logits, int vocab, const int32_t* d_nsel, int32_t* am, int n_max, hipStream_t s);
+void launch_step_update(const MbState& st, int compact, hipStream_t s);
+void launch_fill_i32(int32_t* p, int32_t v, size_t n, hipStream_t s);
+
+}  // namespace ss
+
+#endif

@@ -1,0 +1,680 @@
+// gfx950 kernels of the decode path.  One wavefront = 64 lanes; matrix work uses
+// v_mfma_f32_16x16x32_bf16 (A: 16 rows x 32 k, B: 32 k x 16 cols, 8 bf16 per lane;
+// D: lane holds rows 4*(lane/16)..+3 of column lane%16).
+//
+// Convention for every contraction here: the weight strip is the A operand (its 16 output
+// columns become D's rows) and the activation strip is the B operand (its 16 token rows become
+// D's columns), so a lane ends up with 4 consecutive output columns of one token row.
+#include "ss_kernels.h"
+
+#include <hip/hip_runtime.h>
+
+#include "ss_internal.h"
+
+namespace ss {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));  // one 16-byte operand fragment
+
+// ------------------------------------------------------------------------------------------ helpers
+__device__ __forceinline__ float bf2f(bf16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+
+__device__ __forceinline__ bf16_t f2bf(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    u += 0x7FFFu + ((u >> 16) & 1u);  // round to nearest, ties to even (inputs are finite)
+    return (bf16_t)(u >> 16);
+}
+
+// Element (r, k) of a packed [rows, Kp] matrix.
+__device__ __forceinline__ size_t pk_index(int r, int k, int Kp)
+{
+    return ((size_t)(r >> 4) * (size_t)(Kp >> 5) + (size_t)(k >> 5)) * 512u +
+           (size_t)(((((k & 31) >> 3) << 4) + (r & 15)) * 8 + (k & 7));
+}
+
+__device__ __forceinline__ float wave_sum(float v)
+{
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, 64);
+    return v;
+}
+
+__device__ __forceinline__ float wave_max(float v)
+{
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) v = fmaxf(v, __shfl_xor(v, m, 64));
+    return v;
+}
+
+// ------------------------------------------------------------------------------------------ weight packing
+// src is row-major [n_src, k] (bf16 bits or fp32); source row r lands in packed row
+// (r/16 * blk_stride + blk_off) * 16 + r%16.  One thread moves 8 consecutive k.
+__global__ void k_pack_weight(const void* __restrict__ src, int src_f32, bf16_t* __restrict__ dst, int n_src, int k,
+                              int kp, int blk_stride, int blk_off)
+{
+    const int groups = k >> 3;
+    const size_t total = (size_t)n_src * groups;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += (size_t)gridDim.x * blockDim.x) {
+        const int r = (int)(i / groups), kg = (int)(i % groups);
+        bf16_t v[8];
+        if (src_f32) {
+            const float* sp = (const float*)src + (size_t)r * k + kg * 8;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] = f2bf(sp[e]);
+        } else {
+            const uint4 raw = *(const uint4*)((const bf16_t*)src + (size_t)r * k + kg * 8);
+            *(uint4*)v = raw;
+        }
+        const int rd = ((r >> 4) * blk_stride + blk_off) * 16 + (r & 15);
+        *(uint4*)(dst + pk_index(rd, kg * 8, kp)) = *(const uint4*)v;
+    }
+}
+
+__global__ void k_cast_rows(const void* __restrict__ src, int src_f32, bf16_t* __restrict__ dst, size_t count)
+{
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += (size_t)gridDim.x * blockDim.x)
+        dst[i] = src_f32 ? f2bf(((const float*)src)[i]) : ((const bf16_t*)src)[i];
+}
+
+__global__ void k_fill_i32(int32_t* p, int32_t v, size_t n)
+{
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = v;
+}
+
+// ------------------------------------------------------------------------------------------ embedding
+__global__ __launch_bounds__(256) void k_embed(MbState st, const bf16_t* __restrict__ embed, float* __restrict__ x,
+                                               int d)
+{
+    const int j = blockIdx.x;
+    if (j >= *st.d_n) return;
+    const bf16_t* e = embed + (size_t)st.tr_tok[j] * d;
+    float* xr = x + (size_t)j * d;
+    for (int c = threadIdx.x * 8; c < d; c += 256 * 8) {
+        const uint4 raw = *(const uint4*)(e + c);
+        const bf16_t* v = (const bf16_t*)&raw;
+        float4 a = make_float4(bf2f(v[0]), bf2f(v[1]), bf2f(v[2]), bf2f(v[3]));
+        float4 b = make_float4(bf2f(v[4]), bf2f(v[5]), bf2f(v[6]), bf2f(v[7]));
+        *(float4*)(xr + c) = a;
+        *(float4*)(xr + c + 4) = b;
+    }
+}
+
+// ------------------------------------------------------------------------------------------ RMSNorm
+// Row j (or sel[j]) of the residual stream: x += sum over k-slices of the previous projection's
+// partial sums (written back when sel is null), then h = x * rsqrt(mean x^2 + eps) * w as packed bf16.
+constexpr int kNormIters = 8;  // d <= 8 * 1024
+
+__global__ __launch_bounds__(256) void k_rmsnorm(const int32_t* __restrict__ d_count, float* __restrict__ x,
+                                                 const float* __restrict__ part, int ksplit, size_t part_stride,
+                                                 const bf16_t* __restrict__ w, float eps,
+                                                 const int32_t* __restrict__ sel, bf16_t* __restrict__ h, int d)
+{
+    const int j = blockIdx.x;
+    if (j >= *d_count) return;
+    const int src = sel ? sel[j] : j;
+    float4 v[kNormIters];
+    float ss = 0.f;
+#pragma unroll
+    for (int it = 0; it < kNormIters; ++it) {
+        const int c = threadIdx.x * 4 + it * 1024;
+        if (c < d) {
+            float4 a = *(const float4*)(x + (size_t)src * d + c);
+            for (int s = 0; s < ksplit; ++s) {
+                const float4 p = *(const float4*)(part + (size_t)s * part_stride + (size_t)src * d + c);
+                a.x += p.x; a.y += p.y; a.z += p.z; a.w += p.w;
+            }
+            if (part && !sel) *(float4*)(x + (size_t)src * d + c) = a;
+            v[it] = a;
+            ss += a.x * a.x + a.y * a.y + a.z * a.z + a.w * a.w;
+        }
+    }
+    __shared__ float red[4];
+    ss = wave_sum(ss);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
+    __syncthreads();
+    const float tot = red[0] + red[1] + red[2] + red[3];
+    const float r = rsqrtf(tot / (float)d + eps);
+#pragma unroll
+    for (int it = 0; it < kNormIters; ++it) {
+        const int c = threadIdx.x * 4 + it * 1024;
+        if (c < d) {
+            const uint2 wr = *(const uint2*)(w + c);
+            const bf16_t* wv = (const bf16_t*)&wr;
+            bf16_t o[4];
+            o[0] = f2bf(v[it].x * r * bf2f(wv[0]));
+            o[1] = f2bf(v[it].y * r * bf2f(wv[1]));
+            o[2] = f2bf(v[it].z * r * bf2f(wv[2]));
+            o[3] = f2bf(v[it].w * r * bf2f(wv[3]));
+            *(uint2*)(h + pk_index(j, c, d)) = *(const uint2*)o;   // d is a multiple of 64: Kp == d
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------ skinny GEMM
+// Up to 64 token rows (MT strips of 16).  One wavefront owns NB strips of 16 output columns and one
+// k-slice: per 32-wide k-block it loads NB weight operands straight from HBM (1 KiB contiguous each,
+// never re-read by anyone) and MT activation operands (L2 hits), and issues NB*MT MFMAs.  Waves never
+// synchronise; KD k-blocks are loaded per loop trip so that NB*KD KiB of weights are in flight per wave.
+__device__ __forceinline__ float silu_f(float z) { return z / (1.f + __expf(-z)); }
+
+template <int MT, int NB, int KD, int EPI>
+__global__ __launch_bounds__(256) void k_gemm_skinny(GemmArgs a, int n_groups, int kb_per_slice)
+{
+    const int lane = threadIdx.x & 63;
+    const int task = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (task >= n_groups * a.ksplit) return;
+    const int ng = task % n_groups, ks = task / n_groups;
+    const int KB = a.Kp >> 5, NBT = a.N >> 4;
+    const int kb0 = ks * kb_per_slice;
+    const int kb1 = min(KB, kb0 + kb_per_slice);
+    const int nb0 = ng * NB;
+
+    f32x4 acc[NB][MT];
+#pragma unroll
+    for (int i = 0; i < NB; ++i)
+#pragma unroll
+        for (int m = 0; m < MT; ++m) acc[i][m] = (f32x4){0.f, 0.f, 0.f, 0.f};
+
+    const u32x4* Wl = (const u32x4*)a.W + lane;
+    const u32x4* Xl = (const u32x4*)a.X + lane;
+    const int nvalid = min(NB, NBT - nb0);  // wave-uniform
+
+    for (int kb = kb0; kb < kb1; kb += KD) {
+        u32x4 wf[NB][KD], xf[MT][KD];
+#pragma unroll
+        for (int i = 0; i < NB; ++i)
+#pragma unroll
+            for (int q = 0; q < KD; ++q) {
+                const int kk = min(kb + q, kb1 - 1);          // clamped re-read on the tail, result unused
+                const int nb = nb0 + (i < nvalid ? i : 0);
+                wf[i][q] = __builtin_nontemporal_load(Wl + ((size_t)nb * KB + kk) * 64);
+            }
+#pragma unroll
+        for (int m = 0; m < MT; ++m)
+#pragma unroll
+            for (int q = 0; q < KD; ++q) {
+                const int kk = min(kb + q, kb1 - 1);
+                xf[m][q] = Xl[((size_t)m * KB + kk) * 64];
+            }
+#pragma unroll
+        for (int q = 0; q < KD; ++q) {
+            if (kb + q < kb1) {
+#pragma unroll
+                for (int i = 0; i < NB; ++i)
+#pragma unroll
+                    for (int m = 0; m < MT; ++m)
+                        acc[i][m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wf[i][q]),
+                                                                            __builtin_bit_cast(bf16x8, xf[m][q]),
+                                                                            acc[i][m], 0, 0, 0);
+            }
+        }
+    }
+
+    const int col4 = (lane >> 4) * 4;  // first of this lane's 4 consecutive output columns inside a strip
+#pragma unroll
+    for (int m = 0; m < MT; ++m) {
+        const int row = m * 16 + (lane & 15);
+        if (row >= a.m_rows) continue;
+        if (EPI == EPI_PARTIAL) {
+            float* o = a.out + ((size_t)ks * a.m_stride + row) * a.N;
+#pragma unroll
+            for (int i = 0; i < NB; ++i)
+                if (i < nvalid)
+                    *(float4*)(o + (nb0 + i) * 16 + col4) =
+                        make_float4(acc[i][m][0], acc[i][m][1], acc[i][m][2], acc[i][m][3]);
+        } else {
+            // strips alternate gate, up for the same 16 MLP columns
+#pragma unroll
+            for (int i = 0; i + 1 < NB; i += 2)
+                if (i + 1 < nvalid) {
+                    const int f = ((nb0 + i) >> 1) * 16 + col4;
+                    bf16_t o[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) o[e] = f2bf(silu_f(acc[i][m][e]) * acc[i + 1][m][e]);
+                    *(uint2*)(a.out_packed + pk_index(row, f, a.kp_out)) = *(const uint2*)o;
+                }
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------ tiled GEMM
+// 128 token rows x 128 output columns per workgroup, 64 k per trip, both operands staged through LDS in
+// operand order (a wave reads whole 1 KiB blocks, conflict free).  4 waves as 2 (columns) x 2 (rows),
+// each 64 x 64 = 4 x 4 MFMA tiles.  Used for prompt forwards and decode batches above 64 rows.
+template <int EPI>
+__global__ __launch_bounds__(256) void k_gemm_tiled(GemmArgs a, int kb_per_slice)
+{
+    __shared__ uint4 lds[2][2048];  // per stage: W 8 strips x 2 k-blocks x 64 lanes, then X the same
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wn = wave & 1, wm = wave >> 1;
+    const int KB = a.Kp >> 5, NBT = a.N >> 4;
+    const int MBT = (a.m_rows + 15) >> 4;
+    const int nb0 = blockIdx.x * 8, mb0 = blockIdx.y * 8, ks = blockIdx.z;
+    const int kb0 = ks * kb_per_slice, kb1 = min(KB, kb0 + kb_per_slice);
+
+    f32x4 acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int m = 0; m < 4; ++m) acc[i][m] = (f32x4){0.f, 0.f, 0.f, 0.f};
+
+    const uint4* W4 = (const uint4*)a.W;
+    const uint4* X4 = (const uint4*)a.X;
+    uint4 stage[8];
+    auto gload = [&](int kb) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int c = tid + i * 256;            // 0..2047
+            const int isx = c >> 10, cc = c & 1023;
+            const int strip = cc >> 7, within = cc & 127;   // two k-blocks of one strip are contiguous
+            if (!isx) {
+                const int nb = min(nb0 + strip, NBT - 1);
+                stage[i] = W4[((size_t)nb * KB + kb) * 64 + within];
+            } else {
+                const int mb = min(mb0 + strip, MBT - 1);
+                stage[i] = X4[((size_t)mb * KB + kb) * 64 + within];
+            }
+        }
+    };
+    auto lstore = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) lds[buf][tid + i * 256] = stage[i];
+    };
+
+    if (kb0 < kb1) {   // an empty k-slice still writes its zeros below
+        gload(kb0);
+        lstore(0);
+    }
+    __syncthreads();
+    int buf = 0;
+    for (int kb = kb0; kb < kb1; kb += 2) {
+        const bool more = kb + 2 < kb1;
+        if (more) gload(kb + 2);
+#pragma unroll
+        for (int kk = 0; kk < 2; ++kk) {
+            uint4 wf[4], xf[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) wf[i] = lds[buf][((wn * 4 + i) * 2 + kk) * 64 + lane];
+#pragma unroll
+            for (int m = 0; m < 4; ++m) xf[m] = lds[buf][1024 + ((wm * 4 + m) * 2 + kk) * 64 + lane];
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int m = 0; m < 4; ++m)
+                    acc[i][m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wf[i]),
+                                                                        __builtin_bit_cast(bf16x8, xf[m]), acc[i][m],
+                                                                        0, 0, 0);
+        }
+        if (more) lstore(buf ^ 1);
+        __syncthreads();
+        buf ^= 1;
+    }
+
+    const int col4 = (lane >> 4) * 4;
+#pragma unroll
+    for (int m = 0; m < 4; ++m) {
+        const int row = (mb0 + wm * 4 + m) * 16 + (lane & 15);
+        if (row >= a.m_rows) continue;
+        if (EPI == EPI_PARTIAL) {
+            float* o = a.out + ((size_t)ks * a.m_stride + row) * a.N;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int nb = nb0 + wn * 4 + i;
+                if (nb < NBT)
+                    *(float4*)(o + nb * 16 + col4) = make_float4(acc[i][m][0], acc[i][m][1], acc[i][m][2], acc[i][m][3]);
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < 4; i += 2) {
+                const int nb = nb0 + wn * 4 + i;
+                if (nb + 1 < NBT) {
+                    const int f = (nb >> 1) * 16 + col4;
+                    bf16_t o[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) o[e] = f2bf(silu_f(acc[i][m][e]) * acc[i + 1][m][e]);
+                    *(uint2*)(a.out_packed + pk_index(row, f, a.kp_out)) = *(const uint2*)o;
+                }
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------ RoPE + KV append
+// Token-row j: sums the k-slices of its [q | k | v] projection, rotates q and k at the row's position
+// (pairs e, e + hd/2; cos/sin from a table indexed [pos][e]), stores q as fp32 and k, v as bf16 into the
+// row's key/value slab: element (head h, slot s, e) of row i lives at so[i]*d + (h*cap[i] + s)*hd + e.
+__global__ __launch_bounds__(256) void k_rope_append(MbState st, const float* __restrict__ part, int ksplit,
+                                                     size_t part_stride, float* __restrict__ qrot,
+                                                     bf16_t* __restrict__ kc, bf16_t* __restrict__ vc,
+                                                     const float* __restrict__ rcos, const float* __restrict__ rsin,
+                                                     int d, int H, int hd)
+{
+    const int j = blockIdx.x;
+    if (j >= *st.d_n) return;
+    const int row = st.tr_row[j], pos = st.tr_pos[j];
+    const int half = hd >> 1;
+    const size_t slab = (size_t)st.row_so[row] * d;
+    const int cap = st.row_cap[row];
+    const float* p0 = part + (size_t)j * 3 * d;
+    for (int idx = threadIdx.x; idx < (d >> 1); idx += 256) {
+        const int h = idx / half, e = idx - h * half;
+        const int c = h * hd + e;
+        float q1 = 0.f, q2 = 0.f, k1 = 0.f, k2 = 0.f, v1 = 0.f, v2 = 0.f;
+        for (int s = 0; s < ksplit; ++s) {
+            const float* p = p0 + (size_t)s * part_stride;
+            q1 += p[c]; q2 += p[c + half];
+            k1 += p[d + c]; k2 += p[d + c + half];
+            v1 += p[2 * d + c]; v2 += p[2 * d + c + half];
+        }
+        const float cs = rcos[(size_t)pos * half + e], sn = rsin[(size_t)pos * half + e];
+        qrot[(size_t)j * d + c] = q1 * cs - q2 * sn;
+        qrot[(size_t)j * d + c + half] = q1 * sn + q2 * cs;
+        const size_t o = slab + ((size_t)h * cap + pos) * hd + e;
+        kc[o] = f2bf(k1 * cs - k2 * sn);
+        kc[o + half] = f2bf(k1 * sn + k2 * cs);
+        vc[o] = f2bf(v1);
+        vc[o + half] = f2bf(v2);
+    }
+}
+
+// ------------------------------------------------------------------------------------------ attention
+// One workgroup per (token-row, head): softmax(q.K^T / sqrt(hd)) V over the row's own slots 0..pos.
+// Two passes, exactly the max-subtracted definition: scores to LDS, block max and sum, then the weighted
+// sum of V.  A wave's load covers 64/LPK consecutive keys (LPK = hd/8 lanes of 16 bytes per key), so K
+// and V are each streamed once, fully coalesced.
+template <int HD>
+__global__ __launch_bounds__(256) void k_attention(MbState st, const float* __restrict__ qrot,
+                                                   const bf16_t* __restrict__ kc, const bf16_t* __restrict__ vc,
+                                                   bf16_t* __restrict__ out, int d)
+{
+    constexpr int LPK = HD / 8;       // lanes per key
+    constexpr int KPW = 64 / LPK;     // keys per wave load
+    __shared__ float sc[kMaxPos];
+    __shared__ float red[8];
+    __shared__ float oacc[4][HD];
+    const int j = blockIdx.x, h = blockIdx.y;
+    if (j >= *st.d_n) return;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int row = st.tr_row[j], ctx = st.tr_pos[j] + 1;
+    const int cap = st.row_cap[row];
+    const size_t base = (size_t)st.row_so[row] * d + (size_t)h * cap * HD;
+    const int sub = lane % LPK, kin = lane / LPK;
+    const float scale = rsqrtf((float)HD);
+
+    float q[8];
+    {
+        const float* qp = qrot + (size_t)j * d + h * HD + sub * 8;
+        const float4 a = *(const float4*)qp, b = *(const float4*)(qp + 4);
+        q[0] = a.x; q[1] = a.y; q[2] = a.z; q[3] = a.w; q[4] = b.x; q[5] = b.y; q[6] = b.z; q[7] = b.w;
+    }
+    float mx = -3.0e38f;
+#pragma unroll 4
+    for (int s0 = wave * KPW; s0 < ctx; s0 += 4 * KPW) {
+        const int s = s0 + kin;
+        float part = 0.f;
+        if (s < ctx) {
+            const uint4 raw = *(const uint4*)(kc + base + (size_t)s * HD + sub * 8);
+            const bf16_t* kv = (const bf16_t*)&raw;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) part += q[e] * bf2f(kv[e]);
+        }
+#pragma unroll
+        for (int m = 1; m < LPK; m <<= 1) part += __shfl_xor(part, m, 64);
+        part *= scale;
+        if (s < ctx) {
+            if (sub == 0) sc[s] = part;
+            mx = fmaxf(mx, part);
+        }
+    }
+    mx = wave_max(mx);
+    if (lane == 0) red[wave] = mx;
+    __syncthreads();
+    mx = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    float sum = 0.f;
+    for (int s = tid; s < ctx; s += 256) {
+        const float p = __expf(sc[s] - mx);
+        sc[s] = p;
+        sum += p;
+    }
+    sum = wave_sum(sum);
+    if (lane == 0) red[4 + wave] = sum;
+    __syncthreads();
+    const float inv = 1.f / (red[4] + red[5] + red[6] + red[7]);
+
+    float o[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll 4
+    for (int s0 = wave * KPW; s0 < ctx; s0 += 4 * KPW) {
+        const int s = s0 + kin;
+        if (s < ctx) {
+            const float p = sc[s];
+            const uint4 raw = *(const uint4*)(vc + base + (size_t)s * HD + sub * 8);
+            const bf16_t* vv = (const bf16_t*)&raw;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) o[e] += p * bf2f(vv[e]);
+        }
+    }
+#pragma unroll
+    for (int m = LPK; m < 64; m <<= 1)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o[e] += __shfl_xor(o[e], m, 64);
+    if (kin == 0)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) oacc[wave][sub * 8 + e] = o[e];
+    __syncthreads();
+    if (tid < HD / 4) {
+        bf16_t r[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int c = tid * 4 + e;
+            r[e] = f2bf((oacc[0][c] + oacc[1][c] + oacc[2][c] + oacc[3][c]) * inv);
+        }
+        *(uint2*)(out + pk_index(j, h * HD + tid * 4, d)) = *(const uint2*)r;
+    }
+}
+
+// ------------------------------------------------------------------------------------------ argmax
+// Greedy choice per selected row: index of the largest logit, lowest index on exact ties.
+__global__ __launch_bounds__(256) void k_argmax(const float* __restrict__ logits, int vocab,
+                                                const int32_t* __restrict__ d_count, int32_t* __restrict__ am)
+{
+    const int j = blockIdx.x;
+    if (j >= *d_count) return;
+    const float* lg = logits + (size_t)j * vocab;
+    float best = -3.4e38f;
+    int bi = 0x7fffffff;
+    for (int c = threadIdx.x * 4; c < vocab; c += 1024) {
+        const float4 v = *(const float4*)(lg + c);
+        const float vv[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            if (vv[e] > best || (vv[e] == best && c + e < bi)) { best = vv[e]; bi = c + e; }
+    }
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) {
+        const float ob = __shfl_xor(best, m, 64);
+        const int oi = __shfl_xor(bi, m, 64);
+        if (ob > best || (ob == best && oi < bi)) { best = ob; bi = oi; }
+    }
+    __shared__ float sb[4];
+    __shared__ int si[4];
+    if ((threadIdx.x & 63) == 0) { sb[threadIdx.x >> 6] = best; si[threadIdx.x >> 6] = bi; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int w = 1; w < 4; ++w)
+            if (sb[w] > best || (sb[w] == best && si[w] < bi)) { best = sb[w]; bi = si[w]; }
+        am[j] = bi;
+    }
+}
+
+// ------------------------------------------------------------------------------------------ bookkeeping
+// After a forward: slot j's argmax is the row's token number s (s = tokens generated so far).  Emit it if
+// the row still owes tokens, then build the next forward: every surviving slot feeds its token back at
+// position prompt_len + s.  With `compact` a row leaves the live batch once it has emitted its last token;
+// without it the row stays and keeps running on its own output (its later tokens are never emitted).
+__global__ __launch_bounds__(1024) void k_step_update(MbState st, int compact)
+{
+    __shared__ int wave_cnt[16];
+    __shared__ int wave_off[17];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int n = *st.d_nlive;
+    const int s = *st.d_step;
+    int row = -1, tok = 0, keep = 0;
+    if (tid < n) {
+        row = st.live_row[tid];
+        tok = st.am[tid];
+        const int lim = st.row_limit[row];
+        if (s < lim) st.out_tok[(size_t)row * st.max_new + s] = tok;
+        keep = compact ? (s + 1 < lim) : 1;
+    }
+    const unsigned long long bal = __ballot(keep);
+    const int before = __popcll(bal & ((1ull << lane) - 1ull));
+    if (lane == 0) wave_cnt[wave] = __popcll(bal);
+    __syncthreads();
+    if (tid == 0) {
+        int a = 0;
+        for (int w = 0; w < 16; ++w) { wave_off[w] = a; a += wave_cnt[w]; }
+        wave_off[16] = a;
+    }
+    __syncthreads();
+    if (keep) {
+        const int jn = wave_off[wave] + before;
+        st.tr_tok[jn] = tok;
+        st.tr_row[jn] = row;
+        st.tr_pos[jn] = st.row_plen[row] + s;
+        st.live_row[jn] = row;
+    }
+    if (tid == 0) {
+        *st.d_n = wave_off[16];
+        *st.d_nlive = wave_off[16];
+        *st.d_step = s + 1;
+    }
+}
+
+// ------------------------------------------------------------------------------------------ launchers
+static inline int grid_for(size_t n, int block)
+{
+    const size_t g = (n + block - 1) / block;
+    return (int)(g > (1u << 20) ? (1u << 20) : (g < 1 ? 1 : g));
+}
+
+void launch_pack_weight(const void* src, int src_f32, bf16_t* dst, int n_src, int k, int kp, int blk_stride,
+                        int blk_off, hipStream_t s)
+{
+    const size_t total = (size_t)n_src * (k / 8);
+    hipLaunchKernelGGL(k_pack_weight, dim3(grid_for(total, 256)), dim3(256), 0, s, src, src_f32, dst, n_src, k, kp,
+                       blk_stride, blk_off);
+}
+
+void launch_cast_rows(const void* src, int src_f32, bf16_t* dst, size_t count, hipStream_t s)
+{
+    hipLaunchKernelGGL(k_cast_rows, dim3(grid_for(count, 256)), dim3(256), 0, s, src, src_f32, dst, count);
+}
+
+void launch_fill_i32(int32_t* p, int32_t v, size_t n, hipStream_t s)
+{
+    if (n == 0) return;
+    hipLaunchKernelGGL(k_fill_i32, dim3(grid_for(n, 256)), dim3(256), 0, s, p, v, n);
+}
+
+void launch_embed(const MbState& st, const bf16_t* embed, float* x, int d, int n_max, hipStream_t s)
+{
+    hipLaunchKernelGGL(k_embed, dim3(n_max), dim3(256), 0, s, st, embed, x, d);
+}
+
+void launch_rmsnorm(const MbState& st, float* x, const float* part, int ksplit, size_t part_stride,
+                    const bf16_t* w, float eps, const int32_t* sel, const int32_t* d_nsel, bf16_t* h_packed, int d,
+                    int n_max, hipStream_t s)
+{
+    hipLaunchKernelGGL(k_rmsnorm, dim3(n_max), dim3(256), 0, s, d_nsel ? d_nsel : st.d_n, x, part,
+                       part ? ksplit : 0, part_stride, w, eps, sel, h_packed, d);
+}
+
+// k-slices: enough wave tasks to cover the chip a few times over, at least 8 k-blocks per slice.
+int gemm_pick_ksplit(int N, int Kp, int m_rows, int epilogue)
+{
+    if (epilogue == EPI_SWIGLU) return 1;
+    const int KB = Kp / 32;
+    if (m_rows <= 64) {
+        const int groups = (N / 16 + 3) / 4;
+        int ks = (2048 + groups - 1) / groups;
+        ks = ks < 1 ? 1 : ks;
+        const int cap = KB / 16 > 0 ? KB / 16 : 1;
+        if (ks > cap) ks = cap;
+        if (ks > 8) ks = 8;
+        return ks;
+    }
+    const int tiles = ((N + 127) / 128) * ((m_rows + 127) / 128);
+    int ks = 1;
+    while (tiles * ks < 256 && ks < 8 && KB / (ks * 2) >= 16) ks *= 2;
+    return ks;
+}
+
+template <int MT, int EPI>
+static void launch_skinny_mt(const GemmArgs& a, hipStream_t s)
+{
+    constexpr int NB = 4, KD = (MT <= 2 ? 4 : 2);
+    const int KB = a.Kp / 32;
+    const int groups = (a.N / 16 + NB - 1) / NB;
+    int kbs = (KB + a.ksplit - 1) / a.ksplit;
+    const int tasks = groups * a.ksplit;
+    hipLaunchKernelGGL((k_gemm_skinny<MT, NB, KD, EPI>), dim3((tasks + 3) / 4), dim3(256), 0, s, a, groups, kbs);
+}
+
+template <int EPI>
+static void launch_gemm_epi(const GemmArgs& a, hipStream_t s)
+{
+    if (a.m_rows <= 64) {
+        const int mt = (a.m_rows + 15) / 16;
+        switch (mt) {
+            case 1: launch_skinny_mt<1, EPI>(a, s); break;
+            case 2: launch_skinny_mt<2, EPI>(a, s); break;
+            case 3: launch_skinny_mt<3, EPI>(a, s); break;
+            default: launch_skinny_mt<4, EPI>(a, s); break;
+        }
+        return;
+    }
+    const int KB = a.Kp / 32;
+    int kbs = (KB + a.ksplit - 1) / a.ksplit;
+    kbs = (kbs + 1) / 2 * 2;  // whole 64-wide trips
+    dim3 grid((a.N + 127) / 128, (a.m_rows + 127) / 128, a.ksplit);
+    hipLaunchKernelGGL((k_gemm_tiled<EPI>), grid, dim3(256), 0, s, a, kbs);
+}
+
+void launch_gemm(const GemmArgs& a, int epilogue, hipStream_t s)
+{
+    if (epilogue == EPI_SWIGLU)
+        launch_gemm_epi<EPI_SWIGLU>(a, s);
+    else
+        launch_gemm_epi<EPI_PARTIAL>(a, s);
+}
+
+void launch_rope_append(const MbState& st, const float* qkv_part, int ksplit, size_t part_stride, float* qrot,
+                        bf16_t* kcache, bf16_t* vcache, const float* rope_cos, const float* rope_sin, int d, int H,
+                        int hd, int n_max, hipStream_t s)
+{
+    hipLaunchKernelGGL(k_rope_append, dim3(n_max), dim3(256), 0, s, st, qkv_part, ksplit, part_stride, qrot, kcache,
+                       vcache, rope_cos, rope_sin, d, H, hd);
+}
+
+void launch_attention(const MbState& st, const float* qrot, const bf16_t* kcache, const bf16_t* vcache,
+                      bf16_t* out_packed, int d, int H, int hd, int n_max, hipStream_t s)
+{
+    if (hd == 128)
+        hipLaunchKernelGGL((k_attention<128>), dim3(n_max, H), dim3(256), 0, s, st, qrot, kcache, vcache, out_packed, d);
+    else
+        hipLaunchKernelGGL((k_attention<64>), dim3(n_max, H), dim3(256), 0, s, st, qrot, kcache, vcache, out_packed, d);
+}
+
+void launch_argmax(const float* logits, int vocab, const int32_t* d_nsel, int32_t* am, int n_max, hipStream_t s)
+{
+    hipLaunchKernelGGL(k_argmax, dim3(n_max), dim3(256), 0, s, logits, vocab, d_nsel, am);
+}
+
+void launch_step_update(const MbState& st, int compact, hipStream_t s)
+{
+    hipLaunchKernelGGL(k_step_update, dim3(1), dim3(1024), 0, s, st, compact);
+}
+
+}  // namespace ss

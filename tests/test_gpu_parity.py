@@ -1,0 +1,271 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle on the same seeded inputs.
+
+Bars (written here, used everywhere below):
+  * integers (plans, lengths, failure flags, counters, -1 padding): bit-exact;
+  * teacher-forced logits: max |gpu - oracle| <= 3e-2 * max |oracle logit| at every position;
+  * greedy tokens: the token the GPU emitted after a prefix must be the oracle's argmax on that same
+    prefix whenever the oracle's top-1/top-2 margin there exceeds 0.1 (random-init models have many
+    near-ties, so free-running sequences may legitimately part ways at a near-tie; every position is
+    therefore checked teacher-forced on the GPU's own prefix).
+"""
+import numpy as np
+import pytest
+
+from paper_2305_13144_amd import binding as ss
+from paper_2305_13144_amd import synth
+from oracle import sched_oracle as so
+from oracle.model_oracle import OracleModel
+
+pytestmark = pytest.mark.gpu
+
+LOGIT_TOL = 3e-2
+MARGIN = 0.1
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+# ------------------------------------------------------------------ helpers
+def check_logits(gpu, ref, what):
+    scale = np.abs(ref).max()
+    err = np.abs(gpu.astype(np.float64) - ref).max(axis=-1)
+    worst = float(err.max())
+    _say(f"  {what}: max|err| = {worst:.3e}  (= {worst / scale:.2e} of max|logit| {scale:.3f})")
+    assert worst <= LOGIT_TOL * scale, what
+    big = np.partition(ref, -2, axis=-1)
+    margin = big[:, -1] - big[:, -2]
+    decided = margin > MARGIN
+    assert (gpu.argmax(-1)[decided] == ref.argmax(-1)[decided]).all(), what
+    return worst / scale
+
+
+def check_tokens_teacher_forced(om, prompt, toks, upto=None, what=""):
+    """Every emitted token must be the oracle's greedy choice on the GPU's own prefix (where decided)."""
+    L = len(toks) if upto is None else min(upto, len(toks))
+    seq = np.concatenate([prompt, toks[:L - 1]]).astype(np.int32) if L > 1 else np.asarray(prompt, np.int32)
+    lg = om.teacher_forced(seq, first=len(prompt) - 1)
+    assert lg.shape[0] == L
+    big = np.partition(lg, -2, axis=-1)
+    margin = big[:, -1] - big[:, -2]
+    ref = lg.argmax(-1)
+    decided = margin > MARGIN
+    bad = [g for g in range(L) if decided[g] and ref[g] != toks[g]]
+    assert not bad, (what, bad[:5])
+    return int(decided.sum()), L
+
+
+def forced_batch(w, rows, extra, rng):
+    """Ragged prompts of the given rows followed by `extra[i]` random forced tokens."""
+    toks, offs, npr = [], [0], []
+    for i, e in zip(rows, extra):
+        p = w.prompt(i)
+        t = np.concatenate([p, rng.integers(0, w.shape.vocab, size=e).astype(np.int32)])
+        toks.append(t)
+        offs.append(offs[-1] + len(t))
+        npr.append(len(p))
+    return np.concatenate(toks).astype(np.int32), np.array(offs, np.int32), np.array(npr, np.int32)
+
+
+def oracle_forced_logits(om, toks, offs, npr):
+    out = []
+    for i in range(len(npr)):
+        out.append(om.teacher_forced(toks[offs[i]:offs[i + 1]], first=int(npr[i]) - 1))
+    return np.concatenate(out, axis=0)
+
+
+# ------------------------------------------------------------------ fixtures
+@pytest.fixture(scope="module")
+def tiny(oracle_built):
+    W = synth.make_weights(synth.TINY, seed=1, norm_jitter=0.1, threads=1)
+    gw = ss.Weights(synth.TINY, W)
+    yield W, OracleModel(synth.TINY, W, "f64"), gw
+    gw.close()
+
+
+@pytest.fixture(scope="module")
+def wide2(oracle_built):
+    """7B widths (d 4096, 32 heads of 128, ffn 11008, vocab 32000) at 2 layers: every kernel at its real shape."""
+    shape = synth.LLAMA7B.with_layers(2)
+    W = synth.make_weights(shape, seed=2, norm_jitter=0.05)
+    gw = ss.Weights(shape, W)
+    yield shape, W, OracleModel(shape, W, "f64"), gw
+    gw.close()
+
+
+# ------------------------------------------------------------------ teacher-forced logits
+def test_tiny_prompt_logits_every_position(tiny):
+    """Prompt (prefill) path position by position: ragged rows, spans several 16-row strips and a ragged tail."""
+    W, om, gw = tiny
+    w = synth.make_workload(1)
+    _say("tiny prompt logits, all positions, 16 ragged rows")
+    got = ss.ss_forward_logits(gw, w.prompt_tokens, w.prompt_offsets, w.prompt_lens, all_prompt_logits=True)
+    ref = np.concatenate([om.teacher_forced(w.prompt(i), first=0) for i in range(w.n)], axis=0)
+    assert got.shape == ref.shape
+    check_logits(got, ref, "tiny prefill")
+
+
+@pytest.mark.parametrize("rows", [1, 5, 16, 23, 40, 64, 100])
+def test_tiny_decode_logits_teacher_forced(tiny, rows):
+    """Prompt forward then decode steps on forced tokens; row counts cover 1..4 strips of the skinny
+    kernel, its ragged tails, and the tiled kernel (100 rows); rows drop out at different steps."""
+    W, om, gw = tiny
+    rng = np.random.default_rng(100 + rows)
+    w = synth.make_group(synth.TINY, rows, 777 + rows, ("uniform", 3, 40), ("uniform", 1, 8), None, 8, 0, ())
+    extra = rng.integers(0, 7, size=rows)
+    toks, offs, npr = forced_batch(w, range(rows), extra, rng)
+    _say(f"tiny teacher-forced decode, {rows} rows")
+    got = ss.ss_forward_logits(gw, toks, offs, npr)
+    ref = oracle_forced_logits(om, toks, offs, npr)
+    assert got.shape == ref.shape
+    check_logits(got, ref, f"tiny decode B={rows}")
+
+
+def test_f32_source_weights_are_rounded_like_the_generator(tiny):
+    """Config 1 ships fp32 weights: the library rounds them to bf16 (nearest even) at load."""
+    W, om, gw = tiny
+    rng = np.random.default_rng(5)
+    specs = synth.TINY.tensor_specs()
+    children = np.random.SeedSequence(99).spawn(len(specs))
+    f32 = []
+    for (name, shp), c in zip(specs, children):
+        g = np.random.Generator(np.random.PCG64(c))
+        f32.append((np.ones(shp) + 0.1 * g.standard_normal(shp) if len(shp) == 1
+                    else 0.02 * g.standard_normal(shp)).astype(np.float32))
+    bits = [synth.f32_to_bf16_bits(t) for t in f32]
+    om2 = OracleModel(synth.TINY, bits, "f64")
+    gw2 = ss.Weights(synth.TINY, f32, ss.SS_F32)
+    gw3 = ss.Weights(synth.TINY, bits, ss.SS_BF16)
+    try:
+        w = synth.make_workload(1)
+        a = ss.ss_forward_logits(gw2, w.prompt_tokens, w.prompt_offsets, w.prompt_lens)
+        b = ss.ss_forward_logits(gw3, w.prompt_tokens, w.prompt_offsets, w.prompt_lens)
+        assert np.array_equal(a, b)               # same bf16 weights either way -> same bits out
+        ref = np.stack([om2.teacher_forced(w.prompt(i), first=len(w.prompt(i)) - 1)[0] for i in range(w.n)])
+        check_logits(a, ref, "fp32-source weights")
+    finally:
+        gw2.close()
+        gw3.close()
+
+
+def test_wide_logits_teacher_forced(wide2):
+    shape, W, om, gw = wide2
+    rng = np.random.default_rng(8)
+    w = synth.make_workload(2, n=6, shape=shape)
+    rows = [0, 1, 2, 3]
+    extra = [3, 0, 5, 2]
+    toks, offs, npr = forced_batch(w, rows, extra, rng)
+    _say(f"7B-width x2 layers teacher-forced: prompts {npr.tolist()} extra {extra}")
+    got = ss.ss_forward_logits(gw, toks, offs, npr)
+    ref = oracle_forced_logits(om, toks, offs, npr)
+    check_logits(got, ref, "wide2 prompt+decode")
+
+
+def test_wide_prompt_forward_through_tiled_kernel(wide2):
+    """> 64 prompt token-rows at real widths: tiled MFMA kernel incl. its ragged row and column tails."""
+    shape, W, om, gw = wide2
+    w = synth.make_workload(2, n=4, shape=shape)
+    _say(f"7B-width x2 layers prompt logits, {int(w.prompt_offsets[-1])} token-rows")
+    got = ss.ss_forward_logits(gw, w.prompt_tokens, w.prompt_offsets, w.prompt_lens)
+    ref = np.stack([om.teacher_forced(w.prompt(i), first=len(w.prompt(i)) - 1)[0] for i in range(w.n)])
+    check_logits(got, ref, "wide2 prefill")
+
+
+# ------------------------------------------------------------------ micro-batch generation
+@pytest.mark.parametrize("flags", [0, ss.SS_COMPACT])
+@pytest.mark.parametrize("cap", [48, 20, 1])
+def test_tiny_microbatch_config1(tiny, flags, cap):
+    """Config 1: 16 queries, one padded batch (and the same with a cap, and with compaction)."""
+    W, om, gw = tiny
+    w = synth.make_workload(1)
+    _say(f"tiny micro-batch cap={cap} flags={flags}")
+    r = ss.ss_decode_microbatch(gw, w.prompt_tokens, w.prompt_offsets, cap, w.target_lens, flags)
+    t = w.target_lens
+    assert np.array_equal(r["lens"], np.minimum(t, cap))
+    assert np.array_equal(r["failed"].astype(bool), t > cap)
+    steps = min(cap, int(t.max()))
+    assert r["stats"]["steps"] == steps and r["stats"]["rows"] == w.n
+    want_rows = int(np.minimum(t, cap).sum()) if flags else w.n * steps
+    assert r["stats"]["row_steps"] == want_rows
+    assert r["stats"]["prompt_tokens"] == int(w.prompt_offsets[-1])
+    decided = total = 0
+    for i in range(w.n):
+        L = int(r["lens"][i])
+        assert (r["tokens"][i, :L] >= 0).all() and (r["tokens"][i, L:] == -1).all()
+        dcd, tot = check_tokens_teacher_forced(om, w.prompt(i), r["tokens"][i, :L], what=f"row {i}")
+        decided += dcd
+        total += tot
+    _say(f"  {decided}/{total} positions had a decided oracle argmax; all matched")
+
+
+def test_compaction_does_not_change_outputs(tiny):
+    """Same micro-batch padded and compacted: identical lengths/flags; tokens equal to the oracle's greedy
+    sequence prefix up to the first undecided position in both."""
+    W, om, gw = tiny
+    w = synth.make_group(synth.TINY, 37, 4242, ("uniform", 4, 30), ("uniform", 1, 30), None, 30, 0, ())
+    a = ss.ss_decode_microbatch(gw, w.prompt_tokens, w.prompt_offsets, 24, w.target_lens, 0)
+    b = ss.ss_decode_microbatch(gw, w.prompt_tokens, w.prompt_offsets, 24, w.target_lens, ss.SS_COMPACT)
+    assert np.array_equal(a["lens"], b["lens"]) and np.array_equal(a["failed"], b["failed"])
+    ref = om.greedy_microbatch(w.prompt_tokens, w.prompt_offsets, 24, w.target_lens)
+    assert np.array_equal(ref["lens"], a["lens"]) and np.array_equal(ref["failed"], a["failed"])
+    for i in range(w.n):
+        L = int(ref["lens"][i])
+        und = np.nonzero(ref["margins"][i, :L] <= MARGIN)[0]
+        k = int(und[0]) if len(und) else L
+        assert np.array_equal(a["tokens"][i, :k], ref["tokens"][i, :k])
+        assert np.array_equal(b["tokens"][i, :k], ref["tokens"][i, :k])
+
+
+def test_wide_microbatch(wide2):
+    shape, W, om, gw = wide2
+    w = synth.make_workload(3, n=16, shape=shape)
+    cap = 6
+    _say("7B-width x2 layers micro-batch of 16, cap 6")
+    r = ss.ss_decode_microbatch(gw, w.prompt_tokens, w.prompt_offsets, cap, w.target_lens, 0)
+    assert np.array_equal(r["lens"], np.minimum(w.target_lens, cap))
+    assert np.array_equal(r["failed"].astype(bool), w.target_lens > cap)
+    for i in (0, 7, 15):
+        check_tokens_teacher_forced(om, w.prompt(i), r["tokens"][i, :int(r["lens"][i])], what=f"row {i}")
+
+
+# ------------------------------------------------------------------ whole group
+@pytest.mark.parametrize("flags", [(), ("SORT", "BIN", "FCR"), ("SORT", "BIN", "FCR", "VBS", "COMPACT"),
+                                   ("SORT", "FCR", "VBS")])
+def test_tiny_group_every_policy_same_answers(tiny, flags):
+    """The schedule must not change any query's output (the paper's 'without compromising' claim):
+    lengths exact, counters equal to the accounting oracle, tokens checked against the model oracle."""
+    W, om, gw = tiny
+    w = synth.make_group(synth.TINY, 96, 31337, ("uniform", 4, 24), ("lognormal", 12.0, 0.7, 1, 40), 0.3, 40, 8,
+                         flags, base_batch=4, max_batch=32)
+    pol = ss.make_policy(flags, 4, 40, 32)
+    pred = w.pred_lens if "SORT" in flags else None
+    _say(f"tiny group of 96, flags={flags}")
+    r = ss.ss_run_group(gw, w.prompt_tokens, w.prompt_offsets, w.target_lens, pred, 8 if "BIN" in flags else 0, pol)
+    assert np.array_equal(r["lens"], w.target_lens)
+    ref = so.run_group(pred, w.target_lens, 8 if "BIN" in flags else 0,
+                       so.Policy(flags=flags, base_batch=4, l_max=40, max_batch=32))
+    s = r["stats"]
+    assert s["steps"] == ref["steps"] and s["padded_row_steps"] == ref["padded_row_steps"]
+    assert s["n_failed"] == ref["n_failed"] and s["useful_tokens"] == ref["useful_tokens"]
+    assert s["n_mb_first"] == ref["first"].n_mb and s["n_mb_failure"] == ref["second"].n_mb
+    want_rows = ref["live_row_steps"] if "COMPACT" in flags else ref["padded_row_steps"]
+    assert s["computed_row_steps"] == want_rows
+    for i in range(0, w.n, 5):
+        t = int(w.target_lens[i])
+        assert (r["tokens"][i, t:] == -1).all()
+        check_tokens_teacher_forced(om, w.prompt(i), r["tokens"][i, :t], what=f"query {i}")
+
+
+# ------------------------------------------------------------------ error paths that need a handle
+def test_invalid_generation_arguments(tiny):
+    W, om, gw = tiny
+    good = dict(prompt_tokens=[1, 2, 3, 4], prompt_offsets=[0, 2, 4], max_new=4, target_lens=[2, 3])
+    for bad in (dict(prompt_offsets=[0, 2, 2]), dict(prompt_offsets=[1, 2, 4]), dict(prompt_tokens=[1, 2, 3, 1024]),
+                dict(prompt_tokens=[1, -2, 3, 4]), dict(max_new=0), dict(target_lens=[2, 0]), dict(max_new=5000),
+                dict(flags=ss.SS_SORT)):
+        args = {**good, **bad}
+        with pytest.raises(ss.SsError) as e:
+            ss.ss_decode_microbatch(gw, **args)
+        assert e.value.code == ss.SS_EINVAL
+    r = ss.ss_decode_microbatch(gw, **good)       # the handle still works after rejected calls
+    assert r["lens"].tolist() == [2, 3]

@@ -1,0 +1,124 @@
+"""CPU tests of the C-ABI library: it loads, exports every symbol the header declares, rejects bad
+arguments, and its host scheduler is bit-exact with the scheduler oracle.  No GPU is touched."""
+import ctypes as C
+import os
+import re
+import zlib
+
+import numpy as np
+import pytest
+
+from paper_2305_13144_amd import binding as ss
+from paper_2305_13144_amd import synth
+from oracle import sched_oracle as so
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(ss.LIB_PATH):
+        from paper_2305_13144_amd import build
+        build.build()
+    return ss.lib()
+
+
+def test_every_declared_symbol_is_exported(lib):
+    header = open(os.path.join(ROOT, "include", "ss.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = sorted(set(re.findall(r"\b(ss_[a-z_]+)\s*\(", header)))
+    assert declared == sorted(ss.EXPORTS)
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def _oracle_policy(flags, b0, lmax, maxb, rule="clamp_floor"):
+    return so.Policy(flags=tuple(flags), base_batch=b0, l_max=lmax, max_batch=maxb, vbs_rule=rule)
+
+
+def _as_pairs(plan):
+    return [(list(m.idx), m.cap) for m in plan]
+
+
+FLAG_SETS = [(), ("SORT",), ("SORT", "FCR"), ("SORT", "BIN"), ("SORT", "BIN", "FCR"), ("SORT", "FCR", "VBS"),
+             ("SORT", "BIN", "FCR", "VBS"), ("SORT", "BIN", "VBS"), ("SORT", "BIN", "FCR", "VBS", "COMPACT")]
+
+
+@pytest.mark.parametrize("cfg", [2, 3, 4, 5])
+def test_schedule_bit_exact_on_configs(lib, cfg):
+    w = synth.make_workload(cfg)
+    pol = ss.make_policy(w.flags, w.base_batch, w.l_max, w.max_batch)
+    got = ss.ss_schedule(w.pred_lens, w.n, w.bin_width, pol)
+    want = so.schedule(w.pred_lens, w.n, w.bin_width, _oracle_policy(w.flags, w.base_batch, w.l_max, w.max_batch))
+    assert got == _as_pairs(want)
+    if w.pred_lens is not None:
+        acc = so.account(want, w.target_lens)
+        gotf = ss.ss_schedule_failures(w.pred_lens, w.n, sorted(acc.failed), w.bin_width, pol)
+        wantf = so.schedule_failures(w.pred_lens, acc.failed, w.bin_width,
+                                     _oracle_policy(w.flags, w.base_batch, w.l_max, w.max_batch))
+        assert gotf == _as_pairs(wantf)
+
+
+@pytest.mark.parametrize("flags", FLAG_SETS)
+@pytest.mark.parametrize("rule", ["clamp_floor", "paper_pow2"])
+def test_schedule_bit_exact_random_groups(lib, flags, rule):
+    rng = np.random.default_rng(zlib.crc32(repr((flags, rule)).encode()))
+    for trial in range(25):
+        n = int(rng.integers(1, 300))
+        lmax = int(rng.choice([48, 100, 512, 1024]))
+        w = int(rng.choice([7, 50, 64, lmax]))
+        b0 = int(rng.choice([1, 2, 16]))
+        maxb = int(rng.choice([b0, 64, 256]))
+        pred = rng.integers(1, int(lmax * 1.3) + 2, size=n).astype(np.int32)
+        binw = w if "BIN" in flags else int(rng.choice([0, w]))
+        pol = ss.make_policy(flags, b0, lmax, maxb, ss.SS_VBS_PAPER_POW2 if rule == "paper_pow2" else 0)
+        opol = _oracle_policy(flags, b0, lmax, maxb, rule)
+        got = ss.ss_schedule(pred if "SORT" in flags else None, n, binw, pol)
+        want = so.schedule(pred if "SORT" in flags else None, n, binw, opol)
+        assert got == _as_pairs(want), (flags, rule, trial)
+        if "SORT" in flags:
+            failed = sorted(rng.choice(n, size=int(rng.integers(0, n + 1)), replace=False).tolist())
+            gotf = ss.ss_schedule_failures(pred, n, failed, binw, pol)
+            wantf = so.schedule_failures(pred, failed, binw, opol)
+            assert gotf == _as_pairs(wantf)
+
+
+def test_schedule_rejects_bad_arguments(lib):
+    pol = ss.make_policy(("SORT", "BIN", "FCR"))
+    pred = np.array([10, 20, 30], np.int32)
+    cases = [
+        dict(pred=pred, n=0, bin=50, pol=pol),
+        dict(pred=pred, n=3, bin=-1, pol=pol),
+        dict(pred=np.array([10, 0, 30], np.int32), n=3, bin=50, pol=pol),
+        dict(pred=None, n=3, bin=50, pol=pol),
+        dict(pred=pred, n=3, bin=0, pol=pol),                                        # SS_BIN needs a bin
+        dict(pred=pred, n=3, bin=50, pol=ss.make_policy(("BIN",))),                  # SS_BIN needs SS_SORT
+        dict(pred=pred, n=3, bin=50, pol=ss.make_policy(("VBS",))),
+        dict(pred=pred, n=3, bin=50, pol=ss.make_policy(("SORT",), base_batch=0)),
+        dict(pred=pred, n=3, bin=50, pol=ss.make_policy(("SORT",), base_batch=16, max_batch=8)),
+        dict(pred=pred, n=3, bin=50, pol=ss.make_policy(("SORT",), base_len=0)),
+        dict(pred=pred, n=3, bin=50, pol=ss.make_policy(("SORT",), vbs_rule=7)),
+    ]
+    for c in cases:
+        with pytest.raises(ss.SsError) as e:
+            ss.ss_schedule(c["pred"], c["n"], c["bin"], c["pol"])
+        assert e.value.code == ss.SS_EINVAL and len(str(e.value)) > 20
+    out = C.POINTER(ss.ss_plan)()
+    assert lib.ss_schedule(None, 3, 0, None, C.byref(out)) == ss.SS_EINVAL
+    assert lib.ss_schedule(None, 3, 0, C.byref(ss.make_policy(())), None) == ss.SS_EINVAL
+    with pytest.raises(ss.SsError):
+        ss.ss_schedule_failures(pred, 3, [5], 50, pol)
+
+
+def test_generation_entry_points_reject_null_without_touching_a_gpu(lib):
+    assert lib.ss_decode_microbatch(None, None, None, 1, 1, None, 0, None, None, None, None, None) == ss.SS_EINVAL
+    assert b"NULL" in lib.ss_last_error()
+    assert lib.ss_forward_logits(None, None, None, 1, None, 0, None, None) == ss.SS_EINVAL
+    assert lib.ss_run_group(None, None, None, 1, None, None, 0, None, None, None, None, None) == ss.SS_EINVAL
+    assert lib.ss_bench_decode_step(None, None, 1, 1, 1, None, None) == ss.SS_EINVAL
+    cfg = ss.ss_model_cfg(2, 250, 4, 64, 688, 1024, 1e4, 1e-6)       # n_heads*head_dim != d_model
+    h = C.c_void_p()
+    arr = (C.c_void_p * 21)()
+    assert lib.ss_weights_create(C.byref(cfg), arr, ss.SS_BF16, C.byref(h)) == ss.SS_EINVAL
+    lib.ss_weights_destroy(None)
+    lib.ss_plan_free(None)
