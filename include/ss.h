@@ -199,6 +199,17 @@ int ss_run_group(ss_weights* w, const int32_t* prompt_tokens, const int32_t* pro
 int ss_bench_decode_step(ss_weights* w, const int32_t* prompt_tokens, int32_t B, int32_t ctx, int32_t iters,
                          double* ms_out, void* hip_stream);
 
+/*
+ * Measurement entry point: the projection kernels of one decode step alone.  Launches, back to back on
+ * one stream, exactly the matrix kernels a B-row decode forward launches (per layer q|k|v, o, gate|up
+ * with the SwiGLU epilogue, down; then the LM head) with the same launch configuration, on whatever the
+ * activation buffers currently hold, `iters` times.  Every weight byte of the model is streamed once per
+ * iteration, so bytes/iteration = the model's weight bytes.  ms_out: host, double[iters], device time of
+ * each iteration (HIP events).  launches_out: host, nullable, number of kernel launches per iteration.
+ */
+int ss_bench_weight_stream(ss_weights* w, int32_t B, int32_t iters, double* ms_out, int32_t* launches_out,
+                           void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -22,7 +22,8 @@ SS_BF16, SS_F32 = 0, 1
 FLAG_BITS = dict(SORT=SS_SORT, BIN=SS_BIN, FCR=SS_FCR, VBS=SS_VBS, COMPACT=SS_COMPACT)
 
 EXPORTS = ["ss_last_error", "ss_schedule", "ss_schedule_failures", "ss_plan_free", "ss_weights_create",
-           "ss_weights_destroy", "ss_decode_microbatch", "ss_forward_logits", "ss_run_group", "ss_bench_decode_step"]
+           "ss_weights_destroy", "ss_decode_microbatch", "ss_forward_logits", "ss_run_group", "ss_bench_decode_step",
+           "ss_bench_weight_stream"]
 
 
 class SsError(RuntimeError):
@@ -88,6 +89,7 @@ def lib():
         L.ss_run_group.argtypes = [vp, i32p, i32p, C.c_int32, i32p, i32p, C.c_int32, C.POINTER(ss_policy), i32p, i32p,
                                    C.POINTER(ss_group_stats), vp]
         L.ss_bench_decode_step.argtypes = [vp, i32p, C.c_int32, C.c_int32, C.c_int32, vp, vp]
+        L.ss_bench_weight_stream.argtypes = [vp, C.c_int32, C.c_int32, vp, vp, vp]
         for name in EXPORTS:
             if name not in ("ss_last_error", "ss_plan_free", "ss_weights_destroy"):
                 getattr(L, name).restype = C.c_int
@@ -215,3 +217,10 @@ def ss_bench_decode_step(w: Weights, prompt_tokens, B: int, ctx: int, iters: int
     ms = np.empty(iters, np.float64)
     _check(lib().ss_bench_decode_step(w.h, _ptr(pt), B, ctx, iters, _ptr(ms), stream))
     return ms
+
+
+def ss_bench_weight_stream(w: Weights, B: int, iters: int, stream: Optional[int] = None):
+    ms = np.empty(iters, np.float64)
+    launches = C.c_int32(0)
+    _check(lib().ss_bench_weight_stream(w.h, B, iters, _ptr(ms), C.byref(launches), stream))
+    return ms, int(launches.value)

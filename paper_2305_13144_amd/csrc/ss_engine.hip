@@ -730,3 +730,65 @@ extern "C" int ss_bench_decode_step(ss_weights* w, const int32_t* prompt_tokens,
     for (auto& e : ev) (void)hipEventDestroy(e);
     return SS_OK;
 }
+
+extern "C" int ss_bench_weight_stream(ss_weights* w, int32_t B, int32_t iters, double* ms_out, int32_t* launches_out,
+                                      void* hip_stream)
+{
+    ss::clear_error();
+    if (!w || !ms_out) return ss::fail(SS_EINVAL, "NULL argument");
+    if (B <= 0 || B > ss::kMaxBatch || iters < 1) return ss::fail(SS_EINVAL, "bad B / iters");
+    BusyGuard guard(w);
+    if (!guard.ok) return ss::fail(SS_ESTATE, "another call is in flight on this handle");
+    hipStream_t s = hip_stream ? (hipStream_t)hip_stream : w->stream;
+    HIPCHK(hipSetDevice(w->device));
+    if (int rc = ensure_workspace(w, B, B, B, (size_t)B, 1)) return rc;
+    const ss_model_cfg& c = w->cfg;
+    const int d = c.d_model, F = c.d_ffn, V = c.vocab, Fp = ss::padded_k(F), n = B;
+    Workspace& ws = w->ws;
+    const int ks_qkv = ss::gemm_pick_ksplit(3 * d, d, n, ss::EPI_PARTIAL);
+    const int ks_o = ss::gemm_pick_ksplit(d, d, n, ss::EPI_PARTIAL);
+    const int ks_d = ss::gemm_pick_ksplit(d, Fp, n, ss::EPI_PARTIAL);
+    std::vector<hipEvent_t> ev(iters + 1);
+    for (auto& e : ev) HIPCHK(hipEventCreate(&e));
+    HIPCHK(hipEventRecord(ev[0], s));
+    int launches = 0;
+    for (int it = 0; it < iters; ++it) {
+        launches = 0;
+        for (int l = 0; l < c.n_layers; ++l) {
+            const Layer& L = w->layers[l];
+            GemmArgs g{};
+            g.W = L.wqkv.p; g.X = ws.h.as<bf16_t>(); g.out = ws.pqkv.as<float>(); g.N = 3 * d; g.Kp = d; g.m_rows = n;
+            g.m_stride = n; g.ksplit = ks_qkv;
+            ss::launch_gemm(g, ss::EPI_PARTIAL, s);
+            g = GemmArgs{};
+            g.W = L.wo.p; g.X = ws.ao.as<bf16_t>(); g.out = ws.pd.as<float>(); g.N = d; g.Kp = d; g.m_rows = n;
+            g.m_stride = n; g.ksplit = ks_o;
+            ss::launch_gemm(g, ss::EPI_PARTIAL, s);
+            g = GemmArgs{};
+            g.W = L.wgu.p; g.X = ws.h.as<bf16_t>(); g.out_packed = ws.act.as<bf16_t>(); g.N = 2 * F; g.Kp = d;
+            g.m_rows = n; g.kp_out = Fp; g.ksplit = 1;
+            ss::launch_gemm(g, ss::EPI_SWIGLU, s);
+            g = GemmArgs{};
+            g.W = L.wd.p; g.X = ws.act.as<bf16_t>(); g.out = ws.pd.as<float>(); g.N = d; g.Kp = Fp; g.m_rows = n;
+            g.m_stride = n; g.ksplit = ks_d;
+            ss::launch_gemm(g, ss::EPI_PARTIAL, s);
+            launches += 4;
+        }
+        GemmArgs g{};
+        g.W = w->lm_head.p; g.X = ws.hsel.as<bf16_t>(); g.out = ws.logits.as<float>(); g.N = V; g.Kp = d; g.m_rows = n;
+        g.m_stride = n; g.ksplit = 1;
+        ss::launch_gemm(g, ss::EPI_PARTIAL, s);
+        launches += 1;
+        HIPCHK(hipEventRecord(ev[it + 1], s));
+    }
+    HIPCHK(hipStreamSynchronize(s));
+    HIPCHK(hipGetLastError());
+    for (int it = 0; it < iters; ++it) {
+        float ms = 0.f;
+        HIPCHK(hipEventElapsedTime(&ms, ev[it], ev[it + 1]));
+        ms_out[it] = ms;
+    }
+    for (auto& e : ev) (void)hipEventDestroy(e);
+    if (launches_out) *launches_out = launches;
+    return SS_OK;
+}
