@@ -232,10 +232,20 @@ void forward(ss_weights* w, int n, int n_sel, const int32_t* d_sel, const int32_
     float* pd = ws.pd.as<float>();
     const int Fp = ss::padded_k(F);
 
-    const int ks_qkv = ss::gemm_pick_ksplit(3 * d, d, n, ss::EPI_PARTIAL);
-    const int ks_o = ss::gemm_pick_ksplit(d, d, n, ss::EPI_PARTIAL);
-    const int ks_d = ss::gemm_pick_ksplit(d, Fp, n, ss::EPI_PARTIAL);
+    const ss::GemmPlan p_qkv = ss::gemm_plan(3 * d, d, n, ss::EPI_PARTIAL), p_o = ss::gemm_plan(d, d, n, ss::EPI_PARTIAL),
+                       p_gu = ss::gemm_plan(2 * F, d, n, ss::EPI_SWIGLU), p_d = ss::gemm_plan(d, Fp, n, ss::EPI_PARTIAL);
+    ss::GemmPlan p_lm = ss::gemm_plan(V, d, n_sel, ss::EPI_PARTIAL);
+    p_lm.ksplit = 1;   // logits are read directly
+    if (n_sel <= 16) p_lm.kd = 8;
+    const int ks_qkv = p_qkv.ksplit, ks_o = p_o.ksplit, ks_d = p_d.ksplit;
     const size_t st_qkv = (size_t)n * 3 * d, st_d = (size_t)n * d;
+    auto mk = [](const bf16_t* W, const bf16_t* X, float* out, bf16_t* outp, int N, int Kp, int rows, int kp_out,
+                 const ss::GemmPlan& p) {
+        GemmArgs g{};
+        g.W = W; g.X = X; g.out = out; g.out_packed = outp; g.N = N; g.Kp = Kp; g.m_rows = rows; g.m_stride = rows;
+        g.kp_out = kp_out; g.ksplit = p.ksplit; g.nb = p.nb; g.kd = p.kd;
+        return g;
+    };
 
     ss::launch_embed(st, w->embed, x, d, n, s);
     for (int l = 0; l < c.n_layers; ++l) {
@@ -243,28 +253,17 @@ void forward(ss_weights* w, int n, int n_sel, const int32_t* d_sel, const int32_
         bf16_t* kc = ws.kv.as<bf16_t>() + (size_t)l * 2 * w->kv_layer_stride;
         bf16_t* vc = kc + w->kv_layer_stride;
         ss::launch_rmsnorm(st, x, l ? pd : nullptr, ks_d, st_d, L.attn_norm, c.rms_eps, nullptr, nullptr, h, d, n, s);
-        GemmArgs g{};
-        g.W = L.wqkv.p; g.X = h; g.out = pqkv; g.N = 3 * d; g.Kp = d; g.m_rows = n; g.m_stride = n; g.ksplit = ks_qkv;
-        ss::launch_gemm(g, ss::EPI_PARTIAL, s);
+        ss::launch_gemm(mk(L.wqkv.p, h, pqkv, nullptr, 3 * d, d, n, 0, p_qkv), ss::EPI_PARTIAL, s);
         ss::launch_rope_append(st, pqkv, ks_qkv, st_qkv, qrot, kc, vc, w->rope_cos, w->rope_sin, d, H, hd, n, s);
         ss::launch_attention(st, qrot, kc, vc, ao, d, H, hd, n, s);
-        g = GemmArgs{};
-        g.W = L.wo.p; g.X = ao; g.out = pd; g.N = d; g.Kp = d; g.m_rows = n; g.m_stride = n; g.ksplit = ks_o;
-        ss::launch_gemm(g, ss::EPI_PARTIAL, s);
+        ss::launch_gemm(mk(L.wo.p, ao, pd, nullptr, d, d, n, 0, p_o), ss::EPI_PARTIAL, s);
         ss::launch_rmsnorm(st, x, pd, ks_o, st_d, L.mlp_norm, c.rms_eps, nullptr, nullptr, h, d, n, s);
-        g = GemmArgs{};
-        g.W = L.wgu.p; g.X = h; g.out_packed = act; g.N = 2 * F; g.Kp = d; g.m_rows = n; g.kp_out = Fp; g.ksplit = 1;
-        ss::launch_gemm(g, ss::EPI_SWIGLU, s);
-        g = GemmArgs{};
-        g.W = L.wd.p; g.X = act; g.out = pd; g.N = d; g.Kp = Fp; g.m_rows = n; g.m_stride = n; g.ksplit = ks_d;
-        ss::launch_gemm(g, ss::EPI_PARTIAL, s);
+        ss::launch_gemm(mk(L.wgu.p, h, nullptr, act, 2 * F, d, n, Fp, p_gu), ss::EPI_SWIGLU, s);
+        ss::launch_gemm(mk(L.wd.p, act, pd, nullptr, d, Fp, n, 0, p_d), ss::EPI_PARTIAL, s);
     }
     bf16_t* hsel = ws.hsel.as<bf16_t>();
     ss::launch_rmsnorm(st, x, pd, ks_d, st_d, w->final_norm, c.rms_eps, d_sel, d_nsel, hsel, d, n_sel, s);
-    GemmArgs g{};
-    g.W = w->lm_head.p; g.X = hsel; g.out = ws.logits.as<float>(); g.N = V; g.Kp = d; g.m_rows = n_sel;
-    g.m_stride = n_sel; g.ksplit = 1;
-    ss::launch_gemm(g, ss::EPI_PARTIAL, s);
+    ss::launch_gemm(mk(w->lm_head.p, hsel, ws.logits.as<float>(), nullptr, V, d, n_sel, 0, p_lm), ss::EPI_PARTIAL, s);
     ss::launch_argmax(ws.logits.as<float>(), V, d_nsel ? d_nsel : st.d_n, st.am, n_sel, s);
 }
 
@@ -745,9 +744,20 @@ extern "C" int ss_bench_weight_stream(ss_weights* w, int32_t B, int32_t iters, d
     const ss_model_cfg& c = w->cfg;
     const int d = c.d_model, F = c.d_ffn, V = c.vocab, Fp = ss::padded_k(F), n = B;
     Workspace& ws = w->ws;
-    const int ks_qkv = ss::gemm_pick_ksplit(3 * d, d, n, ss::EPI_PARTIAL);
-    const int ks_o = ss::gemm_pick_ksplit(d, d, n, ss::EPI_PARTIAL);
-    const int ks_d = ss::gemm_pick_ksplit(d, Fp, n, ss::EPI_PARTIAL);
+    const ss::GemmPlan p_qkv = ss::gemm_plan(3 * d, d, n, ss::EPI_PARTIAL), p_o = ss::gemm_plan(d, d, n, ss::EPI_PARTIAL),
+                       p_gu = ss::gemm_plan(2 * F, d, n, ss::EPI_SWIGLU), p_d = ss::gemm_plan(d, Fp, n, ss::EPI_PARTIAL);
+    ss::GemmPlan p_lm = ss::gemm_plan(V, d, n, ss::EPI_PARTIAL);
+    p_lm.ksplit = 1;
+    if (n <= 16) p_lm.kd = 8;
+    auto mk = [](const bf16_t* W, const bf16_t* X, float* out, bf16_t* outp, int N, int Kp, int rows, int kp_out,
+                 const ss::GemmPlan& p) {
+        GemmArgs g{};
+        g.W = W; g.X = X; g.out = out; g.out_packed = outp; g.N = N; g.Kp = Kp; g.m_rows = rows; g.m_stride = rows;
+        g.kp_out = kp_out; g.ksplit = p.ksplit; g.nb = p.nb; g.kd = p.kd;
+        return g;
+    };
+    bf16_t *h = ws.h.as<bf16_t>(), *ao = ws.ao.as<bf16_t>(), *act = ws.act.as<bf16_t>();
+    float *pqkv = ws.pqkv.as<float>(), *pd = ws.pd.as<float>();
     std::vector<hipEvent_t> ev(iters + 1);
     for (auto& e : ev) HIPCHK(hipEventCreate(&e));
     HIPCHK(hipEventRecord(ev[0], s));
@@ -756,28 +766,14 @@ extern "C" int ss_bench_weight_stream(ss_weights* w, int32_t B, int32_t iters, d
         launches = 0;
         for (int l = 0; l < c.n_layers; ++l) {
             const Layer& L = w->layers[l];
-            GemmArgs g{};
-            g.W = L.wqkv.p; g.X = ws.h.as<bf16_t>(); g.out = ws.pqkv.as<float>(); g.N = 3 * d; g.Kp = d; g.m_rows = n;
-            g.m_stride = n; g.ksplit = ks_qkv;
-            ss::launch_gemm(g, ss::EPI_PARTIAL, s);
-            g = GemmArgs{};
-            g.W = L.wo.p; g.X = ws.ao.as<bf16_t>(); g.out = ws.pd.as<float>(); g.N = d; g.Kp = d; g.m_rows = n;
-            g.m_stride = n; g.ksplit = ks_o;
-            ss::launch_gemm(g, ss::EPI_PARTIAL, s);
-            g = GemmArgs{};
-            g.W = L.wgu.p; g.X = ws.h.as<bf16_t>(); g.out_packed = ws.act.as<bf16_t>(); g.N = 2 * F; g.Kp = d;
-            g.m_rows = n; g.kp_out = Fp; g.ksplit = 1;
-            ss::launch_gemm(g, ss::EPI_SWIGLU, s);
-            g = GemmArgs{};
-            g.W = L.wd.p; g.X = ws.act.as<bf16_t>(); g.out = ws.pd.as<float>(); g.N = d; g.Kp = Fp; g.m_rows = n;
-            g.m_stride = n; g.ksplit = ks_d;
-            ss::launch_gemm(g, ss::EPI_PARTIAL, s);
+            ss::launch_gemm(mk(L.wqkv.p, h, pqkv, nullptr, 3 * d, d, n, 0, p_qkv), ss::EPI_PARTIAL, s);
+            ss::launch_gemm(mk(L.wo.p, ao, pd, nullptr, d, d, n, 0, p_o), ss::EPI_PARTIAL, s);
+            ss::launch_gemm(mk(L.wgu.p, h, nullptr, act, 2 * F, d, n, Fp, p_gu), ss::EPI_SWIGLU, s);
+            ss::launch_gemm(mk(L.wd.p, act, pd, nullptr, d, Fp, n, 0, p_d), ss::EPI_PARTIAL, s);
             launches += 4;
         }
-        GemmArgs g{};
-        g.W = w->lm_head.p; g.X = ws.hsel.as<bf16_t>(); g.out = ws.logits.as<float>(); g.N = V; g.Kp = d; g.m_rows = n;
-        g.m_stride = n; g.ksplit = 1;
-        ss::launch_gemm(g, ss::EPI_PARTIAL, s);
+        ss::launch_gemm(mk(w->lm_head.p, ws.hsel.as<bf16_t>(), ws.logits.as<float>(), nullptr, V, d, n, 0, p_lm),
+                        ss::EPI_PARTIAL, s);
         launches += 1;
         HIPCHK(hipEventRecord(ev[it + 1], s));
     }

@@ -45,7 +45,8 @@ struct GemmArgs {
     int N, Kp, m_rows;   // m_rows: rows to compute (stores are guarded by it)
     int m_stride;        // row stride (in rows) between k-slices of `out`
     int kp_out;          // padded K of out_packed
-    int ksplit;
+    int ksplit;          // outer k-slices (gemm_plan)
+    int nb, kd;          // skinny kernel shape (gemm_plan)
 };
 
 void launch_pack_weight(const void* src, int src_f32, bf16_t* dst, int n_src, int k, int kp, int blk_stride,
@@ -56,7 +57,10 @@ void launch_rmsnorm(const MbState& st, float* x, const float* part, int ksplit, 
                     const bf16_t* w, float eps, const int32_t* sel, const int32_t* d_nsel, bf16_t* h_packed, int d,
                     int n_max, hipStream_t s);
 void launch_gemm(const GemmArgs& a, int epilogue, hipStream_t s);
-int  gemm_pick_ksplit(int N, int Kp, int m_rows, int epilogue);
+struct GemmPlan {
+    int ksplit, nb, kd;
+};
+GemmPlan gemm_plan(int N, int Kp, int m_rows, int epilogue);
 void launch_rope_append(const MbState& st, const float* qkv_part, int ksplit, size_t part_stride, float* qrot,
                         bf16_t* kcache, bf16_t* vcache, const float* rope_cos, const float* rope_sin, int d, int H,
                         int hd, int n_max, hipStream_t s);

@@ -153,23 +153,68 @@ __global__ __launch_bounds__(256) void k_rmsnorm(const int32_t* __restrict__ d_c
 }
 
 // ------------------------------------------------------------------------------------------ skinny GEMM
-// Up to 64 token rows (MT strips of 16).  One wavefront owns NB strips of 16 output columns and one
-// k-slice: per 32-wide k-block it loads NB weight operands straight from HBM (1 KiB contiguous each,
-// never re-read by anyone) and MT activation operands (L2 hits), and issues NB*MT MFMAs.  Waves never
-// synchronise; KD k-blocks are loaded per loop trip so that NB*KD KiB of weights are in flight per wave.
+// Up to 64 token rows (MT strips of 16); the whole cost is streaming the weights once from HBM.
+// A workgroup of 4 wavefronts owns NB strips of 16 output columns and one outer k-slice; its waves cut
+// that slice into 4 contiguous k-ranges, so every wave streams NB contiguous runs of 1 KiB operand
+// blocks (non-temporal: each weight byte is used exactly once per step) and never waits for another
+// wave until the end.  Loads are double-buffered in registers: while the MFMAs of KD k-blocks run, the
+// next KD*NB KiB are already in flight.  The activation operands (MT per k-block) come from L2.
+// At the end waves 1..3 hand their accumulators to wave 0 through LDS; wave 0 runs the epilogue.
 __device__ __forceinline__ float silu_f(float z) { return z / (1.f + __expf(-z)); }
+
+template <int MT, int NB, int KD>
+struct SkinnyFrags {
+    u32x4 w[NB][KD];
+    u32x4 x[MT][KD];
+};
+
+template <int MT, int NB, int KD>
+__device__ __forceinline__ void skinny_load(SkinnyFrags<MT, NB, KD>& f, const u32x4* __restrict__ Wl,
+                                            const u32x4* __restrict__ Xl, int KB, int nb0, int nvalid, int kb,
+                                            int kend)
+{
+#pragma unroll
+    for (int q = 0; q < KD; ++q) {
+        const int kk = min(kb + q, kend - 1);   // tail: clamped re-read, the result is not used
+#pragma unroll
+        for (int i = 0; i < NB; ++i) {
+            const int nb = nb0 + (i < nvalid ? i : 0);
+            f.w[i][q] = __builtin_nontemporal_load(Wl + ((size_t)nb * KB + kk) * 64);
+        }
+#pragma unroll
+        for (int m = 0; m < MT; ++m) f.x[m][q] = Xl[((size_t)m * KB + kk) * 64];
+    }
+}
+
+template <int MT, int NB, int KD>
+__device__ __forceinline__ void skinny_mma(const SkinnyFrags<MT, NB, KD>& f, f32x4 (&acc)[NB][MT], int kb, int kend)
+{
+#pragma unroll
+    for (int q = 0; q < KD; ++q) {
+        if (kb + q < kend) {
+#pragma unroll
+            for (int i = 0; i < NB; ++i)
+#pragma unroll
+                for (int m = 0; m < MT; ++m)
+                    acc[i][m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, f.w[i][q]),
+                                                                        __builtin_bit_cast(bf16x8, f.x[m][q]),
+                                                                        acc[i][m], 0, 0, 0);
+        }
+    }
+}
 
 template <int MT, int NB, int KD, int EPI>
 __global__ __launch_bounds__(256) void k_gemm_skinny(GemmArgs a, int n_groups, int kb_per_slice)
 {
-    const int lane = threadIdx.x & 63;
-    const int task = blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (task >= n_groups * a.ksplit) return;
-    const int ng = task % n_groups, ks = task / n_groups;
+    __shared__ f32x4 red[3][NB][MT][64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int ng = blockIdx.x % n_groups, ks = blockIdx.x / n_groups;
     const int KB = a.Kp >> 5, NBT = a.N >> 4;
-    const int kb0 = ks * kb_per_slice;
-    const int kb1 = min(KB, kb0 + kb_per_slice);
+    const int s0 = ks * kb_per_slice, s1 = min(KB, s0 + kb_per_slice);
+    const int per_wave = (max(s1 - s0, 0) + 3) >> 2;
+    const int kbeg = min(s1, s0 + wave * per_wave), kend = min(s1, kbeg + per_wave);
     const int nb0 = ng * NB;
+    const int nvalid = min(NB, NBT - nb0);  // block-uniform
 
     f32x4 acc[NB][MT];
 #pragma unroll
@@ -179,38 +224,30 @@ __global__ __launch_bounds__(256) void k_gemm_skinny(GemmArgs a, int n_groups, i
 
     const u32x4* Wl = (const u32x4*)a.W + lane;
     const u32x4* Xl = (const u32x4*)a.X + lane;
-    const int nvalid = min(NB, NBT - nb0);  // wave-uniform
-
-    for (int kb = kb0; kb < kb1; kb += KD) {
-        u32x4 wf[NB][KD], xf[MT][KD];
+    if (kbeg < kend) {
+        SkinnyFrags<MT, NB, KD> fa, fb;
+        skinny_load(fa, Wl, Xl, KB, nb0, nvalid, kbeg, kend);
+        for (int kb = kbeg; kb < kend; kb += 2 * KD) {
+            if (kb + KD < kend) skinny_load(fb, Wl, Xl, KB, nb0, nvalid, kb + KD, kend);
+            skinny_mma(fa, acc, kb, kend);
+            if (kb + 2 * KD < kend) skinny_load(fa, Wl, Xl, KB, nb0, nvalid, kb + 2 * KD, kend);
+            if (kb + KD < kend) skinny_mma(fb, acc, kb + KD, kend);
+        }
+    }
+    if (wave > 0) {
 #pragma unroll
         for (int i = 0; i < NB; ++i)
 #pragma unroll
-            for (int q = 0; q < KD; ++q) {
-                const int kk = min(kb + q, kb1 - 1);          // clamped re-read on the tail, result unused
-                const int nb = nb0 + (i < nvalid ? i : 0);
-                wf[i][q] = __builtin_nontemporal_load(Wl + ((size_t)nb * KB + kk) * 64);
-            }
-#pragma unroll
-        for (int m = 0; m < MT; ++m)
-#pragma unroll
-            for (int q = 0; q < KD; ++q) {
-                const int kk = min(kb + q, kb1 - 1);
-                xf[m][q] = Xl[((size_t)m * KB + kk) * 64];
-            }
-#pragma unroll
-        for (int q = 0; q < KD; ++q) {
-            if (kb + q < kb1) {
-#pragma unroll
-                for (int i = 0; i < NB; ++i)
-#pragma unroll
-                    for (int m = 0; m < MT; ++m)
-                        acc[i][m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wf[i][q]),
-                                                                            __builtin_bit_cast(bf16x8, xf[m][q]),
-                                                                            acc[i][m], 0, 0, 0);
-            }
-        }
+            for (int m = 0; m < MT; ++m) red[wave - 1][i][m][lane] = acc[i][m];
     }
+    __syncthreads();
+    if (wave > 0) return;
+#pragma unroll
+    for (int w = 0; w < 3; ++w)
+#pragma unroll
+        for (int i = 0; i < NB; ++i)
+#pragma unroll
+            for (int m = 0; m < MT; ++m) acc[i][m] += red[w][i][m][lane];
 
     const int col4 = (lane >> 4) * 4;  // first of this lane's 4 consecutive output columns inside a strip
 #pragma unroll
@@ -591,35 +628,51 @@ void launch_rmsnorm(const MbState& st, float* x, const float* part, int ksplit, 
                        part ? ksplit : 0, part_stride, w, eps, sel, h_packed, d);
 }
 
-// k-slices: enough wave tasks to cover the chip a few times over, at least 8 k-blocks per slice.
-int gemm_pick_ksplit(int N, int Kp, int m_rows, int epilogue)
+// Launch shape of a projection.  Skinny kernel (<= 64 rows): nb = 2 strips per workgroup, kd k-blocks per
+// register buffer (8 when one strip of rows leaves the registers for it), ksplit outer k-slices whose
+// partial sums the consumer adds.  Measured on the 7B shapes the chip wants thousands of small
+// workgroups: as many k-slices (up to 8) as leave every wave at least 4 k-blocks.  Tiled kernel: ksplit
+// fills the chip when there are few 128x128 tiles.
+GemmPlan gemm_plan(int N, int Kp, int m_rows, int epilogue)
 {
-    if (epilogue == EPI_SWIGLU) return 1;
+    GemmPlan p{1, 2, 4};
     const int KB = Kp / 32;
     if (m_rows <= 64) {
-        const int groups = (N / 16 + 3) / 4;
-        int ks = (2048 + groups - 1) / groups;
-        ks = ks < 1 ? 1 : ks;
-        const int cap = KB / 16 > 0 ? KB / 16 : 1;
-        if (ks > cap) ks = cap;
-        if (ks > 8) ks = 8;
-        return ks;
+        const int mt = (m_rows + 15) / 16;
+        p.kd = mt == 1 ? 4 : (mt == 2 ? 4 : 2);
+        if (epilogue == EPI_SWIGLU) {
+            if (mt == 1) p.kd = 8;
+            return p;
+        }
+        while (p.ksplit < 8 && KB / (p.ksplit * 2 * 4) >= 4) p.ksplit *= 2;
+        return p;
     }
+    if (epilogue == EPI_SWIGLU) return p;
     const int tiles = ((N + 127) / 128) * ((m_rows + 127) / 128);
-    int ks = 1;
-    while (tiles * ks < 256 && ks < 8 && KB / (ks * 2) >= 16) ks *= 2;
-    return ks;
+    while (tiles * p.ksplit < 256 && p.ksplit < 8 && KB / (p.ksplit * 2) >= 16) p.ksplit *= 2;
+    return p;
+}
+
+template <int MT, int NB, int KD, int EPI>
+static void launch_skinny_inst(const GemmArgs& a, hipStream_t s)
+{
+    const int KB = a.Kp / 32;
+    const int groups = (a.N / 16 + NB - 1) / NB;
+    const int kbs = (KB + a.ksplit - 1) / a.ksplit;
+    hipLaunchKernelGGL((k_gemm_skinny<MT, NB, KD, EPI>), dim3(groups * a.ksplit), dim3(256), 0, s, a, groups, kbs);
 }
 
 template <int MT, int EPI>
 static void launch_skinny_mt(const GemmArgs& a, hipStream_t s)
 {
-    constexpr int NB = 4, KD = (MT <= 2 ? 4 : 2);
-    const int KB = a.Kp / 32;
-    const int groups = (a.N / 16 + NB - 1) / NB;
-    int kbs = (KB + a.ksplit - 1) / a.ksplit;
-    const int tasks = groups * a.ksplit;
-    hipLaunchKernelGGL((k_gemm_skinny<MT, NB, KD, EPI>), dim3((tasks + 3) / 4), dim3(256), 0, s, a, groups, kbs);
+    if (a.nb == 2) {
+        if (a.kd == 2) launch_skinny_inst<MT, 2, 2, EPI>(a, s);
+        else if (a.kd == 8) launch_skinny_inst<MT, 2, (MT == 1 ? 8 : 4), EPI>(a, s);
+        else launch_skinny_inst<MT, 2, 4, EPI>(a, s);
+    } else {
+        if (a.kd == 2 || MT > 2) launch_skinny_inst<MT, 4, 2, EPI>(a, s);
+        else launch_skinny_inst<MT, 4, 4, EPI>(a, s);
+    }
 }
 
 template <int EPI>
