@@ -217,7 +217,7 @@ int ensure_workspace(ss_weights* w, int n_max, int B, int n_sel, size_t slots, i
 // Runs the decoder over the token-rows described by the device state (st.d_n of them, at most n of
 // them: n sizes the grids and picks the kernel variants).  Logits are produced for n_sel rows:
 // the rows listed in d_sel, or the first *d_nsel rows when d_sel is null.  Ends with the argmax.
-void forward(ss_weights* w, int n, int n_sel, const int32_t* d_sel, const int32_t* d_nsel, hipStream_t s)
+void forward(ss_weights* w, int n, int n_sel, const int32_t* d_sel, const int32_t* d_nsel, bool decode, hipStream_t s)
 {
     const ss_model_cfg& c = w->cfg;
     const int d = c.d_model, H = c.n_heads, hd = c.head_dim, F = c.d_ffn, V = c.vocab;
@@ -254,8 +254,12 @@ void forward(ss_weights* w, int n, int n_sel, const int32_t* d_sel, const int32_
         bf16_t* vc = kc + w->kv_layer_stride;
         ss::launch_rmsnorm(st, x, l ? pd : nullptr, ks_d, st_d, L.attn_norm, c.rms_eps, nullptr, nullptr, h, d, n, s);
         ss::launch_gemm(mk(L.wqkv.p, h, pqkv, nullptr, 3 * d, d, n, 0, p_qkv), ss::EPI_PARTIAL, s);
-        ss::launch_rope_append(st, pqkv, ks_qkv, st_qkv, qrot, kc, vc, w->rope_cos, w->rope_sin, d, H, hd, n, s);
-        ss::launch_attention(st, qrot, kc, vc, ao, d, H, hd, n, s);
+        if (decode) {   // one token-row per row: rotation and append are fused into the attention kernel
+            ss::launch_attention_decode(st, pqkv, ks_qkv, st_qkv, kc, vc, w->rope_cos, w->rope_sin, ao, d, H, hd, n, s);
+        } else {        // prompt: every key of a row must be in place before any of its queries attends
+            ss::launch_rope_append(st, pqkv, ks_qkv, st_qkv, qrot, kc, vc, w->rope_cos, w->rope_sin, d, H, hd, n, s);
+            ss::launch_attention(st, qrot, kc, vc, ao, d, H, hd, n, s);
+        }
         ss::launch_gemm(mk(L.wo.p, ao, pd, nullptr, d, d, n, 0, p_o), ss::EPI_PARTIAL, s);
         ss::launch_rmsnorm(st, x, pd, ks_o, st_d, L.mlp_norm, c.rms_eps, nullptr, nullptr, h, d, n, s);
         ss::launch_gemm(mk(L.wgu.p, h, nullptr, act, 2 * F, d, n, Fp, p_gu), ss::EPI_SWIGLU, s);
@@ -367,7 +371,7 @@ int decode_microbatch_impl(ss_weights* w, const int32_t* prompt_tokens, const in
     HIPCHK(hipEventCreate(&e1));
     HIPCHK(hipEventCreate(&e2));
     HIPCHK(hipEventRecord(e0, s));
-    forward(w, n_prompt, B, w->d_sel, st.d_nlive, s);
+    forward(w, n_prompt, B, w->d_sel, st.d_nlive, false, s);
     ss::launch_step_update(st, compact, s);
     HIPCHK(hipEventRecord(e1, s));
 
@@ -379,7 +383,7 @@ int decode_microbatch_impl(ss_weights* w, const int32_t* prompt_tokens, const in
         int n_live = B;
         if (compact)
             n_live = (int)(sorted_limit.end() - std::upper_bound(sorted_limit.begin(), sorted_limit.end(), g));
-        forward(w, n_live, n_live, nullptr, nullptr, s);
+        forward(w, n_live, n_live, nullptr, nullptr, true, s);
         ss::launch_step_update(st, compact, s);
         row_steps += n_live;
         if (stats)
@@ -563,7 +567,7 @@ extern "C" int ss_forward_logits(ss_weights* w, const int32_t* tokens, const int
         return rc;
     const int32_t nsel32 = n_sel;
     HIPCHK(hipMemcpyAsync(st.d_nlive, &nsel32, 4, hipMemcpyHostToDevice, s));
-    forward(w, n_p, n_sel, w->d_sel, st.d_nlive, s);
+    forward(w, n_p, n_sel, w->d_sel, st.d_nlive, false, s);
     std::vector<float> lg((size_t)std::max(n_sel, B) * V);
     HIPCHK(hipMemcpyAsync(lg.data(), w->ws.logits.p, (size_t)n_sel * V * 4, hipMemcpyDeviceToHost, s));
     HIPCHK(hipStreamSynchronize(s));
@@ -587,7 +591,7 @@ extern "C" int ss_forward_logits(ss_weights* w, const int32_t* tokens, const int
         HIPCHK(hipMemcpyAsync(st.tr_tok, tok.data(), (size_t)n * 4, hipMemcpyHostToDevice, s));
         HIPCHK(hipMemcpyAsync(st.tr_row, row.data(), (size_t)n * 4, hipMemcpyHostToDevice, s));
         HIPCHK(hipMemcpyAsync(st.tr_pos, pos.data(), (size_t)n * 4, hipMemcpyHostToDevice, s));
-        forward(w, n, n, nullptr, nullptr, s);
+        forward(w, n, n, nullptr, nullptr, true, s);
         HIPCHK(hipMemcpyAsync(lg.data(), w->ws.logits.p, (size_t)n * V * 4, hipMemcpyDeviceToHost, s));
         HIPCHK(hipStreamSynchronize(s));
         for (int j = 0; j < n; ++j)
@@ -710,13 +714,13 @@ extern "C" int ss_bench_decode_step(ss_weights* w, const int32_t* prompt_tokens,
     const MbState& st = w->st;
     if (int rc = upload_prompt_state(w, prompt_tokens, offs.data(), lens.data(), B, slab.data(), limit.data(), sel, s))
         return rc;
-    forward(w, B * ctx, B, w->d_sel, st.d_nlive, s);
+    forward(w, B * ctx, B, w->d_sel, st.d_nlive, false, s);
     ss::launch_step_update(st, 0, s);   // token-rows of the decode step: every row at position ctx
     std::vector<hipEvent_t> ev(iters + 1);
     for (auto& e : ev) HIPCHK(hipEventCreate(&e));
     HIPCHK(hipEventRecord(ev[0], s));
     for (int it = 0; it < iters; ++it) {
-        forward(w, B, B, nullptr, nullptr, s);
+        forward(w, B, B, nullptr, nullptr, true, s);
         HIPCHK(hipEventRecord(ev[it + 1], s));
     }
     HIPCHK(hipStreamSynchronize(s));

@@ -66,6 +66,9 @@ void launch_rope_append(const MbState& st, const float* qkv_part, int ksplit, si
                         int hd, int n_max, hipStream_t s);
 void launch_attention(const MbState& st, const float* qrot, const bf16_t* kcache, const bf16_t* vcache,
                       bf16_t* out_packed, int d, int H, int hd, int n_max, hipStream_t s);
+void launch_attention_decode(const MbState& st, const float* qkv_part, int ksplit, size_t part_stride,
+                             bf16_t* kcache, bf16_t* vcache, const float* rope_cos, const float* rope_sin,
+                             bf16_t* out_packed, int d, int H, int hd, int n_max, hipStream_t s);
 void launch_argmax(const float* logits, int vocab, const int32_t* d_nsel, int32_t* am, int n_max, hipStream_t s);
 void launch_step_update(const MbState& st, int compact, hipStream_t s);
 void launch_fill_i32(int32_t* p, int32_t v, size_t n, hipStream_t s);

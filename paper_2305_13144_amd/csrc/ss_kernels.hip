@@ -420,49 +420,48 @@ __global__ __launch_bounds__(256) void k_rope_append(MbState st, const float* __
 // One workgroup per (token-row, head): softmax(q.K^T / sqrt(hd)) V over the row's own slots 0..pos.
 // Two passes, exactly the max-subtracted definition: scores to LDS, block max and sum, then the weighted
 // sum of V.  A wave's load covers 64/LPK consecutive keys (LPK = hd/8 lanes of 16 bytes per key), so K
-// and V are each streamed once, fully coalesced.
+// and V are each streamed once, fully coalesced; a wave issues AU such loads before it consumes them, so
+// a context of a few hundred slots costs two or three memory round trips, not one per load.
+constexpr int kAttnUnroll = 8;
+
 template <int HD>
-__global__ __launch_bounds__(256) void k_attention(MbState st, const float* __restrict__ qrot,
-                                                   const bf16_t* __restrict__ kc, const bf16_t* __restrict__ vc,
-                                                   bf16_t* __restrict__ out, int d)
+__device__ __forceinline__ void attend(const float* __restrict__ qs, float* __restrict__ sc, float* __restrict__ red,
+                                       float (*__restrict__ oacc)[HD], const bf16_t* __restrict__ kbase,
+                                       const bf16_t* __restrict__ vbase, int ctx, bf16_t* __restrict__ out, int out_r,
+                                       int out_k0, int out_kp)
 {
     constexpr int LPK = HD / 8;       // lanes per key
     constexpr int KPW = 64 / LPK;     // keys per wave load
-    __shared__ float sc[kMaxPos];
-    __shared__ float red[8];
-    __shared__ float oacc[4][HD];
-    const int j = blockIdx.x, h = blockIdx.y;
-    if (j >= *st.d_n) return;
+    constexpr int AU = kAttnUnroll;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int row = st.tr_row[j], ctx = st.tr_pos[j] + 1;
-    const int cap = st.row_cap[row];
-    const size_t base = (size_t)st.row_so[row] * d + (size_t)h * cap * HD;
     const int sub = lane % LPK, kin = lane / LPK;
     const float scale = rsqrtf((float)HD);
-
     float q[8];
-    {
-        const float* qp = qrot + (size_t)j * d + h * HD + sub * 8;
-        const float4 a = *(const float4*)qp, b = *(const float4*)(qp + 4);
-        q[0] = a.x; q[1] = a.y; q[2] = a.z; q[3] = a.w; q[4] = b.x; q[5] = b.y; q[6] = b.z; q[7] = b.w;
-    }
-    float mx = -3.0e38f;
-#pragma unroll 4
-    for (int s0 = wave * KPW; s0 < ctx; s0 += 4 * KPW) {
-        const int s = s0 + kin;
-        float part = 0.f;
-        if (s < ctx) {
-            const uint4 raw = *(const uint4*)(kc + base + (size_t)s * HD + sub * 8);
-            const bf16_t* kv = (const bf16_t*)&raw;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) part += q[e] * bf2f(kv[e]);
+    for (int e = 0; e < 8; ++e) q[e] = qs[sub * 8 + e];
+
+    float mx = -3.0e38f;
+    for (int c0 = wave * KPW; c0 < ctx; c0 += 4 * KPW * AU) {
+        uint4 raw[AU];
+#pragma unroll
+        for (int u = 0; u < AU; ++u) {
+            const int s = c0 + u * 4 * KPW + kin;
+            raw[u] = s < ctx ? *(const uint4*)(kbase + (size_t)s * HD + sub * 8) : make_uint4(0, 0, 0, 0);
         }
 #pragma unroll
-        for (int m = 1; m < LPK; m <<= 1) part += __shfl_xor(part, m, 64);
-        part *= scale;
-        if (s < ctx) {
-            if (sub == 0) sc[s] = part;
-            mx = fmaxf(mx, part);
+        for (int u = 0; u < AU; ++u) {
+            const int s = c0 + u * 4 * KPW + kin;
+            const bf16_t* kv = (const bf16_t*)&raw[u];
+            float part = 0.f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) part += q[e] * bf2f(kv[e]);
+#pragma unroll
+            for (int m = 1; m < LPK; m <<= 1) part += __shfl_xor(part, m, 64);
+            part *= scale;
+            if (s < ctx) {
+                if (sub == 0) sc[s] = part;
+                mx = fmaxf(mx, part);
+            }
         }
     }
     mx = wave_max(mx);
@@ -481,13 +480,18 @@ __global__ __launch_bounds__(256) void k_attention(MbState st, const float* __re
     const float inv = 1.f / (red[4] + red[5] + red[6] + red[7]);
 
     float o[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-#pragma unroll 4
-    for (int s0 = wave * KPW; s0 < ctx; s0 += 4 * KPW) {
-        const int s = s0 + kin;
-        if (s < ctx) {
-            const float p = sc[s];
-            const uint4 raw = *(const uint4*)(vc + base + (size_t)s * HD + sub * 8);
-            const bf16_t* vv = (const bf16_t*)&raw;
+    for (int c0 = wave * KPW; c0 < ctx; c0 += 4 * KPW * AU) {
+        uint4 raw[AU];
+#pragma unroll
+        for (int u = 0; u < AU; ++u) {
+            const int s = c0 + u * 4 * KPW + kin;
+            raw[u] = s < ctx ? *(const uint4*)(vbase + (size_t)s * HD + sub * 8) : make_uint4(0, 0, 0, 0);
+        }
+#pragma unroll
+        for (int u = 0; u < AU; ++u) {
+            const int s = c0 + u * 4 * KPW + kin;
+            const float p = s < ctx ? sc[s] : 0.f;
+            const bf16_t* vv = (const bf16_t*)&raw[u];
 #pragma unroll
             for (int e = 0; e < 8; ++e) o[e] += p * bf2f(vv[e]);
         }
@@ -507,8 +511,73 @@ __global__ __launch_bounds__(256) void k_attention(MbState st, const float* __re
             const int c = tid * 4 + e;
             r[e] = f2bf((oacc[0][c] + oacc[1][c] + oacc[2][c] + oacc[3][c]) * inv);
         }
-        *(uint2*)(out + pk_index(j, h * HD + tid * 4, d)) = *(const uint2*)r;
+        *(uint2*)(out + pk_index(out_r, out_k0 + tid * 4, out_kp)) = *(const uint2*)r;
     }
+}
+
+// Prompt forwards: q was rotated and K, V appended for every token-row by k_rope_append before this runs.
+template <int HD>
+__global__ __launch_bounds__(256) void k_attention(MbState st, const float* __restrict__ qrot,
+                                                   const bf16_t* __restrict__ kc, const bf16_t* __restrict__ vc,
+                                                   bf16_t* __restrict__ out, int d)
+{
+    __shared__ float sc[kMaxPos];
+    __shared__ float red[8];
+    __shared__ float oacc[4][HD];
+    __shared__ float qs[HD];
+    const int j = blockIdx.x, h = blockIdx.y;
+    if (j >= *st.d_n) return;
+    const int row = st.tr_row[j], ctx = st.tr_pos[j] + 1;
+    const size_t base = (size_t)st.row_so[row] * d + (size_t)h * st.row_cap[row] * HD;
+    if (threadIdx.x < HD) qs[threadIdx.x] = qrot[(size_t)j * d + h * HD + threadIdx.x];
+    __syncthreads();
+    attend<HD>(qs, sc, red, oacc, kc + base, vc + base, ctx, out, j, h * HD, d);
+}
+
+// Decode forwards: the (token-row, head) workgroup first finishes its own slice of the q|k|v projection
+// (sums the k-slices, rotates q and k at the row's position, appends k and v to the row's slab), then
+// attends.  Saves a launch and the round trip of q through HBM for every layer of every step.
+template <int HD>
+__global__ __launch_bounds__(256) void k_attention_decode(MbState st, const float* __restrict__ part, int ksplit,
+                                                          size_t part_stride, bf16_t* __restrict__ kc,
+                                                          bf16_t* __restrict__ vc, const float* __restrict__ rcos,
+                                                          const float* __restrict__ rsin, bf16_t* __restrict__ out,
+                                                          int d)
+{
+    __shared__ float sc[kMaxPos];
+    __shared__ float red[8];
+    __shared__ float oacc[4][HD];
+    __shared__ float qs[HD];
+    constexpr int HALF = HD / 2;
+    const int j = blockIdx.x, h = blockIdx.y;
+    if (j >= *st.d_n) return;
+    const int row = st.tr_row[j], pos = st.tr_pos[j];
+    const size_t base = (size_t)st.row_so[row] * d + (size_t)h * st.row_cap[row] * HD;
+    const int which = threadIdx.x / HALF, e = threadIdx.x % HALF;   // 0 q, 1 k, 2 v
+    if (which < 3) {
+        const float* p = part + (size_t)j * 3 * d + (size_t)which * d + h * HD + e;
+        float a = 0.f, b = 0.f;
+        for (int s = 0; s < ksplit; ++s) {
+            a += p[(size_t)s * part_stride];
+            b += p[(size_t)s * part_stride + HALF];
+        }
+        if (which < 2) {
+            const float cs = rcos[(size_t)pos * HALF + e], sn = rsin[(size_t)pos * HALF + e];
+            const float ra = a * cs - b * sn, rb = a * sn + b * cs;
+            a = ra;
+            b = rb;
+        }
+        if (which == 0) {
+            qs[e] = a;
+            qs[e + HALF] = b;
+        } else {
+            bf16_t* dst = (which == 1 ? kc : vc) + base + (size_t)pos * HD + e;
+            dst[0] = f2bf(a);
+            dst[HALF] = f2bf(b);
+        }
+    }
+    __syncthreads();   // the new key/value slot and q are visible to the whole workgroup
+    attend<HD>(qs, sc, red, oacc, kc + base, vc + base, pos + 1, out, j, h * HD, d);
 }
 
 // ------------------------------------------------------------------------------------------ argmax
@@ -709,6 +778,18 @@ void launch_rope_append(const MbState& st, const float* qkv_part, int ksplit, si
 {
     hipLaunchKernelGGL(k_rope_append, dim3(n_max), dim3(256), 0, s, st, qkv_part, ksplit, part_stride, qrot, kcache,
                        vcache, rope_cos, rope_sin, d, H, hd);
+}
+
+void launch_attention_decode(const MbState& st, const float* qkv_part, int ksplit, size_t part_stride,
+                             bf16_t* kcache, bf16_t* vcache, const float* rope_cos, const float* rope_sin,
+                             bf16_t* out_packed, int d, int H, int hd, int n_max, hipStream_t s)
+{
+    if (hd == 128)
+        hipLaunchKernelGGL((k_attention_decode<128>), dim3(n_max, H), dim3(256), 0, s, st, qkv_part, ksplit,
+                           part_stride, kcache, vcache, rope_cos, rope_sin, out_packed, d);
+    else
+        hipLaunchKernelGGL((k_attention_decode<64>), dim3(n_max, H), dim3(256), 0, s, st, qkv_part, ksplit,
+                           part_stride, kcache, vcache, rope_cos, rope_sin, out_packed, d);
 }
 
 void launch_attention(const MbState& st, const float* qrot, const bf16_t* kcache, const bf16_t* vcache,
