@@ -68,10 +68,12 @@ struct Buf {
 };
 
 struct Workspace {
-    Buf x, h, ao, act, qrot, pqkv, pd, hsel, logits, kv, ints, i64s;
+    Buf x, h, h_lo, ao, ao_lo, act, act_lo, qrot, pqkv, pd, hsel, hsel_lo, logits, kv, ints, i64s;
     void release()
     {
-        for (Buf* b : {&x, &h, &ao, &act, &qrot, &pqkv, &pd, &hsel, &logits, &kv, &ints, &i64s}) b->release();
+        for (Buf* b : {&x, &h, &h_lo, &ao, &ao_lo, &act, &act_lo, &qrot, &pqkv, &pd, &hsel, &hsel_lo, &logits, &kv,
+                       &ints, &i64s})
+            b->release();
     }
 };
 
@@ -181,12 +183,16 @@ int ensure_workspace(ss_weights* w, int n_max, int B, int n_sel, size_t slots, i
     int rc;
     if ((rc = ws.x.ensure(nr * d * 4, false))) return rc;
     if ((rc = ws.h.ensure(nr * d * 2, true))) return rc;
+    if ((rc = ws.h_lo.ensure(nr * d * 2, true))) return rc;
     if ((rc = ws.ao.ensure(nr * d * 2, true))) return rc;
+    if ((rc = ws.ao_lo.ensure(nr * d * 2, true))) return rc;
     if ((rc = ws.act.ensure(nr * ss::padded_k(F) * 2, true))) return rc;
+    if ((rc = ws.act_lo.ensure(nr * ss::padded_k(F) * 2, true))) return rc;
     if ((rc = ws.qrot.ensure(nr * d * 4, false))) return rc;
     if ((rc = ws.pqkv.ensure(ks_rows * 3 * d * 4, false))) return rc;
     if ((rc = ws.pd.ensure(ks_rows * d * 4, false))) return rc;
     if ((rc = ws.hsel.ensure((size_t)ss::round_up(n_sel, 128) * d * 2, true))) return rc;
+    if ((rc = ws.hsel_lo.ensure((size_t)ss::round_up(n_sel, 128) * d * 2, true))) return rc;
     if ((rc = ws.logits.ensure((size_t)ss::round_up(n_sel, 16) * V * 4, false))) return rc;
     w->kv_layer_stride = slots * d;
     if ((rc = ws.kv.ensure((size_t)c.n_layers * 2 * slots * d * 2, false))) return rc;
@@ -224,9 +230,9 @@ void forward(ss_weights* w, int n, int n_sel, const int32_t* d_sel, const int32_
     Workspace& ws = w->ws;
     const MbState& st = w->st;
     float* x = ws.x.as<float>();
-    bf16_t* h = ws.h.as<bf16_t>();
-    bf16_t* ao = ws.ao.as<bf16_t>();
-    bf16_t* act = ws.act.as<bf16_t>();
+    bf16_t *h = ws.h.as<bf16_t>(), *h_lo = ws.h_lo.as<bf16_t>();
+    bf16_t *ao = ws.ao.as<bf16_t>(), *ao_lo = ws.ao_lo.as<bf16_t>();
+    bf16_t *act = ws.act.as<bf16_t>(), *act_lo = ws.act_lo.as<bf16_t>();
     float* qrot = ws.qrot.as<float>();
     float* pqkv = ws.pqkv.as<float>();
     float* pd = ws.pd.as<float>();
@@ -236,14 +242,13 @@ void forward(ss_weights* w, int n, int n_sel, const int32_t* d_sel, const int32_
                        p_gu = ss::gemm_plan(2 * F, d, n, ss::EPI_SWIGLU), p_d = ss::gemm_plan(d, Fp, n, ss::EPI_PARTIAL);
     ss::GemmPlan p_lm = ss::gemm_plan(V, d, n_sel, ss::EPI_PARTIAL);
     p_lm.ksplit = 1;   // logits are read directly
-    if (n_sel <= 16) p_lm.kd = 8;
     const int ks_qkv = p_qkv.ksplit, ks_o = p_o.ksplit, ks_d = p_d.ksplit;
     const size_t st_qkv = (size_t)n * 3 * d, st_d = (size_t)n * d;
-    auto mk = [](const bf16_t* W, const bf16_t* X, float* out, bf16_t* outp, int N, int Kp, int rows, int kp_out,
-                 const ss::GemmPlan& p) {
+    auto mk = [](const bf16_t* W, const bf16_t* X, const bf16_t* Xlo, float* out, bf16_t* outp, bf16_t* outp_lo, int N,
+                 int Kp, int rows, int kp_out, const ss::GemmPlan& p) {
         GemmArgs g{};
-        g.W = W; g.X = X; g.out = out; g.out_packed = outp; g.N = N; g.Kp = Kp; g.m_rows = rows; g.m_stride = rows;
-        g.kp_out = kp_out; g.ksplit = p.ksplit; g.nb = p.nb; g.kd = p.kd;
+        g.W = W; g.X = X; g.X_lo = Xlo; g.out = out; g.out_packed = outp; g.out_packed_lo = outp_lo; g.N = N; g.Kp = Kp;
+        g.m_rows = rows; g.m_stride = rows; g.kp_out = kp_out; g.ksplit = p.ksplit; g.nb = p.nb; g.kd = p.kd;
         return g;
     };
 
@@ -252,22 +257,24 @@ void forward(ss_weights* w, int n, int n_sel, const int32_t* d_sel, const int32_
         const Layer& L = w->layers[l];
         bf16_t* kc = ws.kv.as<bf16_t>() + (size_t)l * 2 * w->kv_layer_stride;
         bf16_t* vc = kc + w->kv_layer_stride;
-        ss::launch_rmsnorm(st, x, l ? pd : nullptr, ks_d, st_d, L.attn_norm, c.rms_eps, nullptr, nullptr, h, d, n, s);
-        ss::launch_gemm(mk(L.wqkv.p, h, pqkv, nullptr, 3 * d, d, n, 0, p_qkv), ss::EPI_PARTIAL, s);
+        ss::launch_rmsnorm(st, x, l ? pd : nullptr, ks_d, st_d, L.attn_norm, c.rms_eps, nullptr, nullptr, h, h_lo, d, n, s);
+        ss::launch_gemm(mk(L.wqkv.p, h, h_lo, pqkv, nullptr, nullptr, 3 * d, d, n, 0, p_qkv), ss::EPI_PARTIAL, s);
         if (decode) {   // one token-row per row: rotation and append are fused into the attention kernel
-            ss::launch_attention_decode(st, pqkv, ks_qkv, st_qkv, kc, vc, w->rope_cos, w->rope_sin, ao, d, H, hd, n, s);
+            ss::launch_attention_decode(st, pqkv, ks_qkv, st_qkv, kc, vc, w->rope_cos, w->rope_sin, ao, ao_lo, d, H, hd, n,
+                                        s);
         } else {        // prompt: every key of a row must be in place before any of its queries attends
             ss::launch_rope_append(st, pqkv, ks_qkv, st_qkv, qrot, kc, vc, w->rope_cos, w->rope_sin, d, H, hd, n, s);
-            ss::launch_attention(st, qrot, kc, vc, ao, d, H, hd, n, s);
+            ss::launch_attention(st, qrot, kc, vc, ao, ao_lo, d, H, hd, n, s);
         }
-        ss::launch_gemm(mk(L.wo.p, ao, pd, nullptr, d, d, n, 0, p_o), ss::EPI_PARTIAL, s);
-        ss::launch_rmsnorm(st, x, pd, ks_o, st_d, L.mlp_norm, c.rms_eps, nullptr, nullptr, h, d, n, s);
-        ss::launch_gemm(mk(L.wgu.p, h, nullptr, act, 2 * F, d, n, Fp, p_gu), ss::EPI_SWIGLU, s);
-        ss::launch_gemm(mk(L.wd.p, act, pd, nullptr, d, Fp, n, 0, p_d), ss::EPI_PARTIAL, s);
+        ss::launch_gemm(mk(L.wo.p, ao, ao_lo, pd, nullptr, nullptr, d, d, n, 0, p_o), ss::EPI_PARTIAL, s);
+        ss::launch_rmsnorm(st, x, pd, ks_o, st_d, L.mlp_norm, c.rms_eps, nullptr, nullptr, h, h_lo, d, n, s);
+        ss::launch_gemm(mk(L.wgu.p, h, h_lo, nullptr, act, act_lo, 2 * F, d, n, Fp, p_gu), ss::EPI_SWIGLU, s);
+        ss::launch_gemm(mk(L.wd.p, act, act_lo, pd, nullptr, nullptr, d, Fp, n, 0, p_d), ss::EPI_PARTIAL, s);
     }
-    bf16_t* hsel = ws.hsel.as<bf16_t>();
-    ss::launch_rmsnorm(st, x, pd, ks_d, st_d, w->final_norm, c.rms_eps, d_sel, d_nsel, hsel, d, n_sel, s);
-    ss::launch_gemm(mk(w->lm_head.p, hsel, ws.logits.as<float>(), nullptr, V, d, n_sel, 0, p_lm), ss::EPI_PARTIAL, s);
+    bf16_t *hsel = ws.hsel.as<bf16_t>(), *hsel_lo = ws.hsel_lo.as<bf16_t>();
+    ss::launch_rmsnorm(st, x, pd, ks_d, st_d, w->final_norm, c.rms_eps, d_sel, d_nsel, hsel, hsel_lo, d, n_sel, s);
+    ss::launch_gemm(mk(w->lm_head.p, hsel, hsel_lo, ws.logits.as<float>(), nullptr, nullptr, V, d, n_sel, 0, p_lm),
+                    ss::EPI_PARTIAL, s);
     ss::launch_argmax(ws.logits.as<float>(), V, d_nsel ? d_nsel : st.d_n, st.am, n_sel, s);
 }
 
@@ -752,15 +759,15 @@ extern "C" int ss_bench_weight_stream(ss_weights* w, int32_t B, int32_t iters, d
                        p_gu = ss::gemm_plan(2 * F, d, n, ss::EPI_SWIGLU), p_d = ss::gemm_plan(d, Fp, n, ss::EPI_PARTIAL);
     ss::GemmPlan p_lm = ss::gemm_plan(V, d, n, ss::EPI_PARTIAL);
     p_lm.ksplit = 1;
-    if (n <= 16) p_lm.kd = 8;
-    auto mk = [](const bf16_t* W, const bf16_t* X, float* out, bf16_t* outp, int N, int Kp, int rows, int kp_out,
-                 const ss::GemmPlan& p) {
+    auto mk = [](const bf16_t* W, const bf16_t* X, const bf16_t* Xlo, float* out, bf16_t* outp, bf16_t* outp_lo, int N,
+                 int Kp, int rows, int kp_out, const ss::GemmPlan& p) {
         GemmArgs g{};
-        g.W = W; g.X = X; g.out = out; g.out_packed = outp; g.N = N; g.Kp = Kp; g.m_rows = rows; g.m_stride = rows;
-        g.kp_out = kp_out; g.ksplit = p.ksplit; g.nb = p.nb; g.kd = p.kd;
+        g.W = W; g.X = X; g.X_lo = Xlo; g.out = out; g.out_packed = outp; g.out_packed_lo = outp_lo; g.N = N; g.Kp = Kp;
+        g.m_rows = rows; g.m_stride = rows; g.kp_out = kp_out; g.ksplit = p.ksplit; g.nb = p.nb; g.kd = p.kd;
         return g;
     };
     bf16_t *h = ws.h.as<bf16_t>(), *ao = ws.ao.as<bf16_t>(), *act = ws.act.as<bf16_t>();
+    bf16_t *h_lo = ws.h_lo.as<bf16_t>(), *ao_lo = ws.ao_lo.as<bf16_t>(), *act_lo = ws.act_lo.as<bf16_t>();
     float *pqkv = ws.pqkv.as<float>(), *pd = ws.pd.as<float>();
     std::vector<hipEvent_t> ev(iters + 1);
     for (auto& e : ev) HIPCHK(hipEventCreate(&e));
@@ -770,13 +777,14 @@ extern "C" int ss_bench_weight_stream(ss_weights* w, int32_t B, int32_t iters, d
         launches = 0;
         for (int l = 0; l < c.n_layers; ++l) {
             const Layer& L = w->layers[l];
-            ss::launch_gemm(mk(L.wqkv.p, h, pqkv, nullptr, 3 * d, d, n, 0, p_qkv), ss::EPI_PARTIAL, s);
-            ss::launch_gemm(mk(L.wo.p, ao, pd, nullptr, d, d, n, 0, p_o), ss::EPI_PARTIAL, s);
-            ss::launch_gemm(mk(L.wgu.p, h, nullptr, act, 2 * F, d, n, Fp, p_gu), ss::EPI_SWIGLU, s);
-            ss::launch_gemm(mk(L.wd.p, act, pd, nullptr, d, Fp, n, 0, p_d), ss::EPI_PARTIAL, s);
+            ss::launch_gemm(mk(L.wqkv.p, h, h_lo, pqkv, nullptr, nullptr, 3 * d, d, n, 0, p_qkv), ss::EPI_PARTIAL, s);
+            ss::launch_gemm(mk(L.wo.p, ao, ao_lo, pd, nullptr, nullptr, d, d, n, 0, p_o), ss::EPI_PARTIAL, s);
+            ss::launch_gemm(mk(L.wgu.p, h, h_lo, nullptr, act, act_lo, 2 * F, d, n, Fp, p_gu), ss::EPI_SWIGLU, s);
+            ss::launch_gemm(mk(L.wd.p, act, act_lo, pd, nullptr, nullptr, d, Fp, n, 0, p_d), ss::EPI_PARTIAL, s);
             launches += 4;
         }
-        ss::launch_gemm(mk(w->lm_head.p, ws.hsel.as<bf16_t>(), ws.logits.as<float>(), nullptr, V, d, n, 0, p_lm),
+        ss::launch_gemm(mk(w->lm_head.p, ws.hsel.as<bf16_t>(), ws.hsel_lo.as<bf16_t>(), ws.logits.as<float>(), nullptr,
+                           nullptr, V, d, n, 0, p_lm),
                         ss::EPI_PARTIAL, s);
         launches += 1;
         HIPCHK(hipEventRecord(ev[it + 1], s));

@@ -39,9 +39,11 @@ enum Epilogue { EPI_PARTIAL = 0, EPI_SWIGLU = 1 };
 
 struct GemmArgs {
     const bf16_t* W;     // packed [N, Kp]
-    const bf16_t* X;     // packed [rows, Kp]
+    const bf16_t* X;     // packed [rows, Kp], hi part of the activations
+    const bf16_t* X_lo;  // packed [rows, Kp], lo part (activation = hi + lo)
     float* out;          // EPI_PARTIAL: [ksplit][m_stride][N] fp32
-    bf16_t* out_packed;  // EPI_SWIGLU: packed [rows, kp_out], column f = silu(gate_f) * up_f
+    bf16_t* out_packed;  // EPI_SWIGLU: packed [rows, kp_out], column f = silu(gate_f) * up_f (hi part)
+    bf16_t* out_packed_lo;  //          lo part
     int N, Kp, m_rows;   // m_rows: rows to compute (stores are guarded by it)
     int m_stride;        // row stride (in rows) between k-slices of `out`
     int kp_out;          // padded K of out_packed
@@ -54,8 +56,8 @@ void launch_pack_weight(const void* src, int src_f32, bf16_t* dst, int n_src, in
 void launch_cast_rows(const void* src, int src_f32, bf16_t* dst, size_t count, hipStream_t s);
 void launch_embed(const MbState& st, const bf16_t* embed, float* x, int d, int n_max, hipStream_t s);
 void launch_rmsnorm(const MbState& st, float* x, const float* part, int ksplit, size_t part_stride,
-                    const bf16_t* w, float eps, const int32_t* sel, const int32_t* d_nsel, bf16_t* h_packed, int d,
-                    int n_max, hipStream_t s);
+                    const bf16_t* w, float eps, const int32_t* sel, const int32_t* d_nsel, bf16_t* h_packed,
+                    bf16_t* h_packed_lo, int d, int n_max, hipStream_t s);
 void launch_gemm(const GemmArgs& a, int epilogue, hipStream_t s);
 struct GemmPlan {
     int ksplit, nb, kd;
@@ -65,10 +67,10 @@ void launch_rope_append(const MbState& st, const float* qkv_part, int ksplit, si
                         bf16_t* kcache, bf16_t* vcache, const float* rope_cos, const float* rope_sin, int d, int H,
                         int hd, int n_max, hipStream_t s);
 void launch_attention(const MbState& st, const float* qrot, const bf16_t* kcache, const bf16_t* vcache,
-                      bf16_t* out_packed, int d, int H, int hd, int n_max, hipStream_t s);
+                      bf16_t* out_packed, bf16_t* out_packed_lo, int d, int H, int hd, int n_max, hipStream_t s);
 void launch_attention_decode(const MbState& st, const float* qkv_part, int ksplit, size_t part_stride,
                              bf16_t* kcache, bf16_t* vcache, const float* rope_cos, const float* rope_sin,
-                             bf16_t* out_packed, int d, int H, int hd, int n_max, hipStream_t s);
+                             bf16_t* out_packed, bf16_t* out_packed_lo, int d, int H, int hd, int n_max, hipStream_t s);
 void launch_argmax(const float* logits, int vocab, const int32_t* d_nsel, int32_t* am, int n_max, hipStream_t s);
 void launch_step_update(const MbState& st, int compact, hipStream_t s);
 void launch_fill_i32(int32_t* p, int32_t v, size_t n, hipStream_t s);

@@ -27,6 +27,21 @@ __device__ __forceinline__ bf16_t f2bf(float f)
     return (bf16_t)(u >> 16);
 }
 
+// Activations that feed an MFMA are stored as the sum of two bf16 values, hi = bf16(v) and
+// lo = bf16(v - hi): the contraction runs once per part, so products carry ~16 significand bits of the
+// activation while the weights stay plain bf16.  One bf16 rounding per projection input, six per layer
+// over 32+ layers, is otherwise the dominant term of the logit error.
+__device__ __forceinline__ void split_bf(float v, bf16_t& hi, bf16_t& lo)
+{
+    hi = f2bf(v);
+    lo = f2bf(v - bf2f(hi));
+}
+
+// Key/value slots are stored as IEEE half: the same 2 bytes per element as bf16 with three more
+// significand bits; keys and values are projections of RMS-normalised activations, far inside its range.
+__device__ __forceinline__ float kv2f(bf16_t b) { return (float)__builtin_bit_cast(_Float16, b); }
+__device__ __forceinline__ bf16_t f2kv(float f) { return __builtin_bit_cast(bf16_t, (_Float16)f); }
+
 // Element (r, k) of a packed [rows, Kp] matrix.
 __device__ __forceinline__ size_t pk_index(int r, int k, int Kp)
 {
@@ -104,50 +119,61 @@ __global__ __launch_bounds__(256) void k_embed(MbState st, const bf16_t* __restr
 // ------------------------------------------------------------------------------------------ RMSNorm
 // Row j (or sel[j]) of the residual stream: x += sum over k-slices of the previous projection's
 // partial sums (written back when sel is null), then h = x * rsqrt(mean x^2 + eps) * w as packed bf16.
-constexpr int kNormIters = 8;  // d <= 8 * 1024
+// 1024 threads per row, at most two float4 chunks per thread (d <= 8192); the loads of all k-slices of a
+// chunk are issued together (the slice loop is unrolled with a predicate), so a row costs about one
+// memory round trip instead of one per slice.
+constexpr int kNormMaxSplit = 8;
 
-__global__ __launch_bounds__(256) void k_rmsnorm(const int32_t* __restrict__ d_count, float* __restrict__ x,
-                                                 const float* __restrict__ part, int ksplit, size_t part_stride,
-                                                 const bf16_t* __restrict__ w, float eps,
-                                                 const int32_t* __restrict__ sel, bf16_t* __restrict__ h, int d)
+__global__ __launch_bounds__(1024) void k_rmsnorm(const int32_t* __restrict__ d_count, float* __restrict__ x,
+                                                  const float* __restrict__ part, int ksplit, size_t part_stride,
+                                                  const bf16_t* __restrict__ w, float eps,
+                                                  const int32_t* __restrict__ sel, bf16_t* __restrict__ h,
+                                                  bf16_t* __restrict__ h_lo, int d)
 {
     const int j = blockIdx.x;
     if (j >= *d_count) return;
     const int src = sel ? sel[j] : j;
-    float4 v[kNormIters];
+    float4 v[2];
     float ss = 0.f;
 #pragma unroll
-    for (int it = 0; it < kNormIters; ++it) {
-        const int c = threadIdx.x * 4 + it * 1024;
+    for (int it = 0; it < 2; ++it) {
+        const int c = threadIdx.x * 4 + it * 4096;
         if (c < d) {
             float4 a = *(const float4*)(x + (size_t)src * d + c);
-            for (int s = 0; s < ksplit; ++s) {
-                const float4 p = *(const float4*)(part + (size_t)s * part_stride + (size_t)src * d + c);
-                a.x += p.x; a.y += p.y; a.z += p.z; a.w += p.w;
-            }
-            if (part && !sel) *(float4*)(x + (size_t)src * d + c) = a;
+            float4 p[kNormMaxSplit];
+#pragma unroll
+            for (int s = 0; s < kNormMaxSplit; ++s)
+                p[s] = s < ksplit ? *(const float4*)(part + (size_t)s * part_stride + (size_t)src * d + c)
+                                  : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+            for (int s = 0; s < kNormMaxSplit; ++s) { a.x += p[s].x; a.y += p[s].y; a.z += p[s].z; a.w += p[s].w; }
+            if (ksplit > 0 && !sel) *(float4*)(x + (size_t)src * d + c) = a;
             v[it] = a;
             ss += a.x * a.x + a.y * a.y + a.z * a.z + a.w * a.w;
         }
     }
-    __shared__ float red[4];
+    __shared__ float red[16];
     ss = wave_sum(ss);
     if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
     __syncthreads();
-    const float tot = red[0] + red[1] + red[2] + red[3];
+    float tot = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) tot += red[i];
     const float r = rsqrtf(tot / (float)d + eps);
 #pragma unroll
-    for (int it = 0; it < kNormIters; ++it) {
-        const int c = threadIdx.x * 4 + it * 1024;
+    for (int it = 0; it < 2; ++it) {
+        const int c = threadIdx.x * 4 + it * 4096;
         if (c < d) {
             const uint2 wr = *(const uint2*)(w + c);
             const bf16_t* wv = (const bf16_t*)&wr;
-            bf16_t o[4];
-            o[0] = f2bf(v[it].x * r * bf2f(wv[0]));
-            o[1] = f2bf(v[it].y * r * bf2f(wv[1]));
-            o[2] = f2bf(v[it].z * r * bf2f(wv[2]));
-            o[3] = f2bf(v[it].w * r * bf2f(wv[3]));
-            *(uint2*)(h + pk_index(j, c, d)) = *(const uint2*)o;   // d is a multiple of 64: Kp == d
+            bf16_t o[4], ol[4];
+            split_bf(v[it].x * r * bf2f(wv[0]), o[0], ol[0]);
+            split_bf(v[it].y * r * bf2f(wv[1]), o[1], ol[1]);
+            split_bf(v[it].z * r * bf2f(wv[2]), o[2], ol[2]);
+            split_bf(v[it].w * r * bf2f(wv[3]), o[3], ol[3]);
+            const size_t at = pk_index(j, c, d);   // d is a multiple of 64: Kp == d
+            *(uint2*)(h + at) = *(const uint2*)o;
+            *(uint2*)(h_lo + at) = *(const uint2*)ol;
         }
     }
 }
@@ -166,12 +192,13 @@ template <int MT, int NB, int KD>
 struct SkinnyFrags {
     u32x4 w[NB][KD];
     u32x4 x[MT][KD];
+    u32x4 xl[MT][KD];
 };
 
 template <int MT, int NB, int KD>
 __device__ __forceinline__ void skinny_load(SkinnyFrags<MT, NB, KD>& f, const u32x4* __restrict__ Wl,
-                                            const u32x4* __restrict__ Xl, int KB, int nb0, int nvalid, int kb,
-                                            int kend)
+                                            const u32x4* __restrict__ Xl, const u32x4* __restrict__ Xlo, int KB,
+                                            int nb0, int nvalid, int kb, int kend)
 {
 #pragma unroll
     for (int q = 0; q < KD; ++q) {
@@ -182,7 +209,10 @@ __device__ __forceinline__ void skinny_load(SkinnyFrags<MT, NB, KD>& f, const u3
             f.w[i][q] = __builtin_nontemporal_load(Wl + ((size_t)nb * KB + kk) * 64);
         }
 #pragma unroll
-        for (int m = 0; m < MT; ++m) f.x[m][q] = Xl[((size_t)m * KB + kk) * 64];
+        for (int m = 0; m < MT; ++m) {
+            f.x[m][q] = Xl[((size_t)m * KB + kk) * 64];
+            f.xl[m][q] = Xlo[((size_t)m * KB + kk) * 64];
+        }
     }
 }
 
@@ -195,10 +225,14 @@ __device__ __forceinline__ void skinny_mma(const SkinnyFrags<MT, NB, KD>& f, f32
 #pragma unroll
             for (int i = 0; i < NB; ++i)
 #pragma unroll
-                for (int m = 0; m < MT; ++m)
+                for (int m = 0; m < MT; ++m) {
+                    acc[i][m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, f.w[i][q]),
+                                                                        __builtin_bit_cast(bf16x8, f.xl[m][q]),
+                                                                        acc[i][m], 0, 0, 0);
                     acc[i][m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, f.w[i][q]),
                                                                         __builtin_bit_cast(bf16x8, f.x[m][q]),
                                                                         acc[i][m], 0, 0, 0);
+                }
         }
     }
 }
@@ -224,13 +258,14 @@ __global__ __launch_bounds__(256) void k_gemm_skinny(GemmArgs a, int n_groups, i
 
     const u32x4* Wl = (const u32x4*)a.W + lane;
     const u32x4* Xl = (const u32x4*)a.X + lane;
+    const u32x4* Xlo = (const u32x4*)a.X_lo + lane;
     if (kbeg < kend) {
         SkinnyFrags<MT, NB, KD> fa, fb;
-        skinny_load(fa, Wl, Xl, KB, nb0, nvalid, kbeg, kend);
+        skinny_load(fa, Wl, Xl, Xlo, KB, nb0, nvalid, kbeg, kend);
         for (int kb = kbeg; kb < kend; kb += 2 * KD) {
-            if (kb + KD < kend) skinny_load(fb, Wl, Xl, KB, nb0, nvalid, kb + KD, kend);
+            if (kb + KD < kend) skinny_load(fb, Wl, Xl, Xlo, KB, nb0, nvalid, kb + KD, kend);
             skinny_mma(fa, acc, kb, kend);
-            if (kb + 2 * KD < kend) skinny_load(fa, Wl, Xl, KB, nb0, nvalid, kb + 2 * KD, kend);
+            if (kb + 2 * KD < kend) skinny_load(fa, Wl, Xl, Xlo, KB, nb0, nvalid, kb + 2 * KD, kend);
             if (kb + KD < kend) skinny_mma(fb, acc, kb + KD, kend);
         }
     }
@@ -267,113 +302,128 @@ __global__ __launch_bounds__(256) void k_gemm_skinny(GemmArgs a, int n_groups, i
             for (int i = 0; i + 1 < NB; i += 2)
                 if (i + 1 < nvalid) {
                     const int f = ((nb0 + i) >> 1) * 16 + col4;
-                    bf16_t o[4];
+                    bf16_t o[4], ol[4];
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) o[e] = f2bf(silu_f(acc[i][m][e]) * acc[i + 1][m][e]);
-                    *(uint2*)(a.out_packed + pk_index(row, f, a.kp_out)) = *(const uint2*)o;
+                    for (int e = 0; e < 4; ++e) split_bf(silu_f(acc[i][m][e]) * acc[i + 1][m][e], o[e], ol[e]);
+                    const size_t at = pk_index(row, f, a.kp_out);
+                    *(uint2*)(a.out_packed + at) = *(const uint2*)o;
+                    *(uint2*)(a.out_packed_lo + at) = *(const uint2*)ol;
                 }
         }
     }
 }
 
 // ------------------------------------------------------------------------------------------ tiled GEMM
-// 128 token rows x 128 output columns per workgroup, 64 k per trip, both operands staged through LDS in
-// operand order (a wave reads whole 1 KiB blocks, conflict free).  4 waves as 2 (columns) x 2 (rows),
-// each 64 x 64 = 4 x 4 MFMA tiles.  Used for prompt forwards and decode batches above 64 rows.
-template <int EPI>
+// More than 64 token rows (prompt forwards, large variable batches).  A workgroup computes
+// TMS*16 token rows x 256 output columns; wave w owns 4 strips of 16 columns and every row strip.
+// Weights never touch LDS: they are stored in operand order, so each wave loads its own 4 operand
+// blocks per k-block straight into registers (1 KiB coalesced each) and is the only wave of the
+// workgroup that needs them.  The activation tile (hi and lo parts) is shared by the 4 waves and staged
+// through LDS in operand order: a wave reads whole 1 KiB blocks, conflict free.  Two k-blocks per trip,
+// register/LDS double buffering.  LDS read traffic is 1 KiB per 4 MFMAs per wave = half the LDS peak.
+template <int TMS, int EPI>
 __global__ __launch_bounds__(256) void k_gemm_tiled(GemmArgs a, int kb_per_slice)
 {
-    __shared__ uint4 lds[2][2048];  // per stage: W 8 strips x 2 k-blocks x 64 lanes, then X the same
+    __shared__ uint4 lds[2][2 * TMS * 2 * 64];   // [stage][k-block][row strip][hi, lo][lane]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wn = wave & 1, wm = wave >> 1;
     const int KB = a.Kp >> 5, NBT = a.N >> 4;
     const int MBT = (a.m_rows + 15) >> 4;
-    const int nb0 = blockIdx.x * 8, mb0 = blockIdx.y * 8, ks = blockIdx.z;
+    const int nb0 = blockIdx.x * 16 + wave * 4, mb0 = blockIdx.y * TMS, ks = blockIdx.z;
     const int kb0 = ks * kb_per_slice, kb1 = min(KB, kb0 + kb_per_slice);
+    constexpr int XV = 2 * TMS * 2 * 64 / 256;   // uint4 per thread per stage of the activation tile
 
-    f32x4 acc[4][4];
+    f32x4 acc[4][TMS];
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
-        for (int m = 0; m < 4; ++m) acc[i][m] = (f32x4){0.f, 0.f, 0.f, 0.f};
+        for (int m = 0; m < TMS; ++m) acc[i][m] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
-    const uint4* W4 = (const uint4*)a.W;
-    const uint4* X4 = (const uint4*)a.X;
-    uint4 stage[8];
-    auto gload = [&](int kb) {
+    const uint4* W4 = (const uint4*)a.W + lane;
+    const uint4* Xh = (const uint4*)a.X;
+    const uint4* Xl = (const uint4*)a.X_lo;
+    uint4 xs[XV];
+    auto xload = [&](int kb) {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int c = tid + i * 256;            // 0..2047
-            const int isx = c >> 10, cc = c & 1023;
-            const int strip = cc >> 7, within = cc & 127;   // two k-blocks of one strip are contiguous
-            if (!isx) {
-                const int nb = min(nb0 + strip, NBT - 1);
-                stage[i] = W4[((size_t)nb * KB + kb) * 64 + within];
-            } else {
-                const int mb = min(mb0 + strip, MBT - 1);
-                stage[i] = X4[((size_t)mb * KB + kb) * 64 + within];
-            }
+        for (int i = 0; i < XV; ++i) {
+            const int c = tid + i * 256;
+            const int ln = c & 63, hl = (c >> 6) & 1, ms = (c >> 7) % TMS, kk = c / (128 * TMS);
+            const int mb = min(mb0 + ms, MBT - 1);
+            xs[i] = (hl ? Xl : Xh)[((size_t)mb * KB + kb + kk) * 64 + ln];
         }
     };
-    auto lstore = [&](int buf) {
+    auto xstore = [&](int buf) {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) lds[buf][tid + i * 256] = stage[i];
+        for (int i = 0; i < XV; ++i) lds[buf][tid + i * 256] = xs[i];
+    };
+    auto wload = [&](uint4 (&wr)[2][4], int kb) {
+#pragma unroll
+        for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int nb = min(nb0 + i, NBT - 1);
+                wr[kk][i] = W4[((size_t)nb * KB + kb + kk) * 64];
+            }
+    };
+    auto compute = [&](const uint4 (&wr)[2][4], int buf) {
+#pragma unroll
+        for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+            for (int m = 0; m < TMS; ++m) {
+                const uint4 xh = lds[buf][((kk * TMS + m) * 2 + 0) * 64 + lane];
+                const uint4 xl = lds[buf][((kk * TMS + m) * 2 + 1) * 64 + lane];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    acc[i][m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wr[kk][i]),
+                                                                        __builtin_bit_cast(bf16x8, xl), acc[i][m], 0, 0, 0);
+                    acc[i][m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wr[kk][i]),
+                                                                        __builtin_bit_cast(bf16x8, xh), acc[i][m], 0, 0, 0);
+                }
+            }
     };
 
+    uint4 wa[2][4], wb[2][4];
     if (kb0 < kb1) {   // an empty k-slice still writes its zeros below
-        gload(kb0);
-        lstore(0);
+        xload(kb0);
+        wload(wa, kb0);
+        xstore(0);
     }
     __syncthreads();
-    int buf = 0;
-    for (int kb = kb0; kb < kb1; kb += 2) {
-        const bool more = kb + 2 < kb1;
-        if (more) gload(kb + 2);
-#pragma unroll
-        for (int kk = 0; kk < 2; ++kk) {
-            uint4 wf[4], xf[4];
-#pragma unroll
-            for (int i = 0; i < 4; ++i) wf[i] = lds[buf][((wn * 4 + i) * 2 + kk) * 64 + lane];
-#pragma unroll
-            for (int m = 0; m < 4; ++m) xf[m] = lds[buf][1024 + ((wm * 4 + m) * 2 + kk) * 64 + lane];
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int m = 0; m < 4; ++m)
-                    acc[i][m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wf[i]),
-                                                                        __builtin_bit_cast(bf16x8, xf[m]), acc[i][m],
-                                                                        0, 0, 0);
-        }
-        if (more) lstore(buf ^ 1);
+    for (int kb = kb0; kb < kb1; kb += 4) {
+        const bool more1 = kb + 2 < kb1, more2 = kb + 4 < kb1;
+        if (more1) { xload(kb + 2); wload(wb, kb + 2); }
+        compute(wa, 0);
+        if (more1) xstore(1);
         __syncthreads();
-        buf ^= 1;
+        if (!more1) break;
+        if (more2) { xload(kb + 4); wload(wa, kb + 4); }
+        compute(wb, 1);
+        if (more2) xstore(0);
+        __syncthreads();
     }
 
     const int col4 = (lane >> 4) * 4;
 #pragma unroll
-    for (int m = 0; m < 4; ++m) {
-        const int row = (mb0 + wm * 4 + m) * 16 + (lane & 15);
+    for (int m = 0; m < TMS; ++m) {
+        const int row = (mb0 + m) * 16 + (lane & 15);
         if (row >= a.m_rows) continue;
         if (EPI == EPI_PARTIAL) {
             float* o = a.out + ((size_t)ks * a.m_stride + row) * a.N;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int nb = nb0 + wn * 4 + i;
-                if (nb < NBT)
-                    *(float4*)(o + nb * 16 + col4) = make_float4(acc[i][m][0], acc[i][m][1], acc[i][m][2], acc[i][m][3]);
-            }
+            for (int i = 0; i < 4; ++i)
+                if (nb0 + i < NBT)
+                    *(float4*)(o + (nb0 + i) * 16 + col4) = make_float4(acc[i][m][0], acc[i][m][1], acc[i][m][2], acc[i][m][3]);
         } else {
 #pragma unroll
-            for (int i = 0; i < 4; i += 2) {
-                const int nb = nb0 + wn * 4 + i;
-                if (nb + 1 < NBT) {
-                    const int f = (nb >> 1) * 16 + col4;
-                    bf16_t o[4];
+            for (int i = 0; i < 4; i += 2)
+                if (nb0 + i + 1 < NBT) {
+                    const int f = ((nb0 + i) >> 1) * 16 + col4;
+                    bf16_t o[4], ol[4];
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) o[e] = f2bf(silu_f(acc[i][m][e]) * acc[i + 1][m][e]);
-                    *(uint2*)(a.out_packed + pk_index(row, f, a.kp_out)) = *(const uint2*)o;
+                    for (int e = 0; e < 4; ++e) split_bf(silu_f(acc[i][m][e]) * acc[i + 1][m][e], o[e], ol[e]);
+                    const size_t at = pk_index(row, f, a.kp_out);
+                    *(uint2*)(a.out_packed + at) = *(const uint2*)o;
+                    *(uint2*)(a.out_packed_lo + at) = *(const uint2*)ol;
                 }
-            }
         }
     }
 }
@@ -409,10 +459,10 @@ __global__ __launch_bounds__(256) void k_rope_append(MbState st, const float* __
         qrot[(size_t)j * d + c] = q1 * cs - q2 * sn;
         qrot[(size_t)j * d + c + half] = q1 * sn + q2 * cs;
         const size_t o = slab + ((size_t)h * cap + pos) * hd + e;
-        kc[o] = f2bf(k1 * cs - k2 * sn);
-        kc[o + half] = f2bf(k1 * sn + k2 * cs);
-        vc[o] = f2bf(v1);
-        vc[o + half] = f2bf(v2);
+        kc[o] = f2kv(k1 * cs - k2 * sn);
+        kc[o + half] = f2kv(k1 * sn + k2 * cs);
+        vc[o] = f2kv(v1);
+        vc[o + half] = f2kv(v2);
     }
 }
 
@@ -427,8 +477,8 @@ constexpr int kAttnUnroll = 8;
 template <int HD>
 __device__ __forceinline__ void attend(const float* __restrict__ qs, float* __restrict__ sc, float* __restrict__ red,
                                        float (*__restrict__ oacc)[HD], const bf16_t* __restrict__ kbase,
-                                       const bf16_t* __restrict__ vbase, int ctx, bf16_t* __restrict__ out, int out_r,
-                                       int out_k0, int out_kp)
+                                       const bf16_t* __restrict__ vbase, int ctx, bf16_t* __restrict__ out,
+                                       bf16_t* __restrict__ out_lo, int out_r, int out_k0, int out_kp)
 {
     constexpr int LPK = HD / 8;       // lanes per key
     constexpr int KPW = 64 / LPK;     // keys per wave load
@@ -454,7 +504,7 @@ __device__ __forceinline__ void attend(const float* __restrict__ qs, float* __re
             const bf16_t* kv = (const bf16_t*)&raw[u];
             float part = 0.f;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) part += q[e] * bf2f(kv[e]);
+            for (int e = 0; e < 8; ++e) part += q[e] * kv2f(kv[e]);
 #pragma unroll
             for (int m = 1; m < LPK; m <<= 1) part += __shfl_xor(part, m, 64);
             part *= scale;
@@ -493,7 +543,7 @@ __device__ __forceinline__ void attend(const float* __restrict__ qs, float* __re
             const float p = s < ctx ? sc[s] : 0.f;
             const bf16_t* vv = (const bf16_t*)&raw[u];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) o[e] += p * bf2f(vv[e]);
+            for (int e = 0; e < 8; ++e) o[e] += p * kv2f(vv[e]);
         }
     }
 #pragma unroll
@@ -505,13 +555,15 @@ __device__ __forceinline__ void attend(const float* __restrict__ qs, float* __re
         for (int e = 0; e < 8; ++e) oacc[wave][sub * 8 + e] = o[e];
     __syncthreads();
     if (tid < HD / 4) {
-        bf16_t r[4];
+        bf16_t r[4], rl[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             const int c = tid * 4 + e;
-            r[e] = f2bf((oacc[0][c] + oacc[1][c] + oacc[2][c] + oacc[3][c]) * inv);
+            split_bf((oacc[0][c] + oacc[1][c] + oacc[2][c] + oacc[3][c]) * inv, r[e], rl[e]);
         }
-        *(uint2*)(out + pk_index(out_r, out_k0 + tid * 4, out_kp)) = *(const uint2*)r;
+        const size_t at = pk_index(out_r, out_k0 + tid * 4, out_kp);
+        *(uint2*)(out + at) = *(const uint2*)r;
+        *(uint2*)(out_lo + at) = *(const uint2*)rl;
     }
 }
 
@@ -519,7 +571,7 @@ __device__ __forceinline__ void attend(const float* __restrict__ qs, float* __re
 template <int HD>
 __global__ __launch_bounds__(256) void k_attention(MbState st, const float* __restrict__ qrot,
                                                    const bf16_t* __restrict__ kc, const bf16_t* __restrict__ vc,
-                                                   bf16_t* __restrict__ out, int d)
+                                                   bf16_t* __restrict__ out, bf16_t* __restrict__ out_lo, int d)
 {
     __shared__ float sc[kMaxPos];
     __shared__ float red[8];
@@ -531,7 +583,7 @@ __global__ __launch_bounds__(256) void k_attention(MbState st, const float* __re
     const size_t base = (size_t)st.row_so[row] * d + (size_t)h * st.row_cap[row] * HD;
     if (threadIdx.x < HD) qs[threadIdx.x] = qrot[(size_t)j * d + h * HD + threadIdx.x];
     __syncthreads();
-    attend<HD>(qs, sc, red, oacc, kc + base, vc + base, ctx, out, j, h * HD, d);
+    attend<HD>(qs, sc, red, oacc, kc + base, vc + base, ctx, out, out_lo, j, h * HD, d);
 }
 
 // Decode forwards: the (token-row, head) workgroup first finishes its own slice of the q|k|v projection
@@ -542,7 +594,7 @@ __global__ __launch_bounds__(256) void k_attention_decode(MbState st, const floa
                                                           size_t part_stride, bf16_t* __restrict__ kc,
                                                           bf16_t* __restrict__ vc, const float* __restrict__ rcos,
                                                           const float* __restrict__ rsin, bf16_t* __restrict__ out,
-                                                          int d)
+                                                          bf16_t* __restrict__ out_lo, int d)
 {
     __shared__ float sc[kMaxPos];
     __shared__ float red[8];
@@ -572,12 +624,12 @@ __global__ __launch_bounds__(256) void k_attention_decode(MbState st, const floa
             qs[e + HALF] = b;
         } else {
             bf16_t* dst = (which == 1 ? kc : vc) + base + (size_t)pos * HD + e;
-            dst[0] = f2bf(a);
-            dst[HALF] = f2bf(b);
+            dst[0] = f2kv(a);
+            dst[HALF] = f2kv(b);
         }
     }
     __syncthreads();   // the new key/value slot and q are visible to the whole workgroup
-    attend<HD>(qs, sc, red, oacc, kc + base, vc + base, pos + 1, out, j, h * HD, d);
+    attend<HD>(qs, sc, red, oacc, kc + base, vc + base, pos + 1, out, out_lo, j, h * HD, d);
 }
 
 // ------------------------------------------------------------------------------------------ argmax
@@ -690,11 +742,11 @@ void launch_embed(const MbState& st, const bf16_t* embed, float* x, int d, int n
 }
 
 void launch_rmsnorm(const MbState& st, float* x, const float* part, int ksplit, size_t part_stride,
-                    const bf16_t* w, float eps, const int32_t* sel, const int32_t* d_nsel, bf16_t* h_packed, int d,
-                    int n_max, hipStream_t s)
+                    const bf16_t* w, float eps, const int32_t* sel, const int32_t* d_nsel, bf16_t* h_packed,
+                    bf16_t* h_packed_lo, int d, int n_max, hipStream_t s)
 {
-    hipLaunchKernelGGL(k_rmsnorm, dim3(n_max), dim3(256), 0, s, d_nsel ? d_nsel : st.d_n, x, part,
-                       part ? ksplit : 0, part_stride, w, eps, sel, h_packed, d);
+    hipLaunchKernelGGL(k_rmsnorm, dim3(n_max), dim3(1024), 0, s, d_nsel ? d_nsel : st.d_n, x, part,
+                       part ? ksplit : 0, part_stride, w, eps, sel, h_packed, h_packed_lo, d);
 }
 
 // Launch shape of a projection.  Skinny kernel (<= 64 rows): nb = 2 strips per workgroup, kd k-blocks per
@@ -709,15 +761,12 @@ GemmPlan gemm_plan(int N, int Kp, int m_rows, int epilogue)
     if (m_rows <= 64) {
         const int mt = (m_rows + 15) / 16;
         p.kd = mt == 1 ? 4 : (mt == 2 ? 4 : 2);
-        if (epilogue == EPI_SWIGLU) {
-            if (mt == 1) p.kd = 8;
-            return p;
-        }
+        if (epilogue == EPI_SWIGLU) return p;
         while (p.ksplit < 8 && KB / (p.ksplit * 2 * 4) >= 4) p.ksplit *= 2;
         return p;
     }
     if (epilogue == EPI_SWIGLU) return p;
-    const int tiles = ((N + 127) / 128) * ((m_rows + 127) / 128);
+    const int tiles = ((N + 255) / 256) * ((m_rows + 63) / 64);
     while (tiles * p.ksplit < 256 && p.ksplit < 8 && KB / (p.ksplit * 2) >= 16) p.ksplit *= 2;
     return p;
 }
@@ -736,7 +785,6 @@ static void launch_skinny_mt(const GemmArgs& a, hipStream_t s)
 {
     if (a.nb == 2) {
         if (a.kd == 2) launch_skinny_inst<MT, 2, 2, EPI>(a, s);
-        else if (a.kd == 8) launch_skinny_inst<MT, 2, (MT == 1 ? 8 : 4), EPI>(a, s);
         else launch_skinny_inst<MT, 2, 4, EPI>(a, s);
     } else {
         if (a.kd == 2 || MT > 2) launch_skinny_inst<MT, 4, 2, EPI>(a, s);
@@ -760,8 +808,9 @@ static void launch_gemm_epi(const GemmArgs& a, hipStream_t s)
     const int KB = a.Kp / 32;
     int kbs = (KB + a.ksplit - 1) / a.ksplit;
     kbs = (kbs + 1) / 2 * 2;  // whole 64-wide trips
-    dim3 grid((a.N + 127) / 128, (a.m_rows + 127) / 128, a.ksplit);
-    hipLaunchKernelGGL((k_gemm_tiled<EPI>), grid, dim3(256), 0, s, a, kbs);
+    constexpr int TMS = 4;
+    dim3 grid((a.N + 255) / 256, (a.m_rows + TMS * 16 - 1) / (TMS * 16), a.ksplit);
+    hipLaunchKernelGGL((k_gemm_tiled<TMS, EPI>), grid, dim3(256), 0, s, a, kbs);
 }
 
 void launch_gemm(const GemmArgs& a, int epilogue, hipStream_t s)
@@ -782,23 +831,25 @@ void launch_rope_append(const MbState& st, const float* qkv_part, int ksplit, si
 
 void launch_attention_decode(const MbState& st, const float* qkv_part, int ksplit, size_t part_stride,
                              bf16_t* kcache, bf16_t* vcache, const float* rope_cos, const float* rope_sin,
-                             bf16_t* out_packed, int d, int H, int hd, int n_max, hipStream_t s)
+                             bf16_t* out_packed, bf16_t* out_packed_lo, int d, int H, int hd, int n_max, hipStream_t s)
 {
     if (hd == 128)
         hipLaunchKernelGGL((k_attention_decode<128>), dim3(n_max, H), dim3(256), 0, s, st, qkv_part, ksplit,
-                           part_stride, kcache, vcache, rope_cos, rope_sin, out_packed, d);
+                           part_stride, kcache, vcache, rope_cos, rope_sin, out_packed, out_packed_lo, d);
     else
         hipLaunchKernelGGL((k_attention_decode<64>), dim3(n_max, H), dim3(256), 0, s, st, qkv_part, ksplit,
-                           part_stride, kcache, vcache, rope_cos, rope_sin, out_packed, d);
+                           part_stride, kcache, vcache, rope_cos, rope_sin, out_packed, out_packed_lo, d);
 }
 
 void launch_attention(const MbState& st, const float* qrot, const bf16_t* kcache, const bf16_t* vcache,
-                      bf16_t* out_packed, int d, int H, int hd, int n_max, hipStream_t s)
+                      bf16_t* out_packed, bf16_t* out_packed_lo, int d, int H, int hd, int n_max, hipStream_t s)
 {
     if (hd == 128)
-        hipLaunchKernelGGL((k_attention<128>), dim3(n_max, H), dim3(256), 0, s, st, qrot, kcache, vcache, out_packed, d);
+        hipLaunchKernelGGL((k_attention<128>), dim3(n_max, H), dim3(256), 0, s, st, qrot, kcache, vcache, out_packed,
+                           out_packed_lo, d);
     else
-        hipLaunchKernelGGL((k_attention<64>), dim3(n_max, H), dim3(256), 0, s, st, qrot, kcache, vcache, out_packed, d);
+        hipLaunchKernelGGL((k_attention<64>), dim3(n_max, H), dim3(256), 0, s, st, qrot, kcache, vcache, out_packed,
+                           out_packed_lo, d);
 }
 
 void launch_argmax(const float* logits, int vocab, const int32_t* d_nsel, int32_t* am, int n_max, hipStream_t s)

@@ -1,0 +1,137 @@
+"""GPU parity at the configured sizes: full-depth LLaMA-7B shape (configs 2-4), 13B widths (config 5),
+the variable-batch-size row counts (up to 256 rows), and the whole scheduled group in the launch
+configuration bench.py times.  The oracle cannot run a whole 7B group in reasonable time, so whole-group
+results are checked by exact integer properties plus sampled outputs the oracle computes one by one
+(teacher-forced on the GPU's own prefix; see test_gpu_parity.py for the bars)."""
+import numpy as np
+import pytest
+
+from paper_2305_13144_amd import binding as ss
+from paper_2305_13144_amd import synth
+from oracle import sched_oracle as so
+from oracle.model_oracle import OracleModel
+
+from test_gpu_parity import (check_logits, check_tokens_teacher_forced, forced_batch, oracle_forced_logits, _say)
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def full7b(oracle_built):
+    shape = synth.LLAMA7B
+    _say("generating full-depth 7B weights (seed 2)")
+    W = synth.make_weights(shape, seed=2, threads=16)
+    gw = ss.Weights(shape, W)
+    yield shape, W, OracleModel(shape, W, "f64"), gw
+    gw.close()
+
+
+@pytest.fixture(scope="module")
+def wide13(oracle_built):
+    shape = synth.LLAMA13B.with_layers(2)
+    W = synth.make_weights(shape, seed=5, norm_jitter=0.05, threads=16)
+    gw = ss.Weights(shape, W)
+    yield shape, W, OracleModel(shape, W, "f64"), gw
+    gw.close()
+
+
+def test_7b_full_depth_logits_teacher_forced(full7b):
+    """32 layers: the logit error bar at the depth the benchmark runs at, prompt forward and decode steps."""
+    shape, W, om, gw = full7b
+    w = synth.make_workload(3)
+    rng = np.random.default_rng(21)
+    rows, extra = [3, 10, 17], [4, 0, 6]
+    toks, offs, npr = forced_batch(w, rows, extra, rng)
+    _say(f"7B x32 teacher-forced: prompts {npr.tolist()} + forced {extra}")
+    got = ss.ss_forward_logits(gw, toks, offs, npr)
+    ref = oracle_forced_logits(om, toks, offs, npr)
+    check_logits(got, ref, "7B full depth")
+
+
+def test_7b_config3_first_microbatches(full7b):
+    """The first and a later micro-batch of config 3's plan, generated on the GPU; sampled rows re-derived by
+    the oracle token by token."""
+    shape, W, om, gw = full7b
+    w = synth.make_workload(3)
+    pol = ss.make_policy(w.flags, w.base_batch, w.l_max, w.max_batch)
+    plan = ss.ss_schedule(w.pred_lens, w.n, w.bin_width, pol)
+    for k in (0, 5):
+        idx, cap = plan[k]
+        toks, offs = synth.gather_prompts(w, idx)
+        t = w.target_lens[idx]
+        _say(f"config 3 micro-batch {k}: {len(idx)} rows, cap {cap}")
+        r = ss.ss_decode_microbatch(gw, toks, offs, cap, t, 0)
+        assert np.array_equal(r["lens"], np.minimum(t, cap))
+        assert np.array_equal(r["failed"].astype(bool), t > cap)
+        assert r["stats"]["steps"] == min(cap, int(t.max()))
+        for j in (0, len(idx) - 1):
+            L = int(r["lens"][j])
+            assert (r["tokens"][j, :L] >= 0).all() and (r["tokens"][j, L:] == -1).all()
+            dcd, tot = check_tokens_teacher_forced(om, w.prompt(idx[j]), r["tokens"][j, :L], upto=5, what=f"mb {k} row {j}")
+            _say(f"  row {j}: {dcd}/{tot} decided positions match")
+
+
+def test_7b_whole_group_config3_as_benchmarked(full7b):
+    """ss_run_group on the full config-3 group, exactly what bench.py times."""
+    shape, W, om, gw = full7b
+    w = synth.make_workload(3)
+    pol = ss.make_policy(w.flags, w.base_batch, w.l_max, w.max_batch)
+    _say("7B whole group, config 3 (about half a minute on the GPU)")
+    r = ss.ss_run_group(gw, w.prompt_tokens, w.prompt_offsets, w.target_lens, w.pred_lens, w.bin_width, pol)
+    ref = so.run_group(w.pred_lens, w.target_lens, w.bin_width,
+                       so.Policy(flags=w.flags, base_batch=w.base_batch, l_max=w.l_max, max_batch=w.max_batch))
+    s = r["stats"]
+    assert np.array_equal(r["lens"], w.target_lens)                       # every query emitted once, in full
+    assert s["steps"] == ref["steps"] and s["padded_row_steps"] == ref["padded_row_steps"]
+    assert s["n_failed"] == ref["n_failed"] and s["useful_tokens"] == ref["useful_tokens"] == int(w.target_lens.sum())
+    assert (s["n_mb_first"], s["n_mb_failure"]) == (ref["first"].n_mb, ref["second"].n_mb)
+    for i in range(w.n):
+        t = int(w.target_lens[i])
+        assert (r["tokens"][i, :t] >= 0).all() and (r["tokens"][i, :t] < shape.vocab).all()
+        assert (r["tokens"][i, t:] == -1).all()
+    failed = set(ref["first"].failed)
+    ok = next(i for i in range(w.n) if i not in failed and w.target_lens[i] >= 4)
+    redo = sorted(failed)[0]                                               # a query that went through recomputation
+    for i in (ok, redo):
+        dcd, tot = check_tokens_teacher_forced(om, w.prompt(i), r["tokens"][i, :int(w.target_lens[i])], upto=4,
+                                               what=f"query {i}")
+        _say(f"  query {i}: {dcd}/{tot} decided positions match")
+
+
+def test_13b_widths_logits_and_vbs_batch(wide13):
+    """Config 5's widths (d 5120, 40 heads, ffn 13824) at 2 layers: logits, then a 256-row micro-batch
+    (its largest variable batch size) with compaction, sampled rows against the oracle."""
+    shape, W, om, gw = wide13
+    w = synth.make_workload(5, n=256, shape=shape)
+    rng = np.random.default_rng(22)
+    toks, offs, npr = forced_batch(w, [0, 1, 2], [2, 5, 0], rng)
+    got = ss.ss_forward_logits(gw, toks, offs, npr)
+    check_logits(got, oracle_forced_logits(om, toks, offs, npr), "13B widths")
+    cap = 6
+    t = np.minimum(w.target_lens, 9)
+    _say("13B widths: 256-row micro-batch, cap 6, compaction on")
+    r = ss.ss_decode_microbatch(gw, w.prompt_tokens, w.prompt_offsets, cap, t, ss.SS_COMPACT)
+    assert np.array_equal(r["lens"], np.minimum(t, cap)) and np.array_equal(r["failed"].astype(bool), t > cap)
+    assert r["stats"]["row_steps"] == int(np.minimum(t, cap).sum())
+    for j in (0, 100, 255):
+        check_tokens_teacher_forced(om, w.prompt(j), r["tokens"][j, :int(r["lens"][j])], what=f"row {j}")
+
+
+@pytest.mark.parametrize("rows", [163, 81, 54])
+def test_7b_widths_variable_batch_sizes(rows, oracle_built):
+    """Config 4's batch sizes for the 50/100/150-token bins at 7B widths (2 layers), compaction on and off."""
+    shape = synth.LLAMA7B.with_layers(2)
+    W = synth.make_weights(shape, seed=2, norm_jitter=0.05, threads=16)
+    gw = ss.Weights(shape, W)
+    om = OracleModel(shape, W, "f64")
+    try:
+        w = synth.make_workload(4, n=rows, shape=shape)
+        t = np.minimum(w.target_lens, 7)
+        for flags in (0, ss.SS_COMPACT):
+            _say(f"7B widths: {rows}-row micro-batch flags={flags}")
+            r = ss.ss_decode_microbatch(gw, w.prompt_tokens, w.prompt_offsets, 5, t, flags)
+            assert np.array_equal(r["lens"], np.minimum(t, 5))
+            for j in (0, rows // 2, rows - 1):
+                check_tokens_teacher_forced(om, w.prompt(j), r["tokens"][j, :int(r["lens"][j])], what=f"row {j}")
+    finally:
+        gw.close()
