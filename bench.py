@@ -114,14 +114,30 @@ def main() -> int:
         extras["scheduled_over_vanilla"] = (useful / (st["wall_ms"] / 1e3)) / extras["vanilla_batching"]["useful_tokens_per_s"]
         log(f"vanilla: {sv['wall_ms']:.0f} ms -> ratio {extras['scheduled_over_vanilla']:.3f}")
 
+    if a.roofline_only:
+        # calibration for the HBM byte counters: a plain device-to-device copy of known size (1 GiB read,
+        # 1 GiB written) shows up in the same trace as a copyBuffer dispatch
+        size = 1 << 30
+        src, dst = ctypes.c_void_p(), ctypes.c_void_p()
+        assert hip.hipMalloc(ctypes.byref(src), ctypes.c_size_t(size)) == 0
+        assert hip.hipMalloc(ctypes.byref(dst), ctypes.c_size_t(size)) == 0
+        assert hip.hipMemset(src, 1, ctypes.c_size_t(size)) == 0
+        assert hip.hipMemcpy(dst, src, ctypes.c_size_t(size), 3) == 0     # hipMemcpyDeviceToDevice
+        assert hip.hipDeviceSynchronize() == 0
+        hip.hipFree(src)
+        hip.hipFree(dst)
+
     # ---- roofline: the weight-streaming projection kernel, timed live with HIP events --------------
     B0, ctx = 16, 200
     ms_w, launches = ss.ss_bench_weight_stream(gw, B0, a.step_iters + 3)
     ms_w = ms_w[3:]
     wbytes = shape.weight_bytes_per_step() - (2 * shape.n_layers + 1) * shape.d_model * 2   # matrices only
     ach = wbytes / (ms_w.mean() * 1e-3) / 1e9
+    # HBM bytes per launch from the FETCH_SIZE + WRITE_SIZE counter runs of this same command (7B shape only;
+    # the figures and the copy-kernel scale factors are in profiles/decode_step_7b_hbm_traffic.txt)
+    traffic = (13619.1e6 + 32 * (3.15e6 + 2.10e6 + 0.70e6 + 1.05e6) + 2.05e6) / 129 if shape.name == "llama7b" else None
     roofline = dict(bound="hbm", kernel="k_gemm_skinny (all projection launches of one 16-row decode step)",
-                    achieved=ach, peak=HBM_PEAK_GBS, unit="GB/s", frac=ach / HBM_PEAK_GBS, traffic=None,
+                    achieved=ach, peak=HBM_PEAK_GBS, unit="GB/s", frac=ach / HBM_PEAK_GBS, traffic=traffic,
                     launches_per_step=launches, avg_launch_us=ms_w.mean() * 1e3 / launches,
                     bytes_per_launch=wbytes / launches)
     rng = np.random.default_rng(7)

@@ -749,20 +749,22 @@ void launch_rmsnorm(const MbState& st, float* x, const float* part, int ksplit, 
                        part ? ksplit : 0, part_stride, w, eps, sel, h_packed, h_packed_lo, d);
 }
 
-// Launch shape of a projection.  Skinny kernel (<= 64 rows): nb = 2 strips per workgroup, kd k-blocks per
-// register buffer (8 when one strip of rows leaves the registers for it), ksplit outer k-slices whose
-// partial sums the consumer adds.  Measured on the 7B shapes the chip wants thousands of small
-// workgroups: as many k-slices (up to 8) as leave every wave at least 4 k-blocks.  Tiled kernel: ksplit
-// fills the chip when there are few 128x128 tiles.
+// Launch shape of a projection.  Skinny kernel (<= 64 rows), from sweeps on the 7B shapes: aim at 512+
+// workgroups; 4 strips per workgroup halve the activation re-reads and win when k is short, 2 strips when
+// k is long or when the epilogue forbids k-slices (SwiGLU, logits); k-slices double until there are 512
+// workgroups, at most 8, never leaving a wave fewer than 4 k-blocks.  Tiled kernel: ksplit fills the chip
+// when there are few 64x256 tiles.
 GemmPlan gemm_plan(int N, int Kp, int m_rows, int epilogue)
 {
     GemmPlan p{1, 2, 4};
     const int KB = Kp / 32;
     if (m_rows <= 64) {
         const int mt = (m_rows + 15) / 16;
-        p.kd = mt == 1 ? 4 : (mt == 2 ? 4 : 2);
+        p.kd = mt <= 2 ? 4 : 2;
         if (epilogue == EPI_SWIGLU) return p;
-        while (p.ksplit < 8 && KB / (p.ksplit * 2 * 4) >= 4) p.ksplit *= 2;
+        p.nb = KB > 256 ? 2 : 4;
+        const int groups = (N / 16 + p.nb - 1) / p.nb;
+        while (groups * p.ksplit < 512 && p.ksplit < 8 && KB / (p.ksplit * 2 * 4) >= 4) p.ksplit *= 2;
         return p;
     }
     if (epilogue == EPI_SWIGLU) return p;
