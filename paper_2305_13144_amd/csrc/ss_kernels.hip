@@ -319,18 +319,28 @@ __global__ __launch_bounds__(256) void k_gemm_skinny(GemmArgs a, int n_groups, i
 // Weights never touch LDS: they are stored in operand order, so each wave loads its own 4 operand
 // blocks per k-block straight into registers (1 KiB coalesced each) and is the only wave of the
 // workgroup that needs them.  The activation tile (hi and lo parts) is shared by the 4 waves and staged
-// through LDS in operand order: a wave reads whole 1 KiB blocks, conflict free.  Two k-blocks per trip,
-// register/LDS double buffering.  LDS read traffic is 1 KiB per 4 MFMAs per wave = half the LDS peak.
+// through LDS in operand order (conflict-free 1 KiB reads).  One k-block per trip; both streams run
+// D k-blocks ahead of the MFMAs in a register ring, so with two workgroups per CU about 100 KiB are in
+// flight per CU, enough to keep HBM busy when the weights are streamed once for a decode batch.
+// Workgroup ids are mapped so that the row tiles of one column tile follow each other at a stride of 8:
+// they land on the same XCD (ids are dealt round-robin over the 8 XCDs) at about the same time and share
+// that column tile's weights through its L2.
 template <int TMS, int EPI>
-__global__ __launch_bounds__(256) void k_gemm_tiled(GemmArgs a, int kb_per_slice)
+__global__ __launch_bounds__(256, 2) void k_gemm_tiled(GemmArgs a, int kb_per_slice, int n_ntiles, int n_mtiles)
 {
-    __shared__ uint4 lds[2][2 * TMS * 2 * 64];   // [stage][k-block][row strip][hi, lo][lane]
+    constexpr int D = 4;                        // k-blocks in flight
+    constexpr int XV = TMS * 2 * 64 / 256;      // 16-byte vectors per thread: one k-block of the activation tile, hi + lo
+    __shared__ u32x4 lds[2][TMS * 2 * 64];      // [stage][row strip][hi, lo][lane]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int KB = a.Kp >> 5, NBT = a.N >> 4;
     const int MBT = (a.m_rows + 15) >> 4;
-    const int nb0 = blockIdx.x * 16 + wave * 4, mb0 = blockIdx.y * TMS, ks = blockIdx.z;
+    const int per_slice = ((n_ntiles + 7) >> 3) * 8 * n_mtiles;
+    const int ks = blockIdx.x / per_slice, r = blockIdx.x % per_slice;
+    const int chunk = r / (8 * n_mtiles), within = r % (8 * n_mtiles);
+    const int n_tile = chunk * 8 + (within & 7), m_tile = within >> 3;
+    if (n_tile >= n_ntiles) return;
+    const int nb0 = n_tile * 16 + wave * 4, mb0 = m_tile * TMS;
     const int kb0 = ks * kb_per_slice, kb1 = min(KB, kb0 + kb_per_slice);
-    constexpr int XV = 2 * TMS * 2 * 64 / 256;   // uint4 per thread per stage of the activation tile
 
     f32x4 acc[4][TMS];
 #pragma unroll
@@ -338,68 +348,69 @@ __global__ __launch_bounds__(256) void k_gemm_tiled(GemmArgs a, int kb_per_slice
 #pragma unroll
         for (int m = 0; m < TMS; ++m) acc[i][m] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
-    const uint4* W4 = (const uint4*)a.W + lane;
-    const uint4* Xh = (const uint4*)a.X;
-    const uint4* Xl = (const uint4*)a.X_lo;
-    uint4 xs[XV];
-    auto xload = [&](int kb) {
-#pragma unroll
-        for (int i = 0; i < XV; ++i) {
-            const int c = tid + i * 256;
-            const int ln = c & 63, hl = (c >> 6) & 1, ms = (c >> 7) % TMS, kk = c / (128 * TMS);
-            const int mb = min(mb0 + ms, MBT - 1);
-            xs[i] = (hl ? Xl : Xh)[((size_t)mb * KB + kb + kk) * 64 + ln];
-        }
-    };
-    auto xstore = [&](int buf) {
-#pragma unroll
-        for (int i = 0; i < XV; ++i) lds[buf][tid + i * 256] = xs[i];
-    };
-    auto wload = [&](uint4 (&wr)[2][4], int kb) {
-#pragma unroll
-        for (int kk = 0; kk < 2; ++kk)
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int nb = min(nb0 + i, NBT - 1);
-                wr[kk][i] = W4[((size_t)nb * KB + kb + kk) * 64];
-            }
-    };
-    auto compute = [&](const uint4 (&wr)[2][4], int buf) {
-#pragma unroll
-        for (int kk = 0; kk < 2; ++kk)
-#pragma unroll
-            for (int m = 0; m < TMS; ++m) {
-                const uint4 xh = lds[buf][((kk * TMS + m) * 2 + 0) * 64 + lane];
-                const uint4 xl = lds[buf][((kk * TMS + m) * 2 + 1) * 64 + lane];
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    acc[i][m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wr[kk][i]),
-                                                                        __builtin_bit_cast(bf16x8, xl), acc[i][m], 0, 0, 0);
-                    acc[i][m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wr[kk][i]),
-                                                                        __builtin_bit_cast(bf16x8, xh), acc[i][m], 0, 0, 0);
-                }
-            }
-    };
+    const u32x4* W4 = (const u32x4*)a.W + lane;
+    const u32x4* Xh = (const u32x4*)a.X;
+    const u32x4* Xl = (const u32x4*)a.X_lo;
+    // Ring slots are separately named arrays indexed only by unrolled constants, so that they stay in
+    // registers (a ring indexed through a reference parameter ends up in scratch memory, and every
+    // scratch access waits for all outstanding loads).
+    u32x4 w0[4], w1[4], w2[4], w3[4], x0[XV], x1[XV], x2[XV], x3[XV];
+    static_assert(D == 4, "the ring below is written out for 4 slots");
+#define SS_WLOAD(W_, KB_)                                                                       \
+    _Pragma("unroll") for (int i_ = 0; i_ < 4; ++i_)                                            \
+        W_[i_] = W4[((size_t)min(nb0 + i_, NBT - 1) * KB + (KB_)) * 64];
+#define SS_XLOAD(X_, KB_)                                                                       \
+    _Pragma("unroll") for (int i_ = 0; i_ < XV; ++i_) {                                         \
+        const int c_ = tid + i_ * 256;                                                          \
+        const int ln_ = c_ & 63, hl_ = (c_ >> 6) & 1, ms_ = c_ >> 7;                            \
+        X_[i_] = (hl_ ? Xl : Xh)[((size_t)min(mb0 + ms_, MBT - 1) * KB + (KB_)) * 64 + ln_];    \
+    }
+#define SS_XSTORE(STAGE_, X_)                                                                   \
+    _Pragma("unroll") for (int i_ = 0; i_ < XV; ++i_) lds[STAGE_][tid + i_ * 256] = X_[i_];
+#define SS_COMPUTE(W_, STAGE_)                                                                  \
+    _Pragma("unroll") for (int m_ = 0; m_ < TMS; ++m_) {                                        \
+        const u32x4 xh_ = lds[STAGE_][(m_ * 2 + 0) * 64 + lane];                                \
+        const u32x4 xl_ = lds[STAGE_][(m_ * 2 + 1) * 64 + lane];                                \
+        _Pragma("unroll") for (int i_ = 0; i_ < 4; ++i_) {                                      \
+            acc[i_][m_] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(                              \
+                __builtin_bit_cast(bf16x8, W_[i_]), __builtin_bit_cast(bf16x8, xl_), acc[i_][m_], 0, 0, 0); \
+            acc[i_][m_] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(                              \
+                __builtin_bit_cast(bf16x8, W_[i_]), __builtin_bit_cast(bf16x8, xh_), acc[i_][m_], 0, 0, 0); \
+        }                                                                                       \
+    }
+    // One trip: k-block t from ring slot (WC_, XC_); the next k-block's tile (XN_) goes into the other LDS
+    // stage first; afterwards the slot is refilled D k-blocks ahead.
+#define SS_TRIP(P_, WC_, XC_, XN_)                                                              \
+    {                                                                                           \
+        const int t_ = kb + P_;                                                                 \
+        if (t_ < kb1) {                                                                         \
+            if (t_ + 1 < kb1) { SS_XSTORE((P_ + 1) & 1, XN_) }                                  \
+            SS_COMPUTE(WC_, P_ & 1)                                                             \
+            if (t_ + D < kb1) { SS_WLOAD(WC_, t_ + D) SS_XLOAD(XC_, t_ + D) }                   \
+            __syncthreads();                                                                    \
+        }                                                                                       \
+    }
 
-    uint4 wa[2][4], wb[2][4];
     if (kb0 < kb1) {   // an empty k-slice still writes its zeros below
-        xload(kb0);
-        wload(wa, kb0);
-        xstore(0);
+        const int last = kb1 - 1;   // beyond the slice: a harmless re-read, never consumed
+        SS_WLOAD(w0, kb0) SS_XLOAD(x0, kb0)
+        SS_WLOAD(w1, min(kb0 + 1, last)) SS_XLOAD(x1, min(kb0 + 1, last))
+        SS_WLOAD(w2, min(kb0 + 2, last)) SS_XLOAD(x2, min(kb0 + 2, last))
+        SS_WLOAD(w3, min(kb0 + 3, last)) SS_XLOAD(x3, min(kb0 + 3, last))
+        SS_XSTORE(0, x0)
     }
     __syncthreads();
-    for (int kb = kb0; kb < kb1; kb += 4) {
-        const bool more1 = kb + 2 < kb1, more2 = kb + 4 < kb1;
-        if (more1) { xload(kb + 2); wload(wb, kb + 2); }
-        compute(wa, 0);
-        if (more1) xstore(1);
-        __syncthreads();
-        if (!more1) break;
-        if (more2) { xload(kb + 4); wload(wa, kb + 4); }
-        compute(wb, 1);
-        if (more2) xstore(0);
-        __syncthreads();
+    for (int kb = kb0; kb < kb1; kb += D) {
+        SS_TRIP(0, w0, x0, x1)
+        SS_TRIP(1, w1, x1, x2)
+        SS_TRIP(2, w2, x2, x3)
+        SS_TRIP(3, w3, x3, x0)
     }
+#undef SS_WLOAD
+#undef SS_XLOAD
+#undef SS_XSTORE
+#undef SS_COMPUTE
+#undef SS_TRIP
 
     const int col4 = (lane >> 4) * 4;
 #pragma unroll
@@ -808,11 +819,11 @@ static void launch_gemm_epi(const GemmArgs& a, hipStream_t s)
         return;
     }
     const int KB = a.Kp / 32;
-    int kbs = (KB + a.ksplit - 1) / a.ksplit;
-    kbs = (kbs + 1) / 2 * 2;  // whole 64-wide trips
+    const int kbs = (KB + a.ksplit - 1) / a.ksplit;
     constexpr int TMS = 4;
-    dim3 grid((a.N + 255) / 256, (a.m_rows + TMS * 16 - 1) / (TMS * 16), a.ksplit);
-    hipLaunchKernelGGL((k_gemm_tiled<TMS, EPI>), grid, dim3(256), 0, s, a, kbs);
+    const int n_ntiles = (a.N + 255) / 256, n_mtiles = (a.m_rows + TMS * 16 - 1) / (TMS * 16);
+    const int grid = (n_ntiles + 7) / 8 * 8 * n_mtiles * a.ksplit;
+    hipLaunchKernelGGL((k_gemm_tiled<TMS, EPI>), dim3(grid), dim3(256), 0, s, a, kbs, n_ntiles, n_mtiles);
 }
 
 void launch_gemm(const GemmArgs& a, int epilogue, hipStream_t s)
