@@ -68,10 +68,10 @@ struct Buf {
 };
 
 struct Workspace {
-    Buf x, h, h_lo, ao, ao_lo, act, act_lo, qrot, pqkv, pd, hsel, hsel_lo, logits, kv, ints, i64s;
+    Buf x, h, h_lo, ao, ao_lo, act, act_lo, qrot, pqkv, pd, pgu, hsel, hsel_lo, logits, kv, ints, i64s;
     void release()
     {
-        for (Buf* b : {&x, &h, &h_lo, &ao, &ao_lo, &act, &act_lo, &qrot, &pqkv, &pd, &hsel, &hsel_lo, &logits, &kv,
+        for (Buf* b : {&x, &h, &h_lo, &ao, &ao_lo, &act, &act_lo, &qrot, &pqkv, &pd, &pgu, &hsel, &hsel_lo, &logits, &kv,
                        &ints, &i64s})
             b->release();
     }
@@ -191,6 +191,8 @@ int ensure_workspace(ss_weights* w, int n_max, int B, int n_sel, size_t slots, i
     if ((rc = ws.qrot.ensure(nr * d * 4, false))) return rc;
     if ((rc = ws.pqkv.ensure(ks_rows * 3 * d * 4, false))) return rc;
     if ((rc = ws.pd.ensure(ks_rows * d * 4, false))) return rc;
+    // gate|up partial sums exist only for decode-sized batches run with k-slices
+    if ((rc = ws.pgu.ensure((size_t)8 * std::min(n_max, 1024) * 2 * F * 4, false))) return rc;
     if ((rc = ws.hsel.ensure((size_t)ss::round_up(n_sel, 128) * d * 2, true))) return rc;
     if ((rc = ws.hsel_lo.ensure((size_t)ss::round_up(n_sel, 128) * d * 2, true))) return rc;
     if ((rc = ws.logits.ensure((size_t)ss::round_up(n_sel, 16) * V * 4, false))) return rc;
@@ -250,6 +252,7 @@ void forward(ss_weights* w, int n, int n_sel, const int32_t* d_sel, const int32_
         GemmArgs g{};
         g.W = W; g.X = X; g.X_lo = Xlo; g.out = out; g.out_packed = outp; g.out_packed_lo = outp_lo; g.N = N; g.Kp = Kp;
         g.m_rows = rows; g.m_stride = rows; g.kp_out = kp_out; g.ksplit = p.ksplit; g.nb = p.nb; g.kd = p.kd;
+        g.kp = p.kp;
         return g;
     };
 
@@ -269,7 +272,13 @@ void forward(ss_weights* w, int n, int n_sel, const int32_t* d_sel, const int32_
         }
         ss::launch_gemm(mk(L.wo.p, ao, ao_lo, pd, nullptr, nullptr, d, d, n, 0, p_o), ss::EPI_PARTIAL, s);
         ss::launch_rmsnorm(st, x, pd, ks_o, st_d, L.mlp_norm, c.rms_eps, nullptr, nullptr, h, h_lo, d, n, s);
-        ss::launch_gemm(mk(L.wgu.p, h, h_lo, nullptr, act, act_lo, 2 * F, d, n, Fp, p_gu), ss::EPI_SWIGLU, s);
+        if (p_gu.ksplit == 1) {
+            ss::launch_gemm(mk(L.wgu.p, h, h_lo, nullptr, act, act_lo, 2 * F, d, n, Fp, p_gu), ss::EPI_SWIGLU, s);
+        } else {   // k-sliced: partial sums, then one small kernel adds them and applies SwiGLU
+            ss::launch_gemm(mk(L.wgu.p, h, h_lo, ws.pgu.as<float>(), nullptr, nullptr, 2 * F, d, n, 0, p_gu),
+                            ss::EPI_PARTIAL, s);
+            ss::launch_swiglu_reduce(ws.pgu.as<float>(), p_gu.ksplit, (size_t)n * 2 * F, n, F, Fp, act, act_lo, s);
+        }
         ss::launch_gemm(mk(L.wd.p, act, act_lo, pd, nullptr, nullptr, d, Fp, n, 0, p_d), ss::EPI_PARTIAL, s);
     }
     bf16_t *hsel = ws.hsel.as<bf16_t>(), *hsel_lo = ws.hsel_lo.as<bf16_t>();
@@ -766,6 +775,7 @@ extern "C" int ss_bench_weight_stream(ss_weights* w, int32_t B, int32_t iters, d
         GemmArgs g{};
         g.W = W; g.X = X; g.X_lo = Xlo; g.out = out; g.out_packed = outp; g.out_packed_lo = outp_lo; g.N = N; g.Kp = Kp;
         g.m_rows = rows; g.m_stride = rows; g.kp_out = kp_out; g.ksplit = p.ksplit; g.nb = p.nb; g.kd = p.kd;
+        g.kp = p.kp;
         return g;
     };
     bf16_t *h = ws.h.as<bf16_t>(), *ao = ws.ao.as<bf16_t>(), *act = ws.act.as<bf16_t>();
@@ -781,7 +791,11 @@ extern "C" int ss_bench_weight_stream(ss_weights* w, int32_t B, int32_t iters, d
             const Layer& L = w->layers[l];
             ss::launch_gemm(mk(L.wqkv.p, h, h_lo, pqkv, nullptr, nullptr, 3 * d, d, n, 0, p_qkv), ss::EPI_PARTIAL, s);
             ss::launch_gemm(mk(L.wo.p, ao, ao_lo, pd, nullptr, nullptr, d, d, n, 0, p_o), ss::EPI_PARTIAL, s);
-            ss::launch_gemm(mk(L.wgu.p, h, h_lo, nullptr, act, act_lo, 2 * F, d, n, Fp, p_gu), ss::EPI_SWIGLU, s);
+            if (p_gu.ksplit == 1)
+                ss::launch_gemm(mk(L.wgu.p, h, h_lo, nullptr, act, act_lo, 2 * F, d, n, Fp, p_gu), ss::EPI_SWIGLU, s);
+            else
+                ss::launch_gemm(mk(L.wgu.p, h, h_lo, ws.pgu.as<float>(), nullptr, nullptr, 2 * F, d, n, 0, p_gu),
+                                ss::EPI_PARTIAL, s);
             ss::launch_gemm(mk(L.wd.p, act, act_lo, pd, nullptr, nullptr, d, Fp, n, 0, p_d), ss::EPI_PARTIAL, s);
             launches += 4;
         }

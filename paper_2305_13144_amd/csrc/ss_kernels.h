@@ -49,6 +49,7 @@ struct GemmArgs {
     int kp_out;          // padded K of out_packed
     int ksplit;          // outer k-slices (gemm_plan)
     int nb, kd;          // skinny kernel shape (gemm_plan)
+    int kp;              // tiled kernel: k-parts inside the workgroup (gemm_plan)
 };
 
 void launch_pack_weight(const void* src, int src_f32, bf16_t* dst, int n_src, int k, int kp, int blk_stride,
@@ -60,9 +61,11 @@ void launch_rmsnorm(const MbState& st, float* x, const float* part, int ksplit, 
                     bf16_t* h_packed_lo, int d, int n_max, hipStream_t s);
 void launch_gemm(const GemmArgs& a, int epilogue, hipStream_t s);
 struct GemmPlan {
-    int ksplit, nb, kd;
+    int ksplit, nb, kd, kp;
 };
 GemmPlan gemm_plan(int N, int Kp, int m_rows, int epilogue);
+void launch_swiglu_reduce(const float* part, int ksplit, size_t part_stride, int m_rows, int F, int kp_out,
+                          bf16_t* out, bf16_t* out_lo, hipStream_t s);
 void launch_rope_append(const MbState& st, const float* qkv_part, int ksplit, size_t part_stride, float* qrot,
                         bf16_t* kcache, bf16_t* vcache, const float* rope_cos, const float* rope_sin, int d, int H,
                         int hd, int n_max, hipStream_t s);

@@ -195,6 +195,8 @@ struct SkinnyFrags {
     u32x4 xl[MT][KD];
 };
 
+// Loads for k-blocks kb..kb+KD-1; k-blocks at or beyond kend are clamped re-reads whose activation
+// operands are zeroed in skinny_mma, so they add 0.
 template <int MT, int NB, int KD>
 __device__ __forceinline__ void skinny_load(SkinnyFrags<MT, NB, KD>& f, const u32x4* __restrict__ Wl,
                                             const u32x4* __restrict__ Xl, const u32x4* __restrict__ Xlo, int KB,
@@ -202,7 +204,7 @@ __device__ __forceinline__ void skinny_load(SkinnyFrags<MT, NB, KD>& f, const u3
 {
 #pragma unroll
     for (int q = 0; q < KD; ++q) {
-        const int kk = min(kb + q, kend - 1);   // tail: clamped re-read, the result is not used
+        const int kk = min(kb + q, kend - 1);
 #pragma unroll
         for (int i = 0; i < NB; ++i) {
             const int nb = nb0 + (i < nvalid ? i : 0);
@@ -219,20 +221,20 @@ __device__ __forceinline__ void skinny_load(SkinnyFrags<MT, NB, KD>& f, const u3
 template <int MT, int NB, int KD>
 __device__ __forceinline__ void skinny_mma(const SkinnyFrags<MT, NB, KD>& f, f32x4 (&acc)[NB][MT], int kb, int kend)
 {
+    const u32x4 zero = {0u, 0u, 0u, 0u};
 #pragma unroll
     for (int q = 0; q < KD; ++q) {
-        if (kb + q < kend) {
+        const bool live = kb + q < kend;
 #pragma unroll
-            for (int i = 0; i < NB; ++i)
+        for (int m = 0; m < MT; ++m) {
+            const u32x4 xh = live ? f.x[m][q] : zero, xl = live ? f.xl[m][q] : zero;
 #pragma unroll
-                for (int m = 0; m < MT; ++m) {
-                    acc[i][m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, f.w[i][q]),
-                                                                        __builtin_bit_cast(bf16x8, f.xl[m][q]),
-                                                                        acc[i][m], 0, 0, 0);
-                    acc[i][m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, f.w[i][q]),
-                                                                        __builtin_bit_cast(bf16x8, f.x[m][q]),
-                                                                        acc[i][m], 0, 0, 0);
-                }
+            for (int i = 0; i < NB; ++i) {
+                acc[i][m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, f.w[i][q]),
+                                                                    __builtin_bit_cast(bf16x8, xl), acc[i][m], 0, 0, 0);
+                acc[i][m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, f.w[i][q]),
+                                                                    __builtin_bit_cast(bf16x8, xh), acc[i][m], 0, 0, 0);
+            }
         }
     }
 }
@@ -262,6 +264,9 @@ __global__ __launch_bounds__(256) void k_gemm_skinny(GemmArgs a, int n_groups, i
     if (kbeg < kend) {
         SkinnyFrags<MT, NB, KD> fa, fb;
         skinny_load(fa, Wl, Xl, Xlo, KB, nb0, nvalid, kbeg, kend);
+        // Loads past the wave's k-range are skipped rather than clamped: measured, the wasted re-reads of an
+        // unconditional tail cost more (k-ranges are only 4-40 blocks) than the conservative load-counter waits
+        // the branches cause; latency is hidden by the 12-20 resident waves per CU, not inside a wave.
         for (int kb = kbeg; kb < kend; kb += 2 * KD) {
             if (kb + KD < kend) skinny_load(fb, Wl, Xl, Xlo, KB, nb0, nvalid, kb + KD, kend);
             skinny_mma(fa, acc, kb, kend);
@@ -325,13 +330,19 @@ __global__ __launch_bounds__(256) void k_gemm_skinny(GemmArgs a, int n_groups, i
 // Workgroup ids are mapped so that the row tiles of one column tile follow each other at a stride of 8:
 // they land on the same XCD (ids are dealt round-robin over the 8 XCDs) at about the same time and share
 // that column tile's weights through its L2.
-template <int TMS, int EPI>
-__global__ __launch_bounds__(256, 2) void k_gemm_tiled(GemmArgs a, int kb_per_slice, int n_ntiles, int n_mtiles)
+// With KP = 2 the workgroup has 8 waves: two groups of 4 take the two halves of the k-slice (each with its
+// own LDS stages) and the second group hands its accumulators to the first through LDS at the end.  Used
+// when there are too few tiles to give every CU two workgroups: it doubles the waves per CU and halves
+// the serial k loop without sending partial sums through HBM.
+template <int TMS, int KP, int EPI>
+__global__ __launch_bounds__(256 * KP, 2) void k_gemm_tiled(GemmArgs a, int kb_per_slice, int n_ntiles, int n_mtiles)
 {
     constexpr int D = 4;                        // k-blocks in flight
     constexpr int XV = TMS * 2 * 64 / 256;      // 16-byte vectors per thread: one k-block of the activation tile, hi + lo
-    __shared__ u32x4 lds[2][TMS * 2 * 64];      // [stage][row strip][hi, lo][lane]
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    __shared__ u32x4 lds_all[KP][2][TMS * 2 * 64];            // [k-part][stage][row strip][hi, lo][lane]
+    __shared__ f32x4 red[KP > 1 ? 4 * TMS : 1][KP > 1 ? 256 : 1];
+    const int part = threadIdx.x >> 8, tid = threadIdx.x & 255, lane = tid & 63, wave = tid >> 6;
+    u32x4 (*lds)[TMS * 2 * 64] = lds_all[part];
     const int KB = a.Kp >> 5, NBT = a.N >> 4;
     const int MBT = (a.m_rows + 15) >> 4;
     const int per_slice = ((n_ntiles + 7) >> 3) * 8 * n_mtiles;
@@ -340,7 +351,9 @@ __global__ __launch_bounds__(256, 2) void k_gemm_tiled(GemmArgs a, int kb_per_sl
     const int n_tile = chunk * 8 + (within & 7), m_tile = within >> 3;
     if (n_tile >= n_ntiles) return;
     const int nb0 = n_tile * 16 + wave * 4, mb0 = m_tile * TMS;
-    const int kb0 = ks * kb_per_slice, kb1 = min(KB, kb0 + kb_per_slice);
+    const int s0 = ks * kb_per_slice, s1 = min(KB, s0 + kb_per_slice);
+    const int part_len = (max(s1 - s0, 0) + KP - 1) / KP;      // trips every wave of the workgroup runs
+    const int kb0 = min(s1, s0 + part * part_len), kb1 = min(s1, kb0 + part_len);
 
     f32x4 acc[4][TMS];
 #pragma unroll
@@ -351,9 +364,9 @@ __global__ __launch_bounds__(256, 2) void k_gemm_tiled(GemmArgs a, int kb_per_sl
     const u32x4* W4 = (const u32x4*)a.W + lane;
     const u32x4* Xh = (const u32x4*)a.X;
     const u32x4* Xl = (const u32x4*)a.X_lo;
-    // Ring slots are separately named arrays indexed only by unrolled constants, so that they stay in
-    // registers (a ring indexed through a reference parameter ends up in scratch memory, and every
-    // scratch access waits for all outstanding loads).
+    // Ring slots are separately named arrays of native vectors indexed only by unrolled constants, so
+    // that they stay in registers (a ring that ends up in scratch memory makes every access wait for all
+    // outstanding loads).
     u32x4 w0[4], w1[4], w2[4], w3[4], x0[XV], x1[XV], x2[XV], x3[XV];
     static_assert(D == 4, "the ring below is written out for 4 slots");
 #define SS_WLOAD(W_, KB_)                                                                       \
@@ -365,8 +378,8 @@ __global__ __launch_bounds__(256, 2) void k_gemm_tiled(GemmArgs a, int kb_per_sl
         const int ln_ = c_ & 63, hl_ = (c_ >> 6) & 1, ms_ = c_ >> 7;                            \
         X_[i_] = (hl_ ? Xl : Xh)[((size_t)min(mb0 + ms_, MBT - 1) * KB + (KB_)) * 64 + ln_];    \
     }
-#define SS_XSTORE(STAGE_, X_)                                                                   \
-    _Pragma("unroll") for (int i_ = 0; i_ < XV; ++i_) lds[STAGE_][tid + i_ * 256] = X_[i_];
+#define SS_XSTORE(STAGE_, X_, LIVE_)                                                            \
+    _Pragma("unroll") for (int i_ = 0; i_ < XV; ++i_) lds[STAGE_][tid + i_ * 256] = (LIVE_) ? X_[i_] : zero4;
 #define SS_COMPUTE(W_, STAGE_)                                                                  \
     _Pragma("unroll") for (int m_ = 0; m_ < TMS; ++m_) {                                        \
         const u32x4 xh_ = lds[STAGE_][(m_ * 2 + 0) * 64 + lane];                                \
@@ -379,28 +392,28 @@ __global__ __launch_bounds__(256, 2) void k_gemm_tiled(GemmArgs a, int kb_per_sl
         }                                                                                       \
     }
     // One trip: k-block t from ring slot (WC_, XC_); the next k-block's tile (XN_) goes into the other LDS
-    // stage first; afterwards the slot is refilled D k-blocks ahead.
+    // stage first; afterwards the slot is refilled D k-blocks ahead.  Nothing in a trip is conditional: the
+    // compiler counts outstanding loads statically, and a load issued under a branch makes it wait for every
+    // load in flight at the next use.  K-blocks at or beyond kb1 are clamped re-reads whose activation tile
+    // is stored as zeros, so they add 0; every wave of the workgroup runs the same number of trips.
 #define SS_TRIP(P_, WC_, XC_, XN_)                                                              \
     {                                                                                           \
-        const int t_ = kb + P_;                                                                 \
-        if (t_ < kb1) {                                                                         \
-            if (t_ + 1 < kb1) { SS_XSTORE((P_ + 1) & 1, XN_) }                                  \
-            SS_COMPUTE(WC_, P_ & 1)                                                             \
-            if (t_ + D < kb1) { SS_WLOAD(WC_, t_ + D) SS_XLOAD(XC_, t_ + D) }                   \
-            __syncthreads();                                                                    \
-        }                                                                                       \
+        const int t_ = kb0 + it + P_;                                                           \
+        SS_XSTORE((P_ + 1) & 1, XN_, t_ + 1 < kb1)                                              \
+        SS_COMPUTE(WC_, P_ & 1)                                                                 \
+        SS_WLOAD(WC_, min(t_ + D, last)) SS_XLOAD(XC_, min(t_ + D, last))                       \
+        __syncthreads();                                                                        \
     }
 
-    if (kb0 < kb1) {   // an empty k-slice still writes its zeros below
-        const int last = kb1 - 1;   // beyond the slice: a harmless re-read, never consumed
-        SS_WLOAD(w0, kb0) SS_XLOAD(x0, kb0)
-        SS_WLOAD(w1, min(kb0 + 1, last)) SS_XLOAD(x1, min(kb0 + 1, last))
-        SS_WLOAD(w2, min(kb0 + 2, last)) SS_XLOAD(x2, min(kb0 + 2, last))
-        SS_WLOAD(w3, min(kb0 + 3, last)) SS_XLOAD(x3, min(kb0 + 3, last))
-        SS_XSTORE(0, x0)
-    }
+    const u32x4 zero4 = {0u, 0u, 0u, 0u};
+    const int last = max(min(kb1, KB) - 1, 0);   // beyond the range: a harmless in-bounds re-read
+    SS_WLOAD(w0, min(kb0, last)) SS_XLOAD(x0, min(kb0, last))
+    SS_WLOAD(w1, min(kb0 + 1, last)) SS_XLOAD(x1, min(kb0 + 1, last))
+    SS_WLOAD(w2, min(kb0 + 2, last)) SS_XLOAD(x2, min(kb0 + 2, last))
+    SS_WLOAD(w3, min(kb0 + 3, last)) SS_XLOAD(x3, min(kb0 + 3, last))
+    SS_XSTORE(0, x0, kb0 < kb1)
     __syncthreads();
-    for (int kb = kb0; kb < kb1; kb += D) {
+    for (int it = 0; it < part_len; it += D) {
         SS_TRIP(0, w0, x0, x1)
         SS_TRIP(1, w1, x1, x2)
         SS_TRIP(2, w2, x2, x3)
@@ -411,6 +424,21 @@ __global__ __launch_bounds__(256, 2) void k_gemm_tiled(GemmArgs a, int kb_per_sl
 #undef SS_XSTORE
 #undef SS_COMPUTE
 #undef SS_TRIP
+
+    if (KP > 1) {
+        if (part == 1) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int m = 0; m < TMS; ++m) red[i * TMS + m][tid] = acc[i][m];
+        }
+        __syncthreads();
+        if (part == 1) return;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int m = 0; m < TMS; ++m) acc[i][m] += red[i * TMS + m][tid];
+    }
 
     const int col4 = (lane >> 4) * 4;
 #pragma unroll
@@ -437,6 +465,34 @@ __global__ __launch_bounds__(256, 2) void k_gemm_tiled(GemmArgs a, int kb_per_sl
                 }
         }
     }
+}
+
+// SwiGLU over k-sliced partial sums: the gate|up projection was run with k-slices (its output columns are
+// in strip order: strip 2j = gate columns 16j.., strip 2j+1 = the matching up columns); this adds the
+// slices and writes silu(gate)*up as hi/lo packed activations.  One thread per 4 MLP columns of a row.
+__global__ __launch_bounds__(256) void k_swiglu_reduce(const float* __restrict__ part, int ksplit, size_t part_stride,
+                                                       int m_rows, int F, int kp_out, bf16_t* __restrict__ out,
+                                                       bf16_t* __restrict__ out_lo)
+{
+    const int row = blockIdx.y;
+    const int f = (blockIdx.x * 256 + threadIdx.x) * 4;
+    if (row >= m_rows || f >= F) return;
+    const size_t g_at = (size_t)row * 2 * F + (size_t)(f >> 4) * 32 + (f & 15);
+    float4 g = make_float4(0.f, 0.f, 0.f, 0.f), u = g;
+    for (int s = 0; s < ksplit; ++s) {
+        const float4 a = *(const float4*)(part + (size_t)s * part_stride + g_at);
+        const float4 b = *(const float4*)(part + (size_t)s * part_stride + g_at + 16);
+        g.x += a.x; g.y += a.y; g.z += a.z; g.w += a.w;
+        u.x += b.x; u.y += b.y; u.z += b.z; u.w += b.w;
+    }
+    bf16_t o[4], ol[4];
+    split_bf(silu_f(g.x) * u.x, o[0], ol[0]);
+    split_bf(silu_f(g.y) * u.y, o[1], ol[1]);
+    split_bf(silu_f(g.z) * u.z, o[2], ol[2]);
+    split_bf(silu_f(g.w) * u.w, o[3], ol[3]);
+    const size_t at = pk_index(row, f, kp_out);
+    *(uint2*)(out + at) = *(const uint2*)o;
+    *(uint2*)(out_lo + at) = *(const uint2*)ol;
 }
 
 // ------------------------------------------------------------------------------------------ RoPE + KV append
@@ -767,21 +823,33 @@ void launch_rmsnorm(const MbState& st, float* x, const float* part, int ksplit, 
 // when there are few 64x256 tiles.
 GemmPlan gemm_plan(int N, int Kp, int m_rows, int epilogue)
 {
-    GemmPlan p{1, 2, 4};
+    GemmPlan p{1, 2, 4, 1};
     const int KB = Kp / 32;
     if (m_rows <= 64) {
         const int mt = (m_rows + 15) / 16;
         p.kd = mt <= 2 ? 4 : 2;
-        if (epilogue == EPI_SWIGLU) return p;
+        if (epilogue == EPI_SWIGLU) return p;   // fused epilogue: no k-slices
         p.nb = KB > 256 ? 2 : 4;
         const int groups = (N / 16 + p.nb - 1) / p.nb;
         while (groups * p.ksplit < 512 && p.ksplit < 8 && KB / (p.ksplit * 2 * 4) >= 4) p.ksplit *= 2;
         return p;
     }
-    if (epilogue == EPI_SWIGLU) return p;
+    // Tiled kernel.  Many tiles (prompt forwards): 4-wave workgroups, two per CU, no slicing.  Few tiles
+    // (decode batches of 65-256 rows): measured on the 7B shapes, outer k-slices up to 4 (partial sums
+    // through HBM are small while rows are few) beat everything else; where slicing is impossible an
+    // 8-wave workgroup halves the k range inside the workgroup instead.
     const int tiles = ((N + 255) / 256) * ((m_rows + 63) / 64);
-    while (tiles * p.ksplit < 256 && p.ksplit < 8 && KB / (p.ksplit * 2) >= 16) p.ksplit *= 2;
+    if (tiles >= 512) return p;
+    while (tiles * p.ksplit < 512 && p.ksplit < 4 && KB / (p.ksplit * 2) >= 16) p.ksplit *= 2;
+    if (p.ksplit == 1) p.kp = 2;
     return p;
+}
+
+void launch_swiglu_reduce(const float* part, int ksplit, size_t part_stride, int m_rows, int F, int kp_out,
+                          bf16_t* out, bf16_t* out_lo, hipStream_t s)
+{
+    hipLaunchKernelGGL(k_swiglu_reduce, dim3((F / 4 + 255) / 256, m_rows), dim3(256), 0, s, part, ksplit, part_stride,
+                       m_rows, F, kp_out, out, out_lo);
 }
 
 template <int MT, int NB, int KD, int EPI>
@@ -823,7 +891,10 @@ static void launch_gemm_epi(const GemmArgs& a, hipStream_t s)
     constexpr int TMS = 4;
     const int n_ntiles = (a.N + 255) / 256, n_mtiles = (a.m_rows + TMS * 16 - 1) / (TMS * 16);
     const int grid = (n_ntiles + 7) / 8 * 8 * n_mtiles * a.ksplit;
-    hipLaunchKernelGGL((k_gemm_tiled<TMS, EPI>), dim3(grid), dim3(256), 0, s, a, kbs, n_ntiles, n_mtiles);
+    if (a.kp == 2)
+        hipLaunchKernelGGL((k_gemm_tiled<TMS, 2, EPI>), dim3(grid), dim3(512), 0, s, a, kbs, n_ntiles, n_mtiles);
+    else
+        hipLaunchKernelGGL((k_gemm_tiled<TMS, 1, EPI>), dim3(grid), dim3(256), 0, s, a, kbs, n_ntiles, n_mtiles);
 }
 
 void launch_gemm(const GemmArgs& a, int epilogue, hipStream_t s)
