@@ -244,7 +244,7 @@ void forward(ss_weights* w, int n, int n_sel, const int32_t* d_sel, const int32_
                        p_gu = ss::gemm_plan(2 * F, d, n, ss::EPI_SWIGLU), p_d = ss::gemm_plan(d, Fp, n, ss::EPI_PARTIAL);
     ss::GemmPlan p_lm = ss::gemm_plan(V, d, n_sel, ss::EPI_PARTIAL);
     p_lm.ksplit = 1;   // logits are read directly
-    p_lm.nb = 2;
+    if (n_sel <= 16) p_lm.nb = 2;
     const int ks_qkv = p_qkv.ksplit, ks_o = p_o.ksplit, ks_d = p_d.ksplit;
     const size_t st_qkv = (size_t)n * 3 * d, st_d = (size_t)n * d;
     auto mk = [](const bf16_t* W, const bf16_t* X, const bf16_t* Xlo, float* out, bf16_t* outp, bf16_t* outp_lo, int N,
@@ -769,7 +769,7 @@ extern "C" int ss_bench_weight_stream(ss_weights* w, int32_t B, int32_t iters, d
                        p_gu = ss::gemm_plan(2 * F, d, n, ss::EPI_SWIGLU), p_d = ss::gemm_plan(d, Fp, n, ss::EPI_PARTIAL);
     ss::GemmPlan p_lm = ss::gemm_plan(V, d, n, ss::EPI_PARTIAL);
     p_lm.ksplit = 1;
-    p_lm.nb = 2;
+    if (n <= 16) p_lm.nb = 2;
     auto mk = [](const bf16_t* W, const bf16_t* X, const bf16_t* Xlo, float* out, bf16_t* outp, bf16_t* outp_lo, int N,
                  int Kp, int rows, int kp_out, const ss::GemmPlan& p) {
         GemmArgs g{};

@@ -581,6 +581,13 @@ __device__ __forceinline__ void attend(const float* __restrict__ qs, float* __re
             }
         }
     }
+    // the first chunk of V does not depend on the scores: get it moving before the reductions
+    uint4 vraw[AU];
+#pragma unroll
+    for (int u = 0; u < AU; ++u) {
+        const int s = wave * KPW + u * 4 * KPW + kin;
+        vraw[u] = s < ctx ? *(const uint4*)(vbase + (size_t)s * HD + sub * 8) : make_uint4(0, 0, 0, 0);
+    }
     mx = wave_max(mx);
     if (lane == 0) red[wave] = mx;
     __syncthreads();
@@ -602,7 +609,10 @@ __device__ __forceinline__ void attend(const float* __restrict__ qs, float* __re
 #pragma unroll
         for (int u = 0; u < AU; ++u) {
             const int s = c0 + u * 4 * KPW + kin;
-            raw[u] = s < ctx ? *(const uint4*)(vbase + (size_t)s * HD + sub * 8) : make_uint4(0, 0, 0, 0);
+            if (c0 == wave * KPW)
+                raw[u] = vraw[u];
+            else
+                raw[u] = s < ctx ? *(const uint4*)(vbase + (size_t)s * HD + sub * 8) : make_uint4(0, 0, 0, 0);
         }
 #pragma unroll
         for (int u = 0; u < AU; ++u) {
@@ -675,10 +685,17 @@ __global__ __launch_bounds__(256) void k_attention_decode(MbState st, const floa
     const int which = threadIdx.x / HALF, e = threadIdx.x % HALF;   // 0 q, 1 k, 2 v
     if (which < 3) {
         const float* p = part + (size_t)j * 3 * d + (size_t)which * d + h * HD + e;
+        float pa[kNormMaxSplit], pb[kNormMaxSplit];   // every k-slice load issued before the first add
+#pragma unroll
+        for (int s = 0; s < kNormMaxSplit; ++s) {
+            pa[s] = s < ksplit ? p[(size_t)s * part_stride] : 0.f;
+            pb[s] = s < ksplit ? p[(size_t)s * part_stride + HALF] : 0.f;
+        }
         float a = 0.f, b = 0.f;
-        for (int s = 0; s < ksplit; ++s) {
-            a += p[(size_t)s * part_stride];
-            b += p[(size_t)s * part_stride + HALF];
+#pragma unroll
+        for (int s = 0; s < kNormMaxSplit; ++s) {
+            a += pa[s];
+            b += pb[s];
         }
         if (which < 2) {
             const float cs = rcos[(size_t)pos * HALF + e], sn = rsin[(size_t)pos * HALF + e];
@@ -827,9 +844,9 @@ GemmPlan gemm_plan(int N, int Kp, int m_rows, int epilogue)
     const int KB = Kp / 32;
     if (m_rows <= 64) {
         const int mt = (m_rows + 15) / 16;
-        p.kd = mt <= 2 ? 4 : 2;
+        p.kd = mt == 1 ? 4 : 2;
         if (epilogue == EPI_SWIGLU) return p;   // fused epilogue: no k-slices
-        p.nb = KB > 256 ? 2 : 4;
+        p.nb = (mt == 1 && KB > 256) ? 2 : 4;   // with several row strips the activation re-reads dominate: 4 strips
         const int groups = (N / 16 + p.nb - 1) / p.nb;
         while (groups * p.ksplit < 512 && p.ksplit < 8 && KB / (p.ksplit * 2 * 4) >= 4) p.ksplit *= 2;
         return p;
