@@ -37,6 +37,44 @@ def decode_step_bytes(shape, B: int, ctx: int) -> int:
     return shape.weight_bytes_per_step() + B * (ctx + 1) * kv + B * kv + B * shape.d_model * 2
 
 
+def ablation(a, ss, gw, wl, shape) -> int:
+    """Table 5 of the paper on the synthetic group: which component buys what on this hardware.
+    Every row is one pass over the same queries with the same predictions (multiplicative lognormal noise,
+    sigma 0.3); 'perfect' uses the true length as the prediction (the paper's upper-bound row of Table 4)."""
+    rows = [("vanilla", (), False), ("sort", ("SORT",), False), ("sort+FCR", ("SORT", "FCR"), False),
+            ("sort+FCR+VBS", ("SORT", "FCR", "VBS"), False), ("binning", ("SORT", "BIN"), False),
+            ("binning+FCR", ("SORT", "BIN", "FCR"), False), ("binning+FCR+VBS", ("SORT", "BIN", "FCR", "VBS"), False),
+            ("binning+FCR+VBS+compaction", ("SORT", "BIN", "FCR", "VBS", "COMPACT"), False),
+            ("binning+FCR+VBS, perfect predictor", ("SORT", "BIN", "FCR", "VBS"), True)]
+    pred = wl.pred_lens
+    if pred is None:   # config 2 carries no predictions: draw config 3's (same group)
+        from paper_2305_13144_amd import synth
+        pred = synth.make_workload(3).pred_lens
+    binw = wl.bin_width or 50
+    useful = int(wl.target_lens.sum())
+    from paper_2305_13144_amd import synth as _synth
+    wt, wo = _synth.gather_prompts(wl, range(min(wl.n, wl.max_batch)))                  # warm-up: workspace growth
+    ss.ss_decode_microbatch(gw, wt, wo, 4, np.full(len(wo) - 1, 4, np.int32), 0)
+    base = None
+    for name, flags, perfect in rows:
+        pol = ss.make_policy(flags, wl.base_batch, wl.l_max, wl.max_batch)
+        p = None if not flags else (wl.target_lens if perfect else pred)
+        r = ss.ss_run_group(gw, wl.prompt_tokens, wl.prompt_offsets, wl.target_lens, p, binw if "BIN" in flags else 0, pol)
+        assert np.array_equal(r["lens"], wl.target_lens)
+        st = r["stats"]
+        tps = useful / (st["wall_ms"] / 1e3)
+        base = base or tps
+        log(f"ablation row '{name}': {st['wall_ms'] / 1e3:.1f} s, {tps:.0f} tok/s")
+        print(json.dumps(dict(ablation=name, group=wl.n, model=shape.name, useful_tokens_per_s=tps,
+                              samples_per_s=wl.n / (st["wall_ms"] / 1e3), vs_vanilla=tps / base, ms=st["wall_ms"],
+                              steps=st["steps"], micro_batches=[st["n_mb_first"], st["n_mb_failure"]],
+                              n_failed=st["n_failed"], padded_row_steps=st["padded_row_steps"],
+                              computed_row_steps=st["computed_row_steps"],
+                              avg_len=st["padded_row_steps"] / (wl.n + st["n_failed"]))), flush=True)
+    gw.close()
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -47,6 +85,9 @@ def main() -> int:
     ap.add_argument("--no-vanilla", action="store_true", help="skip the vanilla-batching comparison run")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--step-iters", type=int, default=20, help="decode-step timing iterations")
+    ap.add_argument("--ablation", action="store_true",
+                    help="instead of the headline run: the paper's Table 5 ablation (Binning x FCR x VBS), a perfect "
+                         "predictor and compaction on the same group, one pass each; prints one JSON line per row")
     ap.add_argument("--roofline-only", action="store_true",
                     help="only the roofline legs (weight-stream kernels and one decode step); the command profiled "
                          "under rocprofv3 for profiles/")
@@ -74,6 +115,9 @@ def main() -> int:
 
     def run(policy, pred, binw):
         return ss.ss_run_group(gw, wl.prompt_tokens, wl.prompt_offsets, wl.target_lens, pred, binw, policy)
+
+    if a.ablation:
+        return ablation(a, ss, gw, wl, shape)
 
     # ---- timed region: W warmup passes, then exactly K passes over the group ----------------------
     if a.roofline_only:

@@ -718,20 +718,30 @@ __global__ __launch_bounds__(256) void k_attention_decode(MbState st, const floa
 
 // ------------------------------------------------------------------------------------------ argmax
 // Greedy choice per selected row: index of the largest logit, lowest index on exact ties.
-__global__ __launch_bounds__(256) void k_argmax(const float* __restrict__ logits, int vocab,
-                                                const int32_t* __restrict__ d_count, int32_t* __restrict__ am)
+// 1024 threads per row, all of a thread's loads issued before the first compare.
+__global__ __launch_bounds__(1024) void k_argmax(const float* __restrict__ logits, int vocab,
+                                                 const int32_t* __restrict__ d_count, int32_t* __restrict__ am)
 {
     const int j = blockIdx.x;
     if (j >= *d_count) return;
     const float* lg = logits + (size_t)j * vocab;
     float best = -3.4e38f;
     int bi = 0x7fffffff;
-    for (int c = threadIdx.x * 4; c < vocab; c += 1024) {
-        const float4 v = *(const float4*)(lg + c);
-        const float vv[4] = {v.x, v.y, v.z, v.w};
+    for (int c0 = threadIdx.x * 4; c0 < vocab; c0 += 4096 * 4) {
+        float4 v[4];
 #pragma unroll
-        for (int e = 0; e < 4; ++e)
-            if (vv[e] > best || (vv[e] == best && c + e < bi)) { best = vv[e]; bi = c + e; }
+        for (int u = 0; u < 4; ++u) {
+            const int c = c0 + u * 4096;
+            v[u] = c < vocab ? *(const float4*)(lg + c) : make_float4(-3.4e38f, -3.4e38f, -3.4e38f, -3.4e38f);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int c = c0 + u * 4096;
+            const float vv[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (c < vocab && (vv[e] > best || (vv[e] == best && c + e < bi))) { best = vv[e]; bi = c + e; }
+        }
     }
 #pragma unroll
     for (int m = 32; m >= 1; m >>= 1) {
@@ -739,12 +749,12 @@ __global__ __launch_bounds__(256) void k_argmax(const float* __restrict__ logits
         const int oi = __shfl_xor(bi, m, 64);
         if (ob > best || (ob == best && oi < bi)) { best = ob; bi = oi; }
     }
-    __shared__ float sb[4];
-    __shared__ int si[4];
+    __shared__ float sb[16];
+    __shared__ int si[16];
     if ((threadIdx.x & 63) == 0) { sb[threadIdx.x >> 6] = best; si[threadIdx.x >> 6] = bi; }
     __syncthreads();
     if (threadIdx.x == 0) {
-        for (int w = 1; w < 4; ++w)
+        for (int w = 1; w < 16; ++w)
             if (sb[w] > best || (sb[w] == best && si[w] < bi)) { best = sb[w]; bi = si[w]; }
         am[j] = bi;
     }
@@ -955,7 +965,7 @@ void launch_attention(const MbState& st, const float* qrot, const bf16_t* kcache
 
 void launch_argmax(const float* logits, int vocab, const int32_t* d_nsel, int32_t* am, int n_max, hipStream_t s)
 {
-    hipLaunchKernelGGL(k_argmax, dim3(n_max), dim3(256), 0, s, logits, vocab, d_nsel, am);
+    hipLaunchKernelGGL(k_argmax, dim3(n_max), dim3(1024), 0, s, logits, vocab, d_nsel, am);
 }
 
 void launch_step_update(const MbState& st, int compact, hipStream_t s)

@@ -228,6 +228,23 @@ def test_wide_microbatch(wide2):
         check_tokens_teacher_forced(om, w.prompt(i), r["tokens"][i, :int(r["lens"][i])], what=f"row {i}")
 
 
+def test_exact_ties_pick_the_lowest_token_id(tiny):
+    """Every LM-head row identical -> all logits of a position are bit-equal -> greedy must emit id 0 (the
+    oracle's rule: lowest index on exact ties), on the prompt forward and on every decode step."""
+    W, om, gw = tiny
+    W2 = [t.copy() for t in W]
+    W2[-1][:] = W2[-1][17]
+    gw2 = ss.Weights(synth.TINY, W2)
+    try:
+        w = synth.make_workload(1)
+        r = ss.ss_decode_microbatch(gw2, w.prompt_tokens, w.prompt_offsets, 12, w.target_lens, 0)
+        ref = OracleModel(synth.TINY, W2, "f64").greedy_microbatch(w.prompt_tokens, w.prompt_offsets, 12, w.target_lens)
+        assert (ref["tokens"][ref["tokens"] >= 0] == 0).all()
+        assert np.array_equal(r["tokens"], ref["tokens"])
+    finally:
+        gw2.close()
+
+
 # ------------------------------------------------------------------ whole group
 @pytest.mark.parametrize("flags", [(), ("SORT", "BIN", "FCR"), ("SORT", "BIN", "FCR", "VBS", "COMPACT"),
                                    ("SORT", "FCR", "VBS")])
