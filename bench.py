@@ -101,6 +101,7 @@ def main() -> int:
     from paper_2305_13144_amd import synth
 
     ss.lib()  # fail loudly if the HIP library is missing
+    ss.ss_set_verbose(1 if (a.cfg >= 4 or a.ablation) else 0)   # long groups: a progress line per micro-batch
     wl = synth.make_workload(a.cfg)
     shape = wl.shape if a.layers <= 0 else wl.shape.with_layers(a.layers)
     t0 = time.time()

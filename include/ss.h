@@ -29,6 +29,10 @@ typedef enum { SS_OK = 0, SS_EINVAL = -1, SS_ENOMEM = -2, SS_EDEVICE = -3, SS_ES
 /* Thread-local text of the last error on this thread ("" if none).  Host pointer, library-owned. */
 const char* ss_last_error(void);
 
+/* Progress lines: level 1 makes ss_run_group print one line per finished micro-batch to stderr (long groups
+ * take minutes); level 0 (default) prints nothing.  Process-wide. */
+void ss_set_verbose(int32_t level);
+
 /* ------------------------------------------------------------------ scheduler (host only) */
 
 /* Policy flags.  0 = vanilla batching: arrival order, fixed batch, cap = base_len (Sec. 4.2 baseline). */
@@ -106,7 +110,8 @@ typedef struct ss_weights ss_weights; /* opaque; owns packed bf16 weights and a 
  *            embed[vocab,d]; per layer attn_norm[d], wq[d,d], wk[d,d], wv[d,d], wo[d,d], mlp_norm[d],
  *            wg[ffn,d], wu[ffn,d], wd[d,ffn]; final_norm[d]; lm_head[vocab,d].
  *            The caller keeps ownership; the data is copied.
- * Requires n_heads*head_dim == d_model, head_dim in {64, 128}, d_model % 32 == 0, d_ffn % 16 == 0, vocab % 16 == 0.
+ * Requires n_heads*head_dim == d_model, head_dim in {64, 128}, d_model % 64 == 0 and <= 8192, d_ffn % 16 == 0,
+ * vocab % 16 == 0.
  * Errors: SS_EINVAL (shape), SS_EDEVICE (no usable GPU / HIP error), SS_ENOMEM.
  */
 int  ss_weights_create(const ss_model_cfg* cfg, const void* const* tensors, int32_t src_dtype, ss_weights** out);

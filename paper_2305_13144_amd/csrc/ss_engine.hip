@@ -7,6 +7,7 @@
 #include <atomic>
 #include <chrono>
 #include <cmath>
+#include <cstdio>
 #include <cstring>
 #include <numeric>
 #include <vector>
@@ -682,6 +683,12 @@ extern "C" int ss_run_group(ss_weights* w, const int32_t* prompt_tokens, const i
             gs.prefill_ms += st.prefill_ms;
             gs.decode_ms += st.decode_ms;
             (first ? gs.n_mb_first : gs.n_mb_failure) += 1;
+            if (ss::verbose() > 0) {
+                std::fprintf(stderr, "[ss] %s micro-batch %d/%d: %d rows, cap %d, %d steps, %.0f ms\n",
+                             first ? "first-pass" : "recompute", k + 1, pl->n_mb, B, cap, st.steps,
+                             st.prefill_ms + st.decode_ms);
+                std::fflush(stderr);
+            }
         }
         return SS_OK;
     };

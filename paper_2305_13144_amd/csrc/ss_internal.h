@@ -12,6 +12,7 @@ namespace ss {
 // Records a thread-local message and returns `code` (printf-style).
 int fail(int code, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
 void clear_error();
+int verbose();   // ss_set_verbose level
 
 constexpr int kMaxPos = 4096;     // positions per row (prompt + generated) the attention kernel supports
 constexpr int kMaxBatch = 1024;   // rows per micro-batch the bookkeeping kernel supports

@@ -117,6 +117,41 @@ def test_13b_widths_logits_and_vbs_batch(wide13):
         check_tokens_teacher_forced(om, w.prompt(j), r["tokens"][j, :int(r["lens"][j])], what=f"row {j}")
 
 
+def test_13b_full_depth_config5_microbatch(oracle_built):
+    """Config 5 at its real size: LLaMA-13B shape, 40 layers.  Teacher-forced logits, then the first
+    micro-batch of its plan (the largest variable batch) generated with compaction; sampled rows re-derived
+    by the oracle."""
+    shape = synth.LLAMA13B
+    _say("generating full-depth 13B weights (seed 5)")
+    W = synth.make_weights(shape, seed=5, threads=16)
+    gw = ss.Weights(shape, W)
+    om = OracleModel(shape, W, "f64")
+    try:
+        w = synth.make_workload(5)
+        rng = np.random.default_rng(23)
+        toks, offs, npr = forced_batch(w, [2, 9], [3, 0], rng)
+        _say(f"13B x40 teacher-forced: prompts {npr.tolist()}")
+        got = ss.ss_forward_logits(gw, toks, offs, npr)
+        check_logits(got, oracle_forced_logits(om, toks, offs, npr), "13B full depth")
+        pol = ss.make_policy(w.flags, w.base_batch, w.l_max, w.max_batch)
+        plan = ss.ss_schedule(w.pred_lens, w.n, w.bin_width, pol)
+        idx, cap = plan[0]
+        ptoks, poffs = synth.gather_prompts(w, idx)
+        t = w.target_lens[idx]
+        _say(f"config 5 micro-batch 0: {len(idx)} rows, cap {cap}")
+        r = ss.ss_decode_microbatch(gw, ptoks, poffs, cap, t, ss.SS_COMPACT)
+        assert np.array_equal(r["lens"], np.minimum(t, cap))
+        assert np.array_equal(r["failed"].astype(bool), t > cap)
+        assert r["stats"]["row_steps"] == int(np.minimum(t, cap).sum())
+        shortest = int(np.argmin(poffs[1:] - poffs[:-1]))
+        for j in (shortest,):
+            L = int(r["lens"][j])
+            dcd, tot = check_tokens_teacher_forced(om, w.prompt(idx[j]), r["tokens"][j, :L], upto=3, what=f"row {j}")
+            _say(f"  row {j}: {dcd}/{tot} decided positions match")
+    finally:
+        gw.close()
+
+
 @pytest.mark.parametrize("rows", [163, 81, 54])
 def test_7b_widths_variable_batch_sizes(rows, oracle_built):
     """Config 4's batch sizes for the 50/100/150-token bins at 7B widths (2 layers), compaction on and off."""
