@@ -75,6 +75,49 @@ def ablation(a, ss, gw, wl, shape) -> int:
     return 0
 
 
+def sweeps(a, ss, gw, wl, shape) -> int:
+    """Analogues of the paper's Fig. 3 on the synthetic workload, one JSON line per point.
+    batch: throughput against micro-batch size, (a) every row generates a fixed 64 tokens, (b) vanilla batches
+           run until their longest row finishes (a 64-query subset of the group keeps batch 1 affordable).
+    group: throughput against group size for the full policy and for vanilla batching on the same queries."""
+    from paper_2305_13144_amd import synth
+    full = synth.make_workload(4, shape=shape)                      # 1024 queries, with predictions
+    if a.sweep == "batch":
+        sub = list(range(64))
+        for B in (1, 2, 4, 8, 16, 32, 64, 128, 256):
+            idx = list(range(B))
+            toks, offs = synth.gather_prompts(full, idx)
+            ss.ss_decode_microbatch(gw, toks, offs, 2, np.full(B, 2, np.int32), 0)          # workspace growth
+            r = ss.ss_decode_microbatch(gw, toks, offs, 64, np.full(B, 64, np.int32), 0)
+            ms = r["stats"]["prefill_ms"] + r["stats"]["decode_ms"]
+            row = dict(sweep="batch", batch=B, fixed_len_tokens_per_s=B * 64 / (ms / 1e3), fixed_len_ms=ms)
+            if B <= 64:
+                toks, offs = synth.gather_prompts(full, sub)
+                pol = ss.make_policy((), B, full.l_max, max(B, 256))
+                g = ss.ss_run_group(gw, toks, offs, full.target_lens[sub], None, 0, pol)
+                row.update(until_finished_tokens_per_s=int(full.target_lens[sub].sum()) / (g["stats"]["wall_ms"] / 1e3),
+                           until_finished_ms=g["stats"]["wall_ms"], until_finished_steps=g["stats"]["steps"])
+            log(f"sweep batch {B}: {row}")
+            print(json.dumps(row), flush=True)
+    else:
+        for n in (32, 64, 128, 256, 512, 1024):
+            idx = list(range(n))
+            toks, offs = synth.gather_prompts(full, idx)
+            t, pr = full.target_lens[idx], full.pred_lens[idx]
+            useful = int(t.sum())
+            pol = ss.make_policy(full.flags, full.base_batch, full.l_max, full.max_batch)
+            g = ss.ss_run_group(gw, toks, offs, t, pr, full.bin_width, pol)
+            v = ss.ss_run_group(gw, toks, offs, t, None, 0, ss.make_policy((), full.base_batch, full.l_max, full.max_batch))
+            row = dict(sweep="group", group=n, scheduled_tokens_per_s=useful / (g["stats"]["wall_ms"] / 1e3),
+                       vanilla_tokens_per_s=useful / (v["stats"]["wall_ms"] / 1e3),
+                       ratio=v["stats"]["wall_ms"] / g["stats"]["wall_ms"], scheduled_steps=g["stats"]["steps"],
+                       vanilla_steps=v["stats"]["steps"], n_failed=g["stats"]["n_failed"])
+            log(f"sweep group {n}: {row}")
+            print(json.dumps(row), flush=True)
+    gw.close()
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -88,6 +131,9 @@ def main() -> int:
     ap.add_argument("--ablation", action="store_true",
                     help="instead of the headline run: the paper's Table 5 ablation (Binning x FCR x VBS), a perfect "
                          "predictor and compaction on the same group, one pass each; prints one JSON line per row")
+    ap.add_argument("--sweep", choices=["batch", "group"], default=None,
+                    help="instead of the headline run: throughput against micro-batch size or against group size "
+                         "(the paper's Fig. 3a / 3b on the synthetic workload)")
     ap.add_argument("--roofline-only", action="store_true",
                     help="only the roofline legs (weight-stream kernels and one decode step); the command profiled "
                          "under rocprofv3 for profiles/")
@@ -101,7 +147,7 @@ def main() -> int:
     from paper_2305_13144_amd import synth
 
     ss.lib()  # fail loudly if the HIP library is missing
-    ss.ss_set_verbose(1 if (a.cfg >= 4 or a.ablation) else 0)   # long groups: a progress line per micro-batch
+    ss.ss_set_verbose(1 if (a.cfg >= 4 or a.ablation or a.sweep) else 0)   # long groups: a progress line per micro-batch
     wl = synth.make_workload(a.cfg)
     shape = wl.shape if a.layers <= 0 else wl.shape.with_layers(a.layers)
     t0 = time.time()
@@ -119,6 +165,8 @@ def main() -> int:
 
     if a.ablation:
         return ablation(a, ss, gw, wl, shape)
+    if a.sweep:
+        return sweeps(a, ss, gw, wl, shape)
 
     # ---- timed region: W warmup passes, then exactly K passes over the group ----------------------
     if a.roofline_only:

@@ -273,6 +273,25 @@ def test_tiny_group_every_policy_same_answers(tiny, flags):
         check_tokens_teacher_forced(om, w.prompt(i), r["tokens"][i, :t], what=f"query {i}")
 
 
+def test_runs_are_bit_repeatable(tiny, wide2):
+    """Race canary: every reduction is ordered (no float atomics), so two runs of the same call must agree
+    bit for bit - logits and tokens, skinny and tiled kernels, padded and compacted."""
+    W, om, gw = tiny
+    w = synth.make_group(synth.TINY, 90, 99, ("uniform", 4, 30), ("uniform", 1, 20), None, 20, 0, ())
+    a = ss.ss_forward_logits(gw, w.prompt_tokens, w.prompt_offsets, w.prompt_lens)
+    b = ss.ss_forward_logits(gw, w.prompt_tokens, w.prompt_offsets, w.prompt_lens)
+    assert np.array_equal(a.view(np.uint32), b.view(np.uint32))
+    for flags in (0, ss.SS_COMPACT):
+        r1 = ss.ss_decode_microbatch(gw, w.prompt_tokens, w.prompt_offsets, 16, w.target_lens, flags)
+        r2 = ss.ss_decode_microbatch(gw, w.prompt_tokens, w.prompt_offsets, 16, w.target_lens, flags)
+        assert np.array_equal(r1["tokens"], r2["tokens"])
+    shape, W2, om2, gw2 = wide2
+    w2 = synth.make_workload(3, n=16, shape=shape)
+    r1 = ss.ss_decode_microbatch(gw2, w2.prompt_tokens, w2.prompt_offsets, 8, w2.target_lens, 0)
+    r2 = ss.ss_decode_microbatch(gw2, w2.prompt_tokens, w2.prompt_offsets, 8, w2.target_lens, 0)
+    assert np.array_equal(r1["tokens"], r2["tokens"])
+
+
 # ------------------------------------------------------------------ error paths that need a handle
 def test_invalid_generation_arguments(tiny):
     W, om, gw = tiny

@@ -1,0 +1,83 @@
+"""The host scheduler under AddressSanitizer + UBSan (host code only: plain g++, no GPU, no HIP).
+A small C++ driver is compiled together with the scheduler sources and hammers ss_schedule /
+ss_schedule_failures / ss_plan_free with random groups and every flag combination, checking the plan
+invariants (each query exactly once, offsets monotone, caps in range) in C++ as well."""
+import os
+import shutil
+import subprocess
+import textwrap
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+CSRC = os.path.join(ROOT, "paper_2305_13144_amd", "csrc")
+
+DRIVER = textwrap.dedent(r"""
+    #include <cstdint>
+    #include <cstdio>
+    #include <cstdlib>
+    #include <vector>
+    #include "ss.h"
+    static uint64_t s = 88172645463325252ull;
+    static uint32_t rnd() { s ^= s << 13; s ^= s >> 7; s ^= s << 17; return (uint32_t)(s >> 11); }
+    static void check(const ss_plan* p, int n, const ss_policy& pol) {
+        if (p->n != n) { std::printf("bad n\n"); std::exit(2); }
+        std::vector<int> seen(n, 0);
+        if (p->mb_offsets[0] != 0 || p->mb_offsets[p->n_mb] != n) { std::printf("bad offsets\n"); std::exit(2); }
+        for (int k = 0; k < p->n_mb; ++k) {
+            if (p->mb_offsets[k + 1] <= p->mb_offsets[k]) { std::printf("empty micro-batch\n"); std::exit(2); }
+            if (p->mb_cap[k] < 1 || p->mb_cap[k] > pol.base_len) { std::printf("bad cap\n"); std::exit(2); }
+        }
+        for (int i = 0; i < n; ++i) {
+            int q = p->query_idx[i];
+            if (q < 0 || q >= n || seen[q]++) { std::printf("not a permutation\n"); std::exit(2); }
+        }
+    }
+    int main() {
+        const uint32_t flagsets[] = {0, SS_SORT, SS_SORT | SS_FCR, SS_SORT | SS_BIN, SS_SORT | SS_BIN | SS_FCR,
+                                     SS_SORT | SS_FCR | SS_VBS, SS_SORT | SS_BIN | SS_FCR | SS_VBS | SS_COMPACT};
+        for (int trial = 0; trial < 3000; ++trial) {
+            int n = 1 + rnd() % 400;
+            ss_policy pol;
+            pol.flags = flagsets[rnd() % 7];
+            pol.base_batch = 1 + rnd() % 20;
+            pol.max_batch = pol.base_batch + rnd() % 300;
+            pol.base_len = 1 + rnd() % 1100;
+            pol.vbs_rule = rnd() % 2;
+            int bin = (pol.flags & SS_BIN) ? 1 + rnd() % 100 : (int)(rnd() % 2) * (1 + rnd() % 100);
+            std::vector<int32_t> pred(n);
+            for (auto& v : pred) v = 1 + rnd() % (pol.base_len * 2 + 3);
+            ss_plan* p = nullptr;
+            if (ss_schedule(pred.data(), n, bin, &pol, &p) != SS_OK) { std::printf("schedule: %s\n", ss_last_error()); return 3; }
+            check(p, n, pol);
+            ss_plan_free(p);
+            std::vector<int32_t> failed;
+            for (int i = 0; i < n; ++i) if (rnd() % 4 == 0) failed.push_back(i);
+            if (ss_schedule_failures(pred.data(), n, failed.data(), (int)failed.size(), bin, &pol, &p) != SS_OK) return 4;
+            if (p->n != (int)failed.size()) return 5;
+            ss_plan_free(p);
+        }
+        // error paths must not leak or touch the output
+        ss_plan* p = nullptr;
+        ss_policy bad = {SS_BIN, 16, 512, 256, 0};
+        int32_t one = 5;
+        if (ss_schedule(&one, 1, 50, &bad, &p) != SS_EINVAL || p != nullptr) return 6;
+        std::printf("ok\n");
+        return 0;
+    }
+""")
+
+
+@pytest.mark.skipif(shutil.which("g++") is None, reason="g++ not available")
+def test_scheduler_under_asan_ubsan(tmp_path):
+    drv = tmp_path / "driver.cpp"
+    drv.write_text(DRIVER)
+    exe = tmp_path / "driver"
+    cmd = ["g++", "-std=c++17", "-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=all", "-static-libasan",
+           "-I", os.path.join(ROOT, "include"), str(drv), os.path.join(CSRC, "ss_sched.cpp"),
+           os.path.join(CSRC, "ss_common.cpp"), "-o", str(exe)]
+    subprocess.run(cmd, check=True, capture_output=True, text=True)
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=1:abort_on_error=0")
+    r = subprocess.run([str(exe)], capture_output=True, text=True, env=env, timeout=120)
+    assert r.returncode == 0, r.stdout + r.stderr
+    assert r.stdout.strip() == "ok"
