@@ -220,6 +220,21 @@ def main() -> int:
         hip.hipFree(src)
         hip.hipFree(dst)
 
+    if not a.roofline_only and wl.pred_lens is not None:
+        # Length-perception overhead, simulated (Sec. 4.1, "Overhead of Length Prediction": one prompt forward plus
+        # 2-3 generated tokens per query before anything can be scheduled).  No predictor is built; this only puts
+        # its cost next to the gain: every query gets a prompt forward + 3 tokens, 64 queries per micro-batch.
+        t_p = 0.0
+        for lo in range(0, wl.n, 64):
+            idx = list(range(lo, min(wl.n, lo + 64)))
+            ptk, pof = synth.gather_prompts(wl, idx)
+            rp = ss.ss_decode_microbatch(gw, ptk, pof, 3, np.full(len(idx), 3, np.int32), 0)
+            t_p += rp["stats"]["prefill_ms"] + rp["stats"]["decode_ms"]
+        extras["simulated_length_perception"] = dict(
+            what="prompt forward + 3 generated tokens for every query, 64 per micro-batch, before scheduling",
+            ms=t_p, useful_tokens_per_s_including_it=useful / ((st["wall_ms"] + t_p) / 1e3))
+        log(f"simulated perception overhead: {t_p:.0f} ms on top of {st['wall_ms']:.0f} ms")
+
     # ---- roofline: the weight-streaming projection kernel, timed live with HIP events --------------
     B0, ctx = 16, 200
     ms_w, launches = ss.ss_bench_weight_stream(gw, B0, a.step_iters + 3)
