@@ -243,7 +243,7 @@ def main() -> int:
     ach = wbytes / (ms_w.mean() * 1e-3) / 1e9
     # HBM bytes per launch from the FETCH_SIZE + WRITE_SIZE counter runs of this same command (7B shape only;
     # the figures and the copy-kernel scale factors are in profiles/decode_step_7b_hbm_traffic.txt)
-    traffic = (13619.1e6 + 32 * (3.15e6 + 2.10e6 + 0.70e6 + 1.05e6) + 2.05e6) / 129 if shape.name == "llama7b" else None
+    traffic = (13617.4e6 + 225.9e6) / 129 if shape.name == "llama7b" else None
     roofline = dict(bound="hbm", kernel="k_gemm_skinny (all projection launches of one 16-row decode step)",
                     achieved=ach, peak=HBM_PEAK_GBS, unit="GB/s", frac=ach / HBM_PEAK_GBS, traffic=traffic,
                     launches_per_step=launches, avg_launch_us=ms_w.mean() * 1e3 / launches,
