@@ -128,6 +128,8 @@ def main() -> int:
     ap.add_argument("--no-vanilla", action="store_true", help="skip the vanilla-batching comparison run")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--step-iters", type=int, default=20, help="decode-step timing iterations")
+    ap.add_argument("--step-rows", type=int, default=16, help="rows of the timed decode step (roofline legs)")
+    ap.add_argument("--step-ctx", type=int, default=200, help="context length of the timed decode step")
     ap.add_argument("--ablation", action="store_true",
                     help="instead of the headline run: the paper's Table 5 ablation (Binning x FCR x VBS), a perfect "
                          "predictor and compaction on the same group, one pass each; prints one JSON line per row")
@@ -236,7 +238,7 @@ def main() -> int:
         log(f"simulated perception overhead: {t_p:.0f} ms on top of {st['wall_ms']:.0f} ms")
 
     # ---- roofline: the weight-streaming projection kernel, timed live with HIP events --------------
-    B0, ctx = 16, 200
+    B0, ctx = a.step_rows, a.step_ctx
     ms_w, launches = ss.ss_bench_weight_stream(gw, B0, a.step_iters + 3)
     ms_w = ms_w[3:]
     wbytes = shape.weight_bytes_per_step() - (2 * shape.n_layers + 1) * shape.d_model * 2   # matrices only
@@ -244,7 +246,7 @@ def main() -> int:
     # HBM bytes per launch from the FETCH_SIZE + WRITE_SIZE counter runs of this same command (7B shape only;
     # the figures and the copy-kernel scale factors are in profiles/decode_step_7b_hbm_traffic.txt)
     traffic = (13617.4e6 + 225.9e6) / 129 if shape.name == "llama7b" else None
-    roofline = dict(bound="hbm", kernel="k_gemm_skinny (all projection launches of one 16-row decode step)",
+    roofline = dict(bound="hbm", kernel=f"k_gemm_skinny (all projection launches of one {B0}-row decode step)",
                     achieved=ach, peak=HBM_PEAK_GBS, unit="GB/s", frac=ach / HBM_PEAK_GBS, traffic=traffic,
                     launches_per_step=launches, avg_launch_us=ms_w.mean() * 1e3 / launches,
                     bytes_per_launch=wbytes / launches)
@@ -255,7 +257,7 @@ def main() -> int:
     extras["decode_step"] = dict(rows=B0, ctx=ctx, ms=float(ms_s.mean()), ms_min=float(ms_s.min()),
                                  algorithmic_bytes=sbytes, achieved_GBs=sbytes / (ms_s.mean() * 1e-3) / 1e9,
                                  frac_of_hbm_peak=sbytes / (ms_s.mean() * 1e-3) / 1e9 / HBM_PEAK_GBS)
-    log(f"weight stream: {ms_w.mean():.3f} ms/iter -> {ach:.0f} GB/s; decode step B=16 ctx=200: "
+    log(f"weight stream: {ms_w.mean():.3f} ms/iter -> {ach:.0f} GB/s; decode step B={B0} ctx={ctx}: "
         f"{ms_s.mean():.3f} ms -> {extras['decode_step']['achieved_GBs']:.0f} GB/s")
     gw.close()
 
