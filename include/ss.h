@@ -33,6 +33,11 @@ const char* ss_last_error(void);
  * take minutes); level 0 (default) prints nothing.  Process-wide. */
 void ss_set_verbose(int32_t level);
 
+/* Testing aid: which kernel runs the projections of at most 64 token-rows.  0 (default): chosen per shape;
+ * 1: always the kernel whose waves split the k range; 2: always the kernel that stages activations once per
+ * workgroup.  Results agree to fp32 rounding order.  Process-wide; other values are ignored. */
+void ss_set_gemm_mode(int32_t mode);
+
 /* ------------------------------------------------------------------ scheduler (host only) */
 
 /* Policy flags.  0 = vanilla batching: arrival order, fixed batch, cap = base_len (Sec. 4.2 baseline). */

@@ -21,7 +21,7 @@ SS_VBS_CLAMP_FLOOR, SS_VBS_PAPER_POW2 = 0, 1
 SS_BF16, SS_F32 = 0, 1
 FLAG_BITS = dict(SORT=SS_SORT, BIN=SS_BIN, FCR=SS_FCR, VBS=SS_VBS, COMPACT=SS_COMPACT)
 
-EXPORTS = ["ss_last_error", "ss_set_verbose", "ss_schedule", "ss_schedule_failures", "ss_plan_free", "ss_weights_create",
+EXPORTS = ["ss_last_error", "ss_set_verbose", "ss_set_gemm_mode", "ss_schedule", "ss_schedule_failures", "ss_plan_free", "ss_weights_create",
            "ss_weights_destroy", "ss_decode_microbatch", "ss_forward_logits", "ss_run_group", "ss_bench_decode_step",
            "ss_bench_weight_stream"]
 
@@ -77,6 +77,8 @@ def lib():
         L.ss_last_error.restype = C.c_char_p
         L.ss_set_verbose.argtypes = [C.c_int32]
         L.ss_set_verbose.restype = None
+        L.ss_set_gemm_mode.argtypes = [C.c_int32]
+        L.ss_set_gemm_mode.restype = None
         L.ss_schedule.argtypes = [i32p, C.c_int32, C.c_int32, C.POINTER(ss_policy), C.POINTER(C.POINTER(ss_plan))]
         L.ss_schedule_failures.argtypes = [i32p, C.c_int32, i32p, C.c_int32, C.c_int32, C.POINTER(ss_policy),
                                            C.POINTER(C.POINTER(ss_plan))]
@@ -93,7 +95,7 @@ def lib():
         L.ss_bench_decode_step.argtypes = [vp, i32p, C.c_int32, C.c_int32, C.c_int32, vp, vp]
         L.ss_bench_weight_stream.argtypes = [vp, C.c_int32, C.c_int32, vp, vp, vp]
         for name in EXPORTS:
-            if name not in ("ss_last_error", "ss_set_verbose", "ss_plan_free", "ss_weights_destroy"):
+            if name not in ("ss_last_error", "ss_set_verbose", "ss_set_gemm_mode", "ss_plan_free", "ss_weights_destroy"):
                 getattr(L, name).restype = C.c_int
         _lib = L
     return _lib
@@ -114,6 +116,10 @@ def _ptr(a: Optional[np.ndarray]):
 
 def ss_set_verbose(level: int) -> None:
     lib().ss_set_verbose(level)
+
+
+def ss_set_gemm_mode(mode: int) -> None:
+    lib().ss_set_gemm_mode(mode)
 
 
 def make_policy(flags: Sequence[str] = (), base_batch: int = 16, base_len: int = 512, max_batch: int = 256,

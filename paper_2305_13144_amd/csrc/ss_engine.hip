@@ -90,6 +90,8 @@ struct ss_weights {
     bf16_t* final_norm = nullptr;
     PackedMat lm_head;
     float *rope_cos = nullptr, *rope_sin = nullptr;
+    bf16_t* zero_blk = nullptr;   // 1 KiB of zeros (see GemmArgs::zero_blk)
+    int n_cu = 256;               // compute units of the device
     Workspace ws;
     std::atomic<int> busy{0};
     int32_t* d_sel = nullptr;  // carved from ws.ints
@@ -222,6 +224,34 @@ int ensure_workspace(ss_weights* w, int n_max, int B, int n_sel, size_t slots, i
     return SS_OK;
 }
 
+// Launch plans of the five projections of a forward over n token-rows with n_sel logit rows.
+struct Plans {
+    ss::GemmPlan qkv, o, gu, down, lm;
+};
+
+Plans make_plans(const ss_weights* w, int n, int n_sel)
+{
+    const ss_model_cfg& c = w->cfg;
+    const int d = c.d_model, F = c.d_ffn, V = c.vocab, Fp = ss::padded_k(F), cu = w->n_cu;
+    Plans p;
+    p.qkv = ss::gemm_plan(3 * d, d, n, ss::EPI_PARTIAL, cu);
+    p.o = ss::gemm_plan(d, d, n, ss::EPI_PARTIAL, cu);
+    p.gu = ss::gemm_plan(2 * F, d, n, ss::EPI_SWIGLU, cu);
+    p.down = ss::gemm_plan(d, Fp, n, ss::EPI_PARTIAL, cu);
+    p.lm = ss::gemm_plan(V, d, n_sel, ss::EPI_PARTIAL, cu, 1);   // logits are read directly: no k-slices
+    return p;
+}
+
+GemmArgs gemm_args(const ss_weights* w, const bf16_t* W, const bf16_t* X, const bf16_t* Xlo, float* out, bf16_t* outp,
+                   bf16_t* outp_lo, int N, int Kp, int rows, int kp_out, const ss::GemmPlan& p)
+{
+    GemmArgs g{};
+    g.W = W; g.X = X; g.X_lo = Xlo; g.out = out; g.out_packed = outp; g.out_packed_lo = outp_lo; g.N = N; g.Kp = Kp;
+    g.m_rows = rows; g.m_stride = rows; g.kp_out = kp_out; g.ksplit = p.ksplit; g.nb = p.nb; g.kd = p.kd;
+    g.kp = p.kp; g.sweep_p = p.sweep_p; g.sweep_gn = p.sweep_gn; g.zero_blk = w->zero_blk;
+    return g;
+}
+
 // ---------------------------------------------------------------------------------------- one forward
 // Runs the decoder over the token-rows described by the device state (st.d_n of them, at most n of
 // them: n sizes the grids and picks the kernel variants).  Logits are produced for n_sel rows:
@@ -241,20 +271,13 @@ void forward(ss_weights* w, int n, int n_sel, const int32_t* d_sel, const int32_
     float* pd = ws.pd.as<float>();
     const int Fp = ss::padded_k(F);
 
-    const ss::GemmPlan p_qkv = ss::gemm_plan(3 * d, d, n, ss::EPI_PARTIAL), p_o = ss::gemm_plan(d, d, n, ss::EPI_PARTIAL),
-                       p_gu = ss::gemm_plan(2 * F, d, n, ss::EPI_SWIGLU), p_d = ss::gemm_plan(d, Fp, n, ss::EPI_PARTIAL);
-    ss::GemmPlan p_lm = ss::gemm_plan(V, d, n_sel, ss::EPI_PARTIAL);
-    p_lm.ksplit = 1;   // logits are read directly
-    if (n_sel <= 16) p_lm.nb = 2;
+    const Plans pl = make_plans(w, n, n_sel);
+    const ss::GemmPlan &p_qkv = pl.qkv, &p_o = pl.o, &p_gu = pl.gu, &p_d = pl.down, &p_lm = pl.lm;
     const int ks_qkv = p_qkv.ksplit, ks_o = p_o.ksplit, ks_d = p_d.ksplit;
     const size_t st_qkv = (size_t)n * 3 * d, st_d = (size_t)n * d;
-    auto mk = [](const bf16_t* W, const bf16_t* X, const bf16_t* Xlo, float* out, bf16_t* outp, bf16_t* outp_lo, int N,
-                 int Kp, int rows, int kp_out, const ss::GemmPlan& p) {
-        GemmArgs g{};
-        g.W = W; g.X = X; g.X_lo = Xlo; g.out = out; g.out_packed = outp; g.out_packed_lo = outp_lo; g.N = N; g.Kp = Kp;
-        g.m_rows = rows; g.m_stride = rows; g.kp_out = kp_out; g.ksplit = p.ksplit; g.nb = p.nb; g.kd = p.kd;
-        g.kp = p.kp;
-        return g;
+    auto mk = [w](const bf16_t* W, const bf16_t* X, const bf16_t* Xlo, float* out, bf16_t* outp, bf16_t* outp_lo, int N,
+                  int Kp, int rows, int kp_out, const ss::GemmPlan& p) {
+        return gemm_args(w, W, X, Xlo, out, outp, outp_lo, N, Kp, rows, kp_out, p);
     };
 
     ss::launch_embed(st, w->embed, x, d, n, s);
@@ -501,6 +524,12 @@ extern "C" int ss_weights_create(const ss_model_cfg* cfg, const void* const* ten
         }
     }
     void* p = nullptr;
+    if ((rc = dev_alloc(w, &p, 1024, true))) return done(rc);
+    w->zero_blk = (bf16_t*)p;
+    hipDeviceProp_t prop;
+    if (hipGetDeviceProperties(&prop, w->device) != hipSuccess || prop.multiProcessorCount <= 0)
+        return done(ss::fail(SS_EDEVICE, "cannot read the device's compute unit count"));
+    w->n_cu = prop.multiProcessorCount;
     if ((rc = dev_alloc(w, &p, tc.size() * 4, false))) return done(rc);
     w->rope_cos = (float*)p;
     if ((rc = dev_alloc(w, &p, tsn.size() * 4, false))) return done(rc);
@@ -511,6 +540,11 @@ extern "C" int ss_weights_create(const ss_model_cfg* cfg, const void* const* ten
     staging.release();
     *out = w;
     return SS_OK;
+}
+
+extern "C" void ss_set_gemm_mode(int32_t mode)
+{
+    if (mode >= 0 && mode <= 2) ss::set_gemm_mode(mode);
 }
 
 extern "C" void ss_weights_destroy(ss_weights* w)
@@ -772,18 +806,11 @@ extern "C" int ss_bench_weight_stream(ss_weights* w, int32_t B, int32_t iters, d
     const ss_model_cfg& c = w->cfg;
     const int d = c.d_model, F = c.d_ffn, V = c.vocab, Fp = ss::padded_k(F), n = B;
     Workspace& ws = w->ws;
-    const ss::GemmPlan p_qkv = ss::gemm_plan(3 * d, d, n, ss::EPI_PARTIAL), p_o = ss::gemm_plan(d, d, n, ss::EPI_PARTIAL),
-                       p_gu = ss::gemm_plan(2 * F, d, n, ss::EPI_SWIGLU), p_d = ss::gemm_plan(d, Fp, n, ss::EPI_PARTIAL);
-    ss::GemmPlan p_lm = ss::gemm_plan(V, d, n, ss::EPI_PARTIAL);
-    p_lm.ksplit = 1;
-    if (n <= 16) p_lm.nb = 2;
-    auto mk = [](const bf16_t* W, const bf16_t* X, const bf16_t* Xlo, float* out, bf16_t* outp, bf16_t* outp_lo, int N,
-                 int Kp, int rows, int kp_out, const ss::GemmPlan& p) {
-        GemmArgs g{};
-        g.W = W; g.X = X; g.X_lo = Xlo; g.out = out; g.out_packed = outp; g.out_packed_lo = outp_lo; g.N = N; g.Kp = Kp;
-        g.m_rows = rows; g.m_stride = rows; g.kp_out = kp_out; g.ksplit = p.ksplit; g.nb = p.nb; g.kd = p.kd;
-        g.kp = p.kp;
-        return g;
+    const Plans pl = make_plans(w, n, n);
+    const ss::GemmPlan &p_qkv = pl.qkv, &p_o = pl.o, &p_gu = pl.gu, &p_d = pl.down, &p_lm = pl.lm;
+    auto mk = [w](const bf16_t* W, const bf16_t* X, const bf16_t* Xlo, float* out, bf16_t* outp, bf16_t* outp_lo, int N,
+                  int Kp, int rows, int kp_out, const ss::GemmPlan& p) {
+        return gemm_args(w, W, X, Xlo, out, outp, outp_lo, N, Kp, rows, kp_out, p);
     };
     bf16_t *h = ws.h.as<bf16_t>(), *ao = ws.ao.as<bf16_t>(), *act = ws.act.as<bf16_t>();
     bf16_t *h_lo = ws.h_lo.as<bf16_t>(), *ao_lo = ws.ao_lo.as<bf16_t>(), *act_lo = ws.act_lo.as<bf16_t>();

@@ -50,6 +50,9 @@ struct GemmArgs {
     int ksplit;          // outer k-slices (gemm_plan)
     int nb, kd;          // skinny kernel shape (gemm_plan)
     int kp;              // tiled kernel: k-parts inside the workgroup (gemm_plan)
+    int sweep_p;         // > 0: sweep kernel with this many waves per workgroup (gemm_plan)
+    int sweep_gn;        //      its workgroups per k-slice
+    const bf16_t* zero_blk;  // 1 KiB of zeros: operand block read in place of weights beyond a range (sweep kernel)
 };
 
 void launch_pack_weight(const void* src, int src_f32, bf16_t* dst, int n_src, int k, int kp, int blk_stride,
@@ -62,8 +65,14 @@ void launch_rmsnorm(const MbState& st, float* x, const float* part, int ksplit, 
 void launch_gemm(const GemmArgs& a, int epilogue, hipStream_t s);
 struct GemmPlan {
     int ksplit, nb, kd, kp;
+    int sweep_p, sweep_gn;
 };
-GemmPlan gemm_plan(int N, int Kp, int m_rows, int epilogue);
+// n_cu: compute units of the device (the sweep kernel runs one workgroup per unit).
+// max_ksplit: 1 when the consumer reads the output directly (logits).
+GemmPlan gemm_plan(int N, int Kp, int m_rows, int epilogue, int n_cu, int max_ksplit = 8);
+// Testing aid: 0 = choose per shape (default), 1 = never use the sweep kernel, 2 = use it for every
+// projection of at most 64 rows.
+void set_gemm_mode(int mode);
 void launch_swiglu_reduce(const float* part, int ksplit, size_t part_stride, int m_rows, int F, int kp_out,
                           bf16_t* out, bf16_t* out_lo, hipStream_t s);
 void launch_rope_append(const MbState& st, const float* qkv_part, int ksplit, size_t part_stride, float* qrot,

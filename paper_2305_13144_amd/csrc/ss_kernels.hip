@@ -9,6 +9,8 @@
 
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
+
 #include "ss_internal.h"
 
 namespace ss {
@@ -305,6 +307,188 @@ __global__ __launch_bounds__(256) void k_gemm_skinny(GemmArgs a, int n_groups, i
             // strips alternate gate, up for the same 16 MLP columns
 #pragma unroll
             for (int i = 0; i + 1 < NB; i += 2)
+                if (i + 1 < nvalid) {
+                    const int f = ((nb0 + i) >> 1) * 16 + col4;
+                    bf16_t o[4], ol[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) split_bf(silu_f(acc[i][m][e]) * acc[i + 1][m][e], o[e], ol[e]);
+                    const size_t at = pk_index(row, f, a.kp_out);
+                    *(uint2*)(a.out_packed + at) = *(const uint2*)o;
+                    *(uint2*)(a.out_packed_lo + at) = *(const uint2*)ol;
+                }
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------ sweep GEMM
+// Up to 64 token rows again, for projections large enough to give every compute unit one workgroup with several
+// waves of work.  What bounds a weight stream on this chip is the number of bytes a compute unit can have in
+// flight towards L2/HBM, and every byte requested through the vector memory path counts, also an activation
+// operand that hits in L2: in the kernel above, where each wave fetches its own activation operands, those
+// take a quarter of that budget (2 strips) or an eighth (4 strips).  Here the waves of a workgroup own
+// different output strips and sweep the same k-range together, so an activation chunk (KC k-blocks, hi + lo,
+// all row strips) is fetched once per workgroup, staged in LDS (double-buffered, one barrier per chunk) and
+// read from there by every wave; one workgroup per compute unit means once per unit.  No wave shares an
+// output with another: no reduction at the end, and the SwiGLU epilogue stays inside the wave that owns a
+// gate strip and its up strip.  Weight loads run two chunks ahead in two named register slots; nothing in
+// the loop is conditional, so the load counter waits are exact.  K-blocks beyond the k-slice and strips
+// beyond the matrix read a block of zeros instead of weights (an L2 hit) and add 0.
+template <int NBW, int KC>
+struct SweepSlot {
+    u32x4 w[NBW][KC];
+};
+
+template <int NBW, int KC>
+__device__ __forceinline__ void sweep_load_w(SweepSlot<NBW, KC>& f, const u32x4* __restrict__ Wl,
+                                             const u32x4* __restrict__ Zl, int KB, int nb0, int nvalid, int kb, int kend)
+{
+#pragma unroll
+    for (int q = 0; q < KC; ++q) {
+        const bool live = kb + q < kend;
+        const int kk = min(kb + q, kend - 1);
+#pragma unroll
+        for (int i = 0; i < NBW; ++i) {
+            const u32x4* p = (live && i < nvalid) ? Wl + ((size_t)(nb0 + i) * KB + kk) * 64 : Zl;
+            f.w[i][q] = __builtin_nontemporal_load(p);
+        }
+    }
+}
+
+// An activation chunk is 2*KC*MT operand blocks of 64 x 16 bytes, block (m*2 + part)*KC + q = row strip m,
+// part (0 hi, 1 lo), k-block q of the chunk.  Thread t of the workgroup moves pieces t, t + 64P, ...;
+// indices past the end are clamped to the last piece (the same bytes written twice).
+template <int P, int MT, int KC>
+struct SweepStage {
+    static constexpr int PIECES = 2 * KC * MT * 64;
+    static constexpr int XI = (PIECES + 64 * P - 1) / (64 * P);
+    u32x4 v[XI];
+};
+
+template <int P, int MT, int KC>
+__device__ __forceinline__ void sweep_load_x(SweepStage<P, MT, KC>& xs, const u32x4* __restrict__ X,
+                                             const u32x4* __restrict__ Xlo, int KB, int kb, int kend)
+{
+#pragma unroll
+    for (int i = 0; i < SweepStage<P, MT, KC>::XI; ++i) {
+        const int piece = min((int)threadIdx.x + i * 64 * P, SweepStage<P, MT, KC>::PIECES - 1);
+        const int b = piece >> 6, l = piece & 63;
+        const int m = b / (2 * KC), part = (b / KC) & 1, q = b % KC;
+        const int kk = min(kb + q, kend - 1);
+        xs.v[i] = (part ? Xlo : X)[((size_t)m * KB + kk) * 64 + l];
+    }
+}
+
+template <int P, int MT, int KC>
+__device__ __forceinline__ void sweep_store_x(const SweepStage<P, MT, KC>& xs, u32x4* buf)
+{
+#pragma unroll
+    for (int i = 0; i < SweepStage<P, MT, KC>::XI; ++i)
+        buf[min((int)threadIdx.x + i * 64 * P, SweepStage<P, MT, KC>::PIECES - 1)] = xs.v[i];
+}
+
+template <int MT, int NBW, int KC>
+__device__ __forceinline__ void sweep_mma(const SweepSlot<NBW, KC>& f, const u32x4* buf, int lane, f32x4 (&acc)[NBW][MT])
+{
+#pragma unroll
+    for (int q = 0; q < KC; ++q) {
+        u32x4 xh[MT], xl[MT];
+#pragma unroll
+        for (int m = 0; m < MT; ++m) {
+            xh[m] = buf[((m * 2 + 0) * KC + q) * 64 + lane];
+            xl[m] = buf[((m * 2 + 1) * KC + q) * 64 + lane];
+        }
+#pragma unroll
+        for (int m = 0; m < MT; ++m)
+#pragma unroll
+            for (int i = 0; i < NBW; ++i) {
+                acc[i][m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, f.w[i][q]),
+                                                                    __builtin_bit_cast(bf16x8, xl[m]), acc[i][m], 0, 0, 0);
+                acc[i][m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, f.w[i][q]),
+                                                                    __builtin_bit_cast(bf16x8, xh[m]), acc[i][m], 0, 0, 0);
+            }
+    }
+}
+
+// Grid: n_gn workgroups per k-slice x ksplit; workgroup gn of a slice owns units [gn*n_units/n_gn,
+// (gn+1)*n_units/n_gn) (a unit = NBW consecutive strips; at most P of them, checked by the launcher), one per wave.
+template <int P, int MT, int NBW, int EPI>
+__global__ __launch_bounds__(64 * P) void k_gemm_sweep(GemmArgs a, int n_units, int n_gn, int kb_per_slice)
+{
+    constexpr int KC = 4;
+    __shared__ u32x4 xlds[2][SweepStage<P, MT, KC>::PIECES];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int gn = blockIdx.x % n_gn, ks = blockIdx.x / n_gn;
+    const int KB = a.Kp >> 5, NBT = a.N >> 4;
+    const int s0 = ks * kb_per_slice, s1 = min(KB, s0 + kb_per_slice);
+    const int u0 = (int)((long long)gn * n_units / n_gn), u1 = (int)((long long)(gn + 1) * n_units / n_gn);
+    const int unit = u0 + wave;
+    const bool active = unit < u1;
+    const int nb0 = unit * NBW;
+    const int nvalid = active ? max(min(NBW, NBT - nb0), 0) : 0;
+
+    f32x4 acc[NBW][MT];
+#pragma unroll
+    for (int i = 0; i < NBW; ++i)
+#pragma unroll
+        for (int m = 0; m < MT; ++m) acc[i][m] = (f32x4){0.f, 0.f, 0.f, 0.f};
+
+    const u32x4* Wl = (const u32x4*)a.W + lane;
+    const u32x4* Zl = (const u32x4*)a.zero_blk + lane;
+    const u32x4* X = (const u32x4*)a.X;
+    const u32x4* Xlo = (const u32x4*)a.X_lo;
+    const int C = (s1 - s0 + KC - 1) / KC;   // chunks of this slice: the same for every wave of the workgroup
+    if (C > 0) {
+        SweepSlot<NBW, KC> fa, fb;
+        SweepStage<P, MT, KC> xs;
+        sweep_load_x<P, MT, KC>(xs, X, Xlo, KB, s0, s1);
+        sweep_load_w<NBW, KC>(fa, Wl, Zl, KB, nb0, nvalid, s0, s1);
+        __builtin_amdgcn_sched_barrier(0);
+        sweep_store_x<P, MT, KC>(xs, xlds[0]);
+        __builtin_amdgcn_sched_barrier(0);
+        sweep_load_x<P, MT, KC>(xs, X, Xlo, KB, s0 + KC, s1);
+        sweep_load_w<NBW, KC>(fb, Wl, Zl, KB, nb0, nvalid, s0 + KC, s1);
+        __builtin_amdgcn_sched_barrier(0);
+        __syncthreads();
+        // Two chunks per trip (slot fa with LDS buffer 0, slot fb with buffer 1).  Within a chunk: contract it,
+        // write the next chunk's activations (loaded one chunk ago) into the other buffer, start the loads of
+        // the chunk after that, barrier.  A buffer is rewritten one barrier after its last read.
+        for (int c = 0; c < C; c += 2) {
+            const int k2 = s0 + (c + 2) * KC, k3 = k2 + KC;
+            sweep_mma<MT, NBW, KC>(fa, xlds[0], lane, acc);
+            __builtin_amdgcn_sched_barrier(0);
+            sweep_store_x<P, MT, KC>(xs, xlds[1]);
+            __builtin_amdgcn_sched_barrier(0);
+            sweep_load_x<P, MT, KC>(xs, X, Xlo, KB, k2, s1);
+            sweep_load_w<NBW, KC>(fa, Wl, Zl, KB, nb0, nvalid, k2, s1);
+            __builtin_amdgcn_sched_barrier(0);
+            __syncthreads();
+            sweep_mma<MT, NBW, KC>(fb, xlds[1], lane, acc);
+            __builtin_amdgcn_sched_barrier(0);
+            sweep_store_x<P, MT, KC>(xs, xlds[0]);
+            __builtin_amdgcn_sched_barrier(0);
+            sweep_load_x<P, MT, KC>(xs, X, Xlo, KB, k3, s1);
+            sweep_load_w<NBW, KC>(fb, Wl, Zl, KB, nb0, nvalid, k3, s1);
+            __builtin_amdgcn_sched_barrier(0);
+            __syncthreads();
+        }
+    }
+    if (!active) return;
+
+    const int col4 = (lane >> 4) * 4;
+#pragma unroll
+    for (int m = 0; m < MT; ++m) {
+        const int row = m * 16 + (lane & 15);
+        if (row >= a.m_rows) continue;
+        if (EPI == EPI_PARTIAL) {
+            float* o = a.out + ((size_t)ks * a.m_stride + row) * a.N;
+#pragma unroll
+            for (int i = 0; i < NBW; ++i)
+                if (i < nvalid)
+                    *(float4*)(o + (nb0 + i) * 16 + col4) =
+                        make_float4(acc[i][m][0], acc[i][m][1], acc[i][m][2], acc[i][m][3]);
+        } else {
+#pragma unroll
+            for (int i = 0; i + 1 < NBW; i += 2)
                 if (i + 1 < nvalid) {
                     const int f = ((nb0 + i) >> 1) * 16 + col4;
                     bf16_t o[4], ol[4];
@@ -843,22 +1027,47 @@ void launch_rmsnorm(const MbState& st, float* x, const float* part, int ksplit, 
                        part ? ksplit : 0, part_stride, w, eps, sel, h_packed, h_packed_lo, d);
 }
 
-// Launch shape of a projection.  Skinny kernel (<= 64 rows), from sweeps on the 7B shapes: aim at 512+
-// workgroups; 4 strips per workgroup halve the activation re-reads and win when k is short, 2 strips when
-// k is long or when the epilogue forbids k-slices (SwiGLU, logits); k-slices double until there are 512
-// workgroups, at most 8, never leaving a wave fewer than 4 k-blocks.  Tiled kernel: ksplit fills the chip
-// when there are few 64x256 tiles.
-GemmPlan gemm_plan(int N, int Kp, int m_rows, int epilogue)
+// Launch shape of a projection.
+// Sweep kernel (<= 64 rows, at least 256 KiB of weights per compute unit and row strip; below that the launch is
+// too short to amortise its start-up and the skinny kernel's finer split wins): one workgroup per compute unit and
+// k-slice, a wave per output strip (per gate/up strip pair with the SwiGLU epilogue).  k-slices double
+// until every workgroup has about 3 waves of work, as far as the epilogue allows them, never below 16
+// k-blocks per slice; a workgroup has 4 or 8 waves, and when 8 are not enough there are more workgroups.
+// Skinny kernel (<= 64 rows otherwise), from sweeps on the 7B shapes: aim at 512+ workgroups; 4 strips per
+// workgroup halve the activation re-reads and win when k is short, 2 strips when k is long or when the
+// epilogue forbids k-slices (SwiGLU, logits); k-slices double until there are 512 workgroups, at most 8,
+// never leaving a wave fewer than 4 k-blocks.  Tiled kernel: ksplit fills the chip when there are few
+// 64x256 tiles.
+static int g_gemm_mode = 0;
+void set_gemm_mode(int mode) { g_gemm_mode = mode; }
+
+GemmPlan gemm_plan(int N, int Kp, int m_rows, int epilogue, int n_cu, int max_ksplit)
 {
-    GemmPlan p{1, 2, 4, 1};
+    GemmPlan p{1, 2, 4, 1, 0, 0};
     const int KB = Kp / 32;
+    if (epilogue == EPI_SWIGLU) max_ksplit = m_rows <= 64 ? 1 : max_ksplit;   // fused epilogue: no k-slices
     if (m_rows <= 64) {
+        const size_t w_per_cu = (size_t)N * (size_t)Kp * 2 / (size_t)n_cu;
+        const size_t mt_rows = (size_t)(m_rows + 15) / 16;   // activation re-reads grow with the row strips: sweep earlier
+        if (g_gemm_mode == 2 || (g_gemm_mode == 0 && w_per_cu * mt_rows >= ((size_t)256 << 10))) {
+            const int nbw = epilogue == EPI_SWIGLU ? 2 : 1;
+            const int units = (N / 16 + nbw - 1) / nbw;
+            while (units * p.ksplit < 3 * n_cu && p.ksplit * 2 <= max_ksplit && p.ksplit < 8 && KB / (p.ksplit * 2) >= 16)
+                p.ksplit *= 2;
+            int gn = std::max(1, std::min(units, n_cu / p.ksplit));
+            if ((units + gn - 1) / gn > 8) gn = (units + 7) / 8;
+            p.sweep_p = (units + gn - 1) / gn <= 4 ? 4 : 8;
+            p.sweep_gn = gn;
+            return p;
+        }
         const int mt = (m_rows + 15) / 16;
         p.kd = mt == 1 ? 4 : 2;
-        if (epilogue == EPI_SWIGLU) return p;   // fused epilogue: no k-slices
+        if (max_ksplit == 1 && epilogue == EPI_SWIGLU) return p;
         p.nb = (mt == 1 && KB > 256) ? 2 : 4;   // with several row strips the activation re-reads dominate: 4 strips
+        if (max_ksplit == 1 && mt == 1) p.nb = 2;
         const int groups = (N / 16 + p.nb - 1) / p.nb;
-        while (groups * p.ksplit < 512 && p.ksplit < 8 && KB / (p.ksplit * 2 * 4) >= 4) p.ksplit *= 2;
+        while (groups * p.ksplit < 512 && p.ksplit * 2 <= max_ksplit && p.ksplit < 8 && KB / (p.ksplit * 2 * 4) >= 4)
+            p.ksplit *= 2;
         return p;
     }
     // Tiled kernel.  Many tiles (prompt forwards): 4-wave workgroups, two per CU, no slicing.  Few tiles
@@ -867,7 +1076,7 @@ GemmPlan gemm_plan(int N, int Kp, int m_rows, int epilogue)
     // 8-wave workgroup halves the k range inside the workgroup instead.
     const int tiles = ((N + 255) / 256) * ((m_rows + 63) / 64);
     if (tiles >= 512) return p;
-    while (tiles * p.ksplit < 512 && p.ksplit < 4 && KB / (p.ksplit * 2) >= 16) p.ksplit *= 2;
+    while (tiles * p.ksplit < 512 && p.ksplit * 2 <= max_ksplit && p.ksplit < 4 && KB / (p.ksplit * 2) >= 16) p.ksplit *= 2;
     if (p.ksplit == 1) p.kp = 2;
     return p;
 }
@@ -900,9 +1109,38 @@ static void launch_skinny_mt(const GemmArgs& a, hipStream_t s)
     }
 }
 
+template <int P, int MT, int EPI>
+static void launch_sweep_inst(const GemmArgs& a, int units, hipStream_t s)
+{
+    constexpr int NBW = EPI == EPI_SWIGLU ? 2 : 1;
+    const int KB = a.Kp / 32;
+    const int kbs = (KB + a.ksplit - 1) / a.ksplit;
+    hipLaunchKernelGGL((k_gemm_sweep<P, MT, NBW, EPI>), dim3(a.sweep_gn * a.ksplit), dim3(64 * P), 0, s, a, units,
+                       a.sweep_gn, kbs);
+}
+
+template <int P, int EPI>
+static void launch_sweep_p(const GemmArgs& a, int units, hipStream_t s)
+{
+    switch ((a.m_rows + 15) / 16) {
+        case 1: launch_sweep_inst<P, 1, EPI>(a, units, s); break;
+        case 2: launch_sweep_inst<P, 2, EPI>(a, units, s); break;
+        case 3: launch_sweep_inst<P, 3, EPI>(a, units, s); break;
+        default: launch_sweep_inst<P, 4, EPI>(a, units, s); break;
+    }
+}
+
 template <int EPI>
 static void launch_gemm_epi(const GemmArgs& a, hipStream_t s)
 {
+    if (a.m_rows <= 64 && a.sweep_p > 0 && a.sweep_gn > 0 && a.zero_blk) {
+        const int nbw = EPI == EPI_SWIGLU ? 2 : 1;
+        const int units = (a.N / 16 + nbw - 1) / nbw;
+        const int per = (units + a.sweep_gn - 1) / a.sweep_gn;   // most units any workgroup owns
+        if (a.sweep_p == 4 && per <= 4) return launch_sweep_p<4, EPI>(a, units, s);
+        if (per <= 8) return launch_sweep_p<8, EPI>(a, units, s);
+        // a plan this kernel cannot run falls through to the skinny kernel
+    }
     if (a.m_rows <= 64) {
         const int mt = (a.m_rows + 15) / 16;
         switch (mt) {

@@ -121,6 +121,26 @@ def test_tiny_decode_logits_teacher_forced(tiny, rows):
     check_logits(got, ref, f"tiny decode B={rows}")
 
 
+@pytest.mark.parametrize("mode", [1, 2])
+@pytest.mark.parametrize("rows", [1, 16, 23, 40, 64])
+def test_tiny_decode_logits_each_small_batch_projection_kernel(tiny, rows, mode):
+    """Both kernels for projections of at most 64 rows, forced for every projection: the k-splitting one
+    (mode 1) and the one that stages activations once per workgroup (mode 2), here with fewer strips than
+    compute units, idle waves, 1-4 row strips and a k range (ffn 688 -> 22 k-blocks) that ends inside a chunk."""
+    W, om, gw = tiny
+    rng = np.random.default_rng(300 + rows)
+    w = synth.make_group(synth.TINY, rows, 555 + rows, ("uniform", 3, 40), ("uniform", 1, 8), None, 8, 0, ())
+    toks, offs, npr = forced_batch(w, range(rows), rng.integers(0, 5, size=rows), rng)
+    ref = oracle_forced_logits(om, toks, offs, npr)
+    _say(f"tiny teacher-forced decode, {rows} rows, projection kernel mode {mode}")
+    ss.ss_set_gemm_mode(mode)
+    try:
+        got = ss.ss_forward_logits(gw, toks, offs, npr)
+    finally:
+        ss.ss_set_gemm_mode(0)
+    check_logits(got, ref, f"tiny decode B={rows} mode={mode}")
+
+
 def test_f32_source_weights_are_rounded_like_the_generator(tiny):
     """Config 1 ships fp32 weights: the library rounds them to bf16 (nearest even) at load."""
     W, om, gw = tiny
@@ -159,6 +179,23 @@ def test_wide_logits_teacher_forced(wide2):
     got = ss.ss_forward_logits(gw, toks, offs, npr)
     ref = oracle_forced_logits(om, toks, offs, npr)
     check_logits(got, ref, "wide2 prompt+decode")
+
+
+@pytest.mark.parametrize("mode", [1, 2])
+def test_wide_decode_logits_each_small_batch_projection_kernel(wide2, mode):
+    """7B widths, 20 rows (two row strips, the second ragged): every projection through one kernel, then the other."""
+    shape, W, om, gw = wide2
+    rng = np.random.default_rng(18)
+    w = synth.make_workload(2, n=20, shape=shape)
+    toks, offs, npr = forced_batch(w, range(20), [2] * 20, rng)
+    ref = oracle_forced_logits(om, toks, offs, npr)
+    _say(f"7B-width x2 layers, 20 rows, projection kernel mode {mode}")
+    ss.ss_set_gemm_mode(mode)
+    try:
+        got = ss.ss_forward_logits(gw, toks, offs, npr)
+    finally:
+        ss.ss_set_gemm_mode(0)
+    check_logits(got, ref, f"wide2 B=20 mode={mode}")
 
 
 def test_wide_prompt_forward_through_tiled_kernel(wide2):
