@@ -130,6 +130,9 @@ def main() -> int:
     ap.add_argument("--step-iters", type=int, default=20, help="decode-step timing iterations")
     ap.add_argument("--step-rows", type=int, default=16, help="rows of the timed decode step (roofline legs)")
     ap.add_argument("--step-ctx", type=int, default=200, help="context length of the timed decode step")
+    ap.add_argument("--gemm-mode", type=int, default=0, choices=[0, 1, 2],
+                    help="small-batch projection kernel: 0 chosen per shape, 1 always k_gemm_skinny, 2 always k_gemm_sweep "
+                         "(for A/B profiles; anything but 0 is reported in config)")
     ap.add_argument("--ablation", action="store_true",
                     help="instead of the headline run: the paper's Table 5 ablation (Binning x FCR x VBS), a perfect "
                          "predictor and compaction on the same group, one pass each; prints one JSON line per row")
@@ -149,6 +152,7 @@ def main() -> int:
     from paper_2305_13144_amd import synth
 
     ss.lib()  # fail loudly if the HIP library is missing
+    ss.ss_set_gemm_mode(a.gemm_mode)
     ss.ss_set_verbose(1 if (a.cfg >= 4 or a.ablation or a.sweep) else 0)   # long groups: a progress line per micro-batch
     wl = synth.make_workload(a.cfg)
     shape = wl.shape if a.layers <= 0 else wl.shape.with_layers(a.layers)
@@ -233,7 +237,7 @@ def main() -> int:
     ach = wbytes / (ms_w.mean() * 1e-3) / 1e9
     # HBM bytes per launch from the FETCH_SIZE + WRITE_SIZE counter runs of this same command (7B shape only;
     # the figures and the copy-kernel scale factors are in profiles/decode_step_7b_hbm_traffic.txt)
-    traffic = (13617.4e6 + 225.9e6) / 129 if shape.name == "llama7b" else None
+    traffic = (13609.8e6 + 150.4e6) / 129 if shape.name == "llama7b" and a.gemm_mode == 0 and B0 == 16 else None
     roofline = dict(bound="hbm", kernel=f"k_gemm_sweep + k_gemm_skinny (all projection launches of one {B0}-row decode step)",
                     achieved=ach, peak=HBM_PEAK_GBS, unit="GB/s", frac=ach / HBM_PEAK_GBS, traffic=traffic,
                     launches_per_step=launches, avg_launch_us=ms_w.mean() * 1e3 / launches,
@@ -290,7 +294,8 @@ def main() -> int:
                            padded_row_steps=st["padded_row_steps"], computed_row_steps=st["computed_row_steps"],
                            n_failed=st["n_failed"], micro_batches=[st["n_mb_first"], st["n_mb_failure"]],
                            samples_per_s=(wl.n * a.steps / dt if a.steps else 0.0), prefill_ms=st["prefill_ms"], decode_ms=st["decode_ms"],
-                           plan_ms=st["plan_ms"], **({"reduced_layers": a.layers} if a.layers > 0 else {})),
+                           plan_ms=st["plan_ms"], **({"reduced_layers": a.layers} if a.layers > 0 else {}),
+                           **({"gemm_mode": a.gemm_mode} if a.gemm_mode else {})),
                roofline=roofline, cpu_baseline=cpu, paper_context=PAPER_CONTEXT, **extras)
     print(json.dumps(out))
     return 0

@@ -348,8 +348,11 @@ __device__ __forceinline__ void sweep_load_w(SweepSlot<NBW, KC>& f, const u32x4*
         const int kk = min(kb + q, kend - 1);
 #pragma unroll
         for (int i = 0; i < NBW; ++i) {
-            const u32x4* p = (live && i < nvalid) ? Wl + ((size_t)(nb0 + i) * KB + kk) * 64 : Zl;
-            f.w[i][q] = __builtin_nontemporal_load(p);
+            // weights or the zero block: selected by address arithmetic (a select between two pointers can be
+            // compiled into a branch around the load)
+            const uintptr_t wp = (uintptr_t)(Wl + ((size_t)(nb0 + i) * KB + kk) * 64), zp = (uintptr_t)Zl;
+            const uintptr_t mask = (live && i < nvalid) ? ~(uintptr_t)0 : (uintptr_t)0;
+            f.w[i][q] = __builtin_nontemporal_load((const u32x4*)(zp ^ ((wp ^ zp) & mask)));
         }
     }
 }
@@ -409,6 +412,52 @@ __device__ __forceinline__ void sweep_mma(const SweepSlot<NBW, KC>& f, const u32
     }
 }
 
+// The k sweep of one wave.  ACTIVE = false is a wave without a unit (the workgroup got fewer than P): it only
+// moves its share of the activation chunks and keeps the barriers; weight loads for it, even of the zero
+// block, would take their share of the compute unit's memory requests.  The two variants are separate
+// straight-line loops, chosen once per wave, because a load under a branch inside the loop would make
+// every wait there cover all loads in flight.
+template <bool ACTIVE, int P, int MT, int NBW, int KC>
+__device__ __forceinline__ void sweep_run(u32x4* xl0, u32x4* xl1, f32x4 (&acc)[NBW][MT],
+                                          const u32x4* __restrict__ Wl, const u32x4* __restrict__ Zl,
+                                          const u32x4* __restrict__ X, const u32x4* __restrict__ Xlo, int KB, int nb0,
+                                          int nvalid, int s0, int s1, int C, int lane)
+{
+    SweepSlot<NBW, KC> fa, fb;
+    SweepStage<P, MT, KC> xs;
+    sweep_load_x<P, MT, KC>(xs, X, Xlo, KB, s0, s1);
+    if (ACTIVE) sweep_load_w<NBW, KC>(fa, Wl, Zl, KB, nb0, nvalid, s0, s1);
+    __builtin_amdgcn_sched_barrier(0);
+    sweep_store_x<P, MT, KC>(xs, xl0);
+    __builtin_amdgcn_sched_barrier(0);
+    sweep_load_x<P, MT, KC>(xs, X, Xlo, KB, s0 + KC, s1);
+    if (ACTIVE) sweep_load_w<NBW, KC>(fb, Wl, Zl, KB, nb0, nvalid, s0 + KC, s1);
+    __builtin_amdgcn_sched_barrier(0);
+    __syncthreads();
+    // Two chunks per trip (slot fa with LDS buffer 0, slot fb with buffer 1).  Within a chunk: contract it,
+    // write the next chunk's activations (loaded one chunk ago) into the other buffer, start the loads of
+    // the chunk after that, barrier.  A buffer is rewritten one barrier after its last read.
+    for (int c = 0; c < C; c += 2) {
+        const int k2 = s0 + (c + 2) * KC, k3 = k2 + KC;
+        if (ACTIVE) sweep_mma<MT, NBW, KC>(fa, xl0, lane, acc);
+        __builtin_amdgcn_sched_barrier(0);
+        sweep_store_x<P, MT, KC>(xs, xl1);
+        __builtin_amdgcn_sched_barrier(0);
+        sweep_load_x<P, MT, KC>(xs, X, Xlo, KB, k2, s1);
+        if (ACTIVE) sweep_load_w<NBW, KC>(fa, Wl, Zl, KB, nb0, nvalid, k2, s1);
+        __builtin_amdgcn_sched_barrier(0);
+        __syncthreads();
+        if (ACTIVE) sweep_mma<MT, NBW, KC>(fb, xl1, lane, acc);
+        __builtin_amdgcn_sched_barrier(0);
+        sweep_store_x<P, MT, KC>(xs, xl0);
+        __builtin_amdgcn_sched_barrier(0);
+        sweep_load_x<P, MT, KC>(xs, X, Xlo, KB, k3, s1);
+        if (ACTIVE) sweep_load_w<NBW, KC>(fb, Wl, Zl, KB, nb0, nvalid, k3, s1);
+        __builtin_amdgcn_sched_barrier(0);
+        __syncthreads();
+    }
+}
+
 // Grid: n_gn workgroups per k-slice x ksplit; workgroup gn of a slice owns units [gn*n_units/n_gn,
 // (gn+1)*n_units/n_gn) (a unit = NBW consecutive strips; at most P of them, checked by the launcher), one per wave.
 template <int P, int MT, int NBW, int EPI>
@@ -422,9 +471,9 @@ __global__ __launch_bounds__(64 * P) void k_gemm_sweep(GemmArgs a, int n_units, 
     const int s0 = ks * kb_per_slice, s1 = min(KB, s0 + kb_per_slice);
     const int u0 = (int)((long long)gn * n_units / n_gn), u1 = (int)((long long)(gn + 1) * n_units / n_gn);
     const int unit = u0 + wave;
-    const bool active = unit < u1;
     const int nb0 = unit * NBW;
-    const int nvalid = active ? max(min(NBW, NBT - nb0), 0) : 0;
+    const int nvalid = unit < u1 ? max(min(NBW, NBT - nb0), 0) : 0;
+    const bool active = nvalid > 0;   // wave-uniform
 
     f32x4 acc[NBW][MT];
 #pragma unroll
@@ -438,39 +487,10 @@ __global__ __launch_bounds__(64 * P) void k_gemm_sweep(GemmArgs a, int n_units, 
     const u32x4* Xlo = (const u32x4*)a.X_lo;
     const int C = (s1 - s0 + KC - 1) / KC;   // chunks of this slice: the same for every wave of the workgroup
     if (C > 0) {
-        SweepSlot<NBW, KC> fa, fb;
-        SweepStage<P, MT, KC> xs;
-        sweep_load_x<P, MT, KC>(xs, X, Xlo, KB, s0, s1);
-        sweep_load_w<NBW, KC>(fa, Wl, Zl, KB, nb0, nvalid, s0, s1);
-        __builtin_amdgcn_sched_barrier(0);
-        sweep_store_x<P, MT, KC>(xs, xlds[0]);
-        __builtin_amdgcn_sched_barrier(0);
-        sweep_load_x<P, MT, KC>(xs, X, Xlo, KB, s0 + KC, s1);
-        sweep_load_w<NBW, KC>(fb, Wl, Zl, KB, nb0, nvalid, s0 + KC, s1);
-        __builtin_amdgcn_sched_barrier(0);
-        __syncthreads();
-        // Two chunks per trip (slot fa with LDS buffer 0, slot fb with buffer 1).  Within a chunk: contract it,
-        // write the next chunk's activations (loaded one chunk ago) into the other buffer, start the loads of
-        // the chunk after that, barrier.  A buffer is rewritten one barrier after its last read.
-        for (int c = 0; c < C; c += 2) {
-            const int k2 = s0 + (c + 2) * KC, k3 = k2 + KC;
-            sweep_mma<MT, NBW, KC>(fa, xlds[0], lane, acc);
-            __builtin_amdgcn_sched_barrier(0);
-            sweep_store_x<P, MT, KC>(xs, xlds[1]);
-            __builtin_amdgcn_sched_barrier(0);
-            sweep_load_x<P, MT, KC>(xs, X, Xlo, KB, k2, s1);
-            sweep_load_w<NBW, KC>(fa, Wl, Zl, KB, nb0, nvalid, k2, s1);
-            __builtin_amdgcn_sched_barrier(0);
-            __syncthreads();
-            sweep_mma<MT, NBW, KC>(fb, xlds[1], lane, acc);
-            __builtin_amdgcn_sched_barrier(0);
-            sweep_store_x<P, MT, KC>(xs, xlds[0]);
-            __builtin_amdgcn_sched_barrier(0);
-            sweep_load_x<P, MT, KC>(xs, X, Xlo, KB, k3, s1);
-            sweep_load_w<NBW, KC>(fb, Wl, Zl, KB, nb0, nvalid, k3, s1);
-            __builtin_amdgcn_sched_barrier(0);
-            __syncthreads();
-        }
+        if (active)
+            sweep_run<true, P, MT, NBW, KC>(xlds[0], xlds[1], acc, Wl, Zl, X, Xlo, KB, nb0, nvalid, s0, s1, C, lane);
+        else
+            sweep_run<false, P, MT, NBW, KC>(xlds[0], xlds[1], acc, Wl, Zl, X, Xlo, KB, nb0, nvalid, s0, s1, C, lane);
     }
     if (!active) return;
 
