@@ -33,9 +33,10 @@ const char* ss_last_error(void);
  * take minutes); level 0 (default) prints nothing.  Process-wide. */
 void ss_set_verbose(int32_t level);
 
-/* Testing aid: which kernel runs the projections of at most 64 token-rows.  0 (default): chosen per shape;
- * 1: always the kernel whose waves split the k range; 2: always the kernel that stages activations once per
- * workgroup.  Results agree to fp32 rounding order.  Process-wide; other values are ignored. */
+/* Testing aid: which kernel runs the projections of small batches.  0 (default): chosen per shape and row
+ * count; 1: never the kernel that stages activations once per workgroup (then: the k-splitting kernel up to 64
+ * token-rows, the tiled kernel above); 2: that kernel for every projection of at most 128 token-rows.
+ * Results agree to fp32 rounding order.  Process-wide; other values are ignored. */
 void ss_set_gemm_mode(int32_t mode);
 
 /* ------------------------------------------------------------------ scheduler (host only) */

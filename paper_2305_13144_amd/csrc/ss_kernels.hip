@@ -463,7 +463,7 @@ __device__ __forceinline__ void sweep_run(u32x4* xl0, u32x4* xl1, f32x4 (&acc)[N
 template <int P, int MT, int NBW, int EPI>
 __global__ __launch_bounds__(64 * P) void k_gemm_sweep(GemmArgs a, int n_units, int n_gn, int kb_per_slice)
 {
-    constexpr int KC = 4;
+    constexpr int KC = MT > 4 ? 2 : 4;   // k-blocks per chunk: both LDS buffers together stay within 64 KiB
     __shared__ u32x4 xlds[2][SweepStage<P, MT, KC>::PIECES];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int gn = blockIdx.x % n_gn, ks = blockIdx.x / n_gn;
@@ -1048,7 +1048,7 @@ void launch_rmsnorm(const MbState& st, float* x, const float* part, int ksplit, 
 }
 
 // Launch shape of a projection.
-// Sweep kernel (<= 64 rows, at least 256 KiB of weights per compute unit and row strip; below that the launch is
+// Sweep kernel (<= 128 rows, at least 256 KiB of weights per compute unit and row strip; below that the launch is
 // too short to amortise its start-up and the skinny kernel's finer split wins): one workgroup per compute unit and
 // k-slice, a wave per output strip (per gate/up strip pair with the SwiGLU epilogue).  k-slices double
 // until every workgroup has about 3 waves of work, as far as the epilogue allows them, never below 16
@@ -1058,6 +1058,13 @@ void launch_rmsnorm(const MbState& st, float* x, const float* part, int ksplit, 
 // epilogue forbids k-slices (SwiGLU, logits); k-slices double until there are 512 workgroups, at most 8,
 // never leaving a wave fewer than 4 k-blocks.  Tiled kernel: ksplit fills the chip when there are few
 // 64x256 tiles.
+
+// Strips per wave of the sweep kernel: a gate/up pair for the SwiGLU epilogue; with 2 or more row strips also two,
+// so that an activation operand read from LDS feeds two weight strips (at 1 strip per wave the LDS reads of
+// 64 rows, 8 KiB per KiB of weights, bound the kernel; measured: 32 rows 8 % faster, 64 rows 7 %, 16 rows 1 % slower).
+static int sweep_nbw(int epilogue, int m_rows) { return (epilogue == EPI_SWIGLU || m_rows > 16) ? 2 : 1; }
+
+constexpr int kSweepMaxRows = 128;   // 8 row strips: accumulators and the LDS chunk still fit
 static int g_gemm_mode = 0;
 void set_gemm_mode(int mode) { g_gemm_mode = mode; }
 
@@ -1065,12 +1072,12 @@ GemmPlan gemm_plan(int N, int Kp, int m_rows, int epilogue, int n_cu, int max_ks
 {
     GemmPlan p{1, 2, 4, 1, 0, 0};
     const int KB = Kp / 32;
-    if (epilogue == EPI_SWIGLU) max_ksplit = m_rows <= 64 ? 1 : max_ksplit;   // fused epilogue: no k-slices
-    if (m_rows <= 64) {
+    if (m_rows <= kSweepMaxRows) {
         const size_t w_per_cu = (size_t)N * (size_t)Kp * 2 / (size_t)n_cu;
         const size_t mt_rows = (size_t)(m_rows + 15) / 16;   // activation re-reads grow with the row strips: sweep earlier
         if (g_gemm_mode == 2 || (g_gemm_mode == 0 && w_per_cu * mt_rows >= ((size_t)256 << 10))) {
-            const int nbw = epilogue == EPI_SWIGLU ? 2 : 1;
+            if (epilogue == EPI_SWIGLU) max_ksplit = 1;   // fused epilogue: no k-slices
+            const int nbw = sweep_nbw(epilogue, m_rows);
             const int units = (N / 16 + nbw - 1) / nbw;
             while (units * p.ksplit < 3 * n_cu && p.ksplit * 2 <= max_ksplit && p.ksplit < 8 && KB / (p.ksplit * 2) >= 16)
                 p.ksplit *= 2;
@@ -1080,6 +1087,9 @@ GemmPlan gemm_plan(int N, int Kp, int m_rows, int epilogue, int n_cu, int max_ks
             p.sweep_gn = gn;
             return p;
         }
+    }
+    if (m_rows <= 64) {
+        if (epilogue == EPI_SWIGLU) max_ksplit = 1;   // fused epilogue: no k-slices
         const int mt = (m_rows + 15) / 16;
         p.kd = mt == 1 ? 4 : 2;
         if (max_ksplit == 1 && epilogue == EPI_SWIGLU) return p;
@@ -1132,7 +1142,7 @@ static void launch_skinny_mt(const GemmArgs& a, hipStream_t s)
 template <int P, int MT, int EPI>
 static void launch_sweep_inst(const GemmArgs& a, int units, hipStream_t s)
 {
-    constexpr int NBW = EPI == EPI_SWIGLU ? 2 : 1;
+    constexpr int NBW = (EPI == EPI_SWIGLU || MT > 1) ? 2 : 1;
     const int KB = a.Kp / 32;
     const int kbs = (KB + a.ksplit - 1) / a.ksplit;
     hipLaunchKernelGGL((k_gemm_sweep<P, MT, NBW, EPI>), dim3(a.sweep_gn * a.ksplit), dim3(64 * P), 0, s, a, units,
@@ -1146,20 +1156,24 @@ static void launch_sweep_p(const GemmArgs& a, int units, hipStream_t s)
         case 1: launch_sweep_inst<P, 1, EPI>(a, units, s); break;
         case 2: launch_sweep_inst<P, 2, EPI>(a, units, s); break;
         case 3: launch_sweep_inst<P, 3, EPI>(a, units, s); break;
-        default: launch_sweep_inst<P, 4, EPI>(a, units, s); break;
+        case 4: launch_sweep_inst<P, 4, EPI>(a, units, s); break;
+        case 5: launch_sweep_inst<P, 5, EPI>(a, units, s); break;
+        case 6: launch_sweep_inst<P, 6, EPI>(a, units, s); break;
+        case 7: launch_sweep_inst<P, 7, EPI>(a, units, s); break;
+        default: launch_sweep_inst<P, 8, EPI>(a, units, s); break;
     }
 }
 
 template <int EPI>
 static void launch_gemm_epi(const GemmArgs& a, hipStream_t s)
 {
-    if (a.m_rows <= 64 && a.sweep_p > 0 && a.sweep_gn > 0 && a.zero_blk) {
-        const int nbw = EPI == EPI_SWIGLU ? 2 : 1;
+    if (a.m_rows <= kSweepMaxRows && a.sweep_p > 0 && a.sweep_gn > 0 && a.zero_blk) {
+        const int nbw = sweep_nbw(EPI, a.m_rows);
         const int units = (a.N / 16 + nbw - 1) / nbw;
         const int per = (units + a.sweep_gn - 1) / a.sweep_gn;   // most units any workgroup owns
         if (a.sweep_p == 4 && per <= 4) return launch_sweep_p<4, EPI>(a, units, s);
         if (per <= 8) return launch_sweep_p<8, EPI>(a, units, s);
-        // a plan this kernel cannot run falls through to the skinny kernel
+        // a plan this kernel cannot run falls through to the other kernels
     }
     if (a.m_rows <= 64) {
         const int mt = (a.m_rows + 15) / 16;

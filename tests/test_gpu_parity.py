@@ -122,11 +122,12 @@ def test_tiny_decode_logits_teacher_forced(tiny, rows):
 
 
 @pytest.mark.parametrize("mode", [1, 2])
-@pytest.mark.parametrize("rows", [1, 16, 23, 40, 64])
+@pytest.mark.parametrize("rows", [1, 16, 23, 40, 64, 70, 100, 128])
 def test_tiny_decode_logits_each_small_batch_projection_kernel(tiny, rows, mode):
-    """Both kernels for projections of at most 64 rows, forced for every projection: the k-splitting one
-    (mode 1) and the one that stages activations once per workgroup (mode 2), here with fewer strips than
-    compute units, idle waves, 1-4 row strips and a k range (ffn 688 -> 22 k-blocks) that ends inside a chunk."""
+    """Both kernels for small-batch projections, forced for every projection: the k-splitting one (mode 1; the
+    tiled kernel above 64 rows) and the one that stages activations once per workgroup (mode 2, up to 128
+    rows), here with fewer strips than compute units, idle waves, 1-8 row strips with ragged tails and a k
+    range (ffn 688 -> 22 k-blocks) that ends inside a chunk."""
     W, om, gw = tiny
     rng = np.random.default_rng(300 + rows)
     w = synth.make_group(synth.TINY, rows, 555 + rows, ("uniform", 3, 40), ("uniform", 1, 8), None, 8, 0, ())
