@@ -1051,7 +1051,7 @@ void launch_rmsnorm(const MbState& st, float* x, const float* part, int ksplit, 
 // Sweep kernel (<= 128 rows, at least 256 KiB of weights per compute unit and row strip; below that the launch is
 // too short to amortise its start-up and the skinny kernel's finer split wins): one workgroup per compute unit and
 // k-slice, a wave per output strip (per gate/up strip pair with the SwiGLU epilogue).  k-slices double
-// until every workgroup has about 3 waves of work, as far as the epilogue allows them, never below 16
+// until every workgroup has 4 or more waves of work, as far as the epilogue allows them, never below 16
 // k-blocks per slice; a workgroup has 4 or 8 waves, and when 8 are not enough there are more workgroups.
 // Skinny kernel (<= 64 rows otherwise), from sweeps on the 7B shapes: aim at 512+ workgroups; 4 strips per
 // workgroup halve the activation re-reads and win when k is short, 2 strips when k is long or when the
@@ -1079,7 +1079,7 @@ GemmPlan gemm_plan(int N, int Kp, int m_rows, int epilogue, int n_cu, int max_ks
             if (epilogue == EPI_SWIGLU) max_ksplit = 1;   // fused epilogue: no k-slices
             const int nbw = sweep_nbw(epilogue, m_rows);
             const int units = (N / 16 + nbw - 1) / nbw;
-            while (units * p.ksplit < 3 * n_cu && p.ksplit * 2 <= max_ksplit && p.ksplit < 8 && KB / (p.ksplit * 2) >= 16)
+            while (units * p.ksplit < 4 * n_cu && p.ksplit * 2 <= max_ksplit && p.ksplit < 8 && KB / (p.ksplit * 2) >= 16)
                 p.ksplit *= 2;
             int gn = std::max(1, std::min(units, n_cu / p.ksplit));
             if ((units + gn - 1) / gn > 8) gn = (units + 7) / 8;
