@@ -133,9 +133,18 @@ __global__ __launch_bounds__(1024) void k_rmsnorm(const int32_t* __restrict__ d_
                                                   bf16_t* __restrict__ h_lo, int d)
 {
     const int j = blockIdx.x;
-    if (j >= *d_count) return;
-    const int src = sel ? sel[j] : j;
+    // The row count, the row, its partial sums and the norm weights are all requested before anything waits:
+    // the kernel is a chain of dependent round trips otherwise (count, then the row, then the weights), and its
+    // whole cost is latency.  Rows at or beyond the count are loaded as well (the buffers are sized for the grid)
+    // and dropped before the first store; with a selection list the index itself is only valid below the count.
+    const int count = *d_count;
+    int src = j;
+    if (sel) {
+        if (j >= count) return;
+        src = sel[j];
+    }
     float4 v[2];
+    uint2 wr[2];
     float ss = 0.f;
 #pragma unroll
     for (int it = 0; it < 2; ++it) {
@@ -147,11 +156,19 @@ __global__ __launch_bounds__(1024) void k_rmsnorm(const int32_t* __restrict__ d_
             for (int s = 0; s < kNormMaxSplit; ++s)
                 p[s] = s < ksplit ? *(const float4*)(part + (size_t)s * part_stride + (size_t)src * d + c)
                                   : make_float4(0.f, 0.f, 0.f, 0.f);
+            wr[it] = *(const uint2*)(w + c);
 #pragma unroll
             for (int s = 0; s < kNormMaxSplit; ++s) { a.x += p[s].x; a.y += p[s].y; a.z += p[s].z; a.w += p[s].w; }
-            if (ksplit > 0 && !sel) *(float4*)(x + (size_t)src * d + c) = a;
             v[it] = a;
             ss += a.x * a.x + a.y * a.y + a.z * a.z + a.w * a.w;
+        }
+    }
+    if (j >= count) return;   // block-uniform
+    if (ksplit > 0 && !sel) {
+#pragma unroll
+        for (int it = 0; it < 2; ++it) {
+            const int c = threadIdx.x * 4 + it * 4096;
+            if (c < d) *(float4*)(x + (size_t)src * d + c) = v[it];
         }
     }
     __shared__ float red[16];
@@ -166,8 +183,7 @@ __global__ __launch_bounds__(1024) void k_rmsnorm(const int32_t* __restrict__ d_
     for (int it = 0; it < 2; ++it) {
         const int c = threadIdx.x * 4 + it * 4096;
         if (c < d) {
-            const uint2 wr = *(const uint2*)(w + c);
-            const bf16_t* wv = (const bf16_t*)&wr;
+            const bf16_t* wv = (const bf16_t*)&wr[it];
             bf16_t o[4], ol[4];
             split_bf(v[it].x * r * bf2f(wv[0]), o[0], ol[0]);
             split_bf(v[it].y * r * bf2f(wv[1]), o[1], ol[1]);
@@ -883,8 +899,11 @@ __global__ __launch_bounds__(256) void k_attention_decode(MbState st, const floa
     __shared__ float qs[HD];
     constexpr int HALF = HD / 2;
     const int j = blockIdx.x, h = blockIdx.y;
-    if (j >= *st.d_n) return;
+    // count, row and position are requested together (the tables are sized for the grid); only the loads that
+    // are indexed by the row wait for the count check
+    const int count = *st.d_n;
     const int row = st.tr_row[j], pos = st.tr_pos[j];
+    if (j >= count) return;
     const size_t base = (size_t)st.row_so[row] * d + (size_t)h * st.row_cap[row] * HD;
     const int which = threadIdx.x / HALF, e = threadIdx.x % HALF;   // 0 q, 1 k, 2 v
     if (which < 3) {
