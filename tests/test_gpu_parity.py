@@ -142,6 +142,33 @@ def test_tiny_decode_logits_each_small_batch_projection_kernel(tiny, rows, mode)
     check_logits(got, ref, f"tiny decode B={rows} mode={mode}")
 
 
+@pytest.mark.parametrize("rows", [16, 40, 100])
+def test_odd_shape_many_strips_per_workgroup(oracle_built, rows):
+    """A one-layer shape with a very wide MLP (ffn 16448 -> 1028 gate/up strip pairs, 514 k-blocks in the down
+    projection) and a large vocabulary (40000 -> 2500 strips): the activation-staging kernel with 8 waves per
+    workgroup and the SwiGLU epilogue, and with more workgroups than compute units, which none of the LLaMA
+    shapes reaches."""
+    shape = synth.ModelShape("wide-ffn", 1, 256, 4, 64, 16448, 40000)
+    W = synth.make_weights(shape, seed=11, norm_jitter=0.1, threads=4)
+    gw = ss.Weights(shape, W)
+    om = OracleModel(shape, W, "f64")
+    try:
+        rng = np.random.default_rng(400 + rows)
+        w = synth.make_group(shape, rows, 901 + rows, ("uniform", 3, 20), ("uniform", 1, 8), None, 8, 0, ())
+        toks, offs, npr = forced_batch(w, range(rows), rng.integers(0, 4, size=rows), rng)
+        ref = oracle_forced_logits(om, toks, offs, npr)
+        for mode in (0, 2):
+            _say(f"wide-ffn shape, {rows} rows, projection kernel mode {mode}")
+            ss.ss_set_gemm_mode(mode)
+            try:
+                got = ss.ss_forward_logits(gw, toks, offs, npr)
+            finally:
+                ss.ss_set_gemm_mode(0)
+            check_logits(got, ref, f"wide-ffn B={rows} mode={mode}")
+    finally:
+        gw.close()
+
+
 def test_f32_source_weights_are_rounded_like_the_generator(tiny):
     """Config 1 ships fp32 weights: the library rounds them to bf16 (nearest even) at load."""
     W, om, gw = tiny
