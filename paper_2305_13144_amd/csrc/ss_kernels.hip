@@ -337,8 +337,8 @@ __global__ __launch_bounds__(256) void k_gemm_skinny(GemmArgs a, int n_groups, i
 }
 
 // ------------------------------------------------------------------------------------------ sweep GEMM
-// Up to 64 token rows again, for projections large enough to give every compute unit one workgroup with several
-// waves of work.  What bounds a weight stream on this chip is the number of bytes a compute unit can have in
+// Up to 128 token rows (8 row strips), for projections large enough to give every compute unit one workgroup
+// with several waves of work.  What bounds a weight stream on this chip is the number of bytes a compute unit can have in
 // flight towards L2/HBM, and every byte requested through the vector memory path counts, also an activation
 // operand that hits in L2: in the kernel above, where each wave fetches its own activation operands, those
 // take a quarter of that budget (2 strips) or an eighth (4 strips).  Here the waves of a workgroup own
