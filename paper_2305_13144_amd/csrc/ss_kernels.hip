@@ -760,8 +760,9 @@ __global__ __launch_bounds__(256) void k_rope_append(MbState st, const float* __
 // and V are each streamed once, fully coalesced; a wave issues AU such loads before it consumes them, so
 // a context of a few hundred slots costs two or three memory round trips, not one per load.
 constexpr int kAttnUnroll = 8;
+constexpr int kAttnDecodeWaves = 8;   // waves per (row, head) workgroup of the decode kernel: 256 slots per round trip
 
-template <int HD>
+template <int HD, int NW>
 __device__ __forceinline__ void attend(const float* __restrict__ qs, float* __restrict__ sc, float* __restrict__ red,
                                        float (*__restrict__ oacc)[HD], const bf16_t* __restrict__ kbase,
                                        const bf16_t* __restrict__ vbase, int ctx, bf16_t* __restrict__ out,
@@ -778,16 +779,16 @@ __device__ __forceinline__ void attend(const float* __restrict__ qs, float* __re
     for (int e = 0; e < 8; ++e) q[e] = qs[sub * 8 + e];
 
     float mx = -3.0e38f;
-    for (int c0 = wave * KPW; c0 < ctx; c0 += 4 * KPW * AU) {
+    for (int c0 = wave * KPW; c0 < ctx; c0 += NW * KPW * AU) {
         uint4 raw[AU];
 #pragma unroll
         for (int u = 0; u < AU; ++u) {
-            const int s = c0 + u * 4 * KPW + kin;
+            const int s = c0 + u * NW * KPW + kin;
             raw[u] = s < ctx ? *(const uint4*)(kbase + (size_t)s * HD + sub * 8) : make_uint4(0, 0, 0, 0);
         }
 #pragma unroll
         for (int u = 0; u < AU; ++u) {
-            const int s = c0 + u * 4 * KPW + kin;
+            const int s = c0 + u * NW * KPW + kin;
             const bf16_t* kv = (const bf16_t*)&raw[u];
             float part = 0.f;
 #pragma unroll
@@ -805,30 +806,35 @@ __device__ __forceinline__ void attend(const float* __restrict__ qs, float* __re
     uint4 vraw[AU];
 #pragma unroll
     for (int u = 0; u < AU; ++u) {
-        const int s = wave * KPW + u * 4 * KPW + kin;
+        const int s = wave * KPW + u * NW * KPW + kin;
         vraw[u] = s < ctx ? *(const uint4*)(vbase + (size_t)s * HD + sub * 8) : make_uint4(0, 0, 0, 0);
     }
     mx = wave_max(mx);
     if (lane == 0) red[wave] = mx;
     __syncthreads();
-    mx = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    mx = red[0];
+#pragma unroll
+    for (int w = 1; w < NW; ++w) mx = fmaxf(mx, red[w]);
     float sum = 0.f;
-    for (int s = tid; s < ctx; s += 256) {
+    for (int s = tid; s < ctx; s += 64 * NW) {
         const float p = __expf(sc[s] - mx);
         sc[s] = p;
         sum += p;
     }
     sum = wave_sum(sum);
-    if (lane == 0) red[4 + wave] = sum;
+    if (lane == 0) red[NW + wave] = sum;
     __syncthreads();
-    const float inv = 1.f / (red[4] + red[5] + red[6] + red[7]);
+    float tot = 0.f;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) tot += red[NW + w];
+    const float inv = 1.f / tot;
 
     float o[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    for (int c0 = wave * KPW; c0 < ctx; c0 += 4 * KPW * AU) {
+    for (int c0 = wave * KPW; c0 < ctx; c0 += NW * KPW * AU) {
         uint4 raw[AU];
 #pragma unroll
         for (int u = 0; u < AU; ++u) {
-            const int s = c0 + u * 4 * KPW + kin;
+            const int s = c0 + u * NW * KPW + kin;
             if (c0 == wave * KPW)
                 raw[u] = vraw[u];
             else
@@ -836,7 +842,7 @@ __device__ __forceinline__ void attend(const float* __restrict__ qs, float* __re
         }
 #pragma unroll
         for (int u = 0; u < AU; ++u) {
-            const int s = c0 + u * 4 * KPW + kin;
+            const int s = c0 + u * NW * KPW + kin;
             const float p = s < ctx ? sc[s] : 0.f;
             const bf16_t* vv = (const bf16_t*)&raw[u];
 #pragma unroll
@@ -856,7 +862,10 @@ __device__ __forceinline__ void attend(const float* __restrict__ qs, float* __re
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             const int c = tid * 4 + e;
-            split_bf((oacc[0][c] + oacc[1][c] + oacc[2][c] + oacc[3][c]) * inv, r[e], rl[e]);
+            float t = 0.f;
+#pragma unroll
+            for (int w = 0; w < NW; ++w) t += oacc[w][c];
+            split_bf(t * inv, r[e], rl[e]);
         }
         const size_t at = pk_index(out_r, out_k0 + tid * 4, out_kp);
         *(uint2*)(out + at) = *(const uint2*)r;
@@ -880,22 +889,22 @@ __global__ __launch_bounds__(256) void k_attention(MbState st, const float* __re
     const size_t base = (size_t)st.row_so[row] * d + (size_t)h * st.row_cap[row] * HD;
     if (threadIdx.x < HD) qs[threadIdx.x] = qrot[(size_t)j * d + h * HD + threadIdx.x];
     __syncthreads();
-    attend<HD>(qs, sc, red, oacc, kc + base, vc + base, ctx, out, out_lo, j, h * HD, d);
+    attend<HD, 4>(qs, sc, red, oacc, kc + base, vc + base, ctx, out, out_lo, j, h * HD, d);
 }
 
 // Decode forwards: the (token-row, head) workgroup first finishes its own slice of the q|k|v projection
 // (sums the k-slices, rotates q and k at the row's position, appends k and v to the row's slab), then
 // attends.  Saves a launch and the round trip of q through HBM for every layer of every step.
 template <int HD>
-__global__ __launch_bounds__(256) void k_attention_decode(MbState st, const float* __restrict__ part, int ksplit,
+__global__ __launch_bounds__(64 * kAttnDecodeWaves) void k_attention_decode(MbState st, const float* __restrict__ part, int ksplit,
                                                           size_t part_stride, bf16_t* __restrict__ kc,
                                                           bf16_t* __restrict__ vc, const float* __restrict__ rcos,
                                                           const float* __restrict__ rsin, bf16_t* __restrict__ out,
                                                           bf16_t* __restrict__ out_lo, int d)
 {
     __shared__ float sc[kMaxPos];
-    __shared__ float red[8];
-    __shared__ float oacc[4][HD];
+    __shared__ float red[2 * kAttnDecodeWaves];
+    __shared__ float oacc[kAttnDecodeWaves][HD];
     __shared__ float qs[HD];
     constexpr int HALF = HD / 2;
     const int j = blockIdx.x, h = blockIdx.y;
@@ -936,7 +945,7 @@ __global__ __launch_bounds__(256) void k_attention_decode(MbState st, const floa
         }
     }
     __syncthreads();   // the new key/value slot and q are visible to the whole workgroup
-    attend<HD>(qs, sc, red, oacc, kc + base, vc + base, pos + 1, out, out_lo, j, h * HD, d);
+    attend<HD, kAttnDecodeWaves>(qs, sc, red, oacc, kc + base, vc + base, pos + 1, out, out_lo, j, h * HD, d);
 }
 
 // ------------------------------------------------------------------------------------------ argmax
@@ -1236,10 +1245,10 @@ void launch_attention_decode(const MbState& st, const float* qkv_part, int kspli
                              bf16_t* out_packed, bf16_t* out_packed_lo, int d, int H, int hd, int n_max, hipStream_t s)
 {
     if (hd == 128)
-        hipLaunchKernelGGL((k_attention_decode<128>), dim3(n_max, H), dim3(256), 0, s, st, qkv_part, ksplit,
+        hipLaunchKernelGGL((k_attention_decode<128>), dim3(n_max, H), dim3(64 * kAttnDecodeWaves), 0, s, st, qkv_part, ksplit,
                            part_stride, kcache, vcache, rope_cos, rope_sin, out_packed, out_packed_lo, d);
     else
-        hipLaunchKernelGGL((k_attention_decode<64>), dim3(n_max, H), dim3(256), 0, s, st, qkv_part, ksplit,
+        hipLaunchKernelGGL((k_attention_decode<64>), dim3(n_max, H), dim3(64 * kAttnDecodeWaves), 0, s, st, qkv_part, ksplit,
                            part_stride, kcache, vcache, rope_cos, rope_sin, out_packed, out_packed_lo, d);
 }
 
