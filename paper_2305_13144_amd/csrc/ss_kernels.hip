@@ -1076,8 +1076,9 @@ void launch_rmsnorm(const MbState& st, float* x, const float* part, int ksplit, 
 }
 
 // Launch shape of a projection.
-// Sweep kernel (<= 128 rows, at least 256 KiB of weights per compute unit and row strip; below that the launch is
-// too short to amortise its start-up and the skinny kernel's finer split wins): one workgroup per compute unit and
+// Sweep kernel (<= 128 rows, at least 160 KiB of weights per compute unit and row strip; below that the launch is
+// too short to amortise its start-up and the skinny kernel's finer split wins: measured at 16 rows, the 7B o
+// projection, 131 KiB per unit, is 12 % faster in the skinny kernel, the 13B one, 205 KiB, 30 % faster here): one workgroup per compute unit and
 // k-slice, a wave per output strip (per gate/up strip pair with the SwiGLU epilogue).  k-slices double
 // until every workgroup has 4 or more waves of work, as far as the epilogue allows them, never below 16
 // k-blocks per slice; a workgroup has 4 or 8 waves, and when 8 are not enough there are more workgroups.
@@ -1103,7 +1104,7 @@ GemmPlan gemm_plan(int N, int Kp, int m_rows, int epilogue, int n_cu, int max_ks
     if (m_rows <= kSweepMaxRows) {
         const size_t w_per_cu = (size_t)N * (size_t)Kp * 2 / (size_t)n_cu;
         const size_t mt_rows = (size_t)(m_rows + 15) / 16;   // activation re-reads grow with the row strips: sweep earlier
-        if (g_gemm_mode == 2 || (g_gemm_mode == 0 && w_per_cu * mt_rows >= ((size_t)256 << 10))) {
+        if (g_gemm_mode == 2 || (g_gemm_mode == 0 && w_per_cu * mt_rows >= ((size_t)160 << 10))) {
             if (epilogue == EPI_SWIGLU) max_ksplit = 1;   // fused epilogue: no k-slices
             const int nbw = sweep_nbw(epilogue, m_rows);
             const int units = (N / 16 + nbw - 1) / nbw;
