@@ -237,7 +237,7 @@ def main() -> int:
     ach = wbytes / (ms_w.mean() * 1e-3) / 1e9
     # HBM bytes per launch from the FETCH_SIZE + WRITE_SIZE counter runs of this same command (7B shape only;
     # the figures and the copy-kernel scale factors are in profiles/decode_step_7b_hbm_traffic.txt)
-    traffic = (13609.8e6 + 150.4e6) / 129 if shape.name == "llama7b" and a.gemm_mode == 0 and B0 == 16 else None
+    traffic = (13610.4e6 + 175.6e6) / 129 if shape.name == "llama7b" and a.gemm_mode == 0 and B0 == 16 else None
     roofline = dict(bound="hbm", kernel=f"k_gemm_sweep + k_gemm_skinny (all projection launches of one {B0}-row decode step)",
                     achieved=ach, peak=HBM_PEAK_GBS, unit="GB/s", frac=ach / HBM_PEAK_GBS, traffic=traffic,
                     launches_per_step=launches, avg_launch_us=ms_w.mean() * 1e3 / launches,
