@@ -169,6 +169,37 @@ def test_odd_shape_many_strips_per_workgroup(oracle_built, rows):
         gw.close()
 
 
+def test_tiny_long_contexts_decode_logits(tiny):
+    """Contexts of several hundred to 1500 slots: the decode attention takes 256 slots per round trip, so
+    these rows need 2 to 6 of them, with ragged last passes; rows of very different lengths share the batch."""
+    W, om, gw = tiny
+    rng = np.random.default_rng(77)
+    w = synth.make_group(synth.TINY, 5, 4242, ("uniform", 250, 1500), ("uniform", 1, 8), None, 8, 0, ())
+    toks, offs, npr = forced_batch(w, range(5), [6, 3, 5, 4, 6], rng)
+    _say(f"tiny teacher-forced decode at long contexts: prompts {npr.tolist()}")
+    got = ss.ss_forward_logits(gw, toks, offs, npr)
+    ref = oracle_forced_logits(om, toks, offs, npr)
+    assert got.shape == ref.shape
+    check_logits(got, ref, "tiny long contexts")
+
+
+def test_tiny_large_batch_with_compaction_matches_oracle_rows(tiny):
+    """600 rows in one micro-batch (tiled kernels for the prompt and the first steps, then the small-batch
+    kernels as rows finish and compaction shrinks the batch): lengths exact, sampled rows re-derived by the oracle."""
+    W, om, gw = tiny
+    w = synth.make_group(synth.TINY, 600, 31337, ("uniform", 4, 24), ("uniform", 1, 12), None, 12, 0, ())
+    cap = 9
+    _say("tiny 600-row micro-batch, cap 9, compaction on")
+    r = ss.ss_decode_microbatch(gw, w.prompt_tokens, w.prompt_offsets, cap, w.target_lens, ss.SS_COMPACT)
+    assert np.array_equal(r["lens"], np.minimum(w.target_lens, cap))
+    assert np.array_equal(r["failed"].astype(bool), w.target_lens > cap)
+    assert r["stats"]["row_steps"] == int(np.minimum(w.target_lens, cap).sum())
+    for j in (0, 1, 77, 300, 511, 599):
+        L = int(r["lens"][j])
+        assert (r["tokens"][j, :L] >= 0).all() and (r["tokens"][j, L:] == -1).all()
+        check_tokens_teacher_forced(om, w.prompt(j), r["tokens"][j, :L], what=f"row {j}")
+
+
 def test_f32_source_weights_are_rounded_like_the_generator(tiny):
     """Config 1 ships fp32 weights: the library rounds them to bf16 (nearest even) at load."""
     W, om, gw = tiny
