@@ -209,3 +209,10 @@ def gather_prompts(w: Workload, idx) -> Tuple[np.ndarray, np.ndarray]:
     np.cumsum(lens, out=offs[1:])
     toks = np.concatenate([w.prompt(int(i)) for i in idx]) if len(idx) else np.zeros(0, np.int32)
     return toks.astype(np.int32), offs
+
+
+def make_draws(n: int, l_max: int, seed: int) -> np.ndarray:
+    """Uniform draws in [0,1) for (query, token number), float32 [n, l_max]: the random numbers a
+    sampled generation consumes, supplied as an input to both the library and the oracle."""
+    rng = np.random.Generator(np.random.PCG64(np.random.SeedSequence([seed, 0x5A17])))
+    return rng.random((n, l_max), dtype=np.float32)
