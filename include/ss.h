@@ -133,6 +133,8 @@ typedef struct {
     int64_t decode_kv_tokens; /* key/value slots read by decode attention, summed over rows and steps        */
     double  prefill_ms;       /* device time of the prompt forward (HIP events on the call's stream)         */
     double  decode_ms;        /* device time of all decode forwards                                          */
+    int32_t polls;            /* ss_generate_microbatch: host reads of the device's unfinished-row count     */
+    int32_t idle_steps;       /* ss_generate_microbatch: forwards run after the last row had finished        */
 } ss_stats;
 
 /*
@@ -186,6 +188,7 @@ typedef struct {
     double  wall_ms;                  /* host wall time of the whole group, plan building excluded     */
     double  plan_ms;                  /* host time spent building the two plans                        */
     double  prefill_ms, decode_ms;    /* device time (HIP events) summed over micro-batches            */
+    int64_t polls, idle_steps;        /* ss_run_group_generate: summed over micro-batches (see ss_stats) */
 } ss_group_stats;
 
 /*
@@ -199,6 +202,57 @@ typedef struct {
 int ss_run_group(ss_weights* w, const int32_t* prompt_tokens, const int32_t* prompt_offsets, int32_t n,
                  const int32_t* target_lens, const int32_t* pred_lens, int32_t bin, const ss_policy* policy,
                  int32_t* out_tokens, int32_t* out_lens, ss_group_stats* stats, void* hip_stream);
+
+/* ------------------------------------------------------------------ generation that ends by itself */
+
+/*
+ * How rows end and how tokens are chosen when the host does not know the response lengths in advance
+ * (Sec. 5.1: responses are sampled at a temperature and end at the model's end-of-sequence token or at
+ * the limit on new tokens).
+ */
+typedef struct {
+    int32_t eos_id;             /* id that ends a row; it is emitted and counted.  -1 = no such id            */
+    float   temperature;        /* 0 = greedy (largest logit, lowest index on ties); > 0 = draw from
+                                   softmax(logits / temperature) by inverse CDF in vocabulary order:
+                                   the smallest v whose cumulative probability exceeds the draw               */
+    const float* draws;         /* host, float32, draws[i*draws_stride + s] in [0,1) is the draw for token
+                                   number s of row (query) i; ignored (may be NULL) when temperature == 0      */
+    int32_t draws_stride;       /* >= max_new (ss_generate_microbatch) / >= base_len (ss_run_group_generate)  */
+    const int32_t* target_lens; /* host, int32 per row, nullable: a simulated end of sequence after that many
+                                   tokens, whichever of it and eos_id comes first.  The host loop never looks
+                                   at it: the device applies it, the host learns of it by polling             */
+    int32_t sync_every;         /* decode forwards between two host reads of the device's count of unfinished
+                                   rows, >= 1.  Rows that finish between reads leave the live batch at once
+                                   on the device (SS_COMPACT) but keep their place in the launch grids until
+                                   the next read; up to sync_every-1 forwards may run after the last row ended */
+} ss_gen_opts;
+
+/*
+ * ss_decode_microbatch for rows that end by themselves: token choice per `opts`, a row ends when it emits
+ * opts->eos_id, reaches its optional target length, or has emitted max_new tokens.  End detection, the
+ * shrinking of the live batch and the sampling all run on the device; the host only polls a counter.
+ * Given the same weights, prompts and draws the output of a row does not depend on B, on flags, on
+ * sync_every or on the other rows.
+ *   out_lens    host, int32[B]: tokens emitted (the end-of-sequence token included)
+ *   out_failed  host, uint8[B]: the row was still unfinished after max_new tokens (Sec. 4.1 failure)
+ * Other arguments, ownership and errors as ss_decode_microbatch; additionally SS_EINVAL for a NULL opts,
+ * eos_id outside [-1, vocab), temperature < 0 or not finite, sync_every < 1, NULL draws with
+ * temperature > 0, draws_stride < max_new, a draw outside [0,1), target_lens[i] < 1.
+ */
+int ss_generate_microbatch(ss_weights* w, const int32_t* prompt_tokens, const int32_t* prompt_offsets, int32_t B,
+                           int32_t max_new, const ss_gen_opts* opts, uint32_t flags, int32_t* out_tokens,
+                           int32_t* out_lens, uint8_t* out_failed, ss_stats* stats, void* hip_stream);
+
+/*
+ * ss_run_group for rows that end by themselves.  opts->draws and opts->target_lens are indexed by query
+ * (n rows, stride draws_stride >= policy->base_len), so a recomputed query sees the same draws and
+ * repeats its first attempt token for token before going on.  A query that is unfinished at a cap below
+ * policy->base_len is collected and recomputed with cap = base_len; one that is unfinished at base_len is
+ * complete (truncated there).  stats->useful_tokens = sum of out_lens.
+ */
+int ss_run_group_generate(ss_weights* w, const int32_t* prompt_tokens, const int32_t* prompt_offsets, int32_t n,
+                          const int32_t* pred_lens, int32_t bin, const ss_policy* policy, const ss_gen_opts* opts,
+                          int32_t* out_tokens, int32_t* out_lens, ss_group_stats* stats, void* hip_stream);
 
 /*
  * Measurement entry point: time `iters` decode forwards of B rows whose key/value history holds `ctx`

@@ -22,8 +22,8 @@ SS_BF16, SS_F32 = 0, 1
 FLAG_BITS = dict(SORT=SS_SORT, BIN=SS_BIN, FCR=SS_FCR, VBS=SS_VBS, COMPACT=SS_COMPACT)
 
 EXPORTS = ["ss_last_error", "ss_set_verbose", "ss_set_gemm_mode", "ss_schedule", "ss_schedule_failures", "ss_plan_free", "ss_weights_create",
-           "ss_weights_destroy", "ss_decode_microbatch", "ss_forward_logits", "ss_run_group", "ss_bench_decode_step",
-           "ss_bench_weight_stream"]
+           "ss_weights_destroy", "ss_decode_microbatch", "ss_forward_logits", "ss_run_group", "ss_generate_microbatch",
+           "ss_run_group_generate", "ss_bench_decode_step", "ss_bench_weight_stream"]
 
 
 class SsError(RuntimeError):
@@ -49,14 +49,21 @@ class ss_model_cfg(C.Structure):
 
 class ss_stats(C.Structure):
     _fields_ = [("steps", C.c_int32), ("rows", C.c_int32), ("row_steps", C.c_int64), ("prompt_tokens", C.c_int64),
-                ("decode_kv_tokens", C.c_int64), ("prefill_ms", C.c_double), ("decode_ms", C.c_double)]
+                ("decode_kv_tokens", C.c_int64), ("prefill_ms", C.c_double), ("decode_ms", C.c_double),
+                ("polls", C.c_int32), ("idle_steps", C.c_int32)]
 
 
 class ss_group_stats(C.Structure):
     _fields_ = [("n_mb_first", C.c_int32), ("n_mb_failure", C.c_int32), ("n_failed", C.c_int32),
                 ("steps", C.c_int64), ("padded_row_steps", C.c_int64), ("computed_row_steps", C.c_int64),
                 ("useful_tokens", C.c_int64), ("prompt_tokens", C.c_int64), ("wall_ms", C.c_double),
-                ("plan_ms", C.c_double), ("prefill_ms", C.c_double), ("decode_ms", C.c_double)]
+                ("plan_ms", C.c_double), ("prefill_ms", C.c_double), ("decode_ms", C.c_double),
+                ("polls", C.c_int64), ("idle_steps", C.c_int64)]
+
+
+class ss_gen_opts(C.Structure):
+    _fields_ = [("eos_id", C.c_int32), ("temperature", C.c_float), ("draws", C.c_void_p),
+                ("draws_stride", C.c_int32), ("target_lens", C.c_void_p), ("sync_every", C.c_int32)]
 
 
 def _struct_dict(s: C.Structure) -> dict:
@@ -92,6 +99,10 @@ def lib():
         L.ss_forward_logits.argtypes = [vp, i32p, i32p, C.c_int32, i32p, C.c_int32, vp, vp]
         L.ss_run_group.argtypes = [vp, i32p, i32p, C.c_int32, i32p, i32p, C.c_int32, C.POINTER(ss_policy), i32p, i32p,
                                    C.POINTER(ss_group_stats), vp]
+        L.ss_generate_microbatch.argtypes = [vp, i32p, i32p, C.c_int32, C.c_int32, C.POINTER(ss_gen_opts), C.c_uint32,
+                                             i32p, i32p, vp, C.POINTER(ss_stats), vp]
+        L.ss_run_group_generate.argtypes = [vp, i32p, i32p, C.c_int32, i32p, C.c_int32, C.POINTER(ss_policy),
+                                            C.POINTER(ss_gen_opts), i32p, i32p, C.POINTER(ss_group_stats), vp]
         L.ss_bench_decode_step.argtypes = [vp, i32p, C.c_int32, C.c_int32, C.c_int32, vp, vp]
         L.ss_bench_weight_stream.argtypes = [vp, C.c_int32, C.c_int32, vp, vp, vp]
         for name in EXPORTS:
@@ -219,6 +230,50 @@ def ss_run_group(w: Weights, prompt_tokens, prompt_offsets, target_lens, pred_le
     gs = ss_group_stats()
     _check(lib().ss_run_group(w.h, _ptr(pt), _ptr(po), n, _ptr(tl), _ptr(pl), bin, C.byref(policy), _ptr(toks),
                               _ptr(lens), C.byref(gs), stream))
+    return dict(tokens=toks, lens=lens, stats=_struct_dict(gs))
+
+
+def _gen_opts(eos_id: int, temperature: float, draws, target_lens, sync_every: int):
+    """Marshals ss_gen_opts; returns (struct, arrays to keep alive)."""
+    d = None if draws is None else np.ascontiguousarray(draws, dtype=np.float32)
+    tl = None if target_lens is None else _i32(target_lens)
+    o = ss_gen_opts()
+    o.eos_id, o.temperature, o.sync_every = int(eos_id), float(temperature), int(sync_every)
+    o.draws = None if d is None else d.ctypes.data
+    o.draws_stride = 0 if d is None else int(d.shape[1])
+    o.target_lens = None if tl is None else tl.ctypes.data
+    return o, (d, tl)
+
+
+def ss_generate_microbatch(w: Weights, prompt_tokens, prompt_offsets, max_new: int, eos_id: int = -1,
+                           temperature: float = 0.0, draws=None, target_lens=None, sync_every: int = 8,
+                           flags: int = 0, stream: Optional[int] = None) -> dict:
+    pt, po = _i32(prompt_tokens), _i32(prompt_offsets)
+    B = len(po) - 1
+    opts, keep = _gen_opts(eos_id, temperature, draws, target_lens, sync_every)
+    toks = np.empty((B, max_new), np.int32)
+    lens = np.empty(B, np.int32)
+    failed = np.empty(B, np.uint8)
+    st = ss_stats()
+    _check(lib().ss_generate_microbatch(w.h, _ptr(pt), _ptr(po), B, max_new, C.byref(opts), flags, _ptr(toks),
+                                        _ptr(lens), _ptr(failed), C.byref(st), stream))
+    del keep
+    return dict(tokens=toks, lens=lens, failed=failed, stats=_struct_dict(st))
+
+
+def ss_run_group_generate(w: Weights, prompt_tokens, prompt_offsets, pred_lens, bin: int, policy: ss_policy,
+                          eos_id: int = -1, temperature: float = 0.0, draws=None, target_lens=None,
+                          sync_every: int = 8, stream: Optional[int] = None) -> dict:
+    pt, po = _i32(prompt_tokens), _i32(prompt_offsets)
+    pl = None if pred_lens is None else _i32(pred_lens)
+    n = len(po) - 1
+    opts, keep = _gen_opts(eos_id, temperature, draws, target_lens, sync_every)
+    toks = np.empty((n, policy.base_len), np.int32)
+    lens = np.zeros(n, np.int32)
+    gs = ss_group_stats()
+    _check(lib().ss_run_group_generate(w.h, _ptr(pt), _ptr(po), n, _ptr(pl), bin, C.byref(policy), C.byref(opts),
+                                       _ptr(toks), _ptr(lens), C.byref(gs), stream))
+    del keep
     return dict(tokens=toks, lens=lens, stats=_struct_dict(gs))
 
 

@@ -69,11 +69,11 @@ struct Buf {
 };
 
 struct Workspace {
-    Buf x, h, h_lo, ao, ao_lo, act, act_lo, qrot, pqkv, pd, pgu, hsel, hsel_lo, logits, kv, ints, i64s;
+    Buf x, h, h_lo, ao, ao_lo, act, act_lo, qrot, pqkv, pd, pgu, hsel, hsel_lo, logits, kv, ints, i64s, draws;
     void release()
     {
         for (Buf* b : {&x, &h, &h_lo, &ao, &ao_lo, &act, &act_lo, &qrot, &pqkv, &pd, &pgu, &hsel, &hsel_lo, &logits, &kv,
-                       &ints, &i64s})
+                       &ints, &i64s, &draws})
             b->release();
     }
 };
@@ -97,6 +97,10 @@ struct ss_weights {
     int32_t* d_sel = nullptr;  // carved from ws.ints
     MbState st{};
     size_t kv_layer_stride = 0;  // elements between a layer's K and V, and 2x that between layers
+    // token choice of the forward in flight: draws == nullptr selects the argmax
+    const float* cur_draws = nullptr;
+    float cur_inv_temp = 0.f;
+    int32_t* h_poll = nullptr;   // pinned host copy of the 4-int device header (d_n, d_step, d_nlive, d_active)
 };
 
 namespace {
@@ -201,14 +205,14 @@ int ensure_workspace(ss_weights* w, int n_max, int B, int n_sel, size_t slots, i
     if ((rc = ws.logits.ensure((size_t)ss::round_up(n_sel, 16) * V * 4, false))) return rc;
     w->kv_layer_stride = slots * d;
     if ((rc = ws.kv.ensure((size_t)c.n_layers * 2 * slots * d * 2, false))) return rc;
-    // int32 arena: d_n d_step d_nlive (+pad) | tr_tok tr_row tr_pos [n_max] | live_row plen limit cap [B] | am sel [n_sel] | out_tok
+    // int32 arena: d_n d_step d_nlive d_active | tr_tok tr_row tr_pos [n_max] | live_row plen limit cap [B] | am sel [n_sel] | out_tok
     const size_t Bp = ss::round_up(B, 4), np = ss::round_up(n_max, 4), sp = ss::round_up(n_sel, 4);
     const size_t n_i32 = 4 + 3 * np + 4 * Bp + 2 * sp + (size_t)B * max_new;
     if ((rc = ws.ints.ensure(n_i32 * 4, false))) return rc;
     if ((rc = ws.i64s.ensure(Bp * 8, false))) return rc;
     int32_t* q = ws.ints.as<int32_t>();
     MbState& st = w->st;
-    st.d_n = q; st.d_step = q + 1; st.d_nlive = q + 2; q += 4;
+    st.d_n = q; st.d_step = q + 1; st.d_nlive = q + 2; st.d_active = q + 3; q += 4;
     st.tr_tok = q; q += np;
     st.tr_row = q; q += np;
     st.tr_pos = q; q += np;
@@ -255,7 +259,8 @@ GemmArgs gemm_args(const ss_weights* w, const bf16_t* W, const bf16_t* X, const 
 // ---------------------------------------------------------------------------------------- one forward
 // Runs the decoder over the token-rows described by the device state (st.d_n of them, at most n of
 // them: n sizes the grids and picks the kernel variants).  Logits are produced for n_sel rows:
-// the rows listed in d_sel, or the first *d_nsel rows when d_sel is null.  Ends with the argmax.
+// the rows listed in d_sel, or the first *d_nsel rows when d_sel is null.  Ends with the token choice:
+// the argmax, or a draw from the softmax when the handle carries draws (w->cur_draws).
 void forward(ss_weights* w, int n, int n_sel, const int32_t* d_sel, const int32_t* d_nsel, bool decode, hipStream_t s)
 {
     const ss_model_cfg& c = w->cfg;
@@ -309,7 +314,10 @@ void forward(ss_weights* w, int n, int n_sel, const int32_t* d_sel, const int32_
     ss::launch_rmsnorm(st, x, pd, ks_d, st_d, w->final_norm, c.rms_eps, d_sel, d_nsel, hsel, hsel_lo, d, n_sel, s);
     ss::launch_gemm(mk(w->lm_head.p, hsel, hsel_lo, ws.logits.as<float>(), nullptr, nullptr, V, d, n_sel, 0, p_lm),
                     ss::EPI_PARTIAL, s);
-    ss::launch_argmax(ws.logits.as<float>(), V, d_nsel ? d_nsel : st.d_n, st.am, n_sel, s);
+    if (w->cur_draws)
+        ss::launch_sample(ws.logits.as<float>(), V, d_nsel ? d_nsel : st.d_n, st, w->cur_draws, w->cur_inv_temp, n_sel, s);
+    else
+        ss::launch_argmax(ws.logits.as<float>(), V, d_nsel ? d_nsel : st.d_n, st.am, n_sel, s);
 }
 
 int check_prompts(const ss_weights* w, const int32_t* toks, const int32_t* offs, int B)
@@ -360,7 +368,7 @@ int upload_prompt_state(ss_weights* w, const int32_t* toks, const int32_t* offs,
         so[i] = slot;
         slot += slab[i];
     }
-    const int32_t hdr[4] = {n, 0, B, 0};
+    const int32_t hdr[4] = {n, 0, B, B};
     HIPCHK(hipMemcpyAsync(st.d_n, hdr, 16, hipMemcpyHostToDevice, s));
     HIPCHK(hipMemcpyAsync(st.tr_tok, tok.data(), (size_t)n * 4, hipMemcpyHostToDevice, s));
     HIPCHK(hipMemcpyAsync(st.tr_row, row.data(), (size_t)n * 4, hipMemcpyHostToDevice, s));
@@ -375,26 +383,64 @@ int upload_prompt_state(ss_weights* w, const int32_t* toks, const int32_t* offs,
     return SS_OK;
 }
 
+int check_gen_opts(const ss_weights* w, const ss_gen_opts* g, int rows, int need_stride)
+{
+    if (!g) return ss::fail(SS_EINVAL, "opts is NULL");
+    if (g->eos_id < -1 || g->eos_id >= w->cfg.vocab) return ss::fail(SS_EINVAL, "eos_id outside [-1, vocab)");
+    if (!(g->temperature >= 0.f) || !std::isfinite(g->temperature))
+        return ss::fail(SS_EINVAL, "temperature must be finite and >= 0");
+    if (g->sync_every < 1) return ss::fail(SS_EINVAL, "sync_every must be >= 1");
+    if (g->temperature > 0.f) {
+        if (!g->draws) return ss::fail(SS_EINVAL, "draws is NULL with temperature > 0");
+        if (g->draws_stride < need_stride)
+            return ss::fail(SS_EINVAL, "draws_stride %d < %d", g->draws_stride, need_stride);
+        for (int i = 0; i < rows; ++i)
+            for (int t = 0; t < need_stride; ++t) {
+                const float u = g->draws[(size_t)i * g->draws_stride + t];
+                if (!(u >= 0.f && u < 1.f)) return ss::fail(SS_EINVAL, "draw [%d][%d] outside [0,1)", i, t);
+            }
+    }
+    if (g->target_lens)
+        for (int i = 0; i < rows; ++i)
+            if (g->target_lens[i] < 1) return ss::fail(SS_EINVAL, "target_lens[%d] < 1", i);
+    return SS_OK;
+}
+
+// Clears the handle's token-choice state however the call ends.
+struct ChoiceGuard {
+    ss_weights* w;
+    ~ChoiceGuard()
+    {
+        w->cur_draws = nullptr;
+        w->cur_inv_temp = 0.f;
+    }
+};
+
+// One micro-batch.  gen == nullptr: greedy, rows end at target_lens (known to the host, which therefore
+// knows the number of forwards and the live rows of each).  gen != nullptr: token choice and row ends per
+// gen (checked by the caller), target_lens ignored; the host learns how many rows are left by polling.
 int decode_microbatch_impl(ss_weights* w, const int32_t* prompt_tokens, const int32_t* prompt_offsets, int32_t B,
-                           int32_t max_new, const int32_t* target_lens, uint32_t flags, int32_t* out_tokens,
-                           int32_t* out_lens, uint8_t* out_failed, ss_stats* stats, hipStream_t s)
+                           int32_t max_new, const int32_t* target_lens, const ss_gen_opts* gen, uint32_t flags,
+                           int32_t* out_tokens, int32_t* out_lens, uint8_t* out_failed, ss_stats* stats, hipStream_t s)
 {
     if (int rc = check_prompts(w, prompt_tokens, prompt_offsets, B)) return rc;
     if (max_new < 1) return ss::fail(SS_EINVAL, "max_new must be >= 1");
-    if (!target_lens || !out_tokens || !out_lens || !out_failed) return ss::fail(SS_EINVAL, "NULL argument");
+    if (!out_tokens || !out_lens || !out_failed) return ss::fail(SS_EINVAL, "NULL argument");
+    if (!gen && !target_lens) return ss::fail(SS_EINVAL, "NULL argument");
     if (flags & ~SS_COMPACT) return ss::fail(SS_EINVAL, "unknown flag");
+    const int32_t* tl = gen ? gen->target_lens : target_lens;
     std::vector<int32_t> lens(B), slab(B), limit(B), sel(B);
     int n_prompt = prompt_offsets[B], steps = 0;
     size_t slots = 0;
     for (int i = 0; i < B; ++i) {
-        if (target_lens[i] < 1) return ss::fail(SS_EINVAL, "target_lens[%d] < 1", i);
+        if (tl && tl[i] < 1) return ss::fail(SS_EINVAL, "target_lens[%d] < 1", i);
         lens[i] = prompt_offsets[i + 1] - prompt_offsets[i];
         if (lens[i] + max_new > ss::kMaxPos)
             return ss::fail(SS_EINVAL, "row %d: prompt %d + max_new %d exceeds %d positions", i, lens[i], max_new,
                             ss::kMaxPos);
         slab[i] = lens[i] + max_new;
         slots += (size_t)slab[i];
-        limit[i] = std::min(target_lens[i], max_new);
+        limit[i] = tl ? std::min(tl[i], max_new) : max_new;
         steps = std::max(steps, limit[i]);
         sel[i] = prompt_offsets[i + 1] - 1;
     }
@@ -402,9 +448,19 @@ int decode_microbatch_impl(ss_weights* w, const int32_t* prompt_tokens, const in
     if (int rc = ensure_workspace(w, std::max(n_prompt, B), B, B, slots, max_new)) return rc;
     const MbState& st = w->st;
     const int compact = (flags & SS_COMPACT) ? 1 : 0;
+    const int eos_id = gen ? gen->eos_id : -1;
 
     if (int rc = upload_prompt_state(w, prompt_tokens, prompt_offsets, lens.data(), B, slab.data(), limit.data(), sel, s))
         return rc;
+    ChoiceGuard choice{w};
+    if (gen && gen->temperature > 0.f) {
+        if (int rc = w->ws.draws.ensure((size_t)B * max_new * 4, false)) return rc;
+        HIPCHK(hipMemcpy2DAsync(w->ws.draws.p, (size_t)max_new * 4, gen->draws, (size_t)gen->draws_stride * 4,
+                                (size_t)max_new * 4, B, hipMemcpyHostToDevice, s));
+        HIPCHK(hipStreamSynchronize(s));
+        w->cur_draws = w->ws.draws.as<float>();
+        w->cur_inv_temp = 1.f / gen->temperature;
+    }
     ss::launch_fill_i32(st.out_tok, -1, (size_t)B * max_new, s);
 
     hipEvent_t e0, e1, e2;
@@ -413,43 +469,80 @@ int decode_microbatch_impl(ss_weights* w, const int32_t* prompt_tokens, const in
     HIPCHK(hipEventCreate(&e2));
     HIPCHK(hipEventRecord(e0, s));
     forward(w, n_prompt, B, w->d_sel, st.d_nlive, false, s);
-    ss::launch_step_update(st, compact, s);
+    ss::launch_step_update(st, compact, eos_id, s);
     HIPCHK(hipEventRecord(e1, s));
 
     int64_t row_steps = B, kv_tokens = 0;
-    std::vector<int32_t> sorted_limit(limit);
-    std::sort(sorted_limit.begin(), sorted_limit.end());
-    for (int g = 1; g < steps; ++g) {
-        // rows alive for forward g: all of them, or with compaction those that owe more than g tokens
-        int n_live = B;
-        if (compact)
-            n_live = (int)(sorted_limit.end() - std::upper_bound(sorted_limit.begin(), sorted_limit.end(), g));
-        forward(w, n_live, n_live, nullptr, nullptr, true, s);
-        ss::launch_step_update(st, compact, s);
-        row_steps += n_live;
-        if (stats)
-            for (int i = 0; i < B; ++i)
-                if (!compact || limit[i] > g) kv_tokens += lens[i] + g;
+    int forwards = 1, polls = 0;
+    if (!gen) {
+        std::vector<int32_t> sorted_limit(limit);
+        std::sort(sorted_limit.begin(), sorted_limit.end());
+        for (int g = 1; g < steps; ++g) {
+            // rows alive for forward g: all of them, or with compaction those that owe more than g tokens
+            int n_live = B;
+            if (compact)
+                n_live = (int)(sorted_limit.end() - std::upper_bound(sorted_limit.begin(), sorted_limit.end(), g));
+            forward(w, n_live, n_live, nullptr, nullptr, true, s);
+            ss::launch_step_update(st, compact, eos_id, s);
+            row_steps += n_live;
+        }
+        forwards = steps;
+    } else {
+        // The device ends rows and shrinks the live batch by itself; the host sizes the launches by the last
+        // count it has read (an upper bound: the kernels take the true count from device memory) and stops
+        // when a read shows no unfinished row.
+        auto poll = [&](int* n_live, int* active) -> int {
+            HIPCHK(hipMemcpyAsync(w->h_poll, st.d_n, 16, hipMemcpyDeviceToHost, s));
+            HIPCHK(hipStreamSynchronize(s));
+            ++polls;
+            if (compact) *n_live = w->h_poll[2];
+            *active = w->h_poll[3];
+            return SS_OK;
+        };
+        int n_live = B, active = B;
+        if (int rc = poll(&n_live, &active)) return rc;
+        for (int g = 1; g < max_new && active > 0; ++g) {
+            forward(w, n_live, n_live, nullptr, nullptr, true, s);
+            ss::launch_step_update(st, compact, eos_id, s);
+            row_steps += n_live;
+            ++forwards;
+            if (g % gen->sync_every == 0 && g + 1 < max_new)
+                if (int rc = poll(&n_live, &active)) return rc;
+        }
     }
     HIPCHK(hipEventRecord(e2, s));
     HIPCHK(hipMemcpyAsync(out_tokens, st.out_tok, (size_t)B * max_new * 4, hipMemcpyDeviceToHost, s));
+    if (gen) HIPCHK(hipMemcpyAsync(limit.data(), st.row_limit, (size_t)B * 4, hipMemcpyDeviceToHost, s));
     HIPCHK(hipStreamSynchronize(s));
     HIPCHK(hipGetLastError());
+    int longest = 0;
     for (int i = 0; i < B; ++i) {
         out_lens[i] = limit[i];
-        out_failed[i] = target_lens[i] > max_new;
+        longest = std::max(longest, limit[i]);
+        if (!gen) {
+            out_failed[i] = target_lens[i] > max_new;
+        } else {   // unfinished: ran into the cap without its end id and short of its simulated end
+            const bool hit_cap = limit[i] == max_new;
+            const bool ended = out_tokens[(size_t)i * max_new + limit[i] - 1] == eos_id || (tl && tl[i] <= max_new);
+            out_failed[i] = hit_cap && !ended;
+        }
     }
     if (stats) {
+        for (int g = 1; g < forwards; ++g)
+            for (int i = 0; i < B; ++i)
+                if (!compact || limit[i] > g) kv_tokens += lens[i] + g;
         float ms01 = 0.f, ms12 = 0.f;
         HIPCHK(hipEventElapsedTime(&ms01, e0, e1));
         HIPCHK(hipEventElapsedTime(&ms12, e1, e2));
-        stats->steps = steps;
+        stats->steps = forwards;
         stats->rows = B;
         stats->row_steps = row_steps;
         stats->prompt_tokens = n_prompt;
         stats->decode_kv_tokens = kv_tokens;
         stats->prefill_ms = ms01;
         stats->decode_ms = ms12;
+        stats->polls = polls;
+        stats->idle_steps = forwards - longest;
     }
     (void)hipEventDestroy(e0);
     (void)hipEventDestroy(e1);
@@ -482,6 +575,8 @@ extern "C" int ss_weights_create(const ss_model_cfg* cfg, const void* const* ten
     };
     if (hipGetDevice(&w->device) != hipSuccess) return bail(ss::fail(SS_EDEVICE, "hipGetDevice failed"));
     if (hipStreamCreate(&w->stream) != hipSuccess) return bail(ss::fail(SS_EDEVICE, "hipStreamCreate failed"));
+    if (hipHostMalloc((void**)&w->h_poll, 16, hipHostMallocDefault) != hipSuccess)
+        return bail(ss::fail(SS_ENOMEM, "hipHostMalloc failed"));
 
     const int d = cfg->d_model, F = cfg->d_ffn, V = cfg->vocab, f32 = (src_dtype == SS_F32);
     Buf staging;
@@ -555,6 +650,7 @@ extern "C" void ss_weights_destroy(ss_weights* w)
     w->ws.release();
     for (void* p : w->allocs) (void)hipFree(p);
     if (w->stream) (void)hipStreamDestroy(w->stream);
+    if (w->h_poll) (void)hipHostFree(w->h_poll);
     delete w;
 }
 
@@ -568,7 +664,24 @@ extern "C" int ss_decode_microbatch(ss_weights* w, const int32_t* prompt_tokens,
     BusyGuard guard(w);
     if (!guard.ok) return ss::fail(SS_ESTATE, "another call is in flight on this handle");
     hipStream_t s = hip_stream ? (hipStream_t)hip_stream : w->stream;
-    return decode_microbatch_impl(w, prompt_tokens, prompt_offsets, B, max_new, target_lens, flags, out_tokens,
+    return decode_microbatch_impl(w, prompt_tokens, prompt_offsets, B, max_new, target_lens, nullptr, flags, out_tokens,
+                                  out_lens, out_failed, stats, s);
+}
+
+extern "C" int ss_generate_microbatch(ss_weights* w, const int32_t* prompt_tokens, const int32_t* prompt_offsets,
+                                      int32_t B, int32_t max_new, const ss_gen_opts* opts, uint32_t flags,
+                                      int32_t* out_tokens, int32_t* out_lens, uint8_t* out_failed, ss_stats* stats,
+                                      void* hip_stream)
+{
+    ss::clear_error();
+    if (!w) return ss::fail(SS_EINVAL, "weights handle is NULL");
+    if (B <= 0 || B > ss::kMaxBatch) return ss::fail(SS_EINVAL, "B = %d outside [1, %d]", B, ss::kMaxBatch);
+    if (max_new < 1) return ss::fail(SS_EINVAL, "max_new must be >= 1");
+    if (int rc = check_gen_opts(w, opts, B, max_new)) return rc;
+    BusyGuard guard(w);
+    if (!guard.ok) return ss::fail(SS_ESTATE, "another call is in flight on this handle");
+    hipStream_t s = hip_stream ? (hipStream_t)hip_stream : w->stream;
+    return decode_microbatch_impl(w, prompt_tokens, prompt_offsets, B, max_new, nullptr, opts, flags, out_tokens,
                                   out_lens, out_failed, stats, s);
 }
 
@@ -653,21 +766,13 @@ extern "C" int ss_forward_logits(ss_weights* w, const int32_t* tokens, const int
     return SS_OK;
 }
 
-extern "C" int ss_run_group(ss_weights* w, const int32_t* prompt_tokens, const int32_t* prompt_offsets, int32_t n,
-                            const int32_t* target_lens, const int32_t* pred_lens, int32_t bin, const ss_policy* policy,
-                            int32_t* out_tokens, int32_t* out_lens, ss_group_stats* stats, void* hip_stream)
-{
-    ss::clear_error();
-    if (!w) return ss::fail(SS_EINVAL, "weights handle is NULL");
-    if (n <= 0 || !prompt_tokens || !prompt_offsets || !target_lens || !policy || !out_tokens || !out_lens)
-        return ss::fail(SS_EINVAL, "NULL or empty argument");
-    BusyGuard guard(w);
-    if (!guard.ok) return ss::fail(SS_ESTATE, "another call is in flight on this handle");
-    hipStream_t s = hip_stream ? (hipStream_t)hip_stream : w->stream;
-    for (int i = 0; i < n; ++i)
-        if (target_lens[i] < 1 || target_lens[i] > policy->base_len)
-            return ss::fail(SS_EINVAL, "target_lens[%d] outside [1, base_len]", i);
+namespace {
 
+// The group pipeline shared by ss_run_group (gen == nullptr, lengths known) and ss_run_group_generate.
+int run_group_impl(ss_weights* w, const int32_t* prompt_tokens, const int32_t* prompt_offsets, int32_t n,
+                   const int32_t* target_lens, const int32_t* pred_lens, int32_t bin, const ss_policy* policy,
+                   const ss_gen_opts* gen, int32_t* out_tokens, int32_t* out_lens, ss_group_stats* stats, hipStream_t s)
+{
     using clk = std::chrono::steady_clock;
     const auto t_plan0 = clk::now();
     ss_plan* plan = nullptr;
@@ -679,31 +784,47 @@ extern "C" int ss_run_group(ss_weights* w, const int32_t* prompt_tokens, const i
     const uint32_t eflags = policy->flags & SS_COMPACT;
     std::vector<int32_t> failed;
     std::vector<int32_t> mb_toks, mb_offs, mb_tl, mb_out, mb_lens;
+    std::vector<float> mb_draws;
     std::vector<uint8_t> mb_failed;
     for (size_t i = 0; i < (size_t)n * L; ++i) out_tokens[i] = -1;
 
     auto run_plan = [&](const ss_plan* pl, bool first) -> int {
         for (int k = 0; k < pl->n_mb; ++k) {
             const int b0 = pl->mb_offsets[k], B = pl->mb_offsets[k + 1] - b0, cap = pl->mb_cap[k];
+            const int32_t* src_tl = gen ? gen->target_lens : target_lens;
             mb_toks.clear();
             mb_offs.assign(1, 0);
             mb_tl.resize(B);
+            if (gen && gen->temperature > 0.f) mb_draws.resize((size_t)B * cap);
             for (int r = 0; r < B; ++r) {
                 const int qi = pl->query_idx[b0 + r];
                 mb_toks.insert(mb_toks.end(), prompt_tokens + prompt_offsets[qi], prompt_tokens + prompt_offsets[qi + 1]);
                 mb_offs.push_back((int32_t)mb_toks.size());
-                mb_tl[r] = target_lens[qi];
+                if (src_tl) mb_tl[r] = src_tl[qi];
+                if (gen && gen->temperature > 0.f)
+                    std::memcpy(mb_draws.data() + (size_t)r * cap, gen->draws + (size_t)qi * gen->draws_stride,
+                                (size_t)cap * 4);
             }
             mb_out.resize((size_t)B * cap);
             mb_lens.resize(B);
             mb_failed.resize(B);
             ss_stats st{};
-            if (int rc = decode_microbatch_impl(w, mb_toks.data(), mb_offs.data(), B, cap, mb_tl.data(), eflags,
-                                                mb_out.data(), mb_lens.data(), mb_failed.data(), &st, s))
+            ss_gen_opts mbg{};
+            if (gen) {
+                mbg = *gen;
+                mbg.draws = mb_draws.data();
+                mbg.draws_stride = cap;
+                mbg.target_lens = src_tl ? mb_tl.data() : nullptr;
+            }
+            if (int rc = decode_microbatch_impl(w, mb_toks.data(), mb_offs.data(), B, cap, mb_tl.data(),
+                                                gen ? &mbg : nullptr, eflags, mb_out.data(), mb_lens.data(),
+                                                mb_failed.data(), &st, s))
                 return rc;
             for (int r = 0; r < B; ++r) {
                 const int qi = pl->query_idx[b0 + r];
-                if (mb_failed[r]) {   // partial output and key/value state are dropped; recomputed later
+                // unfinished below the global limit: partial output and key/value state are dropped, the
+                // query is recomputed later; unfinished at the global limit is simply the truncated result
+                if (mb_failed[r] && cap < L) {
                     failed.push_back(qi);
                     continue;
                 }
@@ -716,6 +837,8 @@ extern "C" int ss_run_group(ss_weights* w, const int32_t* prompt_tokens, const i
             gs.prompt_tokens += st.prompt_tokens;
             gs.prefill_ms += st.prefill_ms;
             gs.decode_ms += st.decode_ms;
+            gs.polls += st.polls;
+            gs.idle_steps += st.idle_steps;
             (first ? gs.n_mb_first : gs.n_mb_failure) += 1;
             if (ss::verbose() > 0) {
                 std::fprintf(stderr, "[ss] %s micro-batch %d/%d: %d rows, cap %d, %d steps, %.0f ms\n",
@@ -747,9 +870,47 @@ extern "C" int ss_run_group(ss_weights* w, const int32_t* prompt_tokens, const i
     }
     gs.wall_ms = std::chrono::duration<double, std::milli>(clk::now() - t0).count();
     gs.plan_ms = plan_ms;
-    for (int i = 0; i < n; ++i) gs.useful_tokens += target_lens[i];
+    for (int i = 0; i < n; ++i) gs.useful_tokens += gen ? out_lens[i] : target_lens[i];
     if (stats) *stats = gs;
     return SS_OK;
+}
+
+}  // namespace
+
+extern "C" int ss_run_group(ss_weights* w, const int32_t* prompt_tokens, const int32_t* prompt_offsets, int32_t n,
+                            const int32_t* target_lens, const int32_t* pred_lens, int32_t bin, const ss_policy* policy,
+                            int32_t* out_tokens, int32_t* out_lens, ss_group_stats* stats, void* hip_stream)
+{
+    ss::clear_error();
+    if (!w) return ss::fail(SS_EINVAL, "weights handle is NULL");
+    if (n <= 0 || !prompt_tokens || !prompt_offsets || !target_lens || !policy || !out_tokens || !out_lens)
+        return ss::fail(SS_EINVAL, "NULL or empty argument");
+    BusyGuard guard(w);
+    if (!guard.ok) return ss::fail(SS_ESTATE, "another call is in flight on this handle");
+    hipStream_t s = hip_stream ? (hipStream_t)hip_stream : w->stream;
+    for (int i = 0; i < n; ++i)
+        if (target_lens[i] < 1 || target_lens[i] > policy->base_len)
+            return ss::fail(SS_EINVAL, "target_lens[%d] outside [1, base_len]", i);
+    return run_group_impl(w, prompt_tokens, prompt_offsets, n, target_lens, pred_lens, bin, policy, nullptr, out_tokens,
+                          out_lens, stats, s);
+}
+
+extern "C" int ss_run_group_generate(ss_weights* w, const int32_t* prompt_tokens, const int32_t* prompt_offsets,
+                                     int32_t n, const int32_t* pred_lens, int32_t bin, const ss_policy* policy,
+                                     const ss_gen_opts* opts, int32_t* out_tokens, int32_t* out_lens,
+                                     ss_group_stats* stats, void* hip_stream)
+{
+    ss::clear_error();
+    if (!w) return ss::fail(SS_EINVAL, "weights handle is NULL");
+    if (n <= 0 || !prompt_tokens || !prompt_offsets || !policy || !out_tokens || !out_lens)
+        return ss::fail(SS_EINVAL, "NULL or empty argument");
+    if (policy->base_len < 1) return ss::fail(SS_EINVAL, "base_len must be >= 1");
+    if (int rc = check_gen_opts(w, opts, n, policy->base_len)) return rc;
+    BusyGuard guard(w);
+    if (!guard.ok) return ss::fail(SS_ESTATE, "another call is in flight on this handle");
+    hipStream_t s = hip_stream ? (hipStream_t)hip_stream : w->stream;
+    return run_group_impl(w, prompt_tokens, prompt_offsets, n, nullptr, pred_lens, bin, policy, opts, out_tokens,
+                          out_lens, stats, s);
 }
 
 extern "C" int ss_bench_decode_step(ss_weights* w, const int32_t* prompt_tokens, int32_t B, int32_t ctx,
@@ -773,7 +934,7 @@ extern "C" int ss_bench_decode_step(ss_weights* w, const int32_t* prompt_tokens,
     if (int rc = upload_prompt_state(w, prompt_tokens, offs.data(), lens.data(), B, slab.data(), limit.data(), sel, s))
         return rc;
     forward(w, B * ctx, B, w->d_sel, st.d_nlive, false, s);
-    ss::launch_step_update(st, 0, s);   // token-rows of the decode step: every row at position ctx
+    ss::launch_step_update(st, 0, -1, s);   // token-rows of the decode step: every row at position ctx
     std::vector<hipEvent_t> ev(iters + 1);
     for (auto& e : ev) HIPCHK(hipEventCreate(&e));
     HIPCHK(hipEventRecord(ev[0], s));

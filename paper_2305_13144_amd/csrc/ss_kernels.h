@@ -26,8 +26,9 @@ struct MbState {
     int32_t* tr_pos;     // [n_max] position of token-row j inside its row
     int32_t* live_row;   // [B]     rows still in the live batch, in slot order
     int32_t* d_nlive;    // [1]
+    int32_t* d_active;   // [1] rows that still owe tokens after the last bookkeeping step
     int32_t* row_plen;   // [B] prompt length
-    int32_t* row_limit;  // [B] min(target, cap): tokens the row emits
+    int32_t* row_limit;  // [B] min(target, cap): tokens the row emits; lowered by the device when the row emits its end id
     int64_t* row_so;     // [B] first key/value slot of the row's slab
     int32_t* row_cap;    // [B] slots in the row's slab (prompt + cap)
     int32_t* am;         // [n_sel_max] argmax of the selected rows' logits
@@ -84,7 +85,12 @@ void launch_attention_decode(const MbState& st, const float* qkv_part, int kspli
                              bf16_t* kcache, bf16_t* vcache, const float* rope_cos, const float* rope_sin,
                              bf16_t* out_packed, bf16_t* out_packed_lo, int d, int H, int hd, int n_max, hipStream_t s);
 void launch_argmax(const float* logits, int vocab, const int32_t* d_nsel, int32_t* am, int n_max, hipStream_t s);
-void launch_step_update(const MbState& st, int compact, hipStream_t s);
+// Temperature sampling in place of the argmax: st.am[j] for the first *d_nsel selected rows; the draw of slot j
+// is draws[st.live_row[j] * st.max_new + *st.d_step].
+void launch_sample(const float* logits, int vocab, const int32_t* d_nsel, const MbState& st, const float* draws,
+                   float inv_temp, int n_max, hipStream_t s);
+// eos_id: -1 when rows end only at their limit.
+void launch_step_update(const MbState& st, int compact, int eos_id, hipStream_t s);
 void launch_fill_i32(int32_t* p, int32_t v, size_t n, hipStream_t s);
 
 }  // namespace ss

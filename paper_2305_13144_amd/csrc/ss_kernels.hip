@@ -992,34 +992,135 @@ __global__ __launch_bounds__(1024) void k_argmax(const float* __restrict__ logit
     }
 }
 
+// ------------------------------------------------------------------------------------------ sampling
+// Temperature sampling per selected row (Sec. 5.1 of the paper samples responses at a temperature):
+// token = smallest v with  sum_{v' <= v} e_v'  >  u * sum_v' e_v',  e_v = exp((logit_v - max) * inv_temp),
+// u being the draw supplied for (row, token number).  The CDF runs in vocabulary order, so thread t owns
+// the contiguous chunk [t*c, (t+1)*c): it sums its chunk in index order, a workgroup scan of the 1024
+// chunk sums finds the first chunk whose running total exceeds the target, and that chunk's owner walks
+// it again in the same order (same additions, same roundings) to the token.  V-1 when rounding leaves no
+// chunk above the target.  1024 threads per row; the row's logits (just written by the LM head) are read
+// three times from L2.
+__global__ __launch_bounds__(1024) void k_sample(const float* __restrict__ logits, int vocab,
+                                                 const int32_t* __restrict__ d_count, MbState st,
+                                                 const float* __restrict__ draws, float inv_temp)
+{
+    const int j = blockIdx.x;
+    if (j >= *d_count) return;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int row = st.live_row[j];
+    const float u = draws[(size_t)row * st.max_new + *st.d_step];
+    const float* lg = logits + (size_t)j * vocab;
+    const int c = (((vocab + 1023) >> 10) + 3) & ~3;   // floats per thread, a multiple of 4 (vocab % 16 == 0)
+    const int lo = tid * c;
+    const int hi = lo + c < vocab ? lo + c : vocab;    // lo >= vocab: empty chunk
+
+    __shared__ float s_red[16];
+    __shared__ float s_tot[17];
+    __shared__ int s_owner[16];
+
+    float m = -3.4e38f;
+    for (int v = lo; v < hi; v += 4) {
+        const float4 q = *(const float4*)(lg + v);
+        m = fmaxf(fmaxf(m, fmaxf(q.x, q.y)), fmaxf(q.z, q.w));
+    }
+#pragma unroll
+    for (int k = 32; k >= 1; k >>= 1) m = fmaxf(m, __shfl_xor(m, k, 64));
+    if (lane == 0) s_red[wave] = m;
+    __syncthreads();
+    m = s_red[0];
+#pragma unroll
+    for (int w = 1; w < 16; ++w) m = fmaxf(m, s_red[w]);
+
+    float csum = 0.f;
+    for (int v = lo; v < hi; v += 4) {
+        const float4 q = *(const float4*)(lg + v);
+        csum += expf((q.x - m) * inv_temp);
+        csum += expf((q.y - m) * inv_temp);
+        csum += expf((q.z - m) * inv_temp);
+        csum += expf((q.w - m) * inv_temp);
+    }
+    // inclusive scan of the chunk sums: within the wave, then over the 16 wave totals
+    float incl = csum;
+#pragma unroll
+    for (int k = 1; k < 64; k <<= 1) {
+        const float o = __shfl_up(incl, k, 64);
+        if (lane >= k) incl += o;
+    }
+    if (lane == 63) s_tot[wave + 1] = incl;
+    __syncthreads();
+    if (tid == 0) {
+        float a = 0.f;
+        s_tot[0] = 0.f;
+        for (int w = 1; w <= 16; ++w) { a += s_tot[w]; s_tot[w] = a; }
+    }
+    __syncthreads();
+    const float base = s_tot[wave];
+    const float target = u * s_tot[16];
+    const float before = base + (incl - csum);   // running total ahead of this chunk
+    const float upto = base + incl;
+    const unsigned long long hit = __ballot(upto > target);
+    if (lane == 0) s_owner[wave] = hit ? (wave << 6) + __ffsll((long long)hit) - 1 : 0x7fffffff;
+    __syncthreads();
+    int owner = 0x7fffffff;
+#pragma unroll
+    for (int w = 0; w < 16; ++w) owner = s_owner[w] < owner ? s_owner[w] : owner;
+    if (owner == 0x7fffffff) {
+        if (tid == 0) st.am[j] = vocab - 1;
+        return;
+    }
+    if (tid != owner) return;
+    const float want = target - before;
+    float acc = 0.f;
+    int pick = hi - 1;
+    for (int v = lo; v < hi; ++v) {
+        acc += expf((lg[v] - m) * inv_temp);
+        if (acc > want) { pick = v; break; }
+    }
+    st.am[j] = pick;
+}
+
 // ------------------------------------------------------------------------------------------ bookkeeping
-// After a forward: slot j's argmax is the row's token number s (s = tokens generated so far).  Emit it if
-// the row still owes tokens, then build the next forward: every surviving slot feeds its token back at
+// After a forward: slot j's chosen token is the row's token number s (s = tokens generated so far).  Emit it
+// if the row still owes tokens, then build the next forward: every surviving slot feeds its token back at
 // position prompt_len + s.  With `compact` a row leaves the live batch once it has emitted its last token;
 // without it the row stays and keeps running on its own output (its later tokens are never emitted).
-__global__ __launch_bounds__(1024) void k_step_update(MbState st, int compact)
+// A row that emits `eos_id` (never matched when it is -1) has emitted its last token: its limit drops to
+// s + 1, which is also where the host reads the row's length afterwards.  *st.d_active counts the rows that
+// still owe tokens, for a host that does not know the lengths and polls.
+__global__ __launch_bounds__(1024) void k_step_update(MbState st, int compact, int eos_id)
 {
     __shared__ int wave_cnt[16];
+    __shared__ int wave_act[16];
     __shared__ int wave_off[17];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int n = *st.d_nlive;
     const int s = *st.d_step;
-    int row = -1, tok = 0, keep = 0;
+    int row = -1, tok = 0, keep = 0, owes = 0;
     if (tid < n) {
         row = st.live_row[tid];
         tok = st.am[tid];
-        const int lim = st.row_limit[row];
-        if (s < lim) st.out_tok[(size_t)row * st.max_new + s] = tok;
-        keep = compact ? (s + 1 < lim) : 1;
+        int lim = st.row_limit[row];
+        if (s < lim) {
+            st.out_tok[(size_t)row * st.max_new + s] = tok;
+            if (tok == eos_id && s + 1 < lim) {
+                lim = s + 1;
+                st.row_limit[row] = lim;
+            }
+        }
+        owes = s + 1 < lim;
+        keep = compact ? owes : 1;
     }
     const unsigned long long bal = __ballot(keep);
+    const unsigned long long act = __ballot(owes);
     const int before = __popcll(bal & ((1ull << lane) - 1ull));
-    if (lane == 0) wave_cnt[wave] = __popcll(bal);
+    if (lane == 0) { wave_cnt[wave] = __popcll(bal); wave_act[wave] = __popcll(act); }
     __syncthreads();
     if (tid == 0) {
-        int a = 0;
-        for (int w = 0; w < 16; ++w) { wave_off[w] = a; a += wave_cnt[w]; }
+        int a = 0, b = 0;
+        for (int w = 0; w < 16; ++w) { wave_off[w] = a; a += wave_cnt[w]; b += wave_act[w]; }
         wave_off[16] = a;
+        *st.d_active = b;
     }
     __syncthreads();
     if (keep) {
@@ -1269,9 +1370,15 @@ void launch_argmax(const float* logits, int vocab, const int32_t* d_nsel, int32_
     hipLaunchKernelGGL(k_argmax, dim3(n_max), dim3(1024), 0, s, logits, vocab, d_nsel, am);
 }
 
-void launch_step_update(const MbState& st, int compact, hipStream_t s)
+void launch_sample(const float* logits, int vocab, const int32_t* d_nsel, const MbState& st, const float* draws,
+                   float inv_temp, int n_max, hipStream_t s)
 {
-    hipLaunchKernelGGL(k_step_update, dim3(1), dim3(1024), 0, s, st, compact);
+    hipLaunchKernelGGL(k_sample, dim3(n_max), dim3(1024), 0, s, logits, vocab, d_nsel, st, draws, inv_temp);
+}
+
+void launch_step_update(const MbState& st, int compact, int eos_id, hipStream_t s)
+{
+    hipLaunchKernelGGL(k_step_update, dim3(1), dim3(1024), 0, s, st, compact, eos_id);
 }
 
 }  // namespace ss

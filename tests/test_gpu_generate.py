@@ -1,0 +1,336 @@
+"""GPU parity of generation that ends by itself (temperature sampling, a real end-of-sequence id, host
+polling), through the C ABI, against the sampling oracle on the same seeded prompts and draws.
+
+A sampled token is a function of (logits, draw).  The logits are held to the bar of test_gpu_parity.py;
+the function is held to the oracle's rule, and the two checks are made on every emitted position:
+
+  (a) the choice given the logits: the oracle's rule (fp64 softmax, CDF in vocabulary order) applied to the
+      GPU's own teacher-forced logits on the GPU's own prefix must give the emitted token whenever the
+      draw is further from the edges of the chosen CDF interval than rounding can move them.  Those logits
+      come from the same kernels run on a different batch composition (other k-splits, other summation
+      order), measured below to differ by less than GPU_PATH_DELTA; logits that differ by at most delta
+      move every probability by a factor within exp(+-2*delta/T) and hence any CDF value by at most
+      (exp(2*delta/T) - 1)/4; SUM_SLACK covers the kernel's fp32 summation.  For T = 0 the top-2 margin
+      must exceed 2*delta.
+  (b) end to end: the same with the oracle's logits and delta = the measured max |gpu - oracle| logit
+      difference of that row (which must itself meet the logit bar).  On random-init models this decides
+      few positions; they must match, and their number is reported.
+
+Lengths, failure flags, -1 padding and counters are bit-exact against what the row's own tokens imply,
+and against the oracle's whole result for rows decided at every position.
+"""
+import math
+
+import numpy as np
+import pytest
+
+from paper_2305_13144_amd import binding as ss
+from paper_2305_13144_amd import synth
+from oracle import sampling_oracle as sm
+from oracle import sched_oracle as so
+from oracle.model_oracle import OracleModel
+
+from test_gpu_parity import LOGIT_TOL, MARGIN, _say
+
+pytestmark = pytest.mark.gpu
+
+SUM_SLACK = 1e-5        # fp32 summation of the CDF in the kernel against fp64 in the oracle
+GPU_PATH_DELTA = 5e-5   # logits of one prefix computed in two batch compositions, per unit of max |logit| (asserted below)
+
+
+@pytest.fixture(scope="module")
+def tiny(oracle_built):
+    W = synth.make_weights(synth.TINY, seed=1, norm_jitter=0.1, threads=1)
+    gw = ss.Weights(synth.TINY, W)
+    yield W, OracleModel(synth.TINY, W, "f64"), gw
+    gw.close()
+
+
+def undecided_band(delta, T):
+    """Margin below which two evaluations whose logits differ by at most delta may choose differently."""
+    return 2 * delta if T == 0 else (math.exp(2 * delta / T) - 1) / 4 + SUM_SLACK
+
+
+def check_row_on_own_prefix(om, gw, prompt, toks, T, draws, what):
+    """Checks (a) and (b) of the header on every emitted token of one row.
+    Returns (decided given the GPU's logits, decided end to end, positions)."""
+    L = len(toks)
+    seq = np.concatenate([prompt, toks[:L - 1]]).astype(np.int32) if L > 1 else np.asarray(prompt, np.int32)
+    ref = om.teacher_forced(seq, first=len(prompt) - 1)
+    assert ref.shape[0] == L
+    got = ss.ss_forward_logits(gw, seq, [0, len(seq)], [len(prompt)]).astype(np.float64)
+    delta = float(np.abs(got - ref).max())
+    assert delta <= LOGIT_TOL * np.abs(ref).max(), what
+    given = end2end = 0
+    for s in range(L):
+        u = float(draws[s]) if T > 0 else 0.0
+        tok, mg = sm.sample_token(got[s], T, u)
+        if mg > undecided_band(GPU_PATH_DELTA * max(1.0, float(np.abs(got).max())), T):
+            given += 1
+            assert tok == toks[s], (what, "given the logits", s, tok, int(toks[s]), mg)
+        tok, mg = sm.sample_token(ref[s], T, u)
+        if mg > undecided_band(delta, T):
+            end2end += 1
+            assert tok == toks[s], (what, "end to end", s, tok, int(toks[s]), mg, delta)
+    return given, end2end, L
+
+
+def implied_end(toks_row, eos, cap, target=None):
+    """(length, failed) that a row's own emitted tokens imply."""
+    hits = np.flatnonzero(toks_row[:cap] == eos) if eos >= 0 else np.zeros(0, int)
+    length = cap
+    ended = False
+    if len(hits):
+        length, ended = int(hits[0]) + 1, True
+    if target is not None and target <= length:
+        length, ended = int(target), True
+    return length, not ended
+
+
+def polling_protocol(lens, cap, sync):
+    """(forwards, polls) of a host that reads the unfinished-row count after the prompt forward and then after
+    every `sync`-th decode forward (never after the last possible one), and stops on reading zero."""
+    seen = int((np.asarray(lens) > 1).sum())
+    forwards = polls = 1
+    g = 1
+    while g < cap and seen > 0:
+        forwards += 1
+        if g % sync == 0 and g + 1 < cap:
+            polls += 1
+            seen = int((np.asarray(lens) > g + 1).sum())
+        g += 1
+    return forwards, polls
+
+
+# ------------------------------------------------------------------ sampling
+@pytest.mark.parametrize("T", [1.0, 0.5, 0.1])
+def test_tiny_sampled_microbatch_own_prefix(tiny, T):
+    """16 ragged rows, 24 sampled tokens each, no end id: every decided position matches the oracle."""
+    W, om, gw = tiny
+    w = synth.make_workload(1)
+    cap = 24
+    draws = synth.make_draws(w.n, cap, seed=500 + int(T * 10))
+    _say(f"tiny sampled micro-batch T={T}")
+    r = ss.ss_generate_microbatch(gw, w.prompt_tokens, w.prompt_offsets, cap, eos_id=-1, temperature=T, draws=draws,
+                                  sync_every=5)
+    assert (r["lens"] == cap).all() and r["failed"].all()
+    assert r["stats"]["steps"] == cap and r["stats"]["idle_steps"] == 0
+    giv = e2e = tot = 0
+    for i in range(w.n):
+        g, e, L = check_row_on_own_prefix(om, gw, w.prompt(i), r["tokens"][i], T, draws[i], f"T={T} row {i}")
+        giv, e2e, tot = giv + g, e2e + e, tot + L
+    _say(f"  positions decided and equal: {giv}/{tot} given the logits, {e2e}/{tot} end to end")
+    assert giv >= 0.8 * tot
+    # the batch-composition difference that GPU_PATH_DELTA stands for: all rows together against one row alone
+    seqs = [np.concatenate([w.prompt(i), r["tokens"][i, :cap - 1]]).astype(np.int32) for i in range(w.n)]
+    offs = np.concatenate([[0], np.cumsum([len(q) for q in seqs])]).astype(np.int32)
+    together = ss.ss_forward_logits(gw, np.concatenate(seqs), offs, w.prompt_lens)
+    alone = ss.ss_forward_logits(gw, seqs[5], [0, len(seqs[5])], [int(w.prompt_lens[5])])
+    path_delta = float(np.abs(together[5 * cap:6 * cap] - alone).max())
+    _say(f"  same prefix in a batch of 16 and alone: max logit difference {path_delta:.2e}")
+    assert path_delta <= GPU_PATH_DELTA * max(1.0, float(np.abs(alone).max()))
+    # the choice is a function of (weights, prompt, draws) only: compaction flag, poll period and batch
+    # composition change nothing
+    r2 = ss.ss_generate_microbatch(gw, w.prompt_tokens, w.prompt_offsets, cap, eos_id=-1, temperature=T, draws=draws,
+                                   sync_every=1, flags=ss.SS_COMPACT)
+    assert np.array_equal(r2["tokens"], r["tokens"])
+    sub = [3, 11]
+    toks, offs = synth.gather_prompts(w, sub)
+    r3 = ss.ss_generate_microbatch(gw, toks, offs, cap, eos_id=-1, temperature=T, draws=draws[sub], sync_every=24)
+    agree = [(r3["tokens"][k] == r["tokens"][i]).all() for k, i in enumerate(sub)]
+    _say(f"  rows re-run in a batch of 2: identical = {agree}")   # other kernels, other rounding: reported only
+
+
+def test_sampler_distribution_peaked_and_flat_draws(tiny):
+    """Draws at the extremes (0 and just below 1) and a low temperature: first and last tokens of the CDF."""
+    W, om, gw = tiny
+    w = synth.make_workload(1)
+    cap = 6
+    draws = np.zeros((w.n, cap), np.float32)
+    draws[::2] = np.float32(1.0) - np.float32(2.0 ** -24)
+    r = ss.ss_generate_microbatch(gw, w.prompt_tokens, w.prompt_offsets, cap, temperature=0.7, draws=draws)
+    for i in range(w.n):
+        check_row_on_own_prefix(om, gw, w.prompt(i), r["tokens"][i], 0.7, draws[i], f"extreme draws row {i}")
+    # u = 0 always picks token 0 (its mass is positive); u -> 1 picks the last token with non-negligible mass
+    assert (r["tokens"][1::2] == 0).all()
+    assert (r["tokens"][::2] >= synth.TINY.vocab - 4).all()
+
+
+# ------------------------------------------------------------------ end-of-sequence id
+@pytest.mark.parametrize("T,flags,sync", [(0.0, 0, 4), (0.0, ss.SS_COMPACT, 1), (0.1, ss.SS_COMPACT, 3), (0.1, 0, 8)])
+def test_tiny_eos_ends_rows_at_different_steps(tiny, T, flags, sync):
+    """The end id is the token the oracle's unbounded runs emit most often, so rows end at different, data
+    dependent steps that the host does not know; some never end and fail at the cap."""
+    W, om, gw = tiny
+    w = synth.make_workload(1)
+    cap = 28
+    draws = synth.make_draws(w.n, cap, seed=600)
+    free = [sm.generate_query(om, w.prompt(i), cap, -1, T, draws[i]) for i in range(w.n)]
+    ids, counts = np.unique(np.concatenate([np.unique(f["tokens"]) for f in free]), return_counts=True)
+    eos = int(ids[np.argmax(counts)])
+    ends = [int(np.flatnonzero(f["tokens"] == eos)[0]) + 1 if (f["tokens"] == eos).any() else None for f in free]
+    _say(f"tiny eos={eos} T={T} flags={flags} sync_every={sync}: oracle ends {ends}")
+    assert sum(e is not None for e in ends) >= 3
+    r = ss.ss_generate_microbatch(gw, w.prompt_tokens, w.prompt_offsets, cap, eos_id=eos, temperature=T, draws=draws,
+                                  sync_every=sync, flags=flags)
+    exact = giv = tot = 0
+    for i in range(w.n):
+        L = int(r["lens"][i])
+        row = r["tokens"][i]
+        # what the row's own tokens imply: bit-exact
+        assert (row[:L] >= 0).all() and (row[L:] == -1).all()
+        assert (L, bool(r["failed"][i])) == implied_end(row[:L], eos, cap), i
+        assert (row[:L - 1] != eos).all()
+        g, e, _ = check_row_on_own_prefix(om, gw, w.prompt(i), row[:L], T, draws[i], f"eos row {i}")
+        giv, tot = giv + g, tot + L
+        # a row decided end to end at every position: the oracle's whole result, bit-exact
+        if e == L:
+            ref = sm.generate_query(om, w.prompt(i), cap, eos, T, draws[i])
+            exact += 1
+            assert L == ref["length"] and bool(r["failed"][i]) == ref["failed"], i
+            assert np.array_equal(row[:L], ref["tokens"]), i
+    _say(f"  {giv}/{tot} positions decided given the logits and equal; {exact}/{w.n} rows decided end to end at every "
+         f"position and bit-exact; lens {r['lens'].tolist()}")
+    assert giv >= 0.8 * tot
+    assert len(set(r["lens"].tolist())) >= 3
+    st = r["stats"]
+    longest = int(r["lens"].max())
+    assert st["steps"] - longest == st["idle_steps"] and 0 <= st["idle_steps"] < sync
+    assert (st["steps"], st["polls"]) == polling_protocol(r["lens"], cap, sync)
+    if not flags:
+        assert st["row_steps"] == w.n * st["steps"]
+    else:
+        assert st["row_steps"] <= w.n * st["steps"]
+        if sync == 1:   # polled after every forward: exactly the rows that still owed a token were computed
+            assert st["row_steps"] == sum(int(l) for l in r["lens"])
+
+
+def test_tiny_all_rows_end_on_first_token(tiny):
+    """Every row's first token is its end id's position 0 (target length 1): one forward, nothing to decode."""
+    W, om, gw = tiny
+    w = synth.make_workload(1)
+    r = ss.ss_generate_microbatch(gw, w.prompt_tokens, w.prompt_offsets, 9, target_lens=np.ones(w.n, np.int32),
+                                  flags=ss.SS_COMPACT)
+    assert (r["lens"] == 1).all() and not r["failed"].any() and r["stats"]["steps"] == 1
+    assert (r["tokens"][:, 1:] == -1).all()
+    g = ss.ss_decode_microbatch(gw, w.prompt_tokens, w.prompt_offsets, 9, np.ones(w.n, np.int32))
+    assert np.array_equal(g["tokens"], r["tokens"])
+
+
+@pytest.mark.parametrize("flags", [0, ss.SS_COMPACT])
+@pytest.mark.parametrize("sync", [1, 7])
+def test_tiny_polled_target_lengths_equal_known_lengths(tiny, flags, sync):
+    """Simulated ends applied by the device and discovered by polling give the tokens, lengths and failure
+    flags of the entry point whose host knows the lengths (same kernels on the same rows: bit-exact)."""
+    W, om, gw = tiny
+    w = synth.make_workload(1)
+    cap = 20
+    known = ss.ss_decode_microbatch(gw, w.prompt_tokens, w.prompt_offsets, cap, w.target_lens, flags)
+    r = ss.ss_generate_microbatch(gw, w.prompt_tokens, w.prompt_offsets, cap, target_lens=w.target_lens,
+                                  sync_every=sync, flags=flags)
+    assert np.array_equal(r["lens"], known["lens"]) and np.array_equal(r["failed"], known["failed"])
+    assert np.array_equal(r["lens"], np.minimum(w.target_lens, cap))
+    assert np.array_equal(r["failed"].astype(bool), w.target_lens > cap)
+    if sync == 1 or not flags:
+        assert np.array_equal(r["tokens"], known["tokens"])
+    else:   # rows between polls ride in larger launches: other kernel variants, tokens may differ at near-ties
+        same = (r["tokens"] == known["tokens"]).all(axis=1)
+        _say(f"  rows identical to the known-length run: {int(same.sum())}/{w.n}")
+    st = r["stats"]
+    assert st["steps"] == known["stats"]["steps"] + st["idle_steps"] and st["idle_steps"] < sync
+    assert (st["steps"], st["polls"]) == polling_protocol(r["lens"], cap, sync)
+
+
+# ------------------------------------------------------------------ whole group
+def test_tiny_group_generate_with_failures_and_recomputation(tiny):
+    """A scheduled group whose rows end by sampled end ids or simulated ends: queries that overrun their
+    bin's cap are collected and recomputed with the same draws."""
+    W, om, gw = tiny
+    w = synth.make_group(synth.TINY, 64, 4242, ("uniform", 4, 30), ("lognormal", 20.0, 0.7, 1, 64), 0.3, 64, 8,
+                         ("SORT", "BIN", "FCR", "VBS", "COMPACT"), base_batch=4, max_batch=16)
+    T = 0.1
+    draws = synth.make_draws(w.n, w.l_max, seed=700)
+    pol = ss.make_policy(w.flags, w.base_batch, w.l_max, w.max_batch)
+    # the end id: the id that the oracle's forced-length runs of the first queries emit most often
+    probe = [sm.generate_query(om, w.prompt(i), int(w.target_lens[i]), -1, T, draws[i],
+                               target_len=int(w.target_lens[i])) for i in range(12)]
+    ids, counts = np.unique(np.concatenate([p["tokens"] for p in probe]), return_counts=True)
+    eos = int(ids[np.argmax(counts)])
+    _say(f"tiny group of {w.n}, T={T}, eos={eos}")
+    r = ss.ss_run_group_generate(gw, w.prompt_tokens, w.prompt_offsets, w.pred_lens, w.bin_width, pol, eos_id=eos,
+                                 temperature=T, draws=draws, target_lens=w.target_lens, sync_every=4)
+    gs = r["stats"]
+    plan = so.schedule(w.pred_lens, w.n, w.bin_width,
+                       so.Policy(flags=tuple(w.flags), base_batch=w.base_batch, l_max=w.l_max, max_batch=w.max_batch))
+    cap_of = np.zeros(w.n, np.int64)
+    for mb in plan:
+        cap_of[np.asarray(mb.idx)] = mb.cap
+    n_failed = 0
+    decided = total = 0
+    for i in range(w.n):
+        L = int(r["lens"][i])
+        row = r["tokens"][i]
+        assert (row[:L] >= 0).all() and (row[L:] == -1).all()
+        length, failed = implied_end(row[:L], eos, w.l_max, int(w.target_lens[i]))
+        assert L == length and not failed
+        n_failed += L > cap_of[i]
+        if i % 4 == 0:
+            d, _, t = check_row_on_own_prefix(om, gw, w.prompt(i), row[:L], T, draws[i], f"group query {i}")
+            decided += d
+            total += t
+    _say(f"  {decided}/{total} sampled positions decided given the logits and equal; failures {gs['n_failed']}, "
+         f"polls {gs['polls']}, idle forwards {gs['idle_steps']}")
+    assert gs["n_failed"] == n_failed and n_failed >= 1
+    assert gs["useful_tokens"] == int(r["lens"].sum())
+    assert gs["n_mb_first"] == len(plan)
+    assert decided >= 0.8 * total
+
+
+# ------------------------------------------------------------------ full-width vocabulary
+def test_wide_sampled_tokens_vocab_32000(oracle_built):
+    """7B widths at 2 layers: the sampler's chunking at vocab 32000 (1000 busy threads, 24 idle)."""
+    shape = synth.LLAMA7B.with_layers(2)
+    W = synth.make_weights(shape, seed=2, norm_jitter=0.05)
+    gw = ss.Weights(shape, W)
+    try:
+        om = OracleModel(shape, W, "f64")
+        w = synth.make_group(shape, 5, 99, ("uniform", 5, 12), ("uniform", 1, 4), None, 4, 0, ())
+        cap = 4
+        for T in (0.3, 0.05):
+            draws = synth.make_draws(w.n, cap, seed=800)
+            _say(f"wide sampled micro-batch, T={T}")
+            r = ss.ss_generate_microbatch(gw, w.prompt_tokens, w.prompt_offsets, cap, temperature=T, draws=draws)
+            dec = e2e = tot = 0
+            for i in range(w.n):
+                d, e, L = check_row_on_own_prefix(om, gw, w.prompt(i), r["tokens"][i], T, draws[i], f"wide T={T} row {i}")
+                dec, e2e, tot = dec + d, e2e + e, tot + L
+            _say(f"  positions decided and equal: {dec}/{tot} given the logits, {e2e}/{tot} end to end")
+            assert dec >= 0.6 * tot
+    finally:
+        gw.close()
+
+
+# ------------------------------------------------------------------ argument checking
+def test_generate_rejects_bad_options(tiny):
+    W, om, gw = tiny
+    w = synth.make_workload(1)
+    ok = dict(eos_id=-1, temperature=0.5, draws=synth.make_draws(w.n, 8, seed=1), sync_every=2)
+
+    def call(**kw):
+        a = dict(ok)
+        a.update(kw)
+        return ss.ss_generate_microbatch(gw, w.prompt_tokens, w.prompt_offsets, 8, **a)
+
+    call()
+    for bad in (dict(eos_id=-2), dict(eos_id=synth.TINY.vocab), dict(temperature=-0.1), dict(temperature=float("nan")),
+                dict(sync_every=0), dict(draws=None), dict(draws=synth.make_draws(w.n, 7, seed=1)),
+                dict(target_lens=np.zeros(w.n, np.int32))):
+        with pytest.raises(ss.SsError) as e:
+            call(**bad)
+        assert e.value.code == ss.SS_EINVAL, bad
+    d = synth.make_draws(w.n, 8, seed=1)
+    d[3, 2] = 1.0
+    with pytest.raises(ss.SsError):
+        call(draws=d)
+    # the handle is usable after every rejection
+    assert call()["lens"].shape == (w.n,)
