@@ -81,6 +81,34 @@ def sweeps(a, ss, gw, wl, shape) -> int:
            run until their longest row finishes (a 64-query subset of the group keeps batch 1 affordable).
     group: throughput against group size for the full policy and for vanilla batching on the same queries."""
     from paper_2305_13144_amd import synth
+    if a.sweep == "sync":
+        # The configured group with ends the host does not know: the device applies the same lengths and the host
+        # polls every `sync` decode forwards.  T = 0 emits the tokens of the known-length run, so the difference to
+        # it is the polling protocol alone (reads + forwards run after the last row ended); T = 0.5 adds the sampler.
+        pol = ss.make_policy(wl.flags, wl.base_batch, wl.l_max, wl.max_batch)
+        useful = int(wl.target_lens.sum())
+        ss.ss_run_group(gw, wl.prompt_tokens, wl.prompt_offsets, wl.target_lens, wl.pred_lens, wl.bin_width, pol)   # warm
+        k = ss.ss_run_group(gw, wl.prompt_tokens, wl.prompt_offsets, wl.target_lens, wl.pred_lens, wl.bin_width, pol)
+        print(json.dumps(dict(sweep="sync", mode="lengths known to the host", sync_every=None, temperature=0.0,
+                              useful_tokens_per_s=useful / (k["stats"]["wall_ms"] / 1e3), ms=k["stats"]["wall_ms"],
+                              steps=k["stats"]["steps"])), flush=True)
+        draws = synth.make_draws(wl.n, wl.l_max, seed=20230513)
+        for T in (0.0, 0.5):
+            for sync in (1, 2, 4, 8, 16, 32, 64):
+                g = ss.ss_run_group_generate(gw, wl.prompt_tokens, wl.prompt_offsets, wl.pred_lens, wl.bin_width, pol,
+                                             eos_id=-1, temperature=T, draws=draws, target_lens=wl.target_lens,
+                                             sync_every=sync)
+                assert np.array_equal(g["lens"], wl.target_lens)
+                if T == 0.0 and "COMPACT" not in wl.flags:
+                    assert np.array_equal(g["tokens"], k["tokens"])
+                st = g["stats"]
+                row = dict(sweep="sync", mode="ends polled", sync_every=sync, temperature=T,
+                           useful_tokens_per_s=useful / (st["wall_ms"] / 1e3), ms=st["wall_ms"], steps=st["steps"],
+                           polls=st["polls"], idle_steps=st["idle_steps"], vs_known=k["stats"]["wall_ms"] / st["wall_ms"])
+                log(f"sweep sync {row}")
+                print(json.dumps(row), flush=True)
+        gw.close()
+        return 0
     full = synth.make_workload(4, shape=shape)                      # 1024 queries, with predictions
     if a.sweep == "batch":
         sub = list(range(64))
@@ -136,9 +164,12 @@ def main() -> int:
     ap.add_argument("--ablation", action="store_true",
                     help="instead of the headline run: the paper's Table 5 ablation (Binning x FCR x VBS), a perfect "
                          "predictor and compaction on the same group, one pass each; prints one JSON line per row")
-    ap.add_argument("--sweep", choices=["batch", "group"], default=None,
+    ap.add_argument("--sweep", choices=["batch", "group", "sync"], default=None,
                     help="instead of the headline run: throughput against micro-batch size or against group size "
-                         "(the paper's Fig. 3a / 3b on the synthetic workload)")
+                         "(the paper's Fig. 3a / 3b on the synthetic workload), or ('sync') the group run with ends "
+                         "that the host must poll for, against the poll period, greedy and sampled at T=0.5")
+    ap.add_argument("--no-generate", action="store_true",
+                    help="skip the leg that reruns the group with sampled tokens and ends discovered by polling")
     ap.add_argument("--roofline-only", action="store_true",
                     help="only the roofline legs (weight-stream kernels and one decode step); the command profiled "
                          "under rocprofv3 for profiles/")
@@ -212,6 +243,26 @@ def main() -> int:
             padded_row_steps=sv["padded_row_steps"])
         extras["scheduled_over_vanilla"] = (useful / (st["wall_ms"] / 1e3)) / extras["vanilla_batching"]["useful_tokens_per_s"]
         log(f"vanilla: {sv['wall_ms']:.0f} ms -> ratio {extras['scheduled_over_vanilla']:.3f}")
+
+    if not a.roofline_only and not a.no_generate and a.steps > 0:
+        # The same group when the host does not know the lengths (Sec. 5.1 of the paper samples at T = 0.5 and rows
+        # end by themselves): tokens drawn by the sampling kernel, the same lengths applied on the device as
+        # simulated ends, the host polling the unfinished-row count after every decode forward (the period that
+        # profiles/polled_generation_sync_sweep_7b.md shows to be the cheapest).
+        draws = synth.make_draws(wl.n, wl.l_max, seed=20230513)
+        rg = ss.ss_run_group_generate(gw, wl.prompt_tokens, wl.prompt_offsets, wl.pred_lens, wl.bin_width, pol,
+                                      eos_id=-1, temperature=0.5, draws=draws, target_lens=wl.target_lens, sync_every=1)
+        assert np.array_equal(rg["lens"], wl.target_lens)
+        sg = rg["stats"]
+        extras["sampled_polled_generation"] = dict(
+            what="same group and policy; tokens sampled at T=0.5 on the device, ends applied on the device and "
+                 "discovered by the host polling after every decode forward",
+            useful_tokens_per_s=useful / (sg["wall_ms"] / 1e3), ms=sg["wall_ms"], steps=sg["steps"], polls=sg["polls"],
+            idle_steps=sg["idle_steps"], n_failed=sg["n_failed"],
+            over_known_lengths=(useful / (sg["wall_ms"] / 1e3)) / (useful / (st["wall_ms"] / 1e3)))
+        log(f"sampled + polled: {sg['wall_ms']:.0f} ms ({sg['steps']} forwards, {sg['polls']} polls, "
+            f"{sg['idle_steps']} idle) -> {extras['sampled_polled_generation']['over_known_lengths']:.3f} of the "
+            f"known-length pass")
 
     if not a.roofline_only and wl.pred_lens is not None:
         # Length-perception overhead, simulated (Sec. 4.1, "Overhead of Length Prediction": one prompt forward plus
