@@ -406,6 +406,21 @@ int check_gen_opts(const ss_weights* w, const ss_gen_opts* g, int rows, int need
     return SS_OK;
 }
 
+// Three HIP events that are destroyed however the call ends.
+struct Events3 {
+    hipEvent_t e[3] = {nullptr, nullptr, nullptr};
+    int create()
+    {
+        for (auto& x : e) HIPCHK(hipEventCreate(&x));
+        return SS_OK;
+    }
+    ~Events3()
+    {
+        for (auto& x : e)
+            if (x) (void)hipEventDestroy(x);
+    }
+};
+
 // Clears the handle's token-choice state however the call ends.
 struct ChoiceGuard {
     ss_weights* w;
@@ -463,10 +478,9 @@ int decode_microbatch_impl(ss_weights* w, const int32_t* prompt_tokens, const in
     }
     ss::launch_fill_i32(st.out_tok, -1, (size_t)B * max_new, s);
 
-    hipEvent_t e0, e1, e2;
-    HIPCHK(hipEventCreate(&e0));
-    HIPCHK(hipEventCreate(&e1));
-    HIPCHK(hipEventCreate(&e2));
+    Events3 ev;
+    if (int rc = ev.create()) return rc;
+    const hipEvent_t e0 = ev.e[0], e1 = ev.e[1], e2 = ev.e[2];
     HIPCHK(hipEventRecord(e0, s));
     forward(w, n_prompt, B, w->d_sel, st.d_nlive, false, s);
     ss::launch_step_update(st, compact, eos_id, s);
@@ -544,9 +558,6 @@ int decode_microbatch_impl(ss_weights* w, const int32_t* prompt_tokens, const in
         stats->polls = polls;
         stats->idle_steps = forwards - longest;
     }
-    (void)hipEventDestroy(e0);
-    (void)hipEventDestroy(e1);
-    (void)hipEventDestroy(e2);
     return SS_OK;
 }
 

@@ -170,3 +170,33 @@ def test_7b_widths_variable_batch_sizes(rows, oracle_built):
                 check_tokens_teacher_forced(om, w.prompt(j), r["tokens"][j, :int(r["lens"][j])], what=f"row {j}")
     finally:
         gw.close()
+
+
+def test_7b_full_depth_sampled_rows_that_end_by_themselves(full7b):
+    """Full depth, vocabulary 32000, the launch configuration the benchmark's sampled leg runs: 16 rows sampled at
+    T = 0.5 with device-side ends; every emitted token is the oracle's inverse-CDF choice on the GPU's own logits
+    and prefix, lengths and flags are exact, and the logits themselves meet the bar."""
+    from test_gpu_generate import check_row_on_own_prefix
+    shape, W, om, gw = full7b
+    w = synth.make_workload(3)
+    idx = list(range(16))
+    toks, offs = synth.gather_prompts(w, idx)
+    cap = 6
+    t = np.array([1, 2, 3, 4, 5, 6, 7, 8, 6, 6, 6, 6, 3, 3, 9, 1], np.int32)
+    draws = synth.make_draws(16, cap, seed=31)
+    _say("7B x32 sampled micro-batch with device-side ends")
+    for T in (0.5, 0.05):
+        r = ss.ss_generate_microbatch(gw, toks, offs, cap, temperature=T, draws=draws, target_lens=t, sync_every=2,
+                                      flags=ss.SS_COMPACT)
+        assert np.array_equal(r["lens"], np.minimum(t, cap))
+        assert np.array_equal(r["failed"].astype(bool), t > cap)
+        assert r["stats"]["steps"] == cap + 0 and r["stats"]["idle_steps"] == 0
+        dec = tot = 0
+        for j in (5, 14):
+            L = int(r["lens"][j])
+            assert (r["tokens"][j, :L] >= 0).all() and (r["tokens"][j, L:] == -1).all()
+            g, e, L = check_row_on_own_prefix(om, gw, w.prompt(idx[j]), r["tokens"][j, :L], T, draws[j], f"7B T={T} row {j}")
+            dec, tot = dec + g, tot + L
+        _say(f"  T={T}: {dec}/{tot} positions decided given the logits and equal")
+        if T < 0.1:
+            assert dec >= 0.5 * tot
