@@ -389,6 +389,48 @@ def test_runs_are_bit_repeatable(tiny, wide2):
 
 
 # ------------------------------------------------------------------ error paths that need a handle
+def test_limits_longest_row_and_largest_batch(tiny):
+    """The documented maxima: a row that fills all 4096 positions (prompt 4090 + 6 generated; the last decode
+    attention reads 4095 slots in 16 passes), one position more is rejected; a micro-batch of 1024 rows (the
+    bookkeeping kernel's limit, one thread per row), 1025 are rejected; and the smallest call (1 row, 1 token)."""
+    W, om, gw = tiny
+    rng = np.random.default_rng(4096)
+    long_prompt = rng.integers(0, synth.TINY.vocab, size=4090).astype(np.int32)
+    forced = rng.integers(0, synth.TINY.vocab, size=6).astype(np.int32)
+    seq = np.concatenate([long_prompt, forced])
+    _say("tiny row of 4096 positions, teacher-forced")
+    got = ss.ss_forward_logits(gw, seq, [0, 4096], [4090])
+    ref = om.teacher_forced(seq, first=4089)
+    assert got.shape == ref.shape == (7, synth.TINY.vocab)
+    check_logits(got, ref, "4096 positions")
+    r = ss.ss_decode_microbatch(gw, long_prompt, [0, 4090], 6, [6])
+    assert r["lens"].tolist() == [6] and (r["tokens"][0] >= 0).all()
+    check_tokens_teacher_forced(om, long_prompt, r["tokens"][0], what="4096 positions, generated")
+    with pytest.raises(ss.SsError) as e:
+        ss.ss_decode_microbatch(gw, long_prompt, [0, 4090], 7, [7])
+    assert e.value.code == ss.SS_EINVAL
+
+    _say("tiny 1024-row micro-batch")
+    w = synth.make_group(synth.TINY, 1025, 2024, ("uniform", 3, 9), ("uniform", 1, 5), None, 5, 0, ())
+    toks, offs = synth.gather_prompts(w, range(1024))
+    t = w.target_lens[:1024]
+    for flags in (0, ss.SS_COMPACT):
+        r = ss.ss_decode_microbatch(gw, toks, offs, 4, t, flags)
+        assert np.array_equal(r["lens"], np.minimum(t, 4)) and np.array_equal(r["failed"].astype(bool), t > 4)
+        assert r["stats"]["row_steps"] == (int(np.minimum(t, 4).sum()) if flags else 1024 * int(min(4, t.max())))
+        for j in (0, 63, 64, 1000, 1023):
+            L = int(r["lens"][j])
+            assert (r["tokens"][j, :L] >= 0).all() and (r["tokens"][j, L:] == -1).all()
+            check_tokens_teacher_forced(om, w.prompt(j), r["tokens"][j, :L], what=f"1024 rows, row {j}")
+    with pytest.raises(ss.SsError) as e:
+        ss.ss_decode_microbatch(gw, w.prompt_tokens, w.prompt_offsets, 4, w.target_lens, 0)
+    assert e.value.code == ss.SS_EINVAL
+
+    r = ss.ss_decode_microbatch(gw, [5], [0, 1], 1, [1])
+    assert r["lens"].tolist() == [1] and r["stats"]["steps"] == 1
+    check_tokens_teacher_forced(om, np.array([5], np.int32), r["tokens"][0], what="1 row, 1 token")
+
+
 def test_invalid_generation_arguments(tiny):
     W, om, gw = tiny
     good = dict(prompt_tokens=[1, 2, 3, 4], prompt_offsets=[0, 2, 4], max_new=4, target_lens=[2, 3])
