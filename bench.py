@@ -324,7 +324,7 @@ def main() -> int:
     if not a.no_cpu:
         from oracle.model_oracle import OracleModel
         om = OracleModel(shape, W, "f32")
-        rows, cap = [0, 1], 8
+        rows, cap = [0, 1, 2, 3], 32
         toks, offs = synth.gather_prompts(wl, rows)
         tl = np.minimum(wl.target_lens[rows], cap)
         t0 = time.perf_counter()
@@ -332,7 +332,7 @@ def main() -> int:
         dtc = time.perf_counter() - t0
         cpu = dict(value=float(ro["lens"].sum() / dtc), unit="tokens/s", cores=int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1)),
                    kind="oracle",
-                   sample=f"fp32 build of the oracle; queries 0-1 of the group as one micro-batch, cap {cap}: "
+                   sample=f"fp32 build of the oracle; queries 0-{len(rows) - 1} of the group as one micro-batch, cap {cap}: "
                           f"{int(offs[-1])} prompt token-rows + {int(ro['lens'].sum())} generated tokens in {dtc:.1f}s")
         log(f"cpu oracle: {cpu}")
 

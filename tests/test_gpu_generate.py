@@ -284,6 +284,19 @@ def test_tiny_group_generate_with_failures_and_recomputation(tiny):
     assert gs["useful_tokens"] == int(r["lens"].sum())
     assert gs["n_mb_first"] == len(plan)
     assert decided >= 0.8 * total
+    # polled after every forward, the run is step for step the one the scheduler oracle accounts for when it is
+    # given the lengths the rows turned out to have: forwards, padded and computed row-steps, failures, all exact
+    r1 = ss.ss_run_group_generate(gw, w.prompt_tokens, w.prompt_offsets, w.pred_lens, w.bin_width, pol, eos_id=eos,
+                                  temperature=T, draws=draws, target_lens=w.target_lens, sync_every=1)
+    assert np.array_equal(r1["lens"], r["lens"])
+    ref = so.run_group(w.pred_lens, r1["lens"], w.bin_width,
+                       so.Policy(flags=tuple(w.flags), base_batch=w.base_batch, l_max=w.l_max, max_batch=w.max_batch))
+    g1 = r1["stats"]
+    assert g1["idle_steps"] == 0
+    assert g1["steps"] == ref["steps"] and g1["padded_row_steps"] == ref["padded_row_steps"]
+    assert g1["computed_row_steps"] == ref["live_row_steps"]
+    assert g1["n_failed"] == ref["n_failed"] and g1["useful_tokens"] == ref["useful_tokens"]
+    assert g1["n_mb_first"] == ref["first"].n_mb and g1["n_mb_failure"] == ref["second"].n_mb
 
 
 # ------------------------------------------------------------------ full-width vocabulary
