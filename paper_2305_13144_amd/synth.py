@@ -216,3 +216,12 @@ def make_draws(n: int, l_max: int, seed: int) -> np.ndarray:
     sampled generation consumes, supplied as an input to both the library and the oracle."""
     rng = np.random.Generator(np.random.PCG64(np.random.SeedSequence([seed, 0x5A17])))
     return rng.random((n, l_max), dtype=np.float32)
+
+
+def make_predictions_max_of(target_lens: np.ndarray, sigma: float, k: int, seed: int) -> np.ndarray:
+    """Predictions of a predictor trained on the largest of k noisy observations of each length (the paper's
+    Sec. 4.2 builds its training target as the maximum over several generations, which biases predictions
+    upward and trades padding for fewer failures): max(1, rint(t * exp(sigma * max_k z))), z ~ N(0,1)."""
+    rng = np.random.Generator(np.random.PCG64(np.random.SeedSequence([seed, 0xB1A5])))
+    z = rng.standard_normal((len(target_lens), k)).max(axis=1)
+    return np.maximum(1, np.rint(np.asarray(target_lens) * np.exp(sigma * z))).astype(np.int32)
