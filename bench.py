@@ -41,7 +41,9 @@ def ablation(a, ss, gw, wl, shape) -> int:
     """Table 5 of the paper on the synthetic group: which component buys what on this hardware.
     Every row is one pass over the same queries with the same predictions (multiplicative lognormal noise,
     sigma 0.3); 'perfect' uses the true length as the prediction (the paper's upper-bound row of Table 4); 'biased
-    upward' imitates the paper's training target, the maximum over several generations (Sec. 4.2)."""
+    upward' imitates the paper's training target, the maximum over several generations (Sec. 4.2); 'power-of-two
+    batch sizes' is the rule Sec. 4.2 states for its own runs (16 from length 300 on, else 256*50/L rounded to a
+    power of two) in place of the configured clamp(floor(16*L_max/L), 16, 256)."""
     rows = [("vanilla", (), False), ("sort", ("SORT",), False), ("sort+FCR", ("SORT", "FCR"), False),
             ("sort+FCR+VBS", ("SORT", "FCR", "VBS"), False), ("binning", ("SORT", "BIN"), False),
             ("binning+FCR", ("SORT", "BIN", "FCR"), False), ("binning+FCR+VBS", ("SORT", "BIN", "FCR", "VBS"), False),
@@ -49,7 +51,10 @@ def ablation(a, ss, gw, wl, shape) -> int:
             ("binning+FCR+VBS, perfect predictor", ("SORT", "BIN", "FCR", "VBS"), True),
             ("binning+FCR+VBS, predictor biased upward (max of 4 draws)", ("SORT", "BIN", "FCR", "VBS"), "max4"),
             ("binning+FCR+VBS+compaction, predictor biased upward (max of 4 draws)",
-             ("SORT", "BIN", "FCR", "VBS", "COMPACT"), "max4")]
+             ("SORT", "BIN", "FCR", "VBS", "COMPACT"), "max4"),
+            ("binning+FCR+VBS, paper's power-of-two batch sizes", ("SORT", "BIN", "FCR", "VBS"), "pow2"),
+            ("binning+FCR+VBS+compaction, paper's power-of-two batch sizes",
+             ("SORT", "BIN", "FCR", "VBS", "COMPACT"), "pow2")]
     if a.ablation_only:
         rows = [r for r in rows if r[0] == "vanilla" or a.ablation_only in r[0]]
     pred = wl.pred_lens
@@ -64,8 +69,9 @@ def ablation(a, ss, gw, wl, shape) -> int:
     ss.ss_decode_microbatch(gw, wt, wo, 4, np.full(len(wo) - 1, 4, np.int32), 0)
     base = None
     for name, flags, perfect in rows:
-        pol = ss.make_policy(flags, wl.base_batch, wl.l_max, wl.max_batch)
-        p = None if not flags else (pred_max4 if perfect == "max4" else wl.target_lens if perfect else pred)
+        pol = ss.make_policy(flags, wl.base_batch, wl.l_max, wl.max_batch,
+                             ss.SS_VBS_PAPER_POW2 if perfect == "pow2" else ss.SS_VBS_CLAMP_FLOOR)
+        p = None if not flags else (pred_max4 if perfect == "max4" else wl.target_lens if perfect is True else pred)
         r = ss.ss_run_group(gw, wl.prompt_tokens, wl.prompt_offsets, wl.target_lens, p, binw if "BIN" in flags else 0, pol)
         assert np.array_equal(r["lens"], wl.target_lens)
         st = r["stats"]

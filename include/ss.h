@@ -216,8 +216,16 @@ typedef struct {
                                    softmax(logits / temperature) by inverse CDF in vocabulary order:
                                    the smallest v whose cumulative probability exceeds the draw               */
     const float* draws;         /* host, float32, draws[i*draws_stride + s] in [0,1) is the draw for token
-                                   number s of row (query) i; ignored (may be NULL) when temperature == 0      */
-    int32_t draws_stride;       /* >= max_new (ss_generate_microbatch) / >= base_len (ss_run_group_generate)  */
+                                   number s of row (query) i.  NULL with temperature > 0: the draws come from
+                                   the library's counter-based generator instead (seed, draw_ids below)        */
+    int32_t draws_stride;       /* with draws: >= max_new (ss_generate_microbatch) / >= base_len
+                                   (ss_run_group_generate)                                                    */
+    uint64_t seed;              /* generator key.  The draw for token number s of the row with id q is
+                                   (x0 >> 8) * 2^-24, x0 = first output word of Philox4x32-10 (Salmon et al.,
+                                   "Parallel random numbers: as easy as 1, 2, 3", SC 2011) on the counter
+                                   (s, q, 0, 0) under the key (seed mod 2^32, seed >> 32)                       */
+    const int32_t* draw_ids;    /* host, int32 per row (query), >= 0, nullable: the id q of each row; NULL = the
+                                   row's (query's) index.  A row keeps its draws wherever it is scheduled        */
     const int32_t* target_lens; /* host, int32 per row, nullable: a simulated end of sequence after that many
                                    tokens, whichever of it and eos_id comes first.  The host loop never looks
                                    at it: the device applies it, the host learns of it by polling             */
@@ -236,16 +244,16 @@ typedef struct {
  *   out_lens    host, int32[B]: tokens emitted (the end-of-sequence token included)
  *   out_failed  host, uint8[B]: the row was still unfinished after max_new tokens (Sec. 4.1 failure)
  * Other arguments, ownership and errors as ss_decode_microbatch; additionally SS_EINVAL for a NULL opts,
- * eos_id outside [-1, vocab), temperature < 0 or not finite, sync_every < 1, NULL draws with
- * temperature > 0, draws_stride < max_new, a draw outside [0,1), target_lens[i] < 1.
+ * eos_id outside [-1, vocab), temperature < 0 or not finite, sync_every < 1, draws given with
+ * draws_stride < max_new or a draw outside [0,1), draw_ids[i] < 0, target_lens[i] < 1.
  */
 int ss_generate_microbatch(ss_weights* w, const int32_t* prompt_tokens, const int32_t* prompt_offsets, int32_t B,
                            int32_t max_new, const ss_gen_opts* opts, uint32_t flags, int32_t* out_tokens,
                            int32_t* out_lens, uint8_t* out_failed, ss_stats* stats, void* hip_stream);
 
 /*
- * ss_run_group for rows that end by themselves.  opts->draws and opts->target_lens are indexed by query
- * (n rows, stride draws_stride >= policy->base_len), so a recomputed query sees the same draws and
+ * ss_run_group for rows that end by themselves.  opts->draws, opts->draw_ids and opts->target_lens are indexed
+ * by query (n rows, stride draws_stride >= policy->base_len), so a recomputed query sees the same draws and
  * repeats its first attempt token for token before going on.  A query that is unfinished at a cap below
  * policy->base_len is collected and recomputed with cap = base_len; one that is unfinished at base_len is
  * complete (truncated there).  stats->useful_tokens = sum of out_lens.

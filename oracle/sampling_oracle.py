@@ -17,6 +17,12 @@ end-of-sequence token (which is emitted and counted), by an optional forced leng
 The draws are inputs, so the output depends on nothing but (weights, prompt, draws): not on the
 micro-batch a query ran in, on compaction, on how often the host polled, or on a recomputation.
 
+The draws may also come from a counter-based generator, so that a caller needs no table: Philox4x32-10
+(Salmon, Moraes, Dror, Shaw: "Parallel random numbers: as easy as 1, 2, 3", SC 2011, Sec. 3.3 and Table 2 for
+the round function and its constants) on the counter (token number, row id, 0, 0) under a 64-bit key; the
+draw is the top 24 bits of the first output word times 2^-24.  Written here from that definition with Python
+integers; pinned to the published known-answer vectors.
+
 Pins: tests/test_oracle_sampling_pins.py.
 """
 from __future__ import annotations
@@ -102,3 +108,32 @@ def next_token_on_prefix(model, prompt, emitted, temperature: float, u: float):
     seq_toks = np.concatenate([np.asarray(prompt, np.int32), np.asarray(emitted, np.int32)])
     lg = model.teacher_forced(seq_toks, first=len(seq_toks) - 1)[0]
     return sample_token(lg, temperature, u)
+
+
+# --------------------------------------------------------------------------- counter-based draws
+_PHILOX_M = (0xD2511F53, 0xCD9E8D57)     # round multipliers
+_PHILOX_W = (0x9E3779B9, 0xBB67AE85)     # key schedule increments (golden ratio, sqrt(3) - 1)
+_MASK = 0xFFFFFFFF
+
+
+def philox4x32_10(counter, key):
+    """Ten rounds of the Philox 4x32 bijection: four 32-bit counter words, two key words -> four words."""
+    c = [int(x) & _MASK for x in counter]
+    k = [int(x) & _MASK for x in key]
+    for _ in range(10):
+        p0 = _PHILOX_M[0] * c[0]
+        p1 = _PHILOX_M[1] * c[2]
+        c = [(p1 >> 32) ^ c[1] ^ k[0], p1 & _MASK, (p0 >> 32) ^ c[3] ^ k[1], p0 & _MASK]
+        k = [(k[0] + _PHILOX_W[0]) & _MASK, (k[1] + _PHILOX_W[1]) & _MASK]
+    return tuple(c)
+
+
+def generated_draw(seed: int, row_id: int, token_number: int) -> np.float32:
+    """The draw in [0,1) for token `token_number` of the row with id `row_id` under the 64-bit `seed`."""
+    x0 = philox4x32_10((token_number, row_id, 0, 0), (seed & _MASK, (seed >> 32) & _MASK))[0]
+    return np.float32((x0 >> 8) * 2.0 ** -24)
+
+
+def generated_draws(seed: int, row_ids, n_tokens: int) -> np.ndarray:
+    """Table float32 [len(row_ids), n_tokens] of generated_draw."""
+    return np.array([[generated_draw(seed, int(q), s) for s in range(n_tokens)] for q in row_ids], np.float32)

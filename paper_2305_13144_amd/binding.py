@@ -63,7 +63,8 @@ class ss_group_stats(C.Structure):
 
 class ss_gen_opts(C.Structure):
     _fields_ = [("eos_id", C.c_int32), ("temperature", C.c_float), ("draws", C.c_void_p),
-                ("draws_stride", C.c_int32), ("target_lens", C.c_void_p), ("sync_every", C.c_int32)]
+                ("draws_stride", C.c_int32), ("seed", C.c_uint64), ("draw_ids", C.c_void_p),
+                ("target_lens", C.c_void_p), ("sync_every", C.c_int32)]
 
 
 def _struct_dict(s: C.Structure) -> dict:
@@ -233,24 +234,27 @@ def ss_run_group(w: Weights, prompt_tokens, prompt_offsets, target_lens, pred_le
     return dict(tokens=toks, lens=lens, stats=_struct_dict(gs))
 
 
-def _gen_opts(eos_id: int, temperature: float, draws, target_lens, sync_every: int):
+def _gen_opts(eos_id: int, temperature: float, draws, target_lens, sync_every: int, seed: int = 0, draw_ids=None):
     """Marshals ss_gen_opts; returns (struct, arrays to keep alive)."""
     d = None if draws is None else np.ascontiguousarray(draws, dtype=np.float32)
     tl = None if target_lens is None else _i32(target_lens)
+    ids = None if draw_ids is None else _i32(draw_ids)
     o = ss_gen_opts()
+    o.seed = int(seed)
+    o.draw_ids = None if ids is None else ids.ctypes.data
     o.eos_id, o.temperature, o.sync_every = int(eos_id), float(temperature), int(sync_every)
     o.draws = None if d is None else d.ctypes.data
     o.draws_stride = 0 if d is None else int(d.shape[1])
     o.target_lens = None if tl is None else tl.ctypes.data
-    return o, (d, tl)
+    return o, (d, tl, ids)
 
 
 def ss_generate_microbatch(w: Weights, prompt_tokens, prompt_offsets, max_new: int, eos_id: int = -1,
                            temperature: float = 0.0, draws=None, target_lens=None, sync_every: int = 8,
-                           flags: int = 0, stream: Optional[int] = None) -> dict:
+                           flags: int = 0, seed: int = 0, draw_ids=None, stream: Optional[int] = None) -> dict:
     pt, po = _i32(prompt_tokens), _i32(prompt_offsets)
     B = len(po) - 1
-    opts, keep = _gen_opts(eos_id, temperature, draws, target_lens, sync_every)
+    opts, keep = _gen_opts(eos_id, temperature, draws, target_lens, sync_every, seed, draw_ids)
     toks = np.empty((B, max_new), np.int32)
     lens = np.empty(B, np.int32)
     failed = np.empty(B, np.uint8)
@@ -263,11 +267,11 @@ def ss_generate_microbatch(w: Weights, prompt_tokens, prompt_offsets, max_new: i
 
 def ss_run_group_generate(w: Weights, prompt_tokens, prompt_offsets, pred_lens, bin: int, policy: ss_policy,
                           eos_id: int = -1, temperature: float = 0.0, draws=None, target_lens=None,
-                          sync_every: int = 8, stream: Optional[int] = None) -> dict:
+                          sync_every: int = 8, seed: int = 0, draw_ids=None, stream: Optional[int] = None) -> dict:
     pt, po = _i32(prompt_tokens), _i32(prompt_offsets)
     pl = None if pred_lens is None else _i32(pred_lens)
     n = len(po) - 1
-    opts, keep = _gen_opts(eos_id, temperature, draws, target_lens, sync_every)
+    opts, keep = _gen_opts(eos_id, temperature, draws, target_lens, sync_every, seed, draw_ids)
     toks = np.empty((n, policy.base_len), np.int32)
     lens = np.zeros(n, np.int32)
     gs = ss_group_stats()

@@ -97,8 +97,11 @@ struct ss_weights {
     int32_t* d_sel = nullptr;  // carved from ws.ints
     MbState st{};
     size_t kv_layer_stride = 0;  // elements between a layer's K and V, and 2x that between layers
-    // token choice of the forward in flight: draws == nullptr selects the argmax
+    // token choice of the forward in flight: cur_inv_temp == 0 selects the argmax; otherwise sampling with the
+    // draws in cur_draws, or (cur_draws == nullptr) generated from (cur_seed, cur_ids[row], token number)
     const float* cur_draws = nullptr;
+    const int32_t* cur_ids = nullptr;
+    uint64_t cur_seed = 0;
     float cur_inv_temp = 0.f;
     int32_t* h_poll = nullptr;   // pinned host copy of the 4-int device header (d_n, d_step, d_nlive, d_active)
 };
@@ -260,7 +263,7 @@ GemmArgs gemm_args(const ss_weights* w, const bf16_t* W, const bf16_t* X, const 
 // Runs the decoder over the token-rows described by the device state (st.d_n of them, at most n of
 // them: n sizes the grids and picks the kernel variants).  Logits are produced for n_sel rows:
 // the rows listed in d_sel, or the first *d_nsel rows when d_sel is null.  Ends with the token choice:
-// the argmax, or a draw from the softmax when the handle carries draws (w->cur_draws).
+// the argmax, or a draw from the softmax when the handle carries a temperature (w->cur_inv_temp).
 void forward(ss_weights* w, int n, int n_sel, const int32_t* d_sel, const int32_t* d_nsel, bool decode, hipStream_t s)
 {
     const ss_model_cfg& c = w->cfg;
@@ -314,8 +317,9 @@ void forward(ss_weights* w, int n, int n_sel, const int32_t* d_sel, const int32_
     ss::launch_rmsnorm(st, x, pd, ks_d, st_d, w->final_norm, c.rms_eps, d_sel, d_nsel, hsel, hsel_lo, d, n_sel, s);
     ss::launch_gemm(mk(w->lm_head.p, hsel, hsel_lo, ws.logits.as<float>(), nullptr, nullptr, V, d, n_sel, 0, p_lm),
                     ss::EPI_PARTIAL, s);
-    if (w->cur_draws)
-        ss::launch_sample(ws.logits.as<float>(), V, d_nsel ? d_nsel : st.d_n, st, w->cur_draws, w->cur_inv_temp, n_sel, s);
+    if (w->cur_inv_temp > 0.f)
+        ss::launch_sample(ws.logits.as<float>(), V, d_nsel ? d_nsel : st.d_n, st, w->cur_draws, w->cur_ids, w->cur_seed,
+                          w->cur_inv_temp, n_sel, s);
     else
         ss::launch_argmax(ws.logits.as<float>(), V, d_nsel ? d_nsel : st.d_n, st.am, n_sel, s);
 }
@@ -390,8 +394,7 @@ int check_gen_opts(const ss_weights* w, const ss_gen_opts* g, int rows, int need
     if (!(g->temperature >= 0.f) || !std::isfinite(g->temperature))
         return ss::fail(SS_EINVAL, "temperature must be finite and >= 0");
     if (g->sync_every < 1) return ss::fail(SS_EINVAL, "sync_every must be >= 1");
-    if (g->temperature > 0.f) {
-        if (!g->draws) return ss::fail(SS_EINVAL, "draws is NULL with temperature > 0");
+    if (g->temperature > 0.f && g->draws) {
         if (g->draws_stride < need_stride)
             return ss::fail(SS_EINVAL, "draws_stride %d < %d", g->draws_stride, need_stride);
         for (int i = 0; i < rows; ++i)
@@ -400,6 +403,9 @@ int check_gen_opts(const ss_weights* w, const ss_gen_opts* g, int rows, int need
                 if (!(u >= 0.f && u < 1.f)) return ss::fail(SS_EINVAL, "draw [%d][%d] outside [0,1)", i, t);
             }
     }
+    if (g->draw_ids)
+        for (int i = 0; i < rows; ++i)
+            if (g->draw_ids[i] < 0) return ss::fail(SS_EINVAL, "draw_ids[%d] < 0", i);
     if (g->target_lens)
         for (int i = 0; i < rows; ++i)
             if (g->target_lens[i] < 1) return ss::fail(SS_EINVAL, "target_lens[%d] < 1", i);
@@ -427,6 +433,8 @@ struct ChoiceGuard {
     ~ChoiceGuard()
     {
         w->cur_draws = nullptr;
+        w->cur_ids = nullptr;
+        w->cur_seed = 0;
         w->cur_inv_temp = 0.f;
     }
 };
@@ -469,11 +477,21 @@ int decode_microbatch_impl(ss_weights* w, const int32_t* prompt_tokens, const in
         return rc;
     ChoiceGuard choice{w};
     if (gen && gen->temperature > 0.f) {
-        if (int rc = w->ws.draws.ensure((size_t)B * max_new * 4, false)) return rc;
-        HIPCHK(hipMemcpy2DAsync(w->ws.draws.p, (size_t)max_new * 4, gen->draws, (size_t)gen->draws_stride * 4,
-                                (size_t)max_new * 4, B, hipMemcpyHostToDevice, s));
-        HIPCHK(hipStreamSynchronize(s));
-        w->cur_draws = w->ws.draws.as<float>();
+        if (gen->draws) {
+            if (int rc = w->ws.draws.ensure((size_t)B * max_new * 4, false)) return rc;
+            HIPCHK(hipMemcpy2DAsync(w->ws.draws.p, (size_t)max_new * 4, gen->draws, (size_t)gen->draws_stride * 4,
+                                    (size_t)max_new * 4, B, hipMemcpyHostToDevice, s));
+            HIPCHK(hipStreamSynchronize(s));
+            w->cur_draws = w->ws.draws.as<float>();
+        } else {   // generated on the device from (seed, row id, token number)
+            std::vector<int32_t> ids(B);
+            for (int i = 0; i < B; ++i) ids[i] = gen->draw_ids ? gen->draw_ids[i] : i;
+            if (int rc = w->ws.draws.ensure((size_t)B * 4, false)) return rc;
+            HIPCHK(hipMemcpyAsync(w->ws.draws.p, ids.data(), (size_t)B * 4, hipMemcpyHostToDevice, s));
+            HIPCHK(hipStreamSynchronize(s));
+            w->cur_ids = w->ws.draws.as<int32_t>();
+            w->cur_seed = gen->seed;
+        }
         w->cur_inv_temp = 1.f / gen->temperature;
     }
     ss::launch_fill_i32(st.out_tok, -1, (size_t)B * max_new, s);
@@ -794,7 +812,7 @@ int run_group_impl(ss_weights* w, const int32_t* prompt_tokens, const int32_t* p
     const int L = policy->base_len;
     const uint32_t eflags = policy->flags & SS_COMPACT;
     std::vector<int32_t> failed;
-    std::vector<int32_t> mb_toks, mb_offs, mb_tl, mb_out, mb_lens;
+    std::vector<int32_t> mb_toks, mb_offs, mb_tl, mb_out, mb_lens, mb_ids;
     std::vector<float> mb_draws;
     std::vector<uint8_t> mb_failed;
     for (size_t i = 0; i < (size_t)n * L; ++i) out_tokens[i] = -1;
@@ -806,15 +824,18 @@ int run_group_impl(ss_weights* w, const int32_t* prompt_tokens, const int32_t* p
             mb_toks.clear();
             mb_offs.assign(1, 0);
             mb_tl.resize(B);
-            if (gen && gen->temperature > 0.f) mb_draws.resize((size_t)B * cap);
+            const bool given_draws = gen && gen->temperature > 0.f && gen->draws;
+            if (given_draws) mb_draws.resize((size_t)B * cap);
+            mb_ids.resize(B);
             for (int r = 0; r < B; ++r) {
                 const int qi = pl->query_idx[b0 + r];
                 mb_toks.insert(mb_toks.end(), prompt_tokens + prompt_offsets[qi], prompt_tokens + prompt_offsets[qi + 1]);
                 mb_offs.push_back((int32_t)mb_toks.size());
                 if (src_tl) mb_tl[r] = src_tl[qi];
-                if (gen && gen->temperature > 0.f)
+                if (given_draws)
                     std::memcpy(mb_draws.data() + (size_t)r * cap, gen->draws + (size_t)qi * gen->draws_stride,
                                 (size_t)cap * 4);
+                mb_ids[r] = gen && gen->draw_ids ? gen->draw_ids[qi] : qi;
             }
             mb_out.resize((size_t)B * cap);
             mb_lens.resize(B);
@@ -823,8 +844,9 @@ int run_group_impl(ss_weights* w, const int32_t* prompt_tokens, const int32_t* p
             ss_gen_opts mbg{};
             if (gen) {
                 mbg = *gen;
-                mbg.draws = mb_draws.data();
+                mbg.draws = given_draws ? mb_draws.data() : nullptr;
                 mbg.draws_stride = cap;
+                mbg.draw_ids = mb_ids.data();
                 mbg.target_lens = src_tl ? mb_tl.data() : nullptr;
             }
             if (int rc = decode_microbatch_impl(w, mb_toks.data(), mb_offs.data(), B, cap, mb_tl.data(),

@@ -85,10 +85,11 @@ void launch_attention_decode(const MbState& st, const float* qkv_part, int kspli
                              bf16_t* kcache, bf16_t* vcache, const float* rope_cos, const float* rope_sin,
                              bf16_t* out_packed, bf16_t* out_packed_lo, int d, int H, int hd, int n_max, hipStream_t s);
 void launch_argmax(const float* logits, int vocab, const int32_t* d_nsel, int32_t* am, int n_max, hipStream_t s);
-// Temperature sampling in place of the argmax: st.am[j] for the first *d_nsel selected rows; the draw of slot j
-// is draws[st.live_row[j] * st.max_new + *st.d_step].
+// Temperature sampling in place of the argmax: st.am[j] for the first *d_nsel selected rows.  The draw of slot j
+// (row r = st.live_row[j], token number t = *st.d_step) is draws[r * st.max_new + t], or with draws == nullptr
+// the counter-based generator's draw for (ids[r], t) under `seed`.
 void launch_sample(const float* logits, int vocab, const int32_t* d_nsel, const MbState& st, const float* draws,
-                   float inv_temp, int n_max, hipStream_t s);
+                   const int32_t* ids, uint64_t seed, float inv_temp, int n_max, hipStream_t s);
 // eos_id: -1 when rows end only at their limit.
 void launch_step_update(const MbState& st, int compact, int eos_id, hipStream_t s);
 void launch_fill_i32(int32_t* p, int32_t v, size_t n, hipStream_t s);

@@ -995,21 +995,42 @@ __global__ __launch_bounds__(1024) void k_argmax(const float* __restrict__ logit
 // ------------------------------------------------------------------------------------------ sampling
 // Temperature sampling per selected row (Sec. 5.1 of the paper samples responses at a temperature):
 // token = smallest v with  sum_{v' <= v} e_v'  >  u * sum_v' e_v',  e_v = exp((logit_v - max) * inv_temp),
-// u being the draw supplied for (row, token number).  The CDF runs in vocabulary order, so thread t owns
+// u being the draw for (row, token number): supplied by the caller, or generated from a counter (below).  The CDF runs in vocabulary order, so thread t owns
 // the contiguous chunk [t*c, (t+1)*c): it sums its chunk in index order, a workgroup scan of the 1024
 // chunk sums finds the first chunk whose running total exceeds the target, and that chunk's owner walks
 // it again in the same order (same additions, same roundings) to the token.  V-1 when rounding leaves no
 // chunk above the target.  1024 threads per row; the row's logits (just written by the LM head) are read
 // three times from L2.
+// Counter-based draw in [0,1): Philox4x32-10 (Salmon, Moraes, Dror, Shaw, SC 2011) on the counter
+// (token number, row id, 0, 0) under the 64-bit key; the top 24 bits of the first output word, scaled by 2^-24.
+__device__ inline float philox_draw(uint32_t k0, uint32_t k1, uint32_t id, uint32_t t)
+{
+    uint32_t c0 = t, c1 = id, c2 = 0u, c3 = 0u;
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        const uint32_t hi0 = __umulhi(0xD2511F53u, c0), lo0 = 0xD2511F53u * c0;
+        const uint32_t hi1 = __umulhi(0xCD9E8D57u, c2), lo1 = 0xCD9E8D57u * c2;
+        c0 = hi1 ^ c1 ^ k0;
+        c1 = lo1;
+        c2 = hi0 ^ c3 ^ k1;
+        c3 = lo0;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    return (float)(c0 >> 8) * (1.0f / 16777216.0f);
+}
+
 __global__ __launch_bounds__(1024) void k_sample(const float* __restrict__ logits, int vocab,
                                                  const int32_t* __restrict__ d_count, MbState st,
-                                                 const float* __restrict__ draws, float inv_temp)
+                                                 const float* __restrict__ draws, const int32_t* __restrict__ ids,
+                                                 uint32_t key0, uint32_t key1, float inv_temp)
 {
     const int j = blockIdx.x;
     if (j >= *d_count) return;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int row = st.live_row[j];
-    const float u = draws[(size_t)row * st.max_new + *st.d_step];
+    const int t = *st.d_step;
+    const float u = draws ? draws[(size_t)row * st.max_new + t] : philox_draw(key0, key1, (uint32_t)ids[row], (uint32_t)t);
     const float* lg = logits + (size_t)j * vocab;
     const int c = (((vocab + 1023) >> 10) + 3) & ~3;   // floats per thread, a multiple of 4 (vocab % 16 == 0)
     const int lo = tid * c;
@@ -1371,9 +1392,10 @@ void launch_argmax(const float* logits, int vocab, const int32_t* d_nsel, int32_
 }
 
 void launch_sample(const float* logits, int vocab, const int32_t* d_nsel, const MbState& st, const float* draws,
-                   float inv_temp, int n_max, hipStream_t s)
+                   const int32_t* ids, uint64_t seed, float inv_temp, int n_max, hipStream_t s)
 {
-    hipLaunchKernelGGL(k_sample, dim3(n_max), dim3(1024), 0, s, logits, vocab, d_nsel, st, draws, inv_temp);
+    hipLaunchKernelGGL(k_sample, dim3(n_max), dim3(1024), 0, s, logits, vocab, d_nsel, st, draws, ids,
+                       (uint32_t)(seed & 0xffffffffu), (uint32_t)(seed >> 32), inv_temp);
 }
 
 void launch_step_update(const MbState& st, int compact, int eos_id, hipStream_t s)

@@ -156,6 +156,38 @@ def test_sampler_distribution_peaked_and_flat_draws(tiny):
     assert (r["tokens"][::2] >= synth.TINY.vocab - 4).all()
 
 
+def test_generated_draws_equal_the_oracles_table(tiny):
+    """Draws generated on the device from (seed, row id, token number) give exactly the tokens that the same call
+    gives when it is handed the oracle's table of those draws: the two generators agree bit for bit."""
+    W, om, gw = tiny
+    w = synth.make_workload(1)
+    cap, seed = 20, (0x1234ABCD << 32) | 0x9E3779B9
+    for ids in (None, np.arange(w.n, dtype=np.int32)[::-1] * 1000 + 7):
+        table = sm.generated_draws(seed, range(w.n) if ids is None else ids, cap)
+        a = ss.ss_generate_microbatch(gw, w.prompt_tokens, w.prompt_offsets, cap, temperature=0.8, seed=seed,
+                                      draw_ids=ids, target_lens=w.target_lens, flags=ss.SS_COMPACT, sync_every=2)
+        b = ss.ss_generate_microbatch(gw, w.prompt_tokens, w.prompt_offsets, cap, temperature=0.8, draws=table,
+                                      target_lens=w.target_lens, flags=ss.SS_COMPACT, sync_every=2)
+        assert np.array_equal(a["tokens"], b["tokens"]) and np.array_equal(a["lens"], b["lens"])
+        g, e, L = check_row_on_own_prefix(om, gw, w.prompt(2), a["tokens"][2, :int(a["lens"][2])], 0.8, table[2],
+                                          "generated draws row 2")
+        _say(f"  generated draws, ids {'default' if ids is None else 'given'}: row 2 decided {g}/{L}")
+    other = ss.ss_generate_microbatch(gw, w.prompt_tokens, w.prompt_offsets, cap, temperature=0.8, seed=seed + 1,
+                                      target_lens=w.target_lens, flags=ss.SS_COMPACT, sync_every=2)
+    assert not np.array_equal(other["tokens"], a["tokens"])
+    # in a scheduled group the id of a row is its query index, wherever the plan puts it, also when it is recomputed
+    wg = synth.make_group(synth.TINY, 40, 555, ("uniform", 4, 20), ("lognormal", 10.0, 0.7, 1, 32), 0.3, 32, 8,
+                          ("SORT", "BIN", "FCR", "VBS", "COMPACT"), base_batch=4, max_batch=16)
+    pol = ss.make_policy(wg.flags, wg.base_batch, wg.l_max, wg.max_batch)
+    table = sm.generated_draws(seed, range(wg.n), wg.l_max)
+    a = ss.ss_run_group_generate(gw, wg.prompt_tokens, wg.prompt_offsets, wg.pred_lens, wg.bin_width, pol,
+                                 temperature=0.8, seed=seed, target_lens=wg.target_lens, sync_every=1)
+    b = ss.ss_run_group_generate(gw, wg.prompt_tokens, wg.prompt_offsets, wg.pred_lens, wg.bin_width, pol,
+                                 temperature=0.8, draws=table, target_lens=wg.target_lens, sync_every=1)
+    assert a["stats"]["n_failed"] >= 1 and np.array_equal(a["lens"], wg.target_lens)
+    assert np.array_equal(a["tokens"], b["tokens"])
+
+
 # ------------------------------------------------------------------ end-of-sequence id
 @pytest.mark.parametrize("T,flags,sync", [(0.0, 0, 4), (0.0, ss.SS_COMPACT, 1), (0.1, ss.SS_COMPACT, 3), (0.1, 0, 8)])
 def test_tiny_eos_ends_rows_at_different_steps(tiny, T, flags, sync):
@@ -336,8 +368,8 @@ def test_generate_rejects_bad_options(tiny):
 
     call()
     for bad in (dict(eos_id=-2), dict(eos_id=synth.TINY.vocab), dict(temperature=-0.1), dict(temperature=float("nan")),
-                dict(sync_every=0), dict(draws=None), dict(draws=synth.make_draws(w.n, 7, seed=1)),
-                dict(target_lens=np.zeros(w.n, np.int32))):
+                dict(sync_every=0), dict(draws=synth.make_draws(w.n, 7, seed=1)),
+                dict(target_lens=np.zeros(w.n, np.int32)), dict(draws=None, draw_ids=np.full(w.n, -1, np.int32))):
         with pytest.raises(ss.SsError) as e:
             call(**bad)
         assert e.value.code == ss.SS_EINVAL, bad

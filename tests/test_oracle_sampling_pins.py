@@ -210,3 +210,39 @@ def test_draws_are_seeded_and_in_range():
     b = synth.make_draws(5, 9, seed=3)
     assert a.dtype == np.float32 and a.shape == (5, 9) and np.array_equal(a, b)
     assert (a >= 0).all() and (a < 1).all() and not np.array_equal(a, synth.make_draws(5, 9, seed=4))
+
+
+# ------------------------------------------------------------------ counter-based draws
+def test_philox_known_answer_vectors():
+    import os
+    path = os.path.join(os.path.dirname(__file__), "golden", "philox4x32_10_kat.txt")
+    n = 0
+    for line in open(path):
+        if line.startswith("#") or not line.strip():
+            continue
+        ctr, key, out = [[int(x, 16) for x in part.split()] for part in line.split("|")]
+        assert sm.philox4x32_10(ctr, key) == tuple(out)
+        n += 1
+    assert n == 3
+
+
+def test_generated_draw_is_top_24_bits_of_the_first_word():
+    # counter (0,0,0,0), key 0: first word 0x6627e8d5 -> 0x6627e8 * 2^-24
+    assert sm.generated_draw(0, 0, 0) == np.float32(0x6627E8 / 2.0 ** 24)
+    # the 64-bit seed supplies the key words: low half first
+    x0 = sm.philox4x32_10((5, 9, 0, 0), (0xA4093822, 0x299F31D0))[0]
+    assert sm.generated_draw((0x299F31D0 << 32) | 0xA4093822, 9, 5) == np.float32((x0 >> 8) / 2.0 ** 24)
+    t = sm.generated_draws(12345, [0, 1, 7], 50)
+    assert t.dtype == np.float32 and t.shape == (3, 50) and (t >= 0).all() and (t < 1).all()
+    assert len(np.unique(t)) == 150                                   # a bijection on distinct counters: no repeats here
+    assert np.array_equal(t[2], sm.generated_draws(12345, [7], 50)[0])  # a row's draws depend on its id only
+    assert not np.array_equal(t, sm.generated_draws(12346, [0, 1, 7], 50))
+
+
+def test_generated_draws_are_uniform():
+    """Kolmogorov-Smirnov distance of 20000 draws to U[0,1) (scipy), and the lag-1 correlation along a row."""
+    import scipy.stats
+    t = sm.generated_draws(2023, range(40), 500).astype(np.float64)
+    assert scipy.stats.kstest(t.ravel(), "uniform").statistic < 0.012
+    x = t - 0.5
+    assert abs((x[:, 1:] * x[:, :-1]).mean() / x.var()) < 0.03
