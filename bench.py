@@ -308,6 +308,14 @@ def main() -> int:
                     achieved=ach, peak=HBM_PEAK_GBS, unit="GB/s", frac=ach / HBM_PEAK_GBS, traffic=traffic,
                     launches_per_step=launches, avg_launch_us=ms_w.mean() * 1e3 / launches,
                     bytes_per_launch=wbytes / launches)
+    # the ceiling for those launches: the same matrices read by a plain stream kernel, launch by launch
+    ms_r, rbytes = ss.ss_bench_read_stream(gw, a.step_iters + 3)
+    ms_r = ms_r[3:]
+    roofline["plain_read_stream"] = dict(
+        what="one plain non-temporal read kernel per weight matrix, same bytes and launch sizes, nothing computed",
+        ms=float(ms_r.mean()), achieved=rbytes / (ms_r.mean() * 1e-3) / 1e9, unit="GB/s",
+        projections_over_stream=float(ms_r.mean() / ms_w.mean()) * wbytes / rbytes)
+    log(f"plain read stream over the same matrices: {ms_r.mean():.3f} ms/iter -> {roofline['plain_read_stream']['achieved']:.0f} GB/s")
     rng = np.random.default_rng(7)
     ptoks = rng.integers(0, shape.vocab, size=B0 * ctx).astype(np.int32)
     ms_s = ss.ss_bench_decode_step(gw, ptoks, B0, ctx, a.step_iters + 3)[3:]

@@ -283,6 +283,15 @@ int ss_bench_decode_step(ss_weights* w, const int32_t* prompt_tokens, int32_t B,
 int ss_bench_weight_stream(ss_weights* w, int32_t B, int32_t iters, double* ms_out, int32_t* launches_out,
                            void* hip_stream);
 
+/*
+ * Measurement entry point: the ceiling ss_bench_weight_stream is compared with.  Launches, back to back on one
+ * stream, one plain read kernel per weight matrix in the order a decode forward uses them (per layer q|k|v, o,
+ * gate|up, down; then the LM head): the same bytes in the same launch sizes, nothing computed, `iters` times.
+ *   ms_out     host, double[iters], device time of each iteration (HIP events)
+ *   bytes_out  host, nullable: bytes read per iteration (each matrix rounded down to whole 64 KiB chunks)
+ */
+int ss_bench_read_stream(ss_weights* w, int32_t iters, double* ms_out, int64_t* bytes_out, void* hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -23,7 +23,7 @@ FLAG_BITS = dict(SORT=SS_SORT, BIN=SS_BIN, FCR=SS_FCR, VBS=SS_VBS, COMPACT=SS_CO
 
 EXPORTS = ["ss_last_error", "ss_set_verbose", "ss_set_gemm_mode", "ss_schedule", "ss_schedule_failures", "ss_plan_free", "ss_weights_create",
            "ss_weights_destroy", "ss_decode_microbatch", "ss_forward_logits", "ss_run_group", "ss_generate_microbatch",
-           "ss_run_group_generate", "ss_bench_decode_step", "ss_bench_weight_stream"]
+           "ss_run_group_generate", "ss_bench_decode_step", "ss_bench_weight_stream", "ss_bench_read_stream"]
 
 
 class SsError(RuntimeError):
@@ -106,6 +106,7 @@ def lib():
                                             C.POINTER(ss_gen_opts), i32p, i32p, C.POINTER(ss_group_stats), vp]
         L.ss_bench_decode_step.argtypes = [vp, i32p, C.c_int32, C.c_int32, C.c_int32, vp, vp]
         L.ss_bench_weight_stream.argtypes = [vp, C.c_int32, C.c_int32, vp, vp, vp]
+        L.ss_bench_read_stream.argtypes = [vp, C.c_int32, vp, vp, vp]
         for name in EXPORTS:
             if name not in ("ss_last_error", "ss_set_verbose", "ss_set_gemm_mode", "ss_plan_free", "ss_weights_destroy"):
                 getattr(L, name).restype = C.c_int
@@ -295,3 +296,10 @@ def ss_bench_weight_stream(w: Weights, B: int, iters: int, stream: Optional[int]
     launches = C.c_int32(0)
     _check(lib().ss_bench_weight_stream(w.h, B, iters, _ptr(ms), C.byref(launches), stream))
     return ms, int(launches.value)
+
+
+def ss_bench_read_stream(w: Weights, iters: int, stream: Optional[int] = None):
+    ms = np.empty(iters, np.float64)
+    nbytes = C.c_int64(0)
+    _check(lib().ss_bench_read_stream(w.h, iters, _ptr(ms), C.byref(nbytes), stream))
+    return ms, int(nbytes.value)

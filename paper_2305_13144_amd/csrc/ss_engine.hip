@@ -1044,3 +1044,42 @@ extern "C" int ss_bench_weight_stream(ss_weights* w, int32_t B, int32_t iters, d
     if (launches_out) *launches_out = launches;
     return SS_OK;
 }
+
+extern "C" int ss_bench_read_stream(ss_weights* w, int32_t iters, double* ms_out, int64_t* bytes_out, void* hip_stream)
+{
+    ss::clear_error();
+    if (!w || !ms_out) return ss::fail(SS_EINVAL, "NULL argument");
+    if (iters < 1) return ss::fail(SS_EINVAL, "bad iters");
+    BusyGuard guard(w);
+    if (!guard.ok) return ss::fail(SS_ESTATE, "another call is in flight on this handle");
+    hipStream_t s = hip_stream ? (hipStream_t)hip_stream : w->stream;
+    HIPCHK(hipSetDevice(w->device));
+    if (int rc = w->ws.ints.ensure(64, false)) return rc;
+    uint32_t* sink = w->ws.ints.as<uint32_t>();
+    auto mat_bytes = [](const PackedMat& m) { return ((size_t)m.N * m.Kp * 2) & ~(size_t)0xffff; };
+    std::vector<hipEvent_t> ev(iters + 1);
+    for (auto& e : ev) HIPCHK(hipEventCreate(&e));
+    HIPCHK(hipEventRecord(ev[0], s));
+    size_t bytes = 0;
+    for (int it = 0; it < iters; ++it) {
+        bytes = 0;
+        for (const Layer& L : w->layers)
+            for (const PackedMat* m : {&L.wqkv, &L.wo, &L.wgu, &L.wd}) {
+                ss::launch_read_stream(m->p, mat_bytes(*m), sink, s);
+                bytes += mat_bytes(*m);
+            }
+        ss::launch_read_stream(w->lm_head.p, mat_bytes(w->lm_head), sink, s);
+        bytes += mat_bytes(w->lm_head);
+        HIPCHK(hipEventRecord(ev[it + 1], s));
+    }
+    HIPCHK(hipStreamSynchronize(s));
+    HIPCHK(hipGetLastError());
+    for (int it = 0; it < iters; ++it) {
+        float ms = 0.f;
+        HIPCHK(hipEventElapsedTime(&ms, ev[it], ev[it + 1]));
+        ms_out[it] = ms;
+    }
+    for (auto& e : ev) (void)hipEventDestroy(e);
+    if (bytes_out) *bytes_out = (int64_t)bytes;
+    return SS_OK;
+}

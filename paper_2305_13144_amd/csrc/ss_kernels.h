@@ -92,6 +92,8 @@ void launch_sample(const float* logits, int vocab, const int32_t* d_nsel, const 
                    const int32_t* ids, uint64_t seed, float inv_temp, int n_max, hipStream_t s);
 // eos_id: -1 when rows end only at their limit.
 void launch_step_update(const MbState& st, int compact, int eos_id, hipStream_t s);
+// Reads the first bytes/65536 chunks of 64 KiB at p and discards them (bandwidth probe).
+void launch_read_stream(const bf16_t* p, size_t bytes, uint32_t* sink, hipStream_t s);
 void launch_fill_i32(int32_t* p, int32_t v, size_t n, hipStream_t s);
 
 }  // namespace ss

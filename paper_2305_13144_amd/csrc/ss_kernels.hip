@@ -1158,6 +1158,27 @@ __global__ __launch_bounds__(1024) void k_step_update(MbState st, int compact, i
     }
 }
 
+// ------------------------------------------------------------------------------------------ read probe
+// Measurement aid: a plain read stream over a packed weight matrix, one wave per 64 KiB chunk, 8 non-temporal
+// 16-byte loads per lane in flight, nothing computed.  The rate it reaches at a projection's size is the
+// ceiling that the projection kernels are compared with.
+__global__ __launch_bounds__(256) void k_read_stream(const u32x4* __restrict__ p, int n_chunks, uint32_t* __restrict__ sink)
+{
+    const int lane = threadIdx.x & 63;
+    const int w = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (w >= n_chunks) return;
+    const u32x4* q = p + (size_t)w * 4096 + lane;   // 64 KiB = 4096 vectors of 16 bytes
+    u32x4 acc = {0u, 0u, 0u, 0u};
+    for (int i = 0; i < 4096; i += 512) {
+        u32x4 v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = __builtin_nontemporal_load(q + i + u * 64);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) acc ^= v[u];
+    }
+    if ((acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x9E3779B9u) sink[0] = 1u;   // keeps the loads alive; bf16 weights never hit it in practice
+}
+
 // ------------------------------------------------------------------------------------------ launchers
 static inline int grid_for(size_t n, int block)
 {
@@ -1389,6 +1410,13 @@ void launch_attention(const MbState& st, const float* qrot, const bf16_t* kcache
 void launch_argmax(const float* logits, int vocab, const int32_t* d_nsel, int32_t* am, int n_max, hipStream_t s)
 {
     hipLaunchKernelGGL(k_argmax, dim3(n_max), dim3(1024), 0, s, logits, vocab, d_nsel, am);
+}
+
+void launch_read_stream(const bf16_t* p, size_t bytes, uint32_t* sink, hipStream_t s)
+{
+    const int n_chunks = (int)(bytes >> 16);
+    if (n_chunks < 1) return;
+    hipLaunchKernelGGL(k_read_stream, dim3((n_chunks + 3) / 4), dim3(256), 0, s, (const u32x4*)p, n_chunks, sink);
 }
 
 void launch_sample(const float* logits, int vocab, const int32_t* d_nsel, const MbState& st, const float* draws,
