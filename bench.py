@@ -94,6 +94,25 @@ def sweeps(a, ss, gw, wl, shape) -> int:
            run until their longest row finishes (a 64-query subset of the group keeps batch 1 affordable).
     group: throughput against group size for the full policy and for vanilla batching on the same queries."""
     from paper_2305_13144_amd import synth
+    if a.sweep == "step":
+        # One decode forward (ss_bench_decode_step: the kernels and launch shapes of a real step) against the number
+        # of live rows at a fixed context, and against the context at 16 rows (the paper's App. D: time per token
+        # grows linearly with the position).
+        rng = np.random.default_rng(7)
+        points = [("rows", B, 100) for B in (1, 2, 4, 8, 16, 24, 32, 48, 64, 65, 81, 96, 128, 129, 163, 200, 256)]
+        points += [("context", 16, c) for c in (25, 50, 100, 200, 400, 800, 1600, 3200, 4000)]
+        for what, B, ctx in points:
+            ptoks = rng.integers(0, shape.vocab, size=B * ctx).astype(np.int32)
+            ms = ss.ss_bench_decode_step(gw, ptoks, B, ctx, 11)[3:]
+            nbytes = decode_step_bytes(shape, B, ctx)
+            row = dict(sweep="step", vary=what, rows=B, ctx=ctx, ms=float(ms.mean()), ms_min=float(ms.min()),
+                       algorithmic_bytes=nbytes, achieved_GBs=nbytes / (ms.mean() * 1e-3) / 1e9,
+                       frac_of_hbm_peak=nbytes / (ms.mean() * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                       mfma_TFLOPs=2.0 * B * (shape.weight_bytes_per_step() / 2) / (ms.mean() * 1e-3) / 1e12)
+            log(f"sweep step {row}")
+            print(json.dumps(row), flush=True)
+        gw.close()
+        return 0
     if a.sweep == "sync":
         # The configured group with ends the host does not know: the device applies the same lengths and the host
         # polls every `sync` decode forwards.  T = 0 emits the tokens of the known-length run, so the difference to
@@ -179,10 +198,11 @@ def main() -> int:
                          "predictor and compaction on the same group, one pass each; prints one JSON line per row")
     ap.add_argument("--ablation-only", default=None,
                     help="with --ablation: run vanilla plus the rows whose name contains this text")
-    ap.add_argument("--sweep", choices=["batch", "group", "sync"], default=None,
+    ap.add_argument("--sweep", choices=["batch", "group", "sync", "step"], default=None,
                     help="instead of the headline run: throughput against micro-batch size or against group size "
-                         "(the paper's Fig. 3a / 3b on the synthetic workload), or ('sync') the group run with ends "
-                         "that the host must poll for, against the poll period, greedy and sampled at T=0.5")
+                         "(the paper's Fig. 3a / 3b on the synthetic workload), ('sync') the group run with ends "
+                         "that the host must poll for, against the poll period, greedy and sampled at T=0.5, or ('step') "
+                         "the time of one decode forward against live rows and against context length (App. D)")
     ap.add_argument("--no-generate", action="store_true",
                     help="skip the leg that reruns the group with sampled tokens and ends discovered by polling")
     ap.add_argument("--roofline-only", action="store_true",

@@ -760,7 +760,7 @@ __global__ __launch_bounds__(256) void k_rope_append(MbState st, const float* __
 // and V are each streamed once, fully coalesced; a wave issues AU such loads before it consumes them, so
 // a context of a few hundred slots costs two or three memory round trips, not one per load.
 constexpr int kAttnUnroll = 8;
-constexpr int kAttnDecodeWaves = 8;   // waves per (row, head) workgroup of the decode kernel: 256 slots per round trip
+constexpr int kAttnWideMaxGroups = 512;   // decode attention: (row, head) workgroups up to which 8 waves each are used
 
 template <int HD, int NW>
 __device__ __forceinline__ void attend(const float* __restrict__ qs, float* __restrict__ sc, float* __restrict__ red,
@@ -895,16 +895,18 @@ __global__ __launch_bounds__(256) void k_attention(MbState st, const float* __re
 // Decode forwards: the (token-row, head) workgroup first finishes its own slice of the q|k|v projection
 // (sums the k-slices, rotates q and k at the row's position, appends k and v to the row's slab), then
 // attends.  Saves a launch and the round trip of q through HBM for every layer of every step.
-template <int HD>
-__global__ __launch_bounds__(64 * kAttnDecodeWaves) void k_attention_decode(MbState st, const float* __restrict__ part, int ksplit,
+// NW waves per workgroup: 8 (256 cache slots per round trip) when the grid is small enough for every workgroup to
+// be resident with room to spare, 4 (128 slots) for larger batches, whose many workgroups already fill the chip.
+template <int HD, int NW>
+__global__ __launch_bounds__(64 * NW) void k_attention_decode(MbState st, const float* __restrict__ part, int ksplit,
                                                           size_t part_stride, bf16_t* __restrict__ kc,
                                                           bf16_t* __restrict__ vc, const float* __restrict__ rcos,
                                                           const float* __restrict__ rsin, bf16_t* __restrict__ out,
                                                           bf16_t* __restrict__ out_lo, int d)
 {
     __shared__ float sc[kMaxPos];
-    __shared__ float red[2 * kAttnDecodeWaves];
-    __shared__ float oacc[kAttnDecodeWaves][HD];
+    __shared__ float red[2 * NW];
+    __shared__ float oacc[NW][HD];
     __shared__ float qs[HD];
     constexpr int HALF = HD / 2;
     const int j = blockIdx.x, h = blockIdx.y;
@@ -945,7 +947,7 @@ __global__ __launch_bounds__(64 * kAttnDecodeWaves) void k_attention_decode(MbSt
         }
     }
     __syncthreads();   // the new key/value slot and q are visible to the whole workgroup
-    attend<HD, kAttnDecodeWaves>(qs, sc, red, oacc, kc + base, vc + base, pos + 1, out, out_lo, j, h * HD, d);
+    attend<HD, NW>(qs, sc, red, oacc, kc + base, vc + base, pos + 1, out, out_lo, j, h * HD, d);
 }
 
 // ------------------------------------------------------------------------------------------ argmax
@@ -1384,16 +1386,31 @@ void launch_rope_append(const MbState& st, const float* qkv_part, int ksplit, si
                        vcache, rope_cos, rope_sin, d, H, hd);
 }
 
+template <int HD, int NW>
+static void launch_attention_decode_inst(const MbState& st, const float* qkv_part, int ksplit, size_t part_stride,
+                                         bf16_t* kcache, bf16_t* vcache, const float* rope_cos, const float* rope_sin,
+                                         bf16_t* out_packed, bf16_t* out_packed_lo, int d, int H, int n_max, hipStream_t s)
+{
+    hipLaunchKernelGGL((k_attention_decode<HD, NW>), dim3(n_max, H), dim3(64 * NW), 0, s, st, qkv_part, ksplit, part_stride,
+                       kcache, vcache, rope_cos, rope_sin, out_packed, out_packed_lo, d);
+}
+
 void launch_attention_decode(const MbState& st, const float* qkv_part, int ksplit, size_t part_stride,
                              bf16_t* kcache, bf16_t* vcache, const float* rope_cos, const float* rope_sin,
                              bf16_t* out_packed, bf16_t* out_packed_lo, int d, int H, int hd, int n_max, hipStream_t s)
 {
-    if (hd == 128)
-        hipLaunchKernelGGL((k_attention_decode<128>), dim3(n_max, H), dim3(64 * kAttnDecodeWaves), 0, s, st, qkv_part, ksplit,
-                           part_stride, kcache, vcache, rope_cos, rope_sin, out_packed, out_packed_lo, d);
-    else
-        hipLaunchKernelGGL((k_attention_decode<64>), dim3(n_max, H), dim3(64 * kAttnDecodeWaves), 0, s, st, qkv_part, ksplit,
-                           part_stride, kcache, vcache, rope_cos, rope_sin, out_packed, out_packed_lo, d);
+    // measured at the 7B shape: 8 waves win at 16 rows (512 workgroups: 14.1 against 14.9 us per layer at context
+    // 200), 4 waves win at 64 rows (2048 workgroups: 25.7 against 36.1 us at context 100)
+    const bool wide = n_max * H <= kAttnWideMaxGroups;
+#define SS_ATTN_ARGS st, qkv_part, ksplit, part_stride, kcache, vcache, rope_cos, rope_sin, out_packed, out_packed_lo, d, H, n_max, s
+    if (hd == 128) {
+        if (wide) launch_attention_decode_inst<128, 8>(SS_ATTN_ARGS);
+        else launch_attention_decode_inst<128, 4>(SS_ATTN_ARGS);
+    } else {
+        if (wide) launch_attention_decode_inst<64, 8>(SS_ATTN_ARGS);
+        else launch_attention_decode_inst<64, 4>(SS_ATTN_ARGS);
+    }
+#undef SS_ATTN_ARGS
 }
 
 void launch_attention(const MbState& st, const float* qrot, const bf16_t* kcache, const bf16_t* vcache,
