@@ -367,7 +367,7 @@ def main() -> int:
     if not a.no_cpu:
         from oracle.model_oracle import OracleModel
         om = OracleModel(shape, W, "f32")
-        rows, cap = [0, 1, 2, 3], 32
+        rows, cap = [0, 1, 2, 3, 4, 5], 48
         toks, offs = synth.gather_prompts(wl, rows)
         tl = np.minimum(wl.target_lens[rows], cap)
         t0 = time.perf_counter()
