@@ -331,6 +331,66 @@ def test_tiny_group_generate_with_failures_and_recomputation(tiny):
     assert g1["n_mb_first"] == ref["first"].n_mb and g1["n_mb_failure"] == ref["second"].n_mb
 
 
+def test_tiny_group_rows_without_any_end_are_truncated_at_the_global_limit(tiny):
+    """No simulated lengths and an end id that almost never comes up (T = 1 over 1024 near-equal logits): a row
+    that is unfinished at a cap below the global limit fails and is recomputed; unfinished at the global limit it
+    is complete.  Every count equals the scheduler oracle's for the lengths the rows turned out to have."""
+    W, om, gw = tiny
+    w = synth.make_group(synth.TINY, 48, 909, ("uniform", 4, 16), ("uniform", 1, 24), 0.3, 24, 8,
+                         ("SORT", "BIN", "FCR", "VBS", "COMPACT"), base_batch=4, max_batch=16)
+    pol = ss.make_policy(w.flags, w.base_batch, w.l_max, w.max_batch)
+    eos, seed = 77, 4242
+    ids = np.arange(w.n, dtype=np.int32) * 3 + 11            # explicit draw ids, indexed by query
+    r = ss.ss_run_group_generate(gw, w.prompt_tokens, w.prompt_offsets, w.pred_lens, w.bin_width, pol, eos_id=eos,
+                                 temperature=1.0, seed=seed, draw_ids=ids, sync_every=1)
+    table = sm.generated_draws(seed, ids, w.l_max)
+    ended = 0
+    for i in range(w.n):
+        L = int(r["lens"][i])
+        row = r["tokens"][i]
+        assert (row[:L] >= 0).all() and (row[L:] == -1).all()
+        length, unfinished = implied_end(row[:L], eos, w.l_max)
+        assert L == length
+        ended += not unfinished
+    _say(f"  {ended}/{w.n} rows met the end id; the others ran to the global limit of {w.l_max}")
+    assert (r["lens"] == w.l_max).sum() >= w.n // 2
+    d, _, t = check_row_on_own_prefix(om, gw, w.prompt(5), r["tokens"][5, :int(r["lens"][5])], 1.0, table[5], "query 5")
+    assert d >= 0.7 * t
+    ref = so.run_group(w.pred_lens, r["lens"], w.bin_width,
+                       so.Policy(flags=tuple(w.flags), base_batch=w.base_batch, l_max=w.l_max, max_batch=w.max_batch))
+    g = r["stats"]
+    assert g["n_failed"] == ref["n_failed"] >= 1 and g["steps"] == ref["steps"]
+    assert g["padded_row_steps"] == ref["padded_row_steps"] and g["computed_row_steps"] == ref["live_row_steps"]
+    assert g["useful_tokens"] == int(r["lens"].sum()) == ref["useful_tokens"]
+
+
+def test_caller_supplied_stream(tiny):
+    """The entry points run on a stream the caller created (here through the HIP runtime the library links
+    against) and return the same results as on the library's own stream."""
+    import ctypes
+    W, om, gw = tiny
+    w = synth.make_workload(1)
+    hip = ctypes.CDLL("libamdhip64.so")
+    stream = ctypes.c_void_p()
+    assert hip.hipStreamCreate(ctypes.byref(stream)) == 0
+    try:
+        a = ss.ss_decode_microbatch(gw, w.prompt_tokens, w.prompt_offsets, 12, w.target_lens, ss.SS_COMPACT)
+        b = ss.ss_decode_microbatch(gw, w.prompt_tokens, w.prompt_offsets, 12, w.target_lens, ss.SS_COMPACT,
+                                    stream=stream.value)
+        assert np.array_equal(a["tokens"], b["tokens"]) and np.array_equal(a["lens"], b["lens"])
+        c = ss.ss_generate_microbatch(gw, w.prompt_tokens, w.prompt_offsets, 12, temperature=0.6, seed=5,
+                                      target_lens=w.target_lens, sync_every=2)
+        d = ss.ss_generate_microbatch(gw, w.prompt_tokens, w.prompt_offsets, 12, temperature=0.6, seed=5,
+                                      target_lens=w.target_lens, sync_every=2, stream=stream.value)
+        assert np.array_equal(c["tokens"], d["tokens"])
+        la = ss.ss_forward_logits(gw, w.prompt(0), [0, len(w.prompt(0))], [len(w.prompt(0))])
+        lb = ss.ss_forward_logits(gw, w.prompt(0), [0, len(w.prompt(0))], [len(w.prompt(0))], stream=stream.value)
+        assert np.array_equal(la, lb)
+    finally:
+        assert hip.hipStreamSynchronize(stream) == 0
+        assert hip.hipStreamDestroy(stream) == 0
+
+
 # ------------------------------------------------------------------ full-width vocabulary
 def test_wide_sampled_tokens_vocab_32000(oracle_built):
     """7B widths at 2 layers: the sampler's chunking at vocab 32000 (1000 busy threads, 24 idle)."""
