@@ -601,14 +601,22 @@ __global__ __launch_bounds__(256 * KP, 2) void k_gemm_tiled(GemmArgs a, int kb_p
 #define SS_XSTORE(STAGE_, X_, LIVE_)                                                            \
     _Pragma("unroll") for (int i_ = 0; i_ < XV; ++i_) lds[STAGE_][tid + i_ * 256] = (LIVE_) ? X_[i_] : zero4;
 #define SS_COMPUTE(W_, STAGE_)                                                                  \
-    _Pragma("unroll") for (int m_ = 0; m_ < TMS; ++m_) {                                        \
-        const u32x4 xh_ = lds[STAGE_][(m_ * 2 + 0) * 64 + lane];                                \
-        const u32x4 xl_ = lds[STAGE_][(m_ * 2 + 1) * 64 + lane];                                \
-        _Pragma("unroll") for (int i_ = 0; i_ < 4; ++i_) {                                      \
-            acc[i_][m_] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(                              \
-                __builtin_bit_cast(bf16x8, W_[i_]), __builtin_bit_cast(bf16x8, xl_), acc[i_][m_], 0, 0, 0); \
-            acc[i_][m_] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(                              \
-                __builtin_bit_cast(bf16x8, W_[i_]), __builtin_bit_cast(bf16x8, xh_), acc[i_][m_], 0, 0, 0); \
+    {                                                                                           \
+        /* every operand read of the trip is issued before the first MFMA (the reads return in  \
+           order, so each MFMA group waits only for its own pair): LDS latency overlaps MFMAs */ \
+        u32x4 xh_[TMS], xl_[TMS];                                                               \
+        _Pragma("unroll") for (int m_ = 0; m_ < TMS; ++m_) {                                    \
+            xl_[m_] = lds[STAGE_][(m_ * 2 + 1) * 64 + lane];                                    \
+            xh_[m_] = lds[STAGE_][(m_ * 2 + 0) * 64 + lane];                                    \
+        }                                                                                       \
+        __builtin_amdgcn_sched_barrier(0x16);   /* only VALU, SALU and global loads may cross */ \
+        _Pragma("unroll") for (int m_ = 0; m_ < TMS; ++m_) {                                    \
+            _Pragma("unroll") for (int i_ = 0; i_ < 4; ++i_) {                                  \
+                acc[i_][m_] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(                          \
+                    __builtin_bit_cast(bf16x8, W_[i_]), __builtin_bit_cast(bf16x8, xl_[m_]), acc[i_][m_], 0, 0, 0); \
+                acc[i_][m_] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(                          \
+                    __builtin_bit_cast(bf16x8, W_[i_]), __builtin_bit_cast(bf16x8, xh_[m_]), acc[i_][m_], 0, 0, 0); \
+            }                                                                                   \
         }                                                                                       \
     }
     // One trip: k-block t from ring slot (WC_, XC_); the next k-block's tile (XN_) goes into the other LDS
