@@ -117,6 +117,10 @@ def test_generation_entry_points_reject_null_without_touching_a_gpu(lib):
     assert lib.ss_run_group(None, None, None, 1, None, None, 0, None, None, None, None, None) == ss.SS_EINVAL
     assert lib.ss_bench_decode_step(None, None, 1, 1, 1, None, None) == ss.SS_EINVAL
     assert lib.ss_bench_weight_stream(None, 1, 1, None, None, None) == ss.SS_EINVAL
+    assert lib.ss_bench_read_stream(None, 1, None, None, None) == ss.SS_EINVAL
+    assert lib.ss_generate_microbatch(None, None, None, 1, 1, None, 0, None, None, None, None, None) == ss.SS_EINVAL
+    assert b"NULL" in lib.ss_last_error()
+    assert lib.ss_run_group_generate(None, None, None, 1, None, 0, None, None, None, None, None, None) == ss.SS_EINVAL
     cfg = ss.ss_model_cfg(2, 250, 4, 64, 688, 1024, 1e4, 1e-6)       # n_heads*head_dim != d_model
     h = C.c_void_p()
     arr = (C.c_void_p * 21)()
