@@ -98,6 +98,40 @@ def test_7b_whole_group_config3_as_benchmarked(full7b):
         _say(f"  query {i}: {dcd}/{tot} decided positions match")
 
 
+def test_7b_whole_group_config4_as_benchmarked(full7b):
+    """ss_run_group on the full config-4 group (1024 queries, variable batch size up to 128 rows, compaction, prompt
+    forwards of several thousand token-rows), exactly what `bench.py --cfg 4` times: every count against the
+    scheduler oracle, every query emitted once and in full, sampled queries re-derived by the oracle."""
+    shape, W, om, gw = full7b
+    w = synth.make_workload(4)
+    pol = ss.make_policy(w.flags, w.base_batch, w.l_max, w.max_batch)
+    _say("7B whole group, config 4 (about 40 s on the GPU)")
+    r = ss.ss_run_group(gw, w.prompt_tokens, w.prompt_offsets, w.target_lens, w.pred_lens, w.bin_width, pol)
+    ref = so.run_group(w.pred_lens, w.target_lens, w.bin_width,
+                       so.Policy(flags=w.flags, base_batch=w.base_batch, l_max=w.l_max, max_batch=w.max_batch))
+    s = r["stats"]
+    assert np.array_equal(r["lens"], w.target_lens)
+    assert s["steps"] == ref["steps"] and s["padded_row_steps"] == ref["padded_row_steps"]
+    assert s["computed_row_steps"] == ref["live_row_steps"]                # compaction: only rows that still owe tokens
+    assert s["n_failed"] == ref["n_failed"] and s["useful_tokens"] == ref["useful_tokens"] == int(w.target_lens.sum())
+    assert (s["n_mb_first"], s["n_mb_failure"]) == (ref["first"].n_mb, ref["second"].n_mb)
+    for i in range(w.n):
+        t = int(w.target_lens[i])
+        assert (r["tokens"][i, :t] >= 0).all() and (r["tokens"][i, :t] < shape.vocab).all()
+        assert (r["tokens"][i, t:] == -1).all()
+    failed = set(ref["first"].failed)
+    plan = so.schedule(w.pred_lens, w.n, w.bin_width,
+                       so.Policy(flags=w.flags, base_batch=w.base_batch, l_max=w.l_max, max_batch=w.max_batch))
+    big = max(plan, key=lambda mb: len(mb.idx))
+    _say(f"  largest micro-batch: {len(big.idx)} rows, cap {big.cap}")
+    in_big = next(i for i in big.idx if i not in failed and w.target_lens[i] >= 3)   # ran in the widest micro-batch
+    redo = sorted(failed)[0]
+    for i in (in_big, redo):
+        dcd, tot = check_tokens_teacher_forced(om, w.prompt(i), r["tokens"][i, :int(w.target_lens[i])], upto=4,
+                                               what=f"query {i}")
+        _say(f"  query {i}: {dcd}/{tot} decided positions match")
+
+
 def test_13b_widths_logits_and_vbs_batch(wide13):
     """Config 5's widths (d 5120, 40 heads, ffn 13824) at 2 layers: logits, then a 256-row micro-batch
     (its largest variable batch size) with compaction, sampled rows against the oracle."""
