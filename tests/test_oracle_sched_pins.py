@@ -106,6 +106,66 @@ def test_hand_enumerated_vbs_bins():
     assert [(m.idx, m.cap) for m in plan] == [([0, 1, 2, 3], 50), ([4, 10, 11], 50), ([5, 6], 100), ([7, 8], 100), ([9], 100)]
 
 
+# ------------------------------------------------------------------ the recomputation pass, enumerated by hand
+# Several failures whose (scheduled length, index) order is not their index order: Sec. 4.1 collects the failures
+# and recomputes them after the group; they are re-batched in the order of their scheduled length.
+PRED_F = [260, 30, 120, 55, 49, 110, 20, 210]
+TRUE_F = [400, 60, 100, 180, 50, 300, 10, 205]
+
+
+def test_hand_enumerated_failure_pass_order_with_bins():
+    pol = so.Policy(flags=("SORT", "BIN", "FCR"), base_batch=2, l_max=512, max_batch=256)
+    r = so.run_group(PRED_F, TRUE_F, 50, pol)
+    # bins: 50 -> {1,4,6}, 100 -> {3}, 150 -> {2,5}, 250 -> {7}, 300 -> {0}
+    assert [(m.idx, m.cap) for m in r["plan"]] == [([1, 4], 50), ([6], 50), ([3], 100), ([2, 5], 150), ([7], 250), ([0], 300)]
+    assert [m["steps"] for m in r["first"].per_mb] == [50, 10, 100, 150, 205, 300]
+    assert r["first"].steps == 815 and r["first"].padded_row_steps == 1015 and r["first"].live_row_steps == 965
+    # 60 > 50, 180 > 100, 300 > 150, 400 > 300 fail; 50 <= 50 does not
+    assert sorted(r["first"].failed) == [0, 1, 3, 5]
+    # by (bin edge, index): 1 (50), 3 (100), 5 (150), 0 (300); batches of 2; the short rows share a batch
+    assert [(m.idx, m.cap) for m in r["failure_plan"]] == [([1, 3], 512), ([5, 0], 512)]
+    assert [m["steps"] for m in r["second"].per_mb] == [180, 400]
+    assert r["second"].steps == 580 and r["second"].padded_row_steps == 1160      # index order would cost 400 + 300
+    assert r["steps"] == 1395 and r["useful_tokens"] == 1305 and r["n_failed"] == 4
+    # the order does not depend on the order the failures are handed over in
+    for given in ([0, 1, 3, 5], [5, 3, 1, 0], [3, 0, 5, 1]):
+        assert [m.idx for m in so.schedule_failures(PRED_F, given, 50, pol)] == [[1, 3], [5, 0]]
+
+
+def test_hand_enumerated_failure_pass_order_without_bins_and_ties():
+    pol = so.Policy(flags=("SORT", "FCR"), base_batch=2, l_max=512)
+    r = so.run_group(PRED_F, TRUE_F, 0, pol)
+    # sorted by prediction: 6(20) 1(30) | 4(49) 3(55) | 5(110) 2(120) | 7(210) 0(260)
+    assert [(m.idx, m.cap) for m in r["plan"]] == [([6, 1], 30), ([4, 3], 55), ([5, 2], 120), ([7, 0], 260)]
+    assert sorted(r["first"].failed) == [0, 1, 3, 5]
+    assert [(m.idx, m.cap) for m in r["failure_plan"]] == [([1, 3], 512), ([5, 0], 512)]
+    assert r["second"].steps == 180 + 400
+    # equal scheduled lengths: the arrival index decides (stable), whatever order the list comes in
+    pred = [80, 70, 80, 70, 60]
+    plan = so.schedule_failures(pred, [4, 2, 0, 3, 1], 50, so.Policy(flags=("SORT", "BIN", "FCR"), base_batch=2, l_max=512))
+    assert [(m.idx, m.cap) for m in plan] == [([0, 1], 512), ([2, 3], 512), ([4], 512)]   # one bin (100): index order
+    plan = so.schedule_failures(pred, [4, 2, 0, 3, 1], 0, so.Policy(flags=("SORT", "FCR"), base_batch=2, l_max=512))
+    assert [m.idx for m in plan] == [[4, 1], [3, 0], [2]]                                   # 60 | 70 70 | 80 80
+
+
+# ------------------------------------------------------------------ VBS without bins, enumerated by hand
+def test_hand_enumerated_vbs_without_bins():
+    """Sec. 4.1 VBS keeps the tokens per batch constant; without bins a chunk of the sorted list is the longest
+    one whose size does not exceed the batch size allowed for its largest prediction."""
+    pol = so.Policy(flags=("SORT", "FCR", "VBS"), base_batch=2, l_max=100, max_batch=8)
+    # allowed batch = clamp(floor(2*100/L), 2, 8): 10, 12, 20, 25 -> 8; 30 -> 6; 40 -> 5; 50 -> 4; 55 -> 3; 70, 100 -> 2
+    assert [pol.batch_for(L) for L in (10, 12, 20, 25, 30, 40, 50, 55, 70, 100)] == [8, 8, 8, 8, 6, 5, 4, 3, 2, 2]
+    pred = [55, 10, 100, 25, 40, 12, 70, 30, 100, 20, 50, 25]
+    # sorted: 1(10) 5(12) 9(20) 3(25) 11(25) 7(30) 4(40) 10(50) 0(55) 6(70) 2(100) 8(100)
+    # chunk 1 takes 6 rows (the 6th has L = 30, which allows 6; a 7th would have L = 40, which allows 5);
+    # chunk 2 takes 3 (the 3rd has L = 55 -> 3; a 4th would have L = 70 -> 2); chunk 3 takes 2 (L = 100 -> 2).
+    plan = so.schedule(pred, len(pred), 0, pol)
+    assert [(m.idx, m.cap) for m in plan] == [([1, 5, 9, 3, 11, 7], 30), ([4, 10, 0], 55), ([6, 2], 100), ([8], 100)]
+    # without FCR the same chunks run to the global limit
+    plan = so.schedule(pred, len(pred), 0, so.Policy(flags=("SORT", "VBS"), base_batch=2, l_max=100, max_batch=8))
+    assert [(m.idx, m.cap) for m in plan] == [([1, 5, 9, 3, 11, 7], 100), ([4, 10, 0], 100), ([6, 2], 100), ([8], 100)]
+
+
 # ------------------------------------------------------------------ invariants on the five configured groups
 def _policy(w):
     return so.Policy(flags=w.flags, base_batch=w.base_batch, l_max=w.l_max, max_batch=w.max_batch)
