@@ -280,7 +280,7 @@ def main() -> int:
         log(f"vanilla: {sv['wall_ms']:.0f} ms -> ratio {extras['scheduled_over_vanilla']:.3f}")
 
     if not a.roofline_only and not a.no_generate and a.steps > 0:
-        # The same group when the host does not know the lengths (Sec. 5.1 of the paper samples at T = 0.5 and rows
+        # The same group when the host does not know the lengths (Sec. 4.2, Experimental Setting, of the paper samples at T = 0.5 and rows
         # end by themselves): tokens drawn by the sampling kernel, the same lengths applied on the device as
         # simulated ends, the host polling the unfinished-row count after every decode forward (the period that
         # profiles/polled_generation_sync_sweep_7b.md shows to be the cheapest).

@@ -36,7 +36,8 @@ void ss_set_verbose(int32_t level);
 /* Testing aid: which kernel runs the projections of small batches.  0 (default): chosen per shape and row
  * count; 1: never the kernel that stages activations once per workgroup (then: the k-splitting kernel up to 64
  * token-rows, the tiled kernel above); 2: that kernel for every projection of at most 128 token-rows.
- * Results agree to fp32 rounding order.  Process-wide; other values are ignored. */
+ * Results agree to fp32 rounding order.  Process-wide (one atomic integer, read when a forward is planned: set it
+ * between calls, not during one); other values are ignored. */
 void ss_set_gemm_mode(int32_t mode);
 
 /* ------------------------------------------------------------------ scheduler (host only) */
@@ -118,6 +119,10 @@ typedef struct ss_weights ss_weights; /* opaque; owns packed bf16 weights and a 
  *            The caller keeps ownership; the data is copied.
  * Requires n_heads*head_dim == d_model, head_dim in {64, 128}, d_model % 64 == 0 and <= 8192, d_ffn % 16 == 0,
  * vocab % 16 == 0.
+ * Precision: weights are bf16; accumulation, softmax and normalisation are fp32; an activation that feeds a
+ * projection is carried as the sum of two bf16 values; key/value cache slots are IEEE half (2 bytes per element,
+ * 11 significand bits), saturating at +-65504.  Source values must be finite: they are not checked.  A row whose
+ * logits are all NaN or -inf yields token id 0, never an id outside the vocabulary.
  * Errors: SS_EINVAL (shape), SS_EDEVICE (no usable GPU / HIP error), SS_ENOMEM.
  */
 int  ss_weights_create(const ss_model_cfg* cfg, const void* const* tensors, int32_t src_dtype, ss_weights** out);
@@ -207,7 +212,7 @@ int ss_run_group(ss_weights* w, const int32_t* prompt_tokens, const int32_t* pro
 
 /*
  * How rows end and how tokens are chosen when the host does not know the response lengths in advance
- * (Sec. 5.1: responses are sampled at a temperature and end at the model's end-of-sequence token or at
+ * (Sec. 4.2, Experimental Setting: responses are sampled at a temperature and end at the model's end-of-sequence token or at
  * the limit on new tokens).
  */
 typedef struct {

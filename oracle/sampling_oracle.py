@@ -1,7 +1,7 @@
 """Oracle of generation with a real end-of-sequence token and temperature sampling
 (TEST INFRASTRUCTURE ONLY: imported by tests, the smoke check and the benchmark's cpu_baseline leg).
 
-Sec. 5.1 (experimental setting) of the paper: responses are sampled at a temperature and a
+Sec. 4.2 (Experimental Setting) of the paper: responses are sampled at a temperature and a
 row stops when the model emits its end-of-sequence token or reaches the limit on new tokens;
 Sec. 4.1: a row that is still unfinished when the micro-batch's limit is reached has failed.
 

@@ -39,9 +39,11 @@ struct Layer {
 struct Buf {
     void* p = nullptr;
     size_t bytes = 0;
+    bool borrowed = false;   // a view into memory owned elsewhere (the static scratch array): never grown or freed
     int ensure(size_t need, bool zero)
     {
         if (need <= bytes) return SS_OK;
+        if (borrowed) return ss::fail(SS_ESTATE, "a borrowed buffer of %zu bytes cannot grow to %zu", bytes, need);
         if (p) (void)hipFree(p);
         p = nullptr;
         bytes = 0;
@@ -60,9 +62,10 @@ struct Buf {
     }
     void release()
     {
-        if (p) (void)hipFree(p);
+        if (p && !borrowed) (void)hipFree(p);
         p = nullptr;
         bytes = 0;
+        borrowed = false;
     }
     template <class T>
     T* as() const { return (T*)p; }
@@ -70,6 +73,9 @@ struct Buf {
 
 struct Workspace {
     Buf x, h, h_lo, ao, ao_lo, act, act_lo, qrot, pqkv, pd, pgu, hsel, hsel_lo, logits, kv, ints, i64s, draws;
+    // Non-null: every buffer is carved out of [arena, arena + arena_bytes) instead of being allocated.
+    char* arena = nullptr;
+    size_t arena_bytes = 0;
     void release()
     {
         for (Buf* b : {&x, &h, &h_lo, &ao, &ao_lo, &act, &act_lo, &qrot, &pqkv, &pd, &pgu, &hsel, &hsel_lo, &logits, &kv,
@@ -104,6 +110,7 @@ struct ss_weights {
     uint64_t cur_seed = 0;
     float cur_inv_temp = 0.f;
     int32_t* h_poll = nullptr;   // pinned host copy of the 4-int device header (d_n, d_step, d_nlive, d_active)
+    hipEvent_t ev[3] = {nullptr, nullptr, nullptr};   // start, end of the prompt forward, end of a micro-batch
 };
 
 namespace {
@@ -183,36 +190,58 @@ int check_cfg(const ss_model_cfg* c)
 // ---------------------------------------------------------------------------------------- workspace
 // n_max token-rows in a forward, B micro-batch rows, n_sel rows whose logits are wanted,
 // slots = total key/value slots of the micro-batch.
-int ensure_workspace(ss_weights* w, int n_max, int B, int n_sel, size_t slots, int max_new)
+int ensure_workspace(ss_weights* w, int n_max, int B, int n_sel, size_t slots, int max_new, hipStream_t s)
 {
     const ss_model_cfg& c = w->cfg;
     const int d = c.d_model, F = c.d_ffn, V = c.vocab;
     Workspace& ws = w->ws;
     const size_t nr = (size_t)ss::round_up(n_max, 128);
-    const size_t ks_rows = std::max<size_t>((size_t)8 * std::min(n_max, 1024), (size_t)n_max);
-    int rc;
-    if ((rc = ws.x.ensure(nr * d * 4, false))) return rc;
-    if ((rc = ws.h.ensure(nr * d * 2, true))) return rc;
-    if ((rc = ws.h_lo.ensure(nr * d * 2, true))) return rc;
-    if ((rc = ws.ao.ensure(nr * d * 2, true))) return rc;
-    if ((rc = ws.ao_lo.ensure(nr * d * 2, true))) return rc;
-    if ((rc = ws.act.ensure(nr * ss::padded_k(F) * 2, true))) return rc;
-    if ((rc = ws.act_lo.ensure(nr * ss::padded_k(F) * 2, true))) return rc;
-    if ((rc = ws.qrot.ensure(nr * d * 4, false))) return rc;
-    if ((rc = ws.pqkv.ensure(ks_rows * 3 * d * 4, false))) return rc;
-    if ((rc = ws.pd.ensure(ks_rows * d * 4, false))) return rc;
-    // gate|up partial sums exist only for decode-sized batches run with k-slices
-    if ((rc = ws.pgu.ensure((size_t)8 * std::min(n_max, 1024) * 2 * F * 4, false))) return rc;
-    if ((rc = ws.hsel.ensure((size_t)ss::round_up(n_sel, 128) * d * 2, true))) return rc;
-    if ((rc = ws.hsel_lo.ensure((size_t)ss::round_up(n_sel, 128) * d * 2, true))) return rc;
-    if ((rc = ws.logits.ensure((size_t)ss::round_up(n_sel, 16) * V * 4, false))) return rc;
-    w->kv_layer_stride = slots * d;
-    if ((rc = ws.kv.ensure((size_t)c.n_layers * 2 * slots * d * 2, false))) return rc;
-    // int32 arena: d_n d_step d_nlive d_active | tr_tok tr_row tr_pos [n_max] | live_row plen limit cap [B] | am sel [n_sel] | out_tok
     const size_t Bp = ss::round_up(B, 4), np = ss::round_up(n_max, 4), sp = ss::round_up(n_sel, 4);
     const size_t n_i32 = 4 + 3 * np + 4 * Bp + 2 * sp + (size_t)B * max_new;
-    if ((rc = ws.ints.ensure(n_i32 * 4, false))) return rc;
-    if ((rc = ws.i64s.ensure(Bp * 8, false))) return rc;
+    w->kv_layer_stride = slots * d;
+    // Partial-sum buffers hold [ksplit][rows][N] for whatever plan a forward over 1..n_max rows gets.
+    // gate|up partial sums exist only when that projection runs with k-slices (never in the sweep kernel).
+    struct Item { Buf* b; size_t bytes; bool zero; };
+    const Item items[] = {
+        {&ws.x, nr * d * 4, false},
+        {&ws.h, nr * d * 2, true},
+        {&ws.h_lo, nr * d * 2, true},
+        {&ws.ao, nr * d * 2, true},
+        {&ws.ao_lo, nr * d * 2, true},
+        {&ws.act, nr * ss::padded_k(F) * 2, true},
+        {&ws.act_lo, nr * ss::padded_k(F) * 2, true},
+        {&ws.qrot, nr * d * 4, false},
+        {&ws.pqkv, ss::gemm_partial_rows_bound(3 * d, n_max) * 3 * d * 4, false},
+        {&ws.pd, ss::gemm_partial_rows_bound(d, n_max) * d * 4, false},
+        {&ws.pgu, ss::gemm_partial_rows_bound(2 * F, n_max, true) * 2 * F * 4, false},
+        {&ws.hsel, (size_t)ss::round_up(n_sel, 128) * d * 2, true},
+        {&ws.hsel_lo, (size_t)ss::round_up(n_sel, 128) * d * 2, true},
+        {&ws.logits, (size_t)ss::round_up(n_sel, 16) * V * 4, false},
+        {&ws.kv, (size_t)c.n_layers * 2 * slots * d * 2, false},
+        {&ws.ints, n_i32 * 4, false},
+        {&ws.i64s, Bp * 8, false},
+    };
+    if (ws.arena) {
+        // Carve the buffers out of the arena.  It keeps the last call's bytes in a different layout, so what
+        // must read as zero (padding columns and rows of the packed activations) is cleared by a kernel.
+        size_t at = 0;
+        for (const Item& it : items) at += (it.bytes + 255) & ~(size_t)255;
+        if (at > ws.arena_bytes)
+            return ss::fail(SS_EINVAL, "this call needs %zu bytes of workspace; the static scratch array holds %zu", at,
+                            ws.arena_bytes);
+        at = 0;
+        for (const Item& it : items) {
+            it.b->p = ws.arena + at;
+            it.b->bytes = it.bytes;
+            it.b->borrowed = true;
+            if (it.zero) ss::launch_fill_i32((int32_t*)it.b->p, 0, it.bytes / 4, s);
+            at += (it.bytes + 255) & ~(size_t)255;
+        }
+    } else {
+        for (const Item& it : items)
+            if (int rc = it.b->ensure(it.bytes, it.zero)) return rc;
+    }
+    // int32 arena: d_n d_step d_nlive d_active | tr_tok tr_row tr_pos [n_max] | live_row plen limit cap [B] | am sel [n_sel] | out_tok
     int32_t* q = ws.ints.as<int32_t>();
     MbState& st = w->st;
     st.d_n = q; st.d_step = q + 1; st.d_nlive = q + 2; st.d_active = q + 3; q += 4;
@@ -412,15 +441,16 @@ int check_gen_opts(const ss_weights* w, const ss_gen_opts* g, int rows, int need
     return SS_OK;
 }
 
-// Three HIP events that are destroyed however the call ends.
-struct Events3 {
-    hipEvent_t e[3] = {nullptr, nullptr, nullptr};
-    int create()
+// iters + 1 HIP events that are destroyed however the call ends.
+struct EventList {
+    std::vector<hipEvent_t> e;
+    int create(int count)
     {
+        e.assign((size_t)count, nullptr);
         for (auto& x : e) HIPCHK(hipEventCreate(&x));
         return SS_OK;
     }
-    ~Events3()
+    ~EventList()
     {
         for (auto& x : e)
             if (x) (void)hipEventDestroy(x);
@@ -468,7 +498,7 @@ int decode_microbatch_impl(ss_weights* w, const int32_t* prompt_tokens, const in
         sel[i] = prompt_offsets[i + 1] - 1;
     }
     HIPCHK(hipSetDevice(w->device));
-    if (int rc = ensure_workspace(w, std::max(n_prompt, B), B, B, slots, max_new)) return rc;
+    if (int rc = ensure_workspace(w, std::max(n_prompt, B), B, B, slots, max_new, s)) return rc;
     const MbState& st = w->st;
     const int compact = (flags & SS_COMPACT) ? 1 : 0;
     const int eos_id = gen ? gen->eos_id : -1;
@@ -496,9 +526,7 @@ int decode_microbatch_impl(ss_weights* w, const int32_t* prompt_tokens, const in
     }
     ss::launch_fill_i32(st.out_tok, -1, (size_t)B * max_new, s);
 
-    Events3 ev;
-    if (int rc = ev.create()) return rc;
-    const hipEvent_t e0 = ev.e[0], e1 = ev.e[1], e2 = ev.e[2];
+    const hipEvent_t e0 = w->ev[0], e1 = w->ev[1], e2 = w->ev[2];   // created with the handle: nothing is created per call
     HIPCHK(hipEventRecord(e0, s));
     forward(w, n_prompt, B, w->d_sel, st.d_nlive, false, s);
     ss::launch_step_update(st, compact, eos_id, s);
@@ -606,6 +634,8 @@ extern "C" int ss_weights_create(const ss_model_cfg* cfg, const void* const* ten
     if (hipStreamCreate(&w->stream) != hipSuccess) return bail(ss::fail(SS_EDEVICE, "hipStreamCreate failed"));
     if (hipHostMalloc((void**)&w->h_poll, 16, hipHostMallocDefault) != hipSuccess)
         return bail(ss::fail(SS_ENOMEM, "hipHostMalloc failed"));
+    for (auto& e : w->ev)
+        if (hipEventCreate(&e) != hipSuccess) return bail(ss::fail(SS_EDEVICE, "hipEventCreate failed"));
 
     const int d = cfg->d_model, F = cfg->d_ffn, V = cfg->vocab, f32 = (src_dtype == SS_F32);
     Buf staging;
@@ -680,6 +710,8 @@ extern "C" void ss_weights_destroy(ss_weights* w)
     for (void* p : w->allocs) (void)hipFree(p);
     if (w->stream) (void)hipStreamDestroy(w->stream);
     if (w->h_poll) (void)hipHostFree(w->h_poll);
+    for (auto& e : w->ev)
+        if (e) (void)hipEventDestroy(e);
     delete w;
 }
 
@@ -749,7 +781,7 @@ extern "C" int ss_forward_logits(ss_weights* w, const int32_t* tokens, const int
     }
     const int n_sel = (int)sel.size();
     HIPCHK(hipSetDevice(w->device));
-    if (int rc = ensure_workspace(w, std::max(n_p, B), B, std::max(n_sel, B), slots, 1)) return rc;
+    if (int rc = ensure_workspace(w, std::max(n_p, B), B, std::max(n_sel, B), slots, 1, s)) return rc;
     const MbState& st = w->st;
     // prompt forward over the first n_prompt[i] tokens of every row
     std::vector<int32_t> ptoks, poffs(B + 1, 0);
@@ -962,14 +994,15 @@ extern "C" int ss_bench_decode_step(ss_weights* w, const int32_t* prompt_tokens,
     for (int i = 0; i <= B; ++i) offs[i] = i * ctx;
     for (int i = 0; i < B; ++i) sel[i] = (i + 1) * ctx - 1;
     HIPCHK(hipSetDevice(w->device));
-    if (int rc = ensure_workspace(w, B * ctx, B, B, (size_t)B * (ctx + 1), 2)) return rc;
+    if (int rc = ensure_workspace(w, B * ctx, B, B, (size_t)B * (ctx + 1), 2, s)) return rc;
     const MbState& st = w->st;
     if (int rc = upload_prompt_state(w, prompt_tokens, offs.data(), lens.data(), B, slab.data(), limit.data(), sel, s))
         return rc;
     forward(w, B * ctx, B, w->d_sel, st.d_nlive, false, s);
     ss::launch_step_update(st, 0, -1, s);   // token-rows of the decode step: every row at position ctx
-    std::vector<hipEvent_t> ev(iters + 1);
-    for (auto& e : ev) HIPCHK(hipEventCreate(&e));
+    EventList evl;
+    if (int rc = evl.create(iters + 1)) return rc;
+    const std::vector<hipEvent_t>& ev = evl.e;
     HIPCHK(hipEventRecord(ev[0], s));
     for (int it = 0; it < iters; ++it) {
         forward(w, B, B, nullptr, nullptr, true, s);
@@ -982,7 +1015,6 @@ extern "C" int ss_bench_decode_step(ss_weights* w, const int32_t* prompt_tokens,
         HIPCHK(hipEventElapsedTime(&ms, ev[it], ev[it + 1]));
         ms_out[it] = ms;
     }
-    for (auto& e : ev) (void)hipEventDestroy(e);
     return SS_OK;
 }
 
@@ -996,7 +1028,7 @@ extern "C" int ss_bench_weight_stream(ss_weights* w, int32_t B, int32_t iters, d
     if (!guard.ok) return ss::fail(SS_ESTATE, "another call is in flight on this handle");
     hipStream_t s = hip_stream ? (hipStream_t)hip_stream : w->stream;
     HIPCHK(hipSetDevice(w->device));
-    if (int rc = ensure_workspace(w, B, B, B, (size_t)B, 1)) return rc;
+    if (int rc = ensure_workspace(w, B, B, B, (size_t)B, 1, s)) return rc;
     const ss_model_cfg& c = w->cfg;
     const int d = c.d_model, F = c.d_ffn, V = c.vocab, Fp = ss::padded_k(F), n = B;
     Workspace& ws = w->ws;
@@ -1009,8 +1041,9 @@ extern "C" int ss_bench_weight_stream(ss_weights* w, int32_t B, int32_t iters, d
     bf16_t *h = ws.h.as<bf16_t>(), *ao = ws.ao.as<bf16_t>(), *act = ws.act.as<bf16_t>();
     bf16_t *h_lo = ws.h_lo.as<bf16_t>(), *ao_lo = ws.ao_lo.as<bf16_t>(), *act_lo = ws.act_lo.as<bf16_t>();
     float *pqkv = ws.pqkv.as<float>(), *pd = ws.pd.as<float>();
-    std::vector<hipEvent_t> ev(iters + 1);
-    for (auto& e : ev) HIPCHK(hipEventCreate(&e));
+    EventList evl;
+    if (int rc = evl.create(iters + 1)) return rc;
+    const std::vector<hipEvent_t>& ev = evl.e;
     HIPCHK(hipEventRecord(ev[0], s));
     int launches = 0;
     for (int it = 0; it < iters; ++it) {
@@ -1040,7 +1073,6 @@ extern "C" int ss_bench_weight_stream(ss_weights* w, int32_t B, int32_t iters, d
         HIPCHK(hipEventElapsedTime(&ms, ev[it], ev[it + 1]));
         ms_out[it] = ms;
     }
-    for (auto& e : ev) (void)hipEventDestroy(e);
     if (launches_out) *launches_out = launches;
     return SS_OK;
 }
@@ -1057,8 +1089,9 @@ extern "C" int ss_bench_read_stream(ss_weights* w, int32_t iters, double* ms_out
     if (int rc = w->ws.ints.ensure(64, false)) return rc;
     uint32_t* sink = w->ws.ints.as<uint32_t>();
     auto mat_bytes = [](const PackedMat& m) { return ((size_t)m.N * m.Kp * 2) & ~(size_t)0xffff; };
-    std::vector<hipEvent_t> ev(iters + 1);
-    for (auto& e : ev) HIPCHK(hipEventCreate(&e));
+    EventList evl;
+    if (int rc = evl.create(iters + 1)) return rc;
+    const std::vector<hipEvent_t>& ev = evl.e;
     HIPCHK(hipEventRecord(ev[0], s));
     size_t bytes = 0;
     for (int it = 0; it < iters; ++it) {
@@ -1079,7 +1112,6 @@ extern "C" int ss_bench_read_stream(ss_weights* w, int32_t iters, double* ms_out
         HIPCHK(hipEventElapsedTime(&ms, ev[it], ev[it + 1]));
         ms_out[it] = ms;
     }
-    for (auto& e : ev) (void)hipEventDestroy(e);
     if (bytes_out) *bytes_out = (int64_t)bytes;
     return SS_OK;
 }

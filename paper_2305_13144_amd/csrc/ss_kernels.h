@@ -6,6 +6,8 @@
 
 #include <cstdint>
 
+#include "ss_plan.h"
+
 namespace ss {
 
 typedef uint16_t bf16_t;  // bf16 bit pattern
@@ -36,8 +38,6 @@ struct MbState {
     int32_t max_new;
 };
 
-enum Epilogue { EPI_PARTIAL = 0, EPI_SWIGLU = 1 };
-
 struct GemmArgs {
     const bf16_t* W;     // packed [N, Kp]
     const bf16_t* X;     // packed [rows, Kp], hi part of the activations
@@ -64,16 +64,6 @@ void launch_rmsnorm(const MbState& st, float* x, const float* part, int ksplit, 
                     const bf16_t* w, float eps, const int32_t* sel, const int32_t* d_nsel, bf16_t* h_packed,
                     bf16_t* h_packed_lo, int d, int n_max, hipStream_t s);
 void launch_gemm(const GemmArgs& a, int epilogue, hipStream_t s);
-struct GemmPlan {
-    int ksplit, nb, kd, kp;
-    int sweep_p, sweep_gn;
-};
-// n_cu: compute units of the device (the sweep kernel runs one workgroup per unit).
-// max_ksplit: 1 when the consumer reads the output directly (logits).
-GemmPlan gemm_plan(int N, int Kp, int m_rows, int epilogue, int n_cu, int max_ksplit = 8);
-// Testing aid: 0 = choose per shape (default), 1 = never use the sweep kernel, 2 = use it for every
-// projection of at most 64 rows.
-void set_gemm_mode(int mode);
 void launch_swiglu_reduce(const float* part, int ksplit, size_t part_stride, int m_rows, int F, int kp_out,
                           bf16_t* out, bf16_t* out_lo, hipStream_t s);
 void launch_rope_append(const MbState& st, const float* qkv_part, int ksplit, size_t part_stride, float* qrot,

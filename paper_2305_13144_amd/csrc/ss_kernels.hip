@@ -42,7 +42,12 @@ __device__ __forceinline__ void split_bf(float v, bf16_t& hi, bf16_t& lo)
 // Key/value slots are stored as IEEE half: the same 2 bytes per element as bf16 with three more
 // significand bits; keys and values are projections of RMS-normalised activations, far inside its range.
 __device__ __forceinline__ float kv2f(bf16_t b) { return (float)__builtin_bit_cast(_Float16, b); }
-__device__ __forceinline__ bf16_t f2kv(float f) { return __builtin_bit_cast(bf16_t, (_Float16)f); }
+// Saturating: a value beyond the half range is stored as the largest finite half, never as infinity (an infinite
+// key would turn the softmax into NaN and the token choice into an arbitrary id).
+__device__ __forceinline__ bf16_t f2kv(float f)
+{
+    return __builtin_bit_cast(bf16_t, (_Float16)fminf(fmaxf(f, -65504.f), 65504.f));
+}
 
 // Element (r, k) of a packed [rows, Kp] matrix.
 __device__ __forceinline__ size_t pk_index(int r, int k, int Kp)
@@ -998,12 +1003,14 @@ __global__ __launch_bounds__(1024) void k_argmax(const float* __restrict__ logit
     if (threadIdx.x == 0) {
         for (int w = 1; w < 16; ++w)
             if (sb[w] > best || (sb[w] == best && si[w] < bi)) { best = sb[w]; bi = si[w]; }
-        am[j] = bi;
+        // no logit compared greater than the start value (a row of NaN or -inf): id 0, never an id outside the
+        // vocabulary, which the next step would use as an embedding row
+        am[j] = (unsigned)bi < (unsigned)vocab ? bi : 0;
     }
 }
 
 // ------------------------------------------------------------------------------------------ sampling
-// Temperature sampling per selected row (Sec. 5.1 of the paper samples responses at a temperature):
+// Temperature sampling per selected row (Sec. 4.2, Experimental Setting: responses are sampled at a temperature):
 // token = smallest v with  sum_{v' <= v} e_v'  >  u * sum_v' e_v',  e_v = exp((logit_v - max) * inv_temp),
 // u being the draw for (row, token number): supplied by the caller, or generated from a counter (below).  The CDF runs in vocabulary order, so thread t owns
 // the contiguous chunk [t*c, (t+1)*c): it sums its chunk in index order, a workgroup scan of the 1024
@@ -1226,71 +1233,6 @@ void launch_rmsnorm(const MbState& st, float* x, const float* part, int ksplit, 
 {
     hipLaunchKernelGGL(k_rmsnorm, dim3(n_max), dim3(1024), 0, s, d_nsel ? d_nsel : st.d_n, x, part,
                        part ? ksplit : 0, part_stride, w, eps, sel, h_packed, h_packed_lo, d);
-}
-
-// Launch shape of a projection.
-// Sweep kernel (<= 128 rows, at least 160 KiB of weights per compute unit and row strip; below that the launch is
-// too short to amortise its start-up and the skinny kernel's finer split wins: measured at 16 rows, the 7B o
-// projection, 131 KiB per unit, is 12 % faster in the skinny kernel, the 13B one, 205 KiB, 30 % faster here): one workgroup per compute unit and
-// k-slice, a wave per output strip (per gate/up strip pair with the SwiGLU epilogue).  k-slices double
-// until every workgroup has 4 or more waves of work, as far as the epilogue allows them, never below 16
-// k-blocks per slice; a workgroup has 4 or 8 waves, and when 8 are not enough there are more workgroups.
-// Skinny kernel (<= 64 rows otherwise), from sweeps on the 7B shapes: aim at 512+ workgroups; 4 strips per
-// workgroup halve the activation re-reads and win when k is short, 2 strips when k is long or when the
-// epilogue forbids k-slices (SwiGLU, logits); k-slices double until there are 512 workgroups, at most 8,
-// never leaving a wave fewer than 4 k-blocks.  Tiled kernel: ksplit fills the chip when there are few
-// 64x256 tiles.
-
-// Strips per wave of the sweep kernel: a gate/up pair for the SwiGLU epilogue; with 2 or more row strips also two,
-// so that an activation operand read from LDS feeds two weight strips (at 1 strip per wave the LDS reads of
-// 64 rows, 8 KiB per KiB of weights, bound the kernel; measured: 32 rows 8 % faster, 64 rows 7 %, 16 rows 1 % slower).
-static int sweep_nbw(int epilogue, int m_rows) { return (epilogue == EPI_SWIGLU || m_rows > 16) ? 2 : 1; }
-
-constexpr int kSweepMaxRows = 128;   // 8 row strips: accumulators and the LDS chunk still fit
-static int g_gemm_mode = 0;
-void set_gemm_mode(int mode) { g_gemm_mode = mode; }
-
-GemmPlan gemm_plan(int N, int Kp, int m_rows, int epilogue, int n_cu, int max_ksplit)
-{
-    GemmPlan p{1, 2, 4, 1, 0, 0};
-    const int KB = Kp / 32;
-    if (m_rows <= kSweepMaxRows) {
-        const size_t w_per_cu = (size_t)N * (size_t)Kp * 2 / (size_t)n_cu;
-        const size_t mt_rows = (size_t)(m_rows + 15) / 16;   // activation re-reads grow with the row strips: sweep earlier
-        if (g_gemm_mode == 2 || (g_gemm_mode == 0 && w_per_cu * mt_rows >= ((size_t)160 << 10))) {
-            if (epilogue == EPI_SWIGLU) max_ksplit = 1;   // fused epilogue: no k-slices
-            const int nbw = sweep_nbw(epilogue, m_rows);
-            const int units = (N / 16 + nbw - 1) / nbw;
-            while (units * p.ksplit < 4 * n_cu && p.ksplit * 2 <= max_ksplit && p.ksplit < 8 && KB / (p.ksplit * 2) >= 16)
-                p.ksplit *= 2;
-            int gn = std::max(1, std::min(units, n_cu / p.ksplit));
-            if ((units + gn - 1) / gn > 8) gn = (units + 7) / 8;
-            p.sweep_p = (units + gn - 1) / gn <= 4 ? 4 : 8;
-            p.sweep_gn = gn;
-            return p;
-        }
-    }
-    if (m_rows <= 64) {
-        if (epilogue == EPI_SWIGLU) max_ksplit = 1;   // fused epilogue: no k-slices
-        const int mt = (m_rows + 15) / 16;
-        p.kd = mt == 1 ? 4 : 2;
-        if (max_ksplit == 1 && epilogue == EPI_SWIGLU) return p;
-        p.nb = (mt == 1 && KB > 256) ? 2 : 4;   // with several row strips the activation re-reads dominate: 4 strips
-        if (max_ksplit == 1 && mt == 1) p.nb = 2;
-        const int groups = (N / 16 + p.nb - 1) / p.nb;
-        while (groups * p.ksplit < 512 && p.ksplit * 2 <= max_ksplit && p.ksplit < 8 && KB / (p.ksplit * 2 * 4) >= 4)
-            p.ksplit *= 2;
-        return p;
-    }
-    // Tiled kernel.  Many tiles (prompt forwards): 4-wave workgroups, two per CU, no slicing.  Few tiles
-    // (decode batches of 65-256 rows): measured on the 7B shapes, outer k-slices up to 4 (partial sums
-    // through HBM are small while rows are few) beat everything else; where slicing is impossible an
-    // 8-wave workgroup halves the k range inside the workgroup instead.
-    const int tiles = ((N + 255) / 256) * ((m_rows + 63) / 64);
-    if (tiles >= 512) return p;
-    while (tiles * p.ksplit < 512 && p.ksplit * 2 <= max_ksplit && p.ksplit < 4 && KB / (p.ksplit * 2) >= 16) p.ksplit *= 2;
-    if (p.ksplit == 1) p.kp = 2;
-    return p;
 }
 
 void launch_swiglu_reduce(const float* part, int ksplit, size_t part_stride, int m_rows, int F, int kp_out,

@@ -1,0 +1,98 @@
+// Which kernel runs a projection, and in which launch shape (host arithmetic only).
+#include "ss_plan.h"
+
+#include <algorithm>
+#include <atomic>
+
+namespace ss {
+
+namespace {
+std::atomic<int> g_gemm_mode{0};
+constexpr int kSmallMaxKsplit = 8;   // sweep and skinny kernels: at most 8 k-slices
+constexpr int kTiledMaxKsplit = 4;   // tiled kernel: at most 4
+constexpr int kTiledFullTiles = 512; // from this many 64x256 tiles on the tiled kernel runs unsliced
+}
+
+void set_gemm_mode(int mode) { g_gemm_mode.store(mode, std::memory_order_relaxed); }
+int gemm_mode() { return g_gemm_mode.load(std::memory_order_relaxed); }
+
+// Launch shape of a projection.
+// Sweep kernel (<= 128 rows, at least 160 KiB of weights per compute unit and row strip; below that the launch is
+// too short to amortise its start-up and the skinny kernel's finer split wins: measured at 16 rows, the 7B o
+// projection, 131 KiB per unit, is 12 % faster in the skinny kernel, the 13B one, 205 KiB, 30 % faster here): one workgroup per compute unit and
+// k-slice, a wave per output strip (per gate/up strip pair with the SwiGLU epilogue).  k-slices double
+// until every workgroup has 4 or more waves of work, as far as the epilogue allows them, never below 16
+// k-blocks per slice; a workgroup has 4 or 8 waves, and when 8 are not enough there are more workgroups.
+// Skinny kernel (<= 64 rows otherwise), from sweeps on the 7B shapes: aim at 512+ workgroups; 4 strips per
+// workgroup halve the activation re-reads and win when k is short, 2 strips when k is long or when the
+// epilogue forbids k-slices (SwiGLU, logits); k-slices double until there are 512 workgroups, at most 8,
+// never leaving a wave fewer than 4 k-blocks.  Tiled kernel: ksplit fills the chip when there are few
+// 64x256 tiles.
+
+// Strips per wave of the sweep kernel: a gate/up pair for the SwiGLU epilogue; with 2 or more row strips also two,
+// so that an activation operand read from LDS feeds two weight strips (at 1 strip per wave the LDS reads of
+// 64 rows, 8 KiB per KiB of weights, bound the kernel; measured: 32 rows 8 % faster, 64 rows 7 %, 16 rows 1 % slower).
+int sweep_nbw(int epilogue, int m_rows) { return (epilogue == EPI_SWIGLU || m_rows > 16) ? 2 : 1; }
+
+GemmPlan gemm_plan(int N, int Kp, int m_rows, int epilogue, int n_cu, int max_ksplit)
+{
+    GemmPlan p{1, 2, 4, 1, 0, 0};
+    const int KB = Kp / 32;
+    const int mode = gemm_mode();
+    if (m_rows <= kSweepMaxRows) {
+        const size_t w_per_cu = (size_t)N * (size_t)Kp * 2 / (size_t)n_cu;
+        const size_t mt_rows = (size_t)(m_rows + 15) / 16;   // activation re-reads grow with the row strips: sweep earlier
+        if (mode == 2 || (mode == 0 && w_per_cu * mt_rows >= ((size_t)160 << 10))) {
+            if (epilogue == EPI_SWIGLU) max_ksplit = 1;   // fused epilogue: no k-slices
+            const int nbw = sweep_nbw(epilogue, m_rows);
+            const int units = (N / 16 + nbw - 1) / nbw;
+            while (units * p.ksplit < 4 * n_cu && p.ksplit * 2 <= max_ksplit && p.ksplit < kSmallMaxKsplit &&
+                   KB / (p.ksplit * 2) >= 16)
+                p.ksplit *= 2;
+            int gn = std::max(1, std::min(units, n_cu / p.ksplit));
+            if ((units + gn - 1) / gn > 8) gn = (units + 7) / 8;
+            p.sweep_p = (units + gn - 1) / gn <= 4 ? 4 : 8;
+            p.sweep_gn = gn;
+            return p;
+        }
+    }
+    if (m_rows <= 64) {
+        if (epilogue == EPI_SWIGLU) max_ksplit = 1;   // fused epilogue: no k-slices
+        const int mt = (m_rows + 15) / 16;
+        p.kd = mt == 1 ? 4 : 2;
+        if (max_ksplit == 1 && epilogue == EPI_SWIGLU) return p;
+        p.nb = (mt == 1 && KB > 256) ? 2 : 4;   // with several row strips the activation re-reads dominate: 4 strips
+        if (max_ksplit == 1 && mt == 1) p.nb = 2;
+        const int groups = (N / 16 + p.nb - 1) / p.nb;
+        while (groups * p.ksplit < 512 && p.ksplit * 2 <= max_ksplit && p.ksplit < kSmallMaxKsplit &&
+               KB / (p.ksplit * 2 * 4) >= 4)
+            p.ksplit *= 2;
+        return p;
+    }
+    // Tiled kernel.  Many tiles (prompt forwards): 4-wave workgroups, two per CU, no slicing.  Few tiles
+    // (decode batches of 65-256 rows): measured on the 7B shapes, outer k-slices up to 4 (partial sums
+    // through HBM are small while rows are few) beat everything else; where slicing is impossible an
+    // 8-wave workgroup halves the k range inside the workgroup instead.
+    const int tiles = ((N + 255) / 256) * ((m_rows + 63) / 64);
+    if (tiles >= kTiledFullTiles) return p;
+    while (tiles * p.ksplit < kTiledFullTiles && p.ksplit * 2 <= max_ksplit && p.ksplit < kTiledMaxKsplit &&
+           KB / (p.ksplit * 2) >= 16)
+        p.ksplit *= 2;
+    if (p.ksplit == 1) p.kp = 2;
+    return p;
+}
+
+size_t gemm_partial_rows_bound(int N, int n_max, bool sliced_only)
+{
+    // up to kSweepMaxRows rows: at most kSmallMaxKsplit slices; above: the tiled kernel slices only while it
+    // has fewer than kTiledFullTiles tiles, i.e. up to 64 * floor((kTiledFullTiles - 1) / column tiles) rows
+    const size_t n = (size_t)std::max(n_max, 1);
+    const size_t col_tiles = (size_t)(N + 255) / 256;
+    const size_t tiled_rows = 64 * ((size_t)(kTiledFullTiles - 1) / std::max<size_t>(col_tiles, 1));
+    size_t need = sliced_only ? 1 : n;
+    need = std::max(need, (size_t)kSmallMaxKsplit * std::min<size_t>(n, (size_t)kSweepMaxRows));
+    need = std::max(need, (size_t)kTiledMaxKsplit * std::min(n, tiled_rows));
+    return need;
+}
+
+}  // namespace ss

@@ -81,3 +81,74 @@ def test_scheduler_under_asan_ubsan(tmp_path):
     r = subprocess.run([str(exe)], capture_output=True, text=True, env=env, timeout=120)
     assert r.returncode == 0, r.stdout + r.stderr
     assert r.stdout.strip() == "ok"
+
+
+PLAN_DRIVER = textwrap.dedent(r"""
+    #include <cstdio>
+    #include <cstdlib>
+    #include "ss_plan.h"
+    // Every plan the projection planner can return for 1..n_max rows must fit the partial-sum buffer the engine
+    // sizes with gemm_partial_rows_bound (the kernels write [ksplit][rows][N] floats into it).
+    int main() {
+        const int dims[] = {64, 256, 512, 1024, 2048, 4096, 5120, 8192};
+        const int ffns[] = {16, 512, 688, 4096, 11008, 13824, 28672};
+        const int row_grid[] = {1, 15, 16, 17, 33, 63, 64, 65, 127, 128, 129, 163, 255, 256, 257, 511, 512, 640, 641,
+                                1023, 1024, 1025, 2311, 2312, 2313, 4642, 4643, 4644, 8191, 8192, 10880, 10881, 32703,
+                                32704, 32705, 100000, 1048576};
+        const int cus[] = {64, 256, 304};
+        long checked = 0;
+        for (int mode = 0; mode <= 2; ++mode) {
+            ss::set_gemm_mode(mode);
+            for (int cu : cus)
+                for (int d : dims)
+                    for (int F : ffns) {
+                        const int Fp = (F + 63) / 64 * 64;
+                        struct { int N, Kp, epi; bool sliced_only; } mats[] = {
+                            {3 * d, d, ss::EPI_PARTIAL, false}, {d, d, ss::EPI_PARTIAL, false},
+                            {2 * F, d, ss::EPI_SWIGLU, true}, {d, Fp, ss::EPI_PARTIAL, false}};
+                        for (auto& m : mats)
+                            for (int n_max : row_grid) {
+                                const size_t cap = ss::gemm_partial_rows_bound(m.N, n_max, m.sliced_only);
+                                for (int n : row_grid) {
+                                    if (n > n_max) break;
+                                    const ss::GemmPlan p = ss::gemm_plan(m.N, m.Kp, n, m.epi, cu);
+                                    if (p.ksplit < 1 || p.ksplit > 8) { std::printf("bad ksplit\n"); return 2; }
+                                    if (m.sliced_only && p.ksplit == 1) continue;
+                                    if ((size_t)p.ksplit * (size_t)n > cap) {
+                                        std::printf("overflow: N %d Kp %d rows %d (n_max %d) ksplit %d > %zu rows\n", m.N,
+                                                    m.Kp, n, n_max, p.ksplit, cap);
+                                        return 3;
+                                    }
+                                    ++checked;
+                                }
+                            }
+                    }
+        }
+        // dense sweep of the row count on the shapes the advisor's replay found overflowing
+        ss::set_gemm_mode(0);
+        for (int n_max = 1; n_max <= 12000; n_max += 7) {
+            const size_t c1 = ss::gemm_partial_rows_bound(1024, n_max), c2 = ss::gemm_partial_rows_bound(2 * 512, n_max, true);
+            for (int n = 1; n <= n_max; n += 13) {
+                if ((size_t)ss::gemm_plan(1024, 4096, n, ss::EPI_PARTIAL, 256).ksplit * n > c1) return 4;
+                if ((size_t)ss::gemm_plan(1024, 1024, n, ss::EPI_PARTIAL, 256).ksplit * n > c1) return 5;
+                const ss::GemmPlan g = ss::gemm_plan(2 * 512, 4096, n, ss::EPI_SWIGLU, 256);
+                if (g.ksplit > 1 && (size_t)g.ksplit * n > c2) return 6;
+            }
+        }
+        std::printf("ok %ld\n", checked);
+        return 0;
+    }
+""")
+
+
+@pytest.mark.skipif(shutil.which("g++") is None, reason="g++ not available")
+def test_projection_plans_fit_their_partial_sum_buffers(tmp_path):
+    drv = tmp_path / "plan_driver.cpp"
+    drv.write_text(PLAN_DRIVER)
+    exe = tmp_path / "plan_driver"
+    cmd = ["g++", "-std=c++17", "-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=all", "-static-libasan",
+           "-I", CSRC, str(drv), os.path.join(CSRC, "ss_plan.cpp"), "-o", str(exe)]
+    subprocess.run(cmd, check=True, capture_output=True, text=True)
+    r = subprocess.run([str(exe)], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 0, r.stdout + r.stderr
+    assert r.stdout.startswith("ok ")

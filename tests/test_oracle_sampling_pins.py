@@ -1,7 +1,7 @@
 """Pins of the sampling / end-of-sequence oracle against things other than itself: closed forms
 (two-token sigmoid, equal logits), a library softmax through stratified draws, invariances of the
 softmax, the greedy limit, an independent library model (torch fp64) for the free-running loop, and
-the truncation property of an end-of-sequence token (Sec. 5.1: temperature sampling, rows end at their
+the truncation property of an end-of-sequence token (Sec. 4.2, Experimental Setting: temperature sampling, rows end at their
 end-of-sequence token or at the limit on new tokens; Sec. 4.1: unfinished at the limit = failed)."""
 import math
 
