@@ -67,7 +67,7 @@ def test_7b_config3_first_microbatches(full7b):
         for j in (0, len(idx) - 1):
             L = int(r["lens"][j])
             assert (r["tokens"][j, :L] >= 0).all() and (r["tokens"][j, L:] == -1).all()
-            dcd, tot = check_tokens_teacher_forced(om, w.prompt(idx[j]), r["tokens"][j, :L], upto=5, what=f"mb {k} row {j}")
+            dcd, tot = check_tokens_teacher_forced(om, w.prompt(idx[j]), r["tokens"][j, :L], upto=16, what=f"mb {k} row {j}")
             _say(f"  row {j}: {dcd}/{tot} decided positions match")
 
 
@@ -93,8 +93,47 @@ def test_7b_whole_group_config3_as_benchmarked(full7b):
     ok = next(i for i in range(w.n) if i not in failed and w.target_lens[i] >= 4)
     redo = sorted(failed)[0]                                               # a query that went through recomputation
     for i in (ok, redo):
-        dcd, tot = check_tokens_teacher_forced(om, w.prompt(i), r["tokens"][i, :int(w.target_lens[i])], upto=4,
+        dcd, tot = check_tokens_teacher_forced(om, w.prompt(i), r["tokens"][i, :int(w.target_lens[i])], upto=16,
                                                what=f"query {i}")
+        _say(f"  query {i}: {dcd}/{tot} decided positions match")
+
+
+def _check_group_against_scheduler_oracle(w, r, ref, vocab, compact):
+    """Every counter of ss_group_stats against the scheduler oracle; every query emitted once, in full, -1 after."""
+    s = r["stats"]
+    assert np.array_equal(r["lens"], w.target_lens)
+    assert s["steps"] == ref["steps"] and s["padded_row_steps"] == ref["padded_row_steps"]
+    assert s["computed_row_steps"] == (ref["live_row_steps"] if compact else ref["padded_row_steps"])
+    assert s["n_failed"] == ref["n_failed"] and s["useful_tokens"] == ref["useful_tokens"] == int(w.target_lens.sum())
+    assert (s["n_mb_first"], s["n_mb_failure"]) == (ref["first"].n_mb, ref["second"].n_mb)
+    prompts_run = int(w.prompt_lens.sum()) + sum(int(w.prompt_lens[i]) for i in ref["first"].failed)
+    assert s["prompt_tokens"] == prompts_run                                 # recomputed queries pay their prompt twice
+    for i in range(w.n):
+        t = int(w.target_lens[i])
+        assert (r["tokens"][i, :t] >= 0).all() and (r["tokens"][i, :t] < vocab).all()
+        assert (r["tokens"][i, t:] == -1).all()
+
+
+def test_7b_whole_group_config2_vanilla_as_benchmarked(full7b):
+    """Config 2: the same 256 queries in arrival order, fixed batches of 16, every batch run to its longest
+    response.  This is the denominator of the scheduled-over-vanilla ratio that bench.py reports."""
+    shape, W, om, gw = full7b
+    w = synth.make_workload(2)
+    assert w.pred_lens is None and w.flags == ()
+    pol = ss.make_policy((), w.base_batch, w.l_max, w.max_batch)
+    _say("7B whole group, config 2 (vanilla batching; about 20 s on the GPU)")
+    r = ss.ss_run_group(gw, w.prompt_tokens, w.prompt_offsets, w.target_lens, None, 0, pol)
+    ref = so.run_group(None, w.target_lens, 0, so.Policy(flags=(), base_batch=w.base_batch, l_max=w.l_max,
+                                                          max_batch=w.max_batch))
+    _check_group_against_scheduler_oracle(w, r, ref, shape.vocab, compact=False)
+    # the definition itself: 16 chunks of 16 in arrival order, each as long as its longest response
+    t = w.target_lens
+    assert r["stats"]["steps"] == sum(int(t[c:c + 16].max()) for c in range(0, w.n, 16))
+    assert r["stats"]["n_failed"] == 0 and r["stats"]["n_mb_failure"] == 0
+    short = sorted(range(w.n), key=lambda i: (int(w.prompt_lens[i]), i))
+    picks = [next(i for i in short if t[i] >= 16), next(i for i in short if t[i] >= 16 and i >= 128)]
+    for i in picks:
+        dcd, tot = check_tokens_teacher_forced(om, w.prompt(i), r["tokens"][i, :int(t[i])], upto=16, what=f"query {i}")
         _say(f"  query {i}: {dcd}/{tot} decided positions match")
 
 
@@ -127,7 +166,7 @@ def test_7b_whole_group_config4_as_benchmarked(full7b):
     in_big = next(i for i in big.idx if i not in failed and w.target_lens[i] >= 3)   # ran in the widest micro-batch
     redo = sorted(failed)[0]
     for i in (in_big, redo):
-        dcd, tot = check_tokens_teacher_forced(om, w.prompt(i), r["tokens"][i, :int(w.target_lens[i])], upto=4,
+        dcd, tot = check_tokens_teacher_forced(om, w.prompt(i), r["tokens"][i, :int(w.target_lens[i])], upto=16,
                                                what=f"query {i}")
         _say(f"  query {i}: {dcd}/{tot} decided positions match")
 
@@ -151,39 +190,71 @@ def test_13b_widths_logits_and_vbs_batch(wide13):
         check_tokens_teacher_forced(om, w.prompt(j), r["tokens"][j, :int(r["lens"][j])], what=f"row {j}")
 
 
-def test_13b_full_depth_config5_microbatch(oracle_built):
-    """Config 5 at its real size: LLaMA-13B shape, 40 layers.  Teacher-forced logits, then the first
-    micro-batch of its plan (the largest variable batch) generated with compaction; sampled rows re-derived
-    by the oracle."""
+@pytest.fixture(scope="module")
+def full13b(oracle_built):
     shape = synth.LLAMA13B
     _say("generating full-depth 13B weights (seed 5)")
     W = synth.make_weights(shape, seed=5, threads=16)
     gw = ss.Weights(shape, W)
-    om = OracleModel(shape, W, "f64")
+    yield shape, W, OracleModel(shape, W, "f64"), gw
+    gw.close()
+
+
+def test_13b_full_depth_config5_microbatch(full13b):
+    """Config 5 at its real size: LLaMA-13B shape, 40 layers.  Teacher-forced logits, then the first
+    micro-batch of its plan (the largest variable batch) generated with compaction; sampled rows re-derived
+    by the oracle over their first 16 tokens."""
+    shape, W, om, gw = full13b
+    w = synth.make_workload(5)
+    rng = np.random.default_rng(23)
+    toks, offs, npr = forced_batch(w, [2, 9], [3, 0], rng)
+    _say(f"13B x40 teacher-forced: prompts {npr.tolist()}")
+    got = ss.ss_forward_logits(gw, toks, offs, npr)
+    check_logits(got, oracle_forced_logits(om, toks, offs, npr), "13B full depth")
+    pol = ss.make_policy(w.flags, w.base_batch, w.l_max, w.max_batch)
+    plan = ss.ss_schedule(w.pred_lens, w.n, w.bin_width, pol)
+    idx, cap = plan[0]
+    ptoks, poffs = synth.gather_prompts(w, idx)
+    t = w.target_lens[idx]
+    _say(f"config 5 micro-batch 0: {len(idx)} rows, cap {cap}")
+    r = ss.ss_decode_microbatch(gw, ptoks, poffs, cap, t, ss.SS_COMPACT)
+    assert np.array_equal(r["lens"], np.minimum(t, cap))
+    assert np.array_equal(r["failed"].astype(bool), t > cap)
+    assert r["stats"]["row_steps"] == int(np.minimum(t, cap).sum())
+    plen = poffs[1:] - poffs[:-1]
+    long_rows = [j for j in np.argsort(plen, kind="stable") if r["lens"][j] >= 16][:4]   # shortest prompts: cheapest for the oracle
+    assert len(long_rows) == 4
+    for j in long_rows:
+        L = int(r["lens"][j])
+        dcd, tot = check_tokens_teacher_forced(om, w.prompt(idx[j]), r["tokens"][j, :L], upto=16, what=f"row {j}")
+        _say(f"  row {j} (prompt {plen[j]}): {dcd}/{tot} decided positions match")
+
+
+def test_13b_whole_group_config5_as_benchmarked(full13b):
+    """ss_run_group on the full config-5 group (LLaMA-13B shape, 1024 queries, bins of 64, variable batch size up
+    to 256 rows, compaction, recomputation pass), exactly what `bench.py --cfg 5` times."""
+    shape, W, om, gw = full13b
+    w = synth.make_workload(5)
+    pol = ss.make_policy(w.flags, w.base_batch, w.l_max, w.max_batch)
+    opol = so.Policy(flags=w.flags, base_batch=w.base_batch, l_max=w.l_max, max_batch=w.max_batch)
+    _say("13B whole group, config 5 (about 100 s on the GPU)")
+    ss.ss_set_verbose(1)
     try:
-        w = synth.make_workload(5)
-        rng = np.random.default_rng(23)
-        toks, offs, npr = forced_batch(w, [2, 9], [3, 0], rng)
-        _say(f"13B x40 teacher-forced: prompts {npr.tolist()}")
-        got = ss.ss_forward_logits(gw, toks, offs, npr)
-        check_logits(got, oracle_forced_logits(om, toks, offs, npr), "13B full depth")
-        pol = ss.make_policy(w.flags, w.base_batch, w.l_max, w.max_batch)
-        plan = ss.ss_schedule(w.pred_lens, w.n, w.bin_width, pol)
-        idx, cap = plan[0]
-        ptoks, poffs = synth.gather_prompts(w, idx)
-        t = w.target_lens[idx]
-        _say(f"config 5 micro-batch 0: {len(idx)} rows, cap {cap}")
-        r = ss.ss_decode_microbatch(gw, ptoks, poffs, cap, t, ss.SS_COMPACT)
-        assert np.array_equal(r["lens"], np.minimum(t, cap))
-        assert np.array_equal(r["failed"].astype(bool), t > cap)
-        assert r["stats"]["row_steps"] == int(np.minimum(t, cap).sum())
-        shortest = int(np.argmin(poffs[1:] - poffs[:-1]))
-        for j in (shortest,):
-            L = int(r["lens"][j])
-            dcd, tot = check_tokens_teacher_forced(om, w.prompt(idx[j]), r["tokens"][j, :L], upto=3, what=f"row {j}")
-            _say(f"  row {j}: {dcd}/{tot} decided positions match")
+        r = ss.ss_run_group(gw, w.prompt_tokens, w.prompt_offsets, w.target_lens, w.pred_lens, w.bin_width, pol)
     finally:
-        gw.close()
+        ss.ss_set_verbose(0)
+    ref = so.run_group(w.pred_lens, w.target_lens, w.bin_width, opol)
+    _check_group_against_scheduler_oracle(w, r, ref, shape.vocab, compact=True)
+    failed = set(ref["first"].failed)
+    big = max(ref["plan"], key=lambda mb: len(mb.idx))
+    _say(f"  largest micro-batch: {len(big.idx)} rows, cap {big.cap}; {len(failed)} queries recomputed")
+    by_prompt = lambda ids: sorted(ids, key=lambda i: (int(w.prompt_lens[i]), i))
+    in_big = next(i for i in by_prompt(big.idx) if i not in failed and w.target_lens[i] >= 8)
+    redo = next(i for i in by_prompt(failed) if w.target_lens[i] >= 16)
+    for i in (in_big, redo):
+        dcd, tot = check_tokens_teacher_forced(om, w.prompt(i), r["tokens"][i, :int(w.target_lens[i])], upto=16,
+                                               what=f"query {i}")
+        _say(f"  query {i}: {dcd}/{tot} decided positions match")
 
 
 @pytest.mark.parametrize("rows", [163, 81, 54])

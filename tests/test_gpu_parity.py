@@ -443,3 +443,35 @@ def test_invalid_generation_arguments(tiny):
         assert e.value.code == ss.SS_EINVAL
     r = ss.ss_decode_microbatch(gw, **good)       # the handle still works after rejected calls
     assert r["lens"].tolist() == [2, 3]
+
+
+def test_second_call_on_a_busy_handle_is_refused(tiny):
+    """One call at a time per handle: while a long call runs on one thread, a call on the same handle from
+    another thread returns SS_ESTATE at once, disturbs nothing, and the handle works afterwards."""
+    import threading
+    W, om, gw = tiny
+    w = synth.make_group(synth.TINY, 512, 4242, ("uniform", 8, 32), ("uniform", 24, 48), None, 48, 0, ())
+    pol = ss.make_policy((), 16, 48, 256)
+    started, result, refused = threading.Event(), {}, []
+
+    def long_call():
+        started.set()
+        result["r"] = ss.ss_run_group(gw, w.prompt_tokens, w.prompt_offsets, w.target_lens, None, 0, pol)
+
+    a = threading.Thread(target=long_call)
+    a.start()
+    started.wait()
+    while a.is_alive():
+        try:
+            ss.ss_decode_microbatch(gw, [1, 2, 3], [0, 3], 2, [2])
+        except ss.SsError as e:
+            assert e.code == ss.SS_ESTATE and "in flight" in str(e)
+            refused.append(e.code)
+    a.join()
+    assert refused, "the long call never overlapped a second one"
+    assert np.array_equal(result["r"]["lens"], w.target_lens)               # the long call was not disturbed
+    r = ss.ss_decode_microbatch(gw, [1, 2, 3], [0, 3], 2, [2])               # and the handle is free again
+    assert r["lens"].tolist() == [2]
+    for i in (0, 511):
+        check_tokens_teacher_forced(om, w.prompt(i), result["r"]["tokens"][i, :int(w.target_lens[i])], upto=8,
+                                    what=f"query {i} of the overlapped call")
