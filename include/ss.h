@@ -168,6 +168,25 @@ int ss_decode_microbatch(ss_weights* w, const int32_t* prompt_tokens, const int3
                          int32_t* out_lens, uint8_t* out_failed, ss_stats* stats, void* hip_stream);
 
 /*
+ * ss_decode_microbatch for callers that cannot allocate device memory (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc): same arguments, same results, but the whole device workspace
+ * (activations, partial sums, the micro-batch's key/value cache, bookkeeping tables) is laid out inside one
+ * static device array of SS_STATIC_SCRATCH_BYTES that the library holds on every GPU it is loaded on until
+ * the process ends.  The call allocates and frees no device memory and creates no stream or event.
+ *   - A call whose workspace does not fit returns SS_EINVAL with a message that gives the bytes needed and the
+ *     bytes available; nothing has run then.  Roughly: activations and partial sums for sum(prompt lengths)
+ *     token-rows plus n_layers * 2 * d_model * 2 bytes per key/value slot, sum(prompt length + max_new) slots.
+ *   - The array keeps the previous call's bytes; the call clears what must read as zero itself.
+ *   - Every static call on one GPU uses that GPU's one array: a second static call on the same GPU while one is
+ *     running (another handle, another thread) is refused with SS_ESTATE; calls that bypass that check race.
+ *   - ss_decode_microbatch and every other entry point are unaffected and may follow or precede it freely.
+ */
+#define SS_STATIC_SCRATCH_BYTES (64u << 20)
+int ss_decode_microbatch_static(ss_weights* w, const int32_t* prompt_tokens, const int32_t* prompt_offsets, int32_t B,
+                                int32_t max_new, const int32_t* target_lens, uint32_t flags, int32_t* out_tokens,
+                                int32_t* out_lens, uint8_t* out_failed, ss_stats* stats, void* hip_stream);
+
+/*
  * Teacher-forced logits (test / measurement entry point).  Each of the B rows is a token sequence
  * tokens[offsets[i] .. offsets[i+1]); the first n_prompt[i] tokens are processed in one prompt forward,
  * the remaining ones are fed one per decode step (all rows advance together, exactly as in

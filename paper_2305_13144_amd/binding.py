@@ -22,7 +22,7 @@ SS_BF16, SS_F32 = 0, 1
 FLAG_BITS = dict(SORT=SS_SORT, BIN=SS_BIN, FCR=SS_FCR, VBS=SS_VBS, COMPACT=SS_COMPACT)
 
 EXPORTS = ["ss_last_error", "ss_set_verbose", "ss_set_gemm_mode", "ss_schedule", "ss_schedule_failures", "ss_plan_free", "ss_weights_create",
-           "ss_weights_destroy", "ss_decode_microbatch", "ss_forward_logits", "ss_run_group", "ss_generate_microbatch",
+           "ss_weights_destroy", "ss_decode_microbatch", "ss_decode_microbatch_static", "ss_forward_logits", "ss_run_group", "ss_generate_microbatch",
            "ss_run_group_generate", "ss_bench_decode_step", "ss_bench_weight_stream", "ss_bench_read_stream"]
 
 
@@ -97,6 +97,7 @@ def lib():
         L.ss_weights_destroy.restype = None
         L.ss_decode_microbatch.argtypes = [vp, i32p, i32p, C.c_int32, C.c_int32, i32p, C.c_uint32, i32p, i32p, vp,
                                            C.POINTER(ss_stats), vp]
+        L.ss_decode_microbatch_static.argtypes = L.ss_decode_microbatch.argtypes
         L.ss_forward_logits.argtypes = [vp, i32p, i32p, C.c_int32, i32p, C.c_int32, vp, vp]
         L.ss_run_group.argtypes = [vp, i32p, i32p, C.c_int32, i32p, i32p, C.c_int32, C.POINTER(ss_policy), i32p, i32p,
                                    C.POINTER(ss_group_stats), vp]
@@ -199,16 +200,23 @@ class Weights:
 
 
 def ss_decode_microbatch(w: Weights, prompt_tokens, prompt_offsets, max_new: int, target_lens, flags: int = 0,
-                         stream: Optional[int] = None) -> dict:
+                         stream: Optional[int] = None, static: bool = False) -> dict:
+    """static=True calls ss_decode_microbatch_static (workspace in the library's static device array)."""
     pt, po, tl = _i32(prompt_tokens), _i32(prompt_offsets), _i32(target_lens)
     B = len(tl)
     toks = np.empty((B, max_new), np.int32)
     lens = np.empty(B, np.int32)
     failed = np.empty(B, np.uint8)
     st = ss_stats()
-    _check(lib().ss_decode_microbatch(w.h, _ptr(pt), _ptr(po), B, max_new, _ptr(tl), flags, _ptr(toks), _ptr(lens),
-                                      _ptr(failed), C.byref(st), stream))
+    fn = lib().ss_decode_microbatch_static if static else lib().ss_decode_microbatch
+    _check(fn(w.h, _ptr(pt), _ptr(po), B, max_new, _ptr(tl), flags, _ptr(toks), _ptr(lens), _ptr(failed), C.byref(st),
+              stream))
     return dict(tokens=toks, lens=lens, failed=failed, stats=_struct_dict(st))
+
+
+def ss_decode_microbatch_static(w: Weights, prompt_tokens, prompt_offsets, max_new: int, target_lens, flags: int = 0,
+                                stream: Optional[int] = None) -> dict:
+    return ss_decode_microbatch(w, prompt_tokens, prompt_offsets, max_new, target_lens, flags, stream, static=True)
 
 
 def ss_forward_logits(w: Weights, tokens, offsets, n_prompt, all_prompt_logits: bool = False,

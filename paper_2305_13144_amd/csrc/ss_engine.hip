@@ -9,6 +9,7 @@
 #include <cmath>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <numeric>
 #include <vector>
 
@@ -27,6 +28,37 @@ using ss::PackedMat;
             return ss::fail(e_ == hipErrorOutOfMemory ? SS_ENOMEM : SS_EDEVICE, "%s: %s", #expr, \
                             hipGetErrorString(e_));                                               \
     } while (0)
+
+// Workspace of ss_decode_microbatch_static: one array per GPU, held until the process ends.  In host code the
+// array's name is only a handle for hipGetSymbolAddress; the device address it returns (per device) is what the
+// kernels and fills get.
+constexpr size_t kStaticScratchBytes = (size_t)SS_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[kMaxDevices] = {};        // device address of `scratch` on each device, once looked up
+std::atomic<int> g_scratch_busy[kMaxDevices];  // 1 while a static call runs on that device
+
+// Device address of this device's copy of `scratch`; `device` must be the current device.
+int scratch_address(int device, void** out)
+{
+    if (device < 0 || device >= kMaxDevices) return ss::fail(SS_EDEVICE, "device ordinal %d not supported", device);
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[device]) {
+        void* ptr = nullptr;
+        hipError_t e = hipGetSymbolAddress((void**)&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !ptr)
+            return ss::fail(SS_EDEVICE, "hipGetSymbolAddress(scratch) on device %d: %s", device, hipGetErrorString(e));
+        g_scratch_ptr[device] = ptr;
+    }
+    *out = g_scratch_ptr[device];
+    return SS_OK;
+}
+
+}  // namespace
 
 namespace {
 
@@ -111,6 +143,7 @@ struct ss_weights {
     float cur_inv_temp = 0.f;
     int32_t* h_poll = nullptr;   // pinned host copy of the 4-int device header (d_n, d_step, d_nlive, d_active)
     hipEvent_t ev[3] = {nullptr, nullptr, nullptr};   // start, end of the prompt forward, end of a micro-batch
+    void* scratch_ptr = nullptr;   // device address of this device's static scratch array
 };
 
 namespace {
@@ -632,6 +665,7 @@ extern "C" int ss_weights_create(const ss_model_cfg* cfg, const void* const* ten
     };
     if (hipGetDevice(&w->device) != hipSuccess) return bail(ss::fail(SS_EDEVICE, "hipGetDevice failed"));
     if (hipStreamCreate(&w->stream) != hipSuccess) return bail(ss::fail(SS_EDEVICE, "hipStreamCreate failed"));
+    if (int rc_s = scratch_address(w->device, &w->scratch_ptr)) return bail(rc_s);
     if (hipHostMalloc((void**)&w->h_poll, 16, hipHostMallocDefault) != hipSuccess)
         return bail(ss::fail(SS_ENOMEM, "hipHostMalloc failed"));
     for (auto& e : w->ev)
@@ -727,6 +761,42 @@ extern "C" int ss_decode_microbatch(ss_weights* w, const int32_t* prompt_tokens,
     hipStream_t s = hip_stream ? (hipStream_t)hip_stream : w->stream;
     return decode_microbatch_impl(w, prompt_tokens, prompt_offsets, B, max_new, target_lens, nullptr, flags, out_tokens,
                                   out_lens, out_failed, stats, s);
+}
+
+extern "C" int ss_decode_microbatch_static(ss_weights* w, const int32_t* prompt_tokens, const int32_t* prompt_offsets,
+                                           int32_t B, int32_t max_new, const int32_t* target_lens, uint32_t flags,
+                                           int32_t* out_tokens, int32_t* out_lens, uint8_t* out_failed,
+                                           ss_stats* stats, void* hip_stream)
+{
+    ss::clear_error();
+    if (!w) return ss::fail(SS_EINVAL, "weights handle is NULL");
+    BusyGuard guard(w);
+    if (!guard.ok) return ss::fail(SS_ESTATE, "another call is in flight on this handle");
+    if (!w->scratch_ptr) return ss::fail(SS_ESTATE, "the static scratch array was not located on this device");
+    // every static call on a GPU shares that GPU's array: overlapping calls (other handles) are refused
+    struct ScratchGuard {
+        std::atomic<int>& f;
+        bool ok;
+        explicit ScratchGuard(std::atomic<int>& f_) : f(f_), ok(f_.exchange(1) == 0) {}
+        ~ScratchGuard()
+        {
+            if (ok) f.store(0);
+        }
+    } sg(g_scratch_busy[w->device]);
+    if (!sg.ok) return ss::fail(SS_ESTATE, "another static call is using this GPU's scratch array");
+    hipStream_t s = hip_stream ? (hipStream_t)hip_stream : w->stream;
+    // The handle's own (allocated, growable) workspace steps aside for the call; every buffer is a view into the
+    // scratch array instead.  decode_microbatch_impl allocates nothing else on the device: its events belong to
+    // the handle, its host staging lives on the host heap.
+    Workspace view;
+    view.arena = (char*)w->scratch_ptr;
+    view.arena_bytes = kStaticScratchBytes;
+    std::swap(w->ws, view);
+    const int rc = decode_microbatch_impl(w, prompt_tokens, prompt_offsets, B, max_new, target_lens, nullptr, flags,
+                                          out_tokens, out_lens, out_failed, stats, s);
+    std::swap(w->ws, view);
+    w->st = MbState{};   // pointed into the scratch array; the next call lays its own state out
+    return rc;
 }
 
 extern "C" int ss_generate_microbatch(ss_weights* w, const int32_t* prompt_tokens, const int32_t* prompt_offsets,
