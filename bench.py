@@ -26,6 +26,9 @@ PAPER_CONTEXT = ("paper, Table 4: 1.22 -> 2.27 samples/s (+86%) on one A100-80GB
                  "10k alpaca-subset prompts, group 256; other hardware and data: context, not a target")
 
 
+T_START = time.time()
+
+
 def log(msg: str) -> None:
     print(f"[bench] {msg}", file=sys.stderr, flush=True)
 
@@ -35,6 +38,27 @@ def decode_step_bytes(shape, B: int, ctx: int) -> int:
     read once, one new key/value slot and one embedding row per live row."""
     kv = shape.kv_bytes_per_token()
     return shape.weight_bytes_per_step() + B * (ctx + 1) * kv + B * kv + B * shape.d_model * 2
+
+
+TRAFFIC_PROFILE = os.path.join("profiles", "decode_step_7b_hbm_traffic.txt")
+
+
+def profile_traffic(shape_name: str, rows: int, ctx: int, gemm_mode: int):
+    """HBM bytes per decode step from the committed rocprofv3 counter summary (FETCH_SIZE + WRITE_SIZE runs of
+    `bench.py --roofline-only`); a figure from that file, not a live one: (None, reason) when the file is absent
+    or was taken at another shape."""
+    path = os.path.join(ROOT, TRAFFIC_PROFILE)
+    if not os.path.exists(path):
+        return None, f"{TRAFFIC_PROFILE} absent"
+    kv = {}
+    for line in open(path):
+        if line.startswith("@") and "=" in line:
+            k, v = line[1:].split("=", 1)
+            kv[k.strip()] = v.strip()
+    want = dict(shape=shape_name, rows=str(rows), ctx=str(ctx), gemm_mode=str(gemm_mode))
+    if any(kv.get(k) != v for k, v in want.items()) or "decode_step_hbm_bytes" not in kv:
+        return None, f"{TRAFFIC_PROFILE} was taken at another shape or launch configuration"
+    return float(kv["decode_step_hbm_bytes"]), f"{TRAFFIC_PROFILE} (rocprofv3 counters of an earlier run, not live)"
 
 
 def ablation(a, ss, gw, wl, shape) -> int:
@@ -203,6 +227,10 @@ def main() -> int:
                          "(the paper's Fig. 3a / 3b on the synthetic workload), ('sync') the group run with ends "
                          "that the host must poll for, against the poll period, greedy and sampled at T=0.5, or ('step') "
                          "the time of one decode forward against live rows and against context length (App. D)")
+    ap.add_argument("--no-cfg4", action="store_true", help="skip the configuration-4 leg of the default run")
+    ap.add_argument("--cfg4-full-before-s", type=float, default=400.0,
+                    help="the configuration-4 leg runs its whole group of 1024 when it starts within this many seconds of "
+                         "the program's start, else the first 512 queries")
     ap.add_argument("--no-generate", action="store_true",
                     help="skip the leg that reruns the group with sampled tokens and ends discovered by polling")
     ap.add_argument("--roofline-only", action="store_true",
@@ -242,7 +270,7 @@ def main() -> int:
 
     # ---- timed region: W warmup passes, then exactly K passes over the group ----------------------
     if a.roofline_only:
-        a.warmup, a.steps, a.no_vanilla, a.no_cpu = 0, 0, True, True
+        a.warmup, a.steps, a.no_vanilla, a.no_cpu, a.no_cfg4 = 0, 0, True, True, True
     for i in range(a.warmup):
         r = run(pol, wl.pred_lens, wl.bin_width)
         log(f"warmup {i}: {r['stats']['wall_ms']:.0f} ms")
@@ -272,6 +300,14 @@ def main() -> int:
     if not a.no_vanilla:
         rv = run(vpol, None, 0)
         sv = rv["stats"]
+        # vanilla batching by its definition: chunks of base_batch in arrival order, each run to its longest response,
+        # every row computed at every step, nothing capped, every query emitted once and in full
+        t_ = wl.target_lens
+        v_steps = sum(int(t_[c:c + wl.base_batch].max()) for c in range(0, wl.n, wl.base_batch))
+        v_padded = sum(int(t_[c:c + wl.base_batch].max()) * len(t_[c:c + wl.base_batch]) for c in range(0, wl.n, wl.base_batch))
+        assert np.array_equal(rv["lens"], t_) and sv["n_failed"] == 0 and sv["n_mb_failure"] == 0
+        assert sv["steps"] == v_steps and sv["padded_row_steps"] == v_padded == sv["computed_row_steps"]
+        assert all((rv["tokens"][i, :t_[i]] >= 0).all() and (rv["tokens"][i, t_[i]:] == -1).all() for i in range(wl.n))
         extras["vanilla_batching"] = dict(
             workload=f"same group, arrival order, batch {wl.base_batch}, no cap (config 2 policy)",
             useful_tokens_per_s=useful / (sv["wall_ms"] / 1e3), ms=sv["wall_ms"], steps=sv["steps"],
@@ -314,37 +350,70 @@ def main() -> int:
             ms=t_p, useful_tokens_per_s_including_it=useful / ((st["wall_ms"] + t_p) / 1e3))
         log(f"simulated perception overhead: {t_p:.0f} ms on top of {st['wall_ms']:.0f} ms")
 
-    # ---- roofline: the weight-streaming projection kernel, timed live with HIP events --------------
+    if not a.roofline_only and a.cfg == 3 and not a.no_cfg4 and a.layers <= 0:
+        # The case the method gains most on this hardware, beside the headline's fixed batch of 16: configuration 4
+        # (same weights, group 1024, variable batch size up to 256 rows, compaction) against vanilla batching on
+        # its own group.  When the run has already taken long (many timed passes), the first 512 queries of that
+        # group stand in for it; the JSON says which.
+        w4 = synth.make_workload(4)
+        n4 = w4.n if (time.time() - T_START) < a.cfg4_full_before_s else 512
+        idx4 = list(range(n4))
+        tk4, of4 = synth.gather_prompts(w4, idx4)
+        t4, p4 = w4.target_lens[idx4], w4.pred_lens[idx4]
+        pol4 = ss.make_policy(w4.flags, w4.base_batch, w4.l_max, w4.max_batch)
+        ss.ss_set_verbose(0)
+        r4 = ss.ss_run_group(gw, tk4, of4, t4, p4, w4.bin_width, pol4)
+        v4 = ss.ss_run_group(gw, tk4, of4, t4, None, 0, ss.make_policy((), w4.base_batch, w4.l_max, w4.max_batch))
+        assert np.array_equal(r4["lens"], t4) and np.array_equal(v4["lens"], t4)
+        u4 = int(t4.sum())
+        s4, sv4 = r4["stats"], v4["stats"]
+        extras["config4"] = dict(
+            workload=f"config 4: {shape.name}, group {n4}" + ("" if n4 == w4.n else f" (first {n4} of {w4.n} queries)")
+                     + f", policy {'+'.join(w4.flags)} bin {w4.bin_width}, batch {w4.base_batch}..{w4.max_batch}",
+            useful_tokens_per_s=u4 / (s4["wall_ms"] / 1e3), ms=s4["wall_ms"], steps=s4["steps"], n_failed=s4["n_failed"],
+            micro_batches=[s4["n_mb_first"], s4["n_mb_failure"]], computed_row_steps=s4["computed_row_steps"],
+            vanilla_useful_tokens_per_s=u4 / (sv4["wall_ms"] / 1e3), vanilla_ms=sv4["wall_ms"], vanilla_steps=sv4["steps"],
+            scheduled_over_vanilla=sv4["wall_ms"] / s4["wall_ms"])
+        log(f"config 4 (group {n4}): {s4['wall_ms']:.0f} ms scheduled, {sv4['wall_ms']:.0f} ms vanilla -> "
+            f"{extras['config4']['scheduled_over_vanilla']:.2f}x")
+
+    # ---- roofline: one whole decode step, timed live with HIP events; its projection launches and a plain read
+    # ---- stream over the same matrices as sub-entries -------------------------------------------------------------
     B0, ctx = a.step_rows, a.step_ctx
     ms_w, launches = ss.ss_bench_weight_stream(gw, B0, a.step_iters + 3)
     log("weight stream iterations (ms): " + " ".join(f"{x:.2f}" for x in ms_w))
     ms_w = ms_w[3:]
     wbytes = shape.weight_bytes_per_step() - (2 * shape.n_layers + 1) * shape.d_model * 2   # matrices only
-    ach = wbytes / (ms_w.mean() * 1e-3) / 1e9
-    # HBM bytes per launch from the FETCH_SIZE + WRITE_SIZE counter runs of this same command (7B shape only;
-    # the figures and the copy-kernel scale factors are in profiles/decode_step_7b_hbm_traffic.txt)
-    traffic = (13610.4e6 + 175.6e6) / 129 if shape.name == "llama7b" and a.gemm_mode == 0 and B0 == 16 else None
-    roofline = dict(bound="hbm", kernel=f"k_gemm_sweep + k_gemm_skinny (all projection launches of one {B0}-row decode step)",
-                    achieved=ach, peak=HBM_PEAK_GBS, unit="GB/s", frac=ach / HBM_PEAK_GBS, traffic=traffic,
-                    launches_per_step=launches, avg_launch_us=ms_w.mean() * 1e3 / launches,
-                    bytes_per_launch=wbytes / launches)
+    ach_w = wbytes / (ms_w.mean() * 1e-3) / 1e9
     # the ceiling for those launches: the same matrices read by a plain stream kernel, launch by launch
     ms_r, rbytes = ss.ss_bench_read_stream(gw, a.step_iters + 3)
     ms_r = ms_r[3:]
-    roofline["plain_read_stream"] = dict(
-        what="one plain non-temporal read kernel per weight matrix, same bytes and launch sizes, nothing computed",
-        ms=float(ms_r.mean()), achieved=rbytes / (ms_r.mean() * 1e-3) / 1e9, unit="GB/s",
-        projections_over_stream=float(ms_r.mean() / ms_w.mean()) * wbytes / rbytes)
-    log(f"plain read stream over the same matrices: {ms_r.mean():.3f} ms/iter -> {roofline['plain_read_stream']['achieved']:.0f} GB/s")
     rng = np.random.default_rng(7)
     ptoks = rng.integers(0, shape.vocab, size=B0 * ctx).astype(np.int32)
     ms_s = ss.ss_bench_decode_step(gw, ptoks, B0, ctx, a.step_iters + 3)[3:]
     sbytes = decode_step_bytes(shape, B0, ctx)
+    ach = sbytes / (ms_s.mean() * 1e-3) / 1e9
+    step_launches = launches + 3 * shape.n_layers + 3     # + attention and two norms per layer, embedding, final norm, token choice
+    traffic, traffic_source = profile_traffic(shape.name, B0, ctx, a.gemm_mode)
+    roofline = dict(bound="hbm",
+                    kernel=f"one whole decode step of {B0} rows at context {ctx}: all {step_launches} launches (projections, "
+                           f"decode attention, RMSNorm, embedding, token choice)",
+                    achieved=ach, peak=HBM_PEAK_GBS, unit="GB/s", frac=ach / HBM_PEAK_GBS, traffic=traffic,
+                    traffic_source=traffic_source, ms=float(ms_s.mean()), ms_min=float(ms_s.min()),
+                    algorithmic_bytes=sbytes, launches_per_step=step_launches,
+                    projection_launches=dict(
+                        what="the projection kernels of that step alone (k_gemm_sweep + k_gemm_skinny), back to back",
+                        ms=float(ms_w.mean()), achieved=ach_w, unit="GB/s", frac=ach_w / HBM_PEAK_GBS, launches=launches,
+                        avg_launch_us=ms_w.mean() * 1e3 / launches, bytes_per_launch=wbytes / launches),
+                    plain_read_stream=dict(
+                        what="one plain non-temporal read kernel per weight matrix, same bytes and launch sizes, nothing computed",
+                        ms=float(ms_r.mean()), achieved=rbytes / (ms_r.mean() * 1e-3) / 1e9, unit="GB/s",
+                        projections_over_stream=float(ms_r.mean() / ms_w.mean()) * wbytes / rbytes))
     extras["decode_step"] = dict(rows=B0, ctx=ctx, ms=float(ms_s.mean()), ms_min=float(ms_s.min()),
-                                 algorithmic_bytes=sbytes, achieved_GBs=sbytes / (ms_s.mean() * 1e-3) / 1e9,
-                                 frac_of_hbm_peak=sbytes / (ms_s.mean() * 1e-3) / 1e9 / HBM_PEAK_GBS)
-    log(f"weight stream: {ms_w.mean():.3f} ms/iter -> {ach:.0f} GB/s; decode step B={B0} ctx={ctx}: "
-        f"{ms_s.mean():.3f} ms -> {extras['decode_step']['achieved_GBs']:.0f} GB/s")
+                                 algorithmic_bytes=sbytes, achieved_GBs=ach, frac_of_hbm_peak=ach / HBM_PEAK_GBS)
+    log(f"plain read stream over the same matrices: {ms_r.mean():.3f} ms/iter -> {roofline['plain_read_stream']['achieved']:.0f} GB/s")
+    log(f"weight stream: {ms_w.mean():.3f} ms/iter -> {ach_w:.0f} GB/s; decode step B={B0} ctx={ctx}: "
+        f"{ms_s.mean():.3f} ms -> {ach:.0f} GB/s = {ach / HBM_PEAK_GBS:.3f} of peak")
     if a.roofline_only:
         # calibration for the HBM byte counters: a plain device-to-device copy of known size (1 GiB read,
         # 1 GiB written) shows up in the same trace as a copyBuffer dispatch.  It runs after the timed legs:
