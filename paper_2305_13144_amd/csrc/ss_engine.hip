@@ -144,6 +144,7 @@ struct ss_weights {
     int32_t* h_poll = nullptr;   // pinned host copy of the 4-int device header (d_n, d_step, d_nlive, d_active)
     hipEvent_t ev[3] = {nullptr, nullptr, nullptr};   // start, end of the prompt forward, end of a micro-batch
     void* scratch_ptr = nullptr;   // device address of this device's static scratch array
+    int prompt_rows = 0, prompt_max_len = 0;   // shape of the prompt forward whose state was uploaded last
 };
 
 namespace {
@@ -230,7 +231,7 @@ int ensure_workspace(ss_weights* w, int n_max, int B, int n_sel, size_t slots, i
     Workspace& ws = w->ws;
     const size_t nr = (size_t)ss::round_up(n_max, 128);
     const size_t Bp = ss::round_up(B, 4), np = ss::round_up(n_max, 4), sp = ss::round_up(n_sel, 4);
-    const size_t n_i32 = 4 + 3 * np + 4 * Bp + 2 * sp + (size_t)B * max_new;
+    const size_t n_i32 = 4 + 3 * np + 5 * Bp + 2 * sp + (size_t)B * max_new;
     w->kv_layer_stride = slots * d;
     // Partial-sum buffers hold [ksplit][rows][N] for whatever plan a forward over 1..n_max rows gets.
     // gate|up partial sums exist only when that projection runs with k-slices (never in the sweep kernel).
@@ -274,7 +275,7 @@ int ensure_workspace(ss_weights* w, int n_max, int B, int n_sel, size_t slots, i
         for (const Item& it : items)
             if (int rc = it.b->ensure(it.bytes, it.zero)) return rc;
     }
-    // int32 arena: d_n d_step d_nlive d_active | tr_tok tr_row tr_pos [n_max] | live_row plen limit cap [B] | am sel [n_sel] | out_tok
+    // int32 arena: d_n d_step d_nlive d_active | tr_tok tr_row tr_pos [n_max] | live_row plen j0 limit cap [B] | am sel [n_sel] | out_tok
     int32_t* q = ws.ints.as<int32_t>();
     MbState& st = w->st;
     st.d_n = q; st.d_step = q + 1; st.d_nlive = q + 2; st.d_active = q + 3; q += 4;
@@ -283,6 +284,7 @@ int ensure_workspace(ss_weights* w, int n_max, int B, int n_sel, size_t slots, i
     st.tr_pos = q; q += np;
     st.live_row = q; q += Bp;
     st.row_plen = q; q += Bp;
+    st.row_j0 = q; q += Bp;
     st.row_limit = q; q += Bp;
     st.row_cap = q; q += Bp;
     st.am = q; q += sp;
@@ -362,7 +364,7 @@ void forward(ss_weights* w, int n, int n_sel, const int32_t* d_sel, const int32_
                                         s);
         } else {        // prompt: every key of a row must be in place before any of its queries attends
             ss::launch_rope_append(st, pqkv, ks_qkv, st_qkv, qrot, kc, vc, w->rope_cos, w->rope_sin, d, H, hd, n, s);
-            ss::launch_attention(st, qrot, kc, vc, ao, ao_lo, d, H, hd, n, s);
+            ss::launch_attention_prompt(st, qrot, kc, vc, ao, ao_lo, d, H, hd, w->prompt_rows, w->prompt_max_len, s);
         }
         ss::launch_gemm(mk(L.wo.p, ao, ao_lo, pd, nullptr, nullptr, d, d, n, 0, p_o), ss::EPI_PARTIAL, s);
         ss::launch_rmsnorm(st, x, pd, ks_o, st_d, L.mlp_norm, c.rms_eps, nullptr, nullptr, h, h_lo, d, n, s);
@@ -419,11 +421,12 @@ int upload_prompt_state(ss_weights* w, const int32_t* toks, const int32_t* offs,
     const MbState& st = w->st;
     int n = 0;
     for (int i = 0; i < B; ++i) n += lens[i];
-    std::vector<int32_t> tok(n), row(n), pos(n), live(B), plen(B);
+    std::vector<int32_t> tok(n), row(n), pos(n), live(B), plen(B), first(B);
     std::vector<int64_t> so(B);
     int at = 0;
     int64_t slot = 0;
     for (int i = 0; i < B; ++i) {
+        first[i] = at;
         for (int t = 0; t < lens[i]; ++t, ++at) {
             tok[at] = toks[offs[i] + t];
             row[at] = i;
@@ -441,6 +444,9 @@ int upload_prompt_state(ss_weights* w, const int32_t* toks, const int32_t* offs,
     HIPCHK(hipMemcpyAsync(st.tr_pos, pos.data(), (size_t)n * 4, hipMemcpyHostToDevice, s));
     HIPCHK(hipMemcpyAsync(st.live_row, live.data(), (size_t)B * 4, hipMemcpyHostToDevice, s));
     HIPCHK(hipMemcpyAsync(st.row_plen, plen.data(), (size_t)B * 4, hipMemcpyHostToDevice, s));
+    HIPCHK(hipMemcpyAsync(st.row_j0, first.data(), (size_t)B * 4, hipMemcpyHostToDevice, s));
+    w->prompt_rows = B;
+    w->prompt_max_len = *std::max_element(plen.begin(), plen.end());
     HIPCHK(hipMemcpyAsync(st.row_limit, limit, (size_t)B * 4, hipMemcpyHostToDevice, s));
     HIPCHK(hipMemcpyAsync(st.row_cap, slab, (size_t)B * 4, hipMemcpyHostToDevice, s));
     HIPCHK(hipMemcpyAsync(st.row_so, so.data(), (size_t)B * 8, hipMemcpyHostToDevice, s));

@@ -30,6 +30,7 @@ struct MbState {
     int32_t* d_nlive;    // [1]
     int32_t* d_active;   // [1] rows that still owe tokens after the last bookkeeping step
     int32_t* row_plen;   // [B] prompt length
+    int32_t* row_j0;     // [B] first token-row of the row in a prompt forward
     int32_t* row_limit;  // [B] min(target, cap): tokens the row emits; lowered by the device when the row emits its end id
     int64_t* row_so;     // [B] first key/value slot of the row's slab
     int32_t* row_cap;    // [B] slots in the row's slab (prompt + cap)
@@ -69,8 +70,11 @@ void launch_swiglu_reduce(const float* part, int ksplit, size_t part_stride, int
 void launch_rope_append(const MbState& st, const float* qkv_part, int ksplit, size_t part_stride, float* qrot,
                         bf16_t* kcache, bf16_t* vcache, const float* rope_cos, const float* rope_sin, int d, int H,
                         int hd, int n_max, hipStream_t s);
-void launch_attention(const MbState& st, const float* qrot, const bf16_t* kcache, const bf16_t* vcache,
-                      bf16_t* out_packed, bf16_t* out_packed_lo, int d, int H, int hd, int n_max, hipStream_t s);
+// Causal attention of a prompt forward: B rows, row i holding st.row_plen[i] token-rows that start at token-row
+// st.row_j0[i]; max_len = the longest row (sizes the grid).
+void launch_attention_prompt(const MbState& st, const float* qrot, const bf16_t* kcache, const bf16_t* vcache,
+                             bf16_t* out_packed, bf16_t* out_packed_lo, int d, int H, int hd, int B, int max_len,
+                             hipStream_t s);
 void launch_attention_decode(const MbState& st, const float* qkv_part, int ksplit, size_t part_stride,
                              bf16_t* kcache, bf16_t* vcache, const float* rope_cos, const float* rope_sin,
                              bf16_t* out_packed, bf16_t* out_packed_lo, int d, int H, int hd, int n_max, hipStream_t s);

@@ -887,22 +887,163 @@ __device__ __forceinline__ void attend(const float* __restrict__ qs, float* __re
 }
 
 // Prompt forwards: q was rotated and K, V appended for every token-row by k_rope_append before this runs.
+// Causal attention of one (row, head, tile of 64 queries) per workgroup; each of its 4 waves owns 16 queries.
+// The row's keys and values are visited in tiles of 32 slots that are staged once in LDS for all 64 queries
+// (K as stored, V transposed), the next tile's global loads in flight while the current one is used.
+// Both contractions run on the matrix cores in half precision, the cache's own format:
+//   S^T = K Q^T   A = K tile (16 keys x 32 head elements), B = Q^T; q is carried as the sum of two halves
+//                 (hi + lo), so the scores see q to ~22 bits like the decode kernel's fp32 dot product;
+//                 D: lane holds, for query lane%16, keys 4*(lane/16)..+3 of a 16-key tile.
+//   O^T = V^T P^T two score tiles (32 keys) form one B operand as they lie in the registers: contraction slot
+//                 8*(lane/16) + j is key 4*(lane/16) + j of the first tile for j < 4, of the second for j >= 4;
+//                 the A operand reads V^T in the same slot order (two 8-byte LDS reads);
+//                 D: lane holds, for query lane%16, output elements 16t + 4*(lane/16)..+3.
+// So a query's running maximum, sum and rescale factor stay in its own lanes: fp32 online softmax with no
+// transposition of the probabilities.  Slots above a query's position are masked before the exponential.
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
+
 template <int HD>
-__global__ __launch_bounds__(256) void k_attention(MbState st, const float* __restrict__ qrot,
-                                                   const bf16_t* __restrict__ kc, const bf16_t* __restrict__ vc,
-                                                   bf16_t* __restrict__ out, bf16_t* __restrict__ out_lo, int d)
+__global__ __launch_bounds__(256) void k_attention_prompt(MbState st, const float* __restrict__ qrot,
+                                                          const bf16_t* __restrict__ kc, const bf16_t* __restrict__ vc,
+                                                          bf16_t* __restrict__ out, bf16_t* __restrict__ out_lo, int d)
 {
-    __shared__ float sc[kMaxPos];
-    __shared__ float red[8];
-    __shared__ float oacc[4][HD];
-    __shared__ float qs[HD];
-    const int j = blockIdx.x, h = blockIdx.y;
-    if (j >= *st.d_n) return;
-    const int row = st.tr_row[j], ctx = st.tr_pos[j] + 1;
+    constexpr int KS = HD / 32;          // steps of the score contraction
+    constexpr int ET = HD / 16;          // 16-element tiles of the output
+    constexpr int OCT = HD / 8;          // 16-byte pieces per key
+    constexpr int KROW = HD + 8;         // halves per staged key row (16 bytes of padding: conflict-free operand reads)
+    constexpr int VROW = 32 + 4;         // halves per row of the transposed value tile (8 bytes of padding)
+    constexpr int PIECES = 32 * OCT;     // 16-byte pieces of a tile
+    constexpr int PPT = PIECES / 256;    // pieces per thread
+    static_assert(PIECES % 256 == 0, "tile pieces per thread");
+    __shared__ __attribute__((aligned(16))) _Float16 k_lds[32 * KROW];
+    __shared__ __attribute__((aligned(16))) _Float16 v_lds[HD * VROW];
+    const int qt = blockIdx.x, h = blockIdx.y, row = blockIdx.z;
+    const int p = st.row_plen[row];      // tokens of this row in the forward: positions 0..p-1
+    const int q0 = qt * 64;
+    if (q0 >= p) return;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int ql = lane & 15, g = lane >> 4;
+    const int j0 = st.row_j0[row];
     const size_t base = (size_t)st.row_so[row] * d + (size_t)h * st.row_cap[row] * HD;
-    if (threadIdx.x < HD) qs[threadIdx.x] = qrot[(size_t)j * d + h * HD + threadIdx.x];
-    __syncthreads();
-    attend<HD, 4>(qs, sc, red, oacc, kc + base, vc + base, ctx, out, out_lo, j, h * HD, d);
+    const u32x4* Kg = (const u32x4*)(kc + base);
+    const u32x4* Vg = (const u32x4*)(vc + base);
+    const int qpos = min(q0 + wave * 16 + ql, p - 1);   // queries past the row's end repeat its last one (never stored)
+    const bool q_valid = q0 + wave * 16 + ql < p;
+    const int wave_last = min(q0 + wave * 16 + 15, p - 1);
+    const int n_keys = min(p, q0 + 64);
+    const int n_tiles = (n_keys + 31) >> 5;
+    const float scale = rsqrtf((float)HD);
+
+    // this lane's query: head elements 32*ks + 8*g .. +7 for every step, split into two halves
+    f16x8 qh[KS], qlo[KS];
+    {
+        const float* qp = qrot + (size_t)(j0 + qpos) * d + h * HD + 8 * g;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            const float4 a = *(const float4*)(qp + 32 * ks), b = *(const float4*)(qp + 32 * ks + 4);
+            const float v[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const _Float16 hi = (_Float16)v[e];
+                qh[ks][e] = hi;
+                qlo[ks][e] = (_Float16)(v[e] - (float)hi);
+            }
+        }
+    }
+    f32x4 o[ET];
+#pragma unroll
+    for (int t = 0; t < ET; ++t) o[t] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    float m_run = -3.0e38f, l_run = 0.f;
+
+    u32x4 kreg[PPT], vreg[PPT];
+    const u32x4 zero4 = {0u, 0u, 0u, 0u};
+    auto load_tile = [&](int t) {
+#pragma unroll
+        for (int i = 0; i < PPT; ++i) {
+            const int c = tid + i * 256;
+            const int key = t * 32 + c / OCT, oct = c % OCT;
+            const bool live = key < n_keys;
+            const size_t at = (size_t)min(key, n_keys - 1) * OCT + oct;
+            const u32x4 kv = Kg[at], vv = Vg[at];
+            kreg[i] = live ? kv : zero4;
+            vreg[i] = live ? vv : zero4;
+        }
+    };
+    load_tile(0);
+    for (int t = 0; t < n_tiles; ++t) {
+        // stage tile t: K rows as stored, V transposed
+#pragma unroll
+        for (int i = 0; i < PPT; ++i) {
+            const int c = tid + i * 256;
+            const int key = c / OCT, oct = c % OCT;
+            *(u32x4*)&k_lds[key * KROW + oct * 8] = kreg[i];
+            const f16x8 vv = __builtin_bit_cast(f16x8, vreg[i]);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v_lds[(oct * 8 + e) * VROW + key] = vv[e];
+        }
+        __syncthreads();
+        if (t + 1 < n_tiles) load_tile(t + 1);
+        const int k0 = t * 32;
+        if (k0 <= wave_last) {   // wave-uniform: tiles wholly above this wave's queries are skipped
+            f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                const f16x8 a0 = *(const f16x8*)&k_lds[ql * KROW + ks * 32 + 8 * g];
+                const f16x8 a1 = *(const f16x8*)&k_lds[(16 + ql) * KROW + ks * 32 + 8 * g];
+                s0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(a0, qlo[ks], s0, 0, 0, 0);
+                s0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(a0, qh[ks], s0, 0, 0, 0);
+                s1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(a1, qlo[ks], s1, 0, 0, 0);
+                s1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(a1, qh[ks], s1, 0, 0, 0);
+            }
+            float sc[8];
+            float mt = -3.0e38f;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                sc[i] = (k0 + 4 * g + i <= qpos) ? s0[i] * scale : -3.0e38f;
+                sc[4 + i] = (k0 + 16 + 4 * g + i <= qpos) ? s1[i] * scale : -3.0e38f;
+            }
+#pragma unroll
+            for (int i = 0; i < 8; ++i) mt = fmaxf(mt, sc[i]);
+            mt = fmaxf(mt, __shfl_xor(mt, 16, 64));
+            mt = fmaxf(mt, __shfl_xor(mt, 32, 64));
+            const float m_new = fmaxf(m_run, mt);
+            const float alpha = __expf(m_run - m_new);
+            float ps = 0.f;
+            f16x8 pb;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const float pv = sc[i] > -1.0e38f ? __expf(sc[i] - m_new) : 0.f;
+                ps += pv;
+                pb[i] = (_Float16)pv;
+            }
+            ps += __shfl_xor(ps, 16, 64);
+            ps += __shfl_xor(ps, 32, 64);
+            l_run = l_run * alpha + ps;
+            m_run = m_new;
+#pragma unroll
+            for (int tt = 0; tt < ET; ++tt) {
+                const _Float16* vr = &v_lds[(tt * 16 + ql) * VROW];
+                const f16x4 lo4 = *(const f16x4*)(vr + 4 * g), hi4 = *(const f16x4*)(vr + 16 + 4 * g);
+                const f16x8 av = {lo4[0], lo4[1], lo4[2], lo4[3], hi4[0], hi4[1], hi4[2], hi4[3]};
+                o[tt] *= alpha;
+                o[tt] = __builtin_amdgcn_mfma_f32_16x16x32_f16(av, pb, o[tt], 0, 0, 0);
+            }
+        }
+        __syncthreads();   // the tile is rewritten next trip
+    }
+    if (!q_valid) return;
+    const float inv = 1.f / l_run;
+    const int j = j0 + qpos;
+#pragma unroll
+    for (int tt = 0; tt < ET; ++tt) {
+        bf16_t r[4], rl[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) split_bf(o[tt][e] * inv, r[e], rl[e]);
+        const size_t at = pk_index(j, h * HD + tt * 16 + 4 * g, d);
+        *(uint2*)(out + at) = *(const uint2*)r;
+        *(uint2*)(out_lo + at) = *(const uint2*)rl;
+    }
 }
 
 // Decode forwards: the (token-row, head) workgroup first finishes its own slice of the q|k|v projection
@@ -1363,14 +1504,16 @@ void launch_attention_decode(const MbState& st, const float* qkv_part, int kspli
 #undef SS_ATTN_ARGS
 }
 
-void launch_attention(const MbState& st, const float* qrot, const bf16_t* kcache, const bf16_t* vcache,
-                      bf16_t* out_packed, bf16_t* out_packed_lo, int d, int H, int hd, int n_max, hipStream_t s)
+void launch_attention_prompt(const MbState& st, const float* qrot, const bf16_t* kcache, const bf16_t* vcache,
+                             bf16_t* out_packed, bf16_t* out_packed_lo, int d, int H, int hd, int B, int max_len,
+                             hipStream_t s)
 {
+    const dim3 grid((max_len + 63) / 64, H, B);
     if (hd == 128)
-        hipLaunchKernelGGL((k_attention<128>), dim3(n_max, H), dim3(256), 0, s, st, qrot, kcache, vcache, out_packed,
+        hipLaunchKernelGGL((k_attention_prompt<128>), grid, dim3(256), 0, s, st, qrot, kcache, vcache, out_packed,
                            out_packed_lo, d);
     else
-        hipLaunchKernelGGL((k_attention<64>), dim3(n_max, H), dim3(256), 0, s, st, qrot, kcache, vcache, out_packed,
+        hipLaunchKernelGGL((k_attention_prompt<64>), grid, dim3(256), 0, s, st, qrot, kcache, vcache, out_packed,
                            out_packed_lo, d);
 }
 
