@@ -128,6 +128,27 @@ typedef struct ss_weights ss_weights; /* opaque; owns packed bf16 weights and a 
 int  ss_weights_create(const ss_model_cfg* cfg, const void* const* tensors, int32_t src_dtype, ss_weights** out);
 void ss_weights_destroy(ss_weights* w);
 
+/*
+ * Per-handle precision switch of the prompt forward ("instruction processing", Sec. 4.1, Overhead of Length
+ * Prediction: it should cost no more than a few generated tokens).  An activation that feeds a projection is
+ * carried as hi + lo (two bf16 values); in prompt forwards of more than 128 token-rows, where the projections are
+ * bound by the matrix cores, a projection whose bit is clear in the mask contracts the hi part only (half the
+ * matrix-core work, bf16 precision of that activation).  Decode forwards always use both parts.
+ *   option SS_OPT_PROMPT_LO_MASK, value = OR of SS_LO_* bits of the projections that keep the lo part
+ *   (SS_LO_ALL: every projection; the default SS_PROMPT_LO_DEFAULT is the cheapest set whose teacher-forced logit
+ *   error stayed below 1e-2 of max|logit| at full depth, a third of the parity bar).
+ * Errors: SS_EINVAL (NULL handle, unknown option, value outside the mask), SS_ESTATE (a call is in flight).
+ */
+#define SS_OPT_PROMPT_LO_MASK 1
+#define SS_LO_QKV 1
+#define SS_LO_O 2
+#define SS_LO_GATE_UP 4
+#define SS_LO_DOWN 8
+#define SS_LO_LM_HEAD 16
+#define SS_LO_ALL 31
+#define SS_PROMPT_LO_DEFAULT SS_LO_ALL
+int ss_set_option(ss_weights* w, int32_t option, int32_t value);
+
 /* ------------------------------------------------------------------ generation */
 
 typedef struct {

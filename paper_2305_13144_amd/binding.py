@@ -18,11 +18,13 @@ LIB_PATH = os.path.join(_HERE, "libss.so")
 SS_OK, SS_EINVAL, SS_ENOMEM, SS_EDEVICE, SS_ESTATE = 0, -1, -2, -3, -4
 SS_SORT, SS_BIN, SS_FCR, SS_VBS, SS_COMPACT = 1, 2, 4, 8, 16
 SS_VBS_CLAMP_FLOOR, SS_VBS_PAPER_POW2 = 0, 1
+SS_OPT_PROMPT_LO_MASK = 1
+SS_LO_QKV, SS_LO_O, SS_LO_GATE_UP, SS_LO_DOWN, SS_LO_LM_HEAD, SS_LO_ALL = 1, 2, 4, 8, 16, 31
 SS_BF16, SS_F32 = 0, 1
 FLAG_BITS = dict(SORT=SS_SORT, BIN=SS_BIN, FCR=SS_FCR, VBS=SS_VBS, COMPACT=SS_COMPACT)
 
 EXPORTS = ["ss_last_error", "ss_set_verbose", "ss_set_gemm_mode", "ss_schedule", "ss_schedule_failures", "ss_plan_free", "ss_weights_create",
-           "ss_weights_destroy", "ss_decode_microbatch", "ss_decode_microbatch_static", "ss_forward_logits", "ss_run_group", "ss_generate_microbatch",
+           "ss_weights_destroy", "ss_set_option", "ss_decode_microbatch", "ss_decode_microbatch_static", "ss_forward_logits", "ss_run_group", "ss_generate_microbatch",
            "ss_run_group_generate", "ss_bench_decode_step", "ss_bench_weight_stream", "ss_bench_read_stream"]
 
 
@@ -93,6 +95,7 @@ def lib():
         L.ss_plan_free.argtypes = [C.POINTER(ss_plan)]
         L.ss_plan_free.restype = None
         L.ss_weights_create.argtypes = [C.POINTER(ss_model_cfg), C.POINTER(vp), C.c_int32, C.POINTER(vp)]
+        L.ss_set_option.argtypes = [vp, C.c_int32, C.c_int32]
         L.ss_weights_destroy.argtypes = [vp]
         L.ss_weights_destroy.restype = None
         L.ss_decode_microbatch.argtypes = [vp, i32p, i32p, C.c_int32, C.c_int32, i32p, C.c_uint32, i32p, i32p, vp,
@@ -186,6 +189,9 @@ class Weights:
         self.h = h
         self.shape = shape
         self._keep = None   # the library copied everything
+
+    def set_option(self, option: int, value: int) -> None:
+        _check(lib().ss_set_option(self.h, option, value))
 
     def close(self) -> None:
         if getattr(self, "h", None):

@@ -145,6 +145,7 @@ struct ss_weights {
     hipEvent_t ev[3] = {nullptr, nullptr, nullptr};   // start, end of the prompt forward, end of a micro-batch
     void* scratch_ptr = nullptr;   // device address of this device's static scratch array
     int prompt_rows = 0, prompt_max_len = 0;   // shape of the prompt forward whose state was uploaded last
+    int prompt_lo_mask = SS_PROMPT_LO_DEFAULT;  // projections whose activations keep their lo part in prompt forwards
 };
 
 namespace {
@@ -352,13 +353,18 @@ void forward(ss_weights* w, int n, int n_sel, const int32_t* d_sel, const int32_
         return gemm_args(w, W, X, Xlo, out, outp, outp_lo, N, Kp, rows, kp_out, p);
     };
 
+    // prompt forwards: which projections run without the activations' lo part in the tiled kernel
+    auto no_lo = [&](int bit) { return (!decode && !(w->prompt_lo_mask & bit)) ? 1 : 0; };
+    auto with_lo = [](GemmArgs g, int no) { g.tiled_no_lo = no; return g; };
+
     ss::launch_embed(st, w->embed, x, d, n, s);
     for (int l = 0; l < c.n_layers; ++l) {
         const Layer& L = w->layers[l];
         bf16_t* kc = ws.kv.as<bf16_t>() + (size_t)l * 2 * w->kv_layer_stride;
         bf16_t* vc = kc + w->kv_layer_stride;
         ss::launch_rmsnorm(st, x, l ? pd : nullptr, ks_d, st_d, L.attn_norm, c.rms_eps, nullptr, nullptr, h, h_lo, d, n, s);
-        ss::launch_gemm(mk(L.wqkv.p, h, h_lo, pqkv, nullptr, nullptr, 3 * d, d, n, 0, p_qkv), ss::EPI_PARTIAL, s);
+        ss::launch_gemm(with_lo(mk(L.wqkv.p, h, h_lo, pqkv, nullptr, nullptr, 3 * d, d, n, 0, p_qkv), no_lo(SS_LO_QKV)),
+                        ss::EPI_PARTIAL, s);
         if (decode) {   // one token-row per row: rotation and append are fused into the attention kernel
             ss::launch_attention_decode(st, pqkv, ks_qkv, st_qkv, kc, vc, w->rope_cos, w->rope_sin, ao, ao_lo, d, H, hd, n,
                                         s);
@@ -366,20 +372,23 @@ void forward(ss_weights* w, int n, int n_sel, const int32_t* d_sel, const int32_
             ss::launch_rope_append(st, pqkv, ks_qkv, st_qkv, qrot, kc, vc, w->rope_cos, w->rope_sin, d, H, hd, n, s);
             ss::launch_attention_prompt(st, qrot, kc, vc, ao, ao_lo, d, H, hd, w->prompt_rows, w->prompt_max_len, s);
         }
-        ss::launch_gemm(mk(L.wo.p, ao, ao_lo, pd, nullptr, nullptr, d, d, n, 0, p_o), ss::EPI_PARTIAL, s);
+        ss::launch_gemm(with_lo(mk(L.wo.p, ao, ao_lo, pd, nullptr, nullptr, d, d, n, 0, p_o), no_lo(SS_LO_O)), ss::EPI_PARTIAL, s);
         ss::launch_rmsnorm(st, x, pd, ks_o, st_d, L.mlp_norm, c.rms_eps, nullptr, nullptr, h, h_lo, d, n, s);
         if (p_gu.ksplit == 1) {
-            ss::launch_gemm(mk(L.wgu.p, h, h_lo, nullptr, act, act_lo, 2 * F, d, n, Fp, p_gu), ss::EPI_SWIGLU, s);
+            ss::launch_gemm(with_lo(mk(L.wgu.p, h, h_lo, nullptr, act, act_lo, 2 * F, d, n, Fp, p_gu), no_lo(SS_LO_GATE_UP)),
+                            ss::EPI_SWIGLU, s);
         } else {   // k-sliced: partial sums, then one small kernel adds them and applies SwiGLU
-            ss::launch_gemm(mk(L.wgu.p, h, h_lo, ws.pgu.as<float>(), nullptr, nullptr, 2 * F, d, n, 0, p_gu),
+            ss::launch_gemm(with_lo(mk(L.wgu.p, h, h_lo, ws.pgu.as<float>(), nullptr, nullptr, 2 * F, d, n, 0, p_gu),
+                                    no_lo(SS_LO_GATE_UP)),
                             ss::EPI_PARTIAL, s);
             ss::launch_swiglu_reduce(ws.pgu.as<float>(), p_gu.ksplit, (size_t)n * 2 * F, n, F, Fp, act, act_lo, s);
         }
-        ss::launch_gemm(mk(L.wd.p, act, act_lo, pd, nullptr, nullptr, d, Fp, n, 0, p_d), ss::EPI_PARTIAL, s);
+        ss::launch_gemm(with_lo(mk(L.wd.p, act, act_lo, pd, nullptr, nullptr, d, Fp, n, 0, p_d), no_lo(SS_LO_DOWN)), ss::EPI_PARTIAL, s);
     }
     bf16_t *hsel = ws.hsel.as<bf16_t>(), *hsel_lo = ws.hsel_lo.as<bf16_t>();
     ss::launch_rmsnorm(st, x, pd, ks_d, st_d, w->final_norm, c.rms_eps, d_sel, d_nsel, hsel, hsel_lo, d, n_sel, s);
-    ss::launch_gemm(mk(w->lm_head.p, hsel, hsel_lo, ws.logits.as<float>(), nullptr, nullptr, V, d, n_sel, 0, p_lm),
+    ss::launch_gemm(with_lo(mk(w->lm_head.p, hsel, hsel_lo, ws.logits.as<float>(), nullptr, nullptr, V, d, n_sel, 0, p_lm),
+                            no_lo(SS_LO_LM_HEAD)),
                     ss::EPI_PARTIAL, s);
     if (w->cur_inv_temp > 0.f)
         ss::launch_sample(ws.logits.as<float>(), V, d_nsel ? d_nsel : st.d_n, st, w->cur_draws, w->cur_ids, w->cur_seed,
@@ -734,6 +743,20 @@ extern "C" int ss_weights_create(const ss_model_cfg* cfg, const void* const* ten
     staging.release();
     *out = w;
     return SS_OK;
+}
+
+extern "C" int ss_set_option(ss_weights* w, int32_t option, int32_t value)
+{
+    ss::clear_error();
+    if (!w) return ss::fail(SS_EINVAL, "weights handle is NULL");
+    BusyGuard guard(w);
+    if (!guard.ok) return ss::fail(SS_ESTATE, "another call is in flight on this handle");
+    if (option == SS_OPT_PROMPT_LO_MASK) {
+        if (value < 0 || value > SS_LO_ALL) return ss::fail(SS_EINVAL, "SS_OPT_PROMPT_LO_MASK takes a mask of SS_LO_* bits");
+        w->prompt_lo_mask = value;
+        return SS_OK;
+    }
+    return ss::fail(SS_EINVAL, "unknown option %d", option);
 }
 
 extern "C" void ss_set_gemm_mode(int32_t mode)

@@ -55,6 +55,7 @@ struct GemmArgs {
     int sweep_p;         // > 0: sweep kernel with this many waves per workgroup (gemm_plan)
     int sweep_gn;        //      its workgroups per k-slice
     const bf16_t* zero_blk;  // 1 KiB of zeros: operand block read in place of weights beyond a range (sweep kernel)
+    int tiled_no_lo;         // nonzero: the tiled kernel leaves the activations' lo part out (ignored by the other kernels)
 };
 
 void launch_pack_weight(const void* src, int src_f32, bf16_t* dst, int n_src, int k, int kp, int blk_stride,

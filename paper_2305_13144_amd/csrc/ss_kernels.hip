@@ -559,15 +559,18 @@ __global__ __launch_bounds__(64 * P) void k_gemm_sweep(GemmArgs a, int n_units, 
 // own LDS stages) and the second group hands its accumulators to the first through LDS at the end.  Used
 // when there are too few tiles to give every CU two workgroups: it doubles the waves per CU and halves
 // the serial k loop without sending partial sums through HBM.
-template <int TMS, int KP, int EPI>
+// LO = false: the activations' lo part is left out (one product per operand pair instead of two): half the
+// matrix-core work and half the staged bytes, at bf16 precision of the activations.
+template <int TMS, int KP, int EPI, bool LO>
 __global__ __launch_bounds__(256 * KP, 2) void k_gemm_tiled(GemmArgs a, int kb_per_slice, int n_ntiles, int n_mtiles)
 {
     constexpr int D = 4;                        // k-blocks in flight
-    constexpr int XV = TMS * 2 * 64 / 256;      // 16-byte vectors per thread: one k-block of the activation tile, hi + lo
-    __shared__ u32x4 lds_all[KP][2][TMS * 2 * 64];            // [k-part][stage][row strip][hi, lo][lane]
+    constexpr int NP = LO ? 2 : 1;              // activation parts: hi, lo
+    constexpr int XV = TMS * NP * 64 / 256;     // 16-byte vectors per thread: one k-block of the activation tile
+    __shared__ u32x4 lds_all[KP][2][TMS * NP * 64];           // [k-part][stage][row strip][hi, lo][lane]
     __shared__ f32x4 red[KP > 1 ? 4 * TMS : 1][KP > 1 ? 256 : 1];
     const int part = threadIdx.x >> 8, tid = threadIdx.x & 255, lane = tid & 63, wave = tid >> 6;
-    u32x4 (*lds)[TMS * 2 * 64] = lds_all[part];
+    u32x4 (*lds)[TMS * NP * 64] = lds_all[part];
     const int KB = a.Kp >> 5, NBT = a.N >> 4;
     const int MBT = (a.m_rows + 15) >> 4;
     const int per_slice = ((n_ntiles + 7) >> 3) * 8 * n_mtiles;
@@ -600,7 +603,7 @@ __global__ __launch_bounds__(256 * KP, 2) void k_gemm_tiled(GemmArgs a, int kb_p
 #define SS_XLOAD(X_, KB_)                                                                       \
     _Pragma("unroll") for (int i_ = 0; i_ < XV; ++i_) {                                         \
         const int c_ = tid + i_ * 256;                                                          \
-        const int ln_ = c_ & 63, hl_ = (c_ >> 6) & 1, ms_ = c_ >> 7;                            \
+        const int ln_ = c_ & 63, hl_ = LO ? (c_ >> 6) & 1 : 0, ms_ = LO ? c_ >> 7 : c_ >> 6;    \
         X_[i_] = (hl_ ? Xl : Xh)[((size_t)min(mb0 + ms_, MBT - 1) * KB + (KB_)) * 64 + ln_];    \
     }
 #define SS_XSTORE(STAGE_, X_, LIVE_)                                                            \
@@ -611,13 +614,13 @@ __global__ __launch_bounds__(256 * KP, 2) void k_gemm_tiled(GemmArgs a, int kb_p
            order, so each MFMA group waits only for its own pair): LDS latency overlaps MFMAs */ \
         u32x4 xh_[TMS], xl_[TMS];                                                               \
         _Pragma("unroll") for (int m_ = 0; m_ < TMS; ++m_) {                                    \
-            xl_[m_] = lds[STAGE_][(m_ * 2 + 1) * 64 + lane];                                    \
-            xh_[m_] = lds[STAGE_][(m_ * 2 + 0) * 64 + lane];                                    \
+            if (LO) xl_[m_] = lds[STAGE_][(m_ * 2 + 1) * 64 + lane];                            \
+            xh_[m_] = lds[STAGE_][(m_ * NP + 0) * 64 + lane];                                   \
         }                                                                                       \
         __builtin_amdgcn_sched_barrier(0x16);   /* only VALU, SALU and global loads may cross */ \
         _Pragma("unroll") for (int m_ = 0; m_ < TMS; ++m_) {                                    \
             _Pragma("unroll") for (int i_ = 0; i_ < 4; ++i_) {                                  \
-                acc[i_][m_] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(                          \
+                if (LO) acc[i_][m_] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(                  \
                     __builtin_bit_cast(bf16x8, W_[i_]), __builtin_bit_cast(bf16x8, xl_[m_]), acc[i_][m_], 0, 0, 0); \
                 acc[i_][m_] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(                          \
                     __builtin_bit_cast(bf16x8, W_[i_]), __builtin_bit_cast(bf16x8, xh_[m_]), acc[i_][m_], 0, 0, 0); \
@@ -1455,10 +1458,14 @@ static void launch_gemm_epi(const GemmArgs& a, hipStream_t s)
     constexpr int TMS = 4;
     const int n_ntiles = (a.N + 255) / 256, n_mtiles = (a.m_rows + TMS * 16 - 1) / (TMS * 16);
     const int grid = (n_ntiles + 7) / 8 * 8 * n_mtiles * a.ksplit;
-    if (a.kp == 2)
-        hipLaunchKernelGGL((k_gemm_tiled<TMS, 2, EPI>), dim3(grid), dim3(512), 0, s, a, kbs, n_ntiles, n_mtiles);
-    else
-        hipLaunchKernelGGL((k_gemm_tiled<TMS, 1, EPI>), dim3(grid), dim3(256), 0, s, a, kbs, n_ntiles, n_mtiles);
+    const bool lo = a.X_lo != nullptr && !a.tiled_no_lo;
+    if (a.kp == 2) {
+        if (lo) hipLaunchKernelGGL((k_gemm_tiled<TMS, 2, EPI, true>), dim3(grid), dim3(512), 0, s, a, kbs, n_ntiles, n_mtiles);
+        else hipLaunchKernelGGL((k_gemm_tiled<TMS, 2, EPI, false>), dim3(grid), dim3(512), 0, s, a, kbs, n_ntiles, n_mtiles);
+    } else {
+        if (lo) hipLaunchKernelGGL((k_gemm_tiled<TMS, 1, EPI, true>), dim3(grid), dim3(256), 0, s, a, kbs, n_ntiles, n_mtiles);
+        else hipLaunchKernelGGL((k_gemm_tiled<TMS, 1, EPI, false>), dim3(grid), dim3(256), 0, s, a, kbs, n_ntiles, n_mtiles);
+    }
 }
 
 void launch_gemm(const GemmArgs& a, int epilogue, hipStream_t s)

@@ -445,6 +445,35 @@ def test_invalid_generation_arguments(tiny):
     assert r["lens"].tolist() == [2, 3]
 
 
+def test_prompt_forward_lo_mask_option(wide2):
+    """The per-handle precision switch of the prompt forward: dropping the lo part of the activations that feed
+    projections (here: every projection) moves the logits by far more than rounding order yet stays inside the
+    bar at this depth; the default (every lo part kept) is restored and reproduces the first result bit for bit;
+    bad arguments are refused."""
+    shape, W, om, gw = wide2
+    rng = np.random.default_rng(77)
+    w = synth.make_group(shape, 8, 4711, ("uniform", 20, 40), ("uniform", 1, 4), None, 4, 0, ())
+    toks, offs, npr = forced_batch(w, range(8), [2] * 8, rng)          # > 128 prompt token-rows: the tiled kernel
+    assert int(npr.sum()) > 128
+    full = ss.ss_forward_logits(gw, toks, offs, npr)
+    try:
+        gw.set_option(ss.SS_OPT_PROMPT_LO_MASK, 0)
+        hi_only = ss.ss_forward_logits(gw, toks, offs, npr)
+    finally:
+        gw.set_option(ss.SS_OPT_PROMPT_LO_MASK, ss.SS_LO_ALL)
+    again = ss.ss_forward_logits(gw, toks, offs, npr)
+    assert np.array_equal(full, again)
+    ref = oracle_forced_logits(om, toks[offs[0]:offs[2]], offs[:3] - offs[0], npr[:2])
+    n_out = int((np.diff(offs)[:2] - npr[:2] + 1).sum())
+    e_full = check_logits(full[:n_out], ref, "every lo part kept")
+    e_hi = check_logits(hi_only[:n_out], ref, "no lo part in the prompt forward")
+    assert e_hi > 2 * e_full
+    for opt, val in ((ss.SS_OPT_PROMPT_LO_MASK, 32), (ss.SS_OPT_PROMPT_LO_MASK, -1), (99, 0)):
+        with pytest.raises(ss.SsError) as e:
+            gw.set_option(opt, val)
+        assert e.value.code == ss.SS_EINVAL
+
+
 def test_second_call_on_a_busy_handle_is_refused(tiny):
     """One call at a time per handle: while a long call runs on one thread, a call on the same handle from
     another thread returns SS_ESTATE at once, disturbs nothing, and the handle works afterwards."""
