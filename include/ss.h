@@ -36,7 +36,9 @@ void ss_set_verbose(int32_t level);
 /* Testing aid: which kernel runs the projections of small batches.  0 (default): chosen per shape and row
  * count; 1: never the kernel that stages activations once per workgroup (then: the k-splitting kernel up to 64
  * token-rows, the tiled kernel above); 2: that kernel for every projection of at most 128 token-rows.
- * Results agree to fp32 rounding order.  Process-wide (one atomic integer, read when a forward is planned: set it
+ * Adding 4 to a mode (4, 5, 6) keeps that kernel from sharing a strip's k-blocks between two wavefronts (what it
+ * does from 17 token-rows on when a workgroup has few strips); for A/B measurements.
+ * Results agree to fp32 rounding order.  Process-wide (atomic integers, read when a forward is planned: set it
  * between calls, not during one); other values are ignored. */
 void ss_set_gemm_mode(int32_t mode);
 

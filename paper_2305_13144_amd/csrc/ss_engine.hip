@@ -320,7 +320,7 @@ GemmArgs gemm_args(const ss_weights* w, const bf16_t* W, const bf16_t* X, const 
     GemmArgs g{};
     g.W = W; g.X = X; g.X_lo = Xlo; g.out = out; g.out_packed = outp; g.out_packed_lo = outp_lo; g.N = N; g.Kp = Kp;
     g.m_rows = rows; g.m_stride = rows; g.kp_out = kp_out; g.ksplit = p.ksplit; g.nb = p.nb; g.kd = p.kd;
-    g.kp = p.kp; g.sweep_p = p.sweep_p; g.sweep_gn = p.sweep_gn; g.zero_blk = w->zero_blk;
+    g.kp = p.kp; g.sweep_p = p.sweep_p; g.sweep_gn = p.sweep_gn; g.sweep_kh = p.sweep_kh; g.zero_blk = w->zero_blk;
     return g;
 }
 
@@ -761,7 +761,7 @@ extern "C" int ss_set_option(ss_weights* w, int32_t option, int32_t value)
 
 extern "C" void ss_set_gemm_mode(int32_t mode)
 {
-    if (mode >= 0 && mode <= 2) ss::set_gemm_mode(mode);
+    if (mode >= 0 && mode <= 6 && (mode & 3) != 3) ss::set_gemm_mode(mode);
 }
 
 extern "C" void ss_weights_destroy(ss_weights* w)

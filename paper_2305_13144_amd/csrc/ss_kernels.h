@@ -54,6 +54,7 @@ struct GemmArgs {
     int kp;              // tiled kernel: k-parts inside the workgroup (gemm_plan)
     int sweep_p;         // > 0: sweep kernel with this many waves per workgroup (gemm_plan)
     int sweep_gn;        //      its workgroups per k-slice
+    int sweep_kh;        //      2: two waves per unit, each half of every chunk's k-blocks (gemm_plan)
     const bf16_t* zero_blk;  // 1 KiB of zeros: operand block read in place of weights beyond a range (sweep kernel)
     int tiled_no_lo;         // nonzero: the tiled kernel leaves the activations' lo part out (ignored by the other kernels)
 };

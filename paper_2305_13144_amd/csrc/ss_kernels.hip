@@ -354,17 +354,22 @@ __global__ __launch_bounds__(256) void k_gemm_skinny(GemmArgs a, int n_groups, i
 // gate strip and its up strip.  Weight loads run two chunks ahead in two named register slots; nothing in
 // the loop is conditional, so the load counter waits are exact.  K-blocks beyond the k-slice and strips
 // beyond the matrix read a block of zeros instead of weights (an L2 hit) and add 0.
-template <int NBW, int KC>
+// With KH = 2 two waves share a unit: wave 2u takes the first half of every chunk's k-blocks, wave 2u + 1 the second
+// (each loads only its own weight blocks and reads only its own operands from LDS); the odd wave hands its
+// accumulators to the even one through LDS at the end.  Used from 17 rows on when a workgroup owns at most 4 units:
+// there the matrix-core and LDS work per weight byte grows with the row strips, and 3 or 4 waves (one per SIMD,
+// nothing to overlap their waits with) no longer keep up with the weight stream.
+template <int NBW, int KQ>
 struct SweepSlot {
-    u32x4 w[NBW][KC];
+    u32x4 w[NBW][KQ];   // KQ = k-blocks of a chunk this wave handles
 };
 
-template <int NBW, int KC>
-__device__ __forceinline__ void sweep_load_w(SweepSlot<NBW, KC>& f, const u32x4* __restrict__ Wl,
+template <int NBW, int KQ>
+__device__ __forceinline__ void sweep_load_w(SweepSlot<NBW, KQ>& f, const u32x4* __restrict__ Wl,
                                              const u32x4* __restrict__ Zl, int KB, int nb0, int nvalid, int kb, int kend)
 {
 #pragma unroll
-    for (int q = 0; q < KC; ++q) {
+    for (int q = 0; q < KQ; ++q) {
         const bool live = kb + q < kend;
         const int kk = min(kb + q, kend - 1);
 #pragma unroll
@@ -410,16 +415,18 @@ __device__ __forceinline__ void sweep_store_x(const SweepStage<P, MT, KC>& xs, u
         buf[min((int)threadIdx.x + i * 64 * P, SweepStage<P, MT, KC>::PIECES - 1)] = xs.v[i];
 }
 
-template <int MT, int NBW, int KC>
-__device__ __forceinline__ void sweep_mma(const SweepSlot<NBW, KC>& f, const u32x4* buf, int lane, f32x4 (&acc)[NBW][MT])
+// q0: first k-block of the chunk this wave handles (0, or KC/2 for the second wave of a pair).
+template <int MT, int NBW, int KC, int KQ>
+__device__ __forceinline__ void sweep_mma(const SweepSlot<NBW, KQ>& f, const u32x4* buf, int lane, int q0,
+                                          f32x4 (&acc)[NBW][MT])
 {
 #pragma unroll
-    for (int q = 0; q < KC; ++q) {
+    for (int q = 0; q < KQ; ++q) {
         u32x4 xh[MT], xl[MT];
 #pragma unroll
         for (int m = 0; m < MT; ++m) {
-            xh[m] = buf[((m * 2 + 0) * KC + q) * 64 + lane];
-            xl[m] = buf[((m * 2 + 1) * KC + q) * 64 + lane];
+            xh[m] = buf[((m * 2 + 0) * KC + q0 + q) * 64 + lane];
+            xl[m] = buf[((m * 2 + 1) * KC + q0 + q) * 64 + lane];
         }
 #pragma unroll
         for (int m = 0; m < MT; ++m)
@@ -438,21 +445,22 @@ __device__ __forceinline__ void sweep_mma(const SweepSlot<NBW, KC>& f, const u32
 // block, would take their share of the compute unit's memory requests.  The two variants are separate
 // straight-line loops, chosen once per wave, because a load under a branch inside the loop would make
 // every wait there cover all loads in flight.
-template <bool ACTIVE, int P, int MT, int NBW, int KC>
+template <bool ACTIVE, int P, int MT, int NBW, int KC, int KH>
 __device__ __forceinline__ void sweep_run(u32x4* xl0, u32x4* xl1, f32x4 (&acc)[NBW][MT],
                                           const u32x4* __restrict__ Wl, const u32x4* __restrict__ Zl,
                                           const u32x4* __restrict__ X, const u32x4* __restrict__ Xlo, int KB, int nb0,
-                                          int nvalid, int s0, int s1, int C, int lane)
+                                          int nvalid, int s0, int s1, int C, int lane, int q0)
 {
-    SweepSlot<NBW, KC> fa, fb;
+    constexpr int KQ = KC / KH;
+    SweepSlot<NBW, KQ> fa, fb;
     SweepStage<P, MT, KC> xs;
     sweep_load_x<P, MT, KC>(xs, X, Xlo, KB, s0, s1);
-    if (ACTIVE) sweep_load_w<NBW, KC>(fa, Wl, Zl, KB, nb0, nvalid, s0, s1);
+    if (ACTIVE) sweep_load_w<NBW, KQ>(fa, Wl, Zl, KB, nb0, nvalid, s0 + q0, s1);
     __builtin_amdgcn_sched_barrier(0);
     sweep_store_x<P, MT, KC>(xs, xl0);
     __builtin_amdgcn_sched_barrier(0);
     sweep_load_x<P, MT, KC>(xs, X, Xlo, KB, s0 + KC, s1);
-    if (ACTIVE) sweep_load_w<NBW, KC>(fb, Wl, Zl, KB, nb0, nvalid, s0 + KC, s1);
+    if (ACTIVE) sweep_load_w<NBW, KQ>(fb, Wl, Zl, KB, nb0, nvalid, s0 + KC + q0, s1);
     __builtin_amdgcn_sched_barrier(0);
     __syncthreads();
     // Two chunks per trip (slot fa with LDS buffer 0, slot fb with buffer 1).  Within a chunk: contract it,
@@ -460,38 +468,44 @@ __device__ __forceinline__ void sweep_run(u32x4* xl0, u32x4* xl1, f32x4 (&acc)[N
     // the chunk after that, barrier.  A buffer is rewritten one barrier after its last read.
     for (int c = 0; c < C; c += 2) {
         const int k2 = s0 + (c + 2) * KC, k3 = k2 + KC;
-        if (ACTIVE) sweep_mma<MT, NBW, KC>(fa, xl0, lane, acc);
+        if (ACTIVE) sweep_mma<MT, NBW, KC, KQ>(fa, xl0, lane, q0, acc);
         __builtin_amdgcn_sched_barrier(0);
         sweep_store_x<P, MT, KC>(xs, xl1);
         __builtin_amdgcn_sched_barrier(0);
         sweep_load_x<P, MT, KC>(xs, X, Xlo, KB, k2, s1);
-        if (ACTIVE) sweep_load_w<NBW, KC>(fa, Wl, Zl, KB, nb0, nvalid, k2, s1);
+        if (ACTIVE) sweep_load_w<NBW, KQ>(fa, Wl, Zl, KB, nb0, nvalid, k2 + q0, s1);
         __builtin_amdgcn_sched_barrier(0);
         __syncthreads();
-        if (ACTIVE) sweep_mma<MT, NBW, KC>(fb, xl1, lane, acc);
+        if (ACTIVE) sweep_mma<MT, NBW, KC, KQ>(fb, xl1, lane, q0, acc);
         __builtin_amdgcn_sched_barrier(0);
         sweep_store_x<P, MT, KC>(xs, xl0);
         __builtin_amdgcn_sched_barrier(0);
         sweep_load_x<P, MT, KC>(xs, X, Xlo, KB, k3, s1);
-        if (ACTIVE) sweep_load_w<NBW, KC>(fb, Wl, Zl, KB, nb0, nvalid, k3, s1);
+        if (ACTIVE) sweep_load_w<NBW, KQ>(fb, Wl, Zl, KB, nb0, nvalid, k3 + q0, s1);
         __builtin_amdgcn_sched_barrier(0);
         __syncthreads();
     }
 }
 
 // Grid: n_gn workgroups per k-slice x ksplit; workgroup gn of a slice owns units [gn*n_units/n_gn,
-// (gn+1)*n_units/n_gn) (a unit = NBW consecutive strips; at most P of them, checked by the launcher), one per wave.
-template <int P, int MT, int NBW, int EPI>
+// (gn+1)*n_units/n_gn) (a unit = NBW consecutive strips; at most P/KH of them, checked by the launcher), one per
+// wave, or with KH = 2 one per pair of waves.
+template <int P, int MT, int NBW, int EPI, int KH>
 __global__ __launch_bounds__(64 * P) void k_gemm_sweep(GemmArgs a, int n_units, int n_gn, int kb_per_slice)
 {
     constexpr int KC = MT > 4 ? 2 : 4;   // k-blocks per chunk: both LDS buffers together stay within 64 KiB
+    static_assert(KC % KH == 0, "a chunk's k-blocks split evenly between the waves of a unit");
     __shared__ u32x4 xlds[2][SweepStage<P, MT, KC>::PIECES];
+    static_assert(KH == 1 || (P / 2) * NBW * MT * 64 <= 2 * SweepStage<P, MT, KC>::PIECES,
+                  "the accumulators of the odd waves fit the staging buffers");
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int gn = blockIdx.x % n_gn, ks = blockIdx.x / n_gn;
     const int KB = a.Kp >> 5, NBT = a.N >> 4;
     const int s0 = ks * kb_per_slice, s1 = min(KB, s0 + kb_per_slice);
     const int u0 = (int)((long long)gn * n_units / n_gn), u1 = (int)((long long)(gn + 1) * n_units / n_gn);
-    const int unit = u0 + wave;
+    const int slot = wave / KH;                   // unit slot of this wave inside the workgroup
+    const int q0 = (wave % KH) * (KC / KH);       // first k-block of every chunk this wave handles
+    const int unit = u0 + slot;
     const int nb0 = unit * NBW;
     const int nvalid = unit < u1 ? max(min(NBW, NBT - nb0), 0) : 0;
     const bool active = nvalid > 0;   // wave-uniform
@@ -509,9 +523,28 @@ __global__ __launch_bounds__(64 * P) void k_gemm_sweep(GemmArgs a, int n_units, 
     const int C = (s1 - s0 + KC - 1) / KC;   // chunks of this slice: the same for every wave of the workgroup
     if (C > 0) {
         if (active)
-            sweep_run<true, P, MT, NBW, KC>(xlds[0], xlds[1], acc, Wl, Zl, X, Xlo, KB, nb0, nvalid, s0, s1, C, lane);
+            sweep_run<true, P, MT, NBW, KC, KH>(xlds[0], xlds[1], acc, Wl, Zl, X, Xlo, KB, nb0, nvalid, s0, s1, C, lane, q0);
         else
-            sweep_run<false, P, MT, NBW, KC>(xlds[0], xlds[1], acc, Wl, Zl, X, Xlo, KB, nb0, nvalid, s0, s1, C, lane);
+            sweep_run<false, P, MT, NBW, KC, KH>(xlds[0], xlds[1], acc, Wl, Zl, X, Xlo, KB, nb0, nvalid, s0, s1, C, lane, q0);
+    }
+    if (KH == 2) {
+        // the odd wave of a pair hands its sums to the even one (the staging buffers are free after the last barrier
+        // of the sweep; with no chunk at all nobody has touched them)
+        f32x4* red = (f32x4*)&xlds[0][0];
+        if (active && (wave & 1)) {
+#pragma unroll
+            for (int i = 0; i < NBW; ++i)
+#pragma unroll
+                for (int m = 0; m < MT; ++m) red[((slot * NBW + i) * MT + m) * 64 + lane] = acc[i][m];
+        }
+        __syncthreads();
+        if (wave & 1) return;
+        if (active) {
+#pragma unroll
+            for (int i = 0; i < NBW; ++i)
+#pragma unroll
+                for (int m = 0; m < MT; ++m) acc[i][m] += red[((slot * NBW + i) * MT + m) * 64 + lane];
+        }
     }
     if (!active) return;
 
@@ -1407,28 +1440,37 @@ static void launch_skinny_mt(const GemmArgs& a, hipStream_t s)
     }
 }
 
-template <int P, int MT, int EPI>
+template <int P, int MT, int NBW, int EPI, int KH>
 static void launch_sweep_inst(const GemmArgs& a, int units, hipStream_t s)
 {
-    constexpr int NBW = (EPI == EPI_SWIGLU || MT > 1) ? 2 : 1;
     const int KB = a.Kp / 32;
     const int kbs = (KB + a.ksplit - 1) / a.ksplit;
-    hipLaunchKernelGGL((k_gemm_sweep<P, MT, NBW, EPI>), dim3(a.sweep_gn * a.ksplit), dim3(64 * P), 0, s, a, units,
+    hipLaunchKernelGGL((k_gemm_sweep<P, MT, NBW, EPI, KH>), dim3(a.sweep_gn * a.ksplit), dim3(64 * P), 0, s, a, units,
                        a.sweep_gn, kbs);
 }
 
-template <int P, int EPI>
-static void launch_sweep_p(const GemmArgs& a, int units, hipStream_t s)
+template <int P, int MT, int EPI, int KH>
+static void launch_sweep_mt(const GemmArgs& a, int units, int nbw, hipStream_t s)
+{
+    // strips per wave (sweep_nbw): always 2 with the SwiGLU epilogue and above 3 row strips
+    if (EPI == EPI_SWIGLU || nbw == 2 || MT > 3)
+        launch_sweep_inst<P, MT, 2, EPI, KH>(a, units, s);
+    else
+        launch_sweep_inst<P, MT, (EPI == EPI_SWIGLU || MT > 3) ? 2 : 1, EPI, KH>(a, units, s);
+}
+
+template <int P, int EPI, int KH>
+static void launch_sweep_p(const GemmArgs& a, int units, int nbw, hipStream_t s)
 {
     switch ((a.m_rows + 15) / 16) {
-        case 1: launch_sweep_inst<P, 1, EPI>(a, units, s); break;
-        case 2: launch_sweep_inst<P, 2, EPI>(a, units, s); break;
-        case 3: launch_sweep_inst<P, 3, EPI>(a, units, s); break;
-        case 4: launch_sweep_inst<P, 4, EPI>(a, units, s); break;
-        case 5: launch_sweep_inst<P, 5, EPI>(a, units, s); break;
-        case 6: launch_sweep_inst<P, 6, EPI>(a, units, s); break;
-        case 7: launch_sweep_inst<P, 7, EPI>(a, units, s); break;
-        default: launch_sweep_inst<P, 8, EPI>(a, units, s); break;
+        case 1: launch_sweep_mt<P, 1, EPI, 1>(a, units, nbw, s); break;   // one row strip: never split
+        case 2: launch_sweep_mt<P, 2, EPI, KH>(a, units, nbw, s); break;
+        case 3: launch_sweep_mt<P, 3, EPI, KH>(a, units, nbw, s); break;
+        case 4: launch_sweep_mt<P, 4, EPI, KH>(a, units, nbw, s); break;
+        case 5: launch_sweep_mt<P, 5, EPI, KH>(a, units, nbw, s); break;
+        case 6: launch_sweep_mt<P, 6, EPI, KH>(a, units, nbw, s); break;
+        case 7: launch_sweep_mt<P, 7, EPI, KH>(a, units, nbw, s); break;
+        default: launch_sweep_mt<P, 8, EPI, KH>(a, units, nbw, s); break;
     }
 }
 
@@ -1439,8 +1481,12 @@ static void launch_gemm_epi(const GemmArgs& a, hipStream_t s)
         const int nbw = sweep_nbw(EPI, a.m_rows);
         const int units = (a.N / 16 + nbw - 1) / nbw;
         const int per = (units + a.sweep_gn - 1) / a.sweep_gn;   // most units any workgroup owns
-        if (a.sweep_p == 4 && per <= 4) return launch_sweep_p<4, EPI>(a, units, s);
-        if (per <= 8) return launch_sweep_p<8, EPI>(a, units, s);
+        if (a.sweep_p == 4 && per <= 4) {
+            // from 17 rows on: 8 waves, two per unit (see SweepSlot)
+            if (a.m_rows > 16 && a.sweep_kh == 2) return launch_sweep_p<8, EPI, 2>(a, units, nbw, s);
+            return launch_sweep_p<4, EPI, 1>(a, units, nbw, s);
+        }
+        if (per <= 8) return launch_sweep_p<8, EPI, 1>(a, units, nbw, s);
         // a plan this kernel cannot run falls through to the other kernels
     }
     if (a.m_rows <= 64) {

@@ -8,12 +8,18 @@ namespace ss {
 
 namespace {
 std::atomic<int> g_gemm_mode{0};
+std::atomic<int> g_sweep_split{1};
 constexpr int kSmallMaxKsplit = 8;   // sweep and skinny kernels: at most 8 k-slices
 constexpr int kTiledMaxKsplit = 4;   // tiled kernel: at most 4
 constexpr int kTiledFullTiles = 512; // from this many 64x256 tiles on the tiled kernel runs unsliced
 }
 
-void set_gemm_mode(int mode) { g_gemm_mode.store(mode, std::memory_order_relaxed); }
+void set_gemm_mode(int mode)
+{
+    // bit 2 (value 4) added to a mode: the sweep kernel never splits a unit between two waves (A/B measurements)
+    g_sweep_split.store((mode & 4) ? 0 : 1, std::memory_order_relaxed);
+    g_gemm_mode.store(mode & 3, std::memory_order_relaxed);
+}
 int gemm_mode() { return g_gemm_mode.load(std::memory_order_relaxed); }
 
 // Launch shape of a projection.
@@ -29,14 +35,17 @@ int gemm_mode() { return g_gemm_mode.load(std::memory_order_relaxed); }
 // never leaving a wave fewer than 4 k-blocks.  Tiled kernel: ksplit fills the chip when there are few
 // 64x256 tiles.
 
-// Strips per wave of the sweep kernel: a gate/up pair for the SwiGLU epilogue; with 2 or more row strips also two,
-// so that an activation operand read from LDS feeds two weight strips (at 1 strip per wave the LDS reads of
-// 64 rows, 8 KiB per KiB of weights, bound the kernel; measured: 32 rows 8 % faster, 64 rows 7 %, 16 rows 1 % slower).
-int sweep_nbw(int epilogue, int m_rows) { return (epilogue == EPI_SWIGLU || m_rows > 16) ? 2 : 1; }
+// Strips per wave of the sweep kernel: a gate/up pair for the SwiGLU epilogue.  Otherwise one strip up to 48 rows and
+// two above: two strips per wave halve the LDS operand reads per weight byte, which is what bounds the kernel from
+// 4 row strips on (one strip per wave reads 8 KiB of LDS per KiB of weights at 64 rows); below that, one strip per
+// wave gives twice the units, so half the k-slices (longer sweeps, half the partial sums) and, with two waves per
+// unit, all 8 waves busy.  Measured on the 7B shapes, decode step at context 100, one against two strips:
+// 17 rows 3.38 / 3.57 ms, 32 rows 3.56 / 3.78, 48 rows 4.12 / 4.29, 64 rows 4.71 / 4.76.
+int sweep_nbw(int epilogue, int m_rows) { return (epilogue == EPI_SWIGLU || m_rows > 48) ? 2 : 1; }
 
 GemmPlan gemm_plan(int N, int Kp, int m_rows, int epilogue, int n_cu, int max_ksplit)
 {
-    GemmPlan p{1, 2, 4, 1, 0, 0};
+    GemmPlan p{1, 2, 4, 1, 0, 0, 1};
     const int KB = Kp / 32;
     const int mode = gemm_mode();
     if (m_rows <= kSweepMaxRows) {
@@ -53,6 +62,9 @@ GemmPlan gemm_plan(int N, int Kp, int m_rows, int epilogue, int n_cu, int max_ks
             if ((units + gn - 1) / gn > 8) gn = (units + 7) / 8;
             p.sweep_p = (units + gn - 1) / gn <= 4 ? 4 : 8;
             p.sweep_gn = gn;
+            // from 17 rows on a workgroup with at most 4 units runs 8 waves, two per unit: the work per weight byte
+            // grows with the row strips and 4 waves (one per SIMD) stop keeping up with the weight stream
+            p.sweep_kh = (p.sweep_p == 4 && m_rows > 16 && g_sweep_split.load(std::memory_order_relaxed)) ? 2 : 1;
             return p;
         }
     }

@@ -14,6 +14,7 @@ constexpr int kSweepMaxRows = 128;   // 8 row strips: accumulators and the LDS c
 struct GemmPlan {
     int ksplit, nb, kd, kp;
     int sweep_p, sweep_gn;
+    int sweep_kh;   // sweep kernel: waves per unit (1 or 2)
 };
 
 // n_cu: compute units of the device (the sweep kernel runs one workgroup per unit).
