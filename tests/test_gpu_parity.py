@@ -341,6 +341,43 @@ def test_exact_ties_pick_the_lowest_token_id(tiny):
         gw2.close()
 
 
+def test_non_finite_logits_and_huge_keys_still_give_ids_inside_the_vocabulary(tiny):
+    """The token id feeds the next step's embedding lookup, so it must be a valid id whatever the arithmetic does:
+    a row whose logits are all NaN yields id 0 greedily (no logit compares greater than the start value) and
+    vocab-1 when sampled (no chunk of the CDF exceeds the draw); keys beyond the half range are stored saturated,
+    so the softmax stays finite."""
+    W, om, gw = tiny
+    w = synth.make_workload(1)
+    nan_head = [t.copy() for t in W]
+    nan_head[-1][:] = 0x7FC0                                   # bf16 quiet NaN in every LM-head weight
+    g1 = ss.Weights(synth.TINY, nan_head)
+    try:
+        r = ss.ss_decode_microbatch(g1, w.prompt_tokens, w.prompt_offsets, 6, w.target_lens, 0)
+        emitted = r["tokens"][r["tokens"] >= 0]
+        assert np.array_equal(r["lens"], np.minimum(w.target_lens, 6)) and (emitted == 0).all()
+        draws = synth.make_draws(w.n, 6, seed=3)
+        g = ss.ss_generate_microbatch(g1, w.prompt_tokens, w.prompt_offsets, 6, temperature=0.7, draws=draws,
+                                      target_lens=w.target_lens, sync_every=1)
+        emitted = g["tokens"][g["tokens"] >= 0]
+        assert (emitted == synth.TINY.vocab - 1).all()
+    finally:
+        g1.close()
+    big_k = [t.copy() for t in W]
+    for l in range(synth.TINY.n_layers):                       # wk of every layer scaled by 2^20: |k| far above 65504
+        wk = big_k[1 + 9 * l + 2]
+        big_k[1 + 9 * l + 2] = synth.f32_to_bf16_bits(synth.bf16_bits_to_f32(wk) * float(2 ** 20))
+    g2 = ss.Weights(synth.TINY, big_k)
+    try:
+        r = ss.ss_decode_microbatch(g2, w.prompt_tokens, w.prompt_offsets, 6, w.target_lens, 0)
+        emitted = r["tokens"][r["tokens"] >= 0]
+        assert np.array_equal(r["lens"], np.minimum(w.target_lens, 6))
+        assert ((emitted >= 0) & (emitted < synth.TINY.vocab)).all()
+        lg = ss.ss_forward_logits(g2, w.prompt_tokens[:w.prompt_offsets[2]], w.prompt_offsets[:3], w.prompt_lens[:2])
+        assert np.isfinite(lg).all()
+    finally:
+        g2.close()
+
+
 # ------------------------------------------------------------------ whole group
 @pytest.mark.parametrize("flags", [(), ("SORT", "BIN", "FCR"), ("SORT", "BIN", "FCR", "VBS", "COMPACT"),
                                    ("SORT", "FCR", "VBS")])
