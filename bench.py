@@ -228,9 +228,10 @@ def main() -> int:
                          "that the host must poll for, against the poll period, greedy and sampled at T=0.5, or ('step') "
                          "the time of one decode forward against live rows and against context length (App. D)")
     ap.add_argument("--no-cfg4", action="store_true", help="skip the configuration-4 leg of the default run")
-    ap.add_argument("--cfg4-full-before-s", type=float, default=400.0,
-                    help="the configuration-4 leg runs its whole group of 1024 when it starts within this many seconds of "
-                         "the program's start, else the first 512 queries")
+    ap.add_argument("--time-budget-s", type=float, default=570.0,
+                    help="seconds the whole program should stay within: the optional legs after the timed passes (the "
+                         "configuration-4 comparison, then the sampled rerun) shrink or are left out, and say so in the JSON, "
+                         "when the passes asked for have already used most of it")
     ap.add_argument("--no-generate", action="store_true",
                     help="skip the leg that reruns the group with sampled tokens and ends discovered by polling")
     ap.add_argument("--roofline-only", action="store_true",
@@ -315,6 +316,28 @@ def main() -> int:
         extras["scheduled_over_vanilla"] = (useful / (st["wall_ms"] / 1e3)) / extras["vanilla_batching"]["useful_tokens_per_s"]
         log(f"vanilla: {sv['wall_ms']:.0f} ms -> ratio {extras['scheduled_over_vanilla']:.3f}")
 
+    pass_s = dt / a.steps if a.steps else 0.0
+    reserve_s = 35.0                                     # roofline legs, cpu_baseline, the perception leg
+    skipped = {}
+
+    def budget_left() -> float:
+        return a.time_budget_s - (time.time() - T_START) - reserve_s
+
+    run_cfg4 = not a.roofline_only and a.cfg == 3 and not a.no_cfg4 and a.layers <= 0 and a.steps > 0
+    # the configuration-4 leg costs about 6.7 timed passes at its full group of 1024 (one scheduled pass, one vanilla pass
+    # over 4x the queries): take the largest power-of-two prefix of its group that fits what is left
+    n4 = 0
+    if run_cfg4:
+        n4 = 1024
+        while n4 > 128 and 6.7 * pass_s * n4 / 1024 > budget_left():
+            n4 //= 2
+        if 6.7 * pass_s * n4 / 1024 > budget_left():
+            skipped["config4"] = f"left out: {budget_left():.0f} s of the {a.time_budget_s:.0f} s budget remained"
+            run_cfg4 = False
+    gen_cost = 1.05 * pass_s + (6.7 * pass_s * n4 / 1024 if run_cfg4 else 0.0)
+    if not a.roofline_only and not a.no_generate and a.steps > 0 and gen_cost > budget_left():
+        skipped["sampled_polled_generation"] = f"left out: {budget_left():.0f} s of the {a.time_budget_s:.0f} s budget remained"
+        a.no_generate = True
     if not a.roofline_only and not a.no_generate and a.steps > 0:
         # The same group when the host does not know the lengths (Sec. 4.2, Experimental Setting, of the paper samples at T = 0.5 and rows
         # end by themselves): tokens drawn by the sampling kernel, the same lengths applied on the device as
@@ -350,13 +373,12 @@ def main() -> int:
             ms=t_p, useful_tokens_per_s_including_it=useful / ((st["wall_ms"] + t_p) / 1e3))
         log(f"simulated perception overhead: {t_p:.0f} ms on top of {st['wall_ms']:.0f} ms")
 
-    if not a.roofline_only and a.cfg == 3 and not a.no_cfg4 and a.layers <= 0:
+    if run_cfg4:
         # The case the method gains most on this hardware, beside the headline's fixed batch of 16: configuration 4
         # (same weights, group 1024, variable batch size up to 256 rows, compaction) against vanilla batching on
-        # its own group.  When the run has already taken long (many timed passes), the first 512 queries of that
-        # group stand in for it; the JSON says which.
+        # its own group.  When the run has already taken long (many timed passes), a prefix of that group stands in
+        # for it; the JSON says which.
         w4 = synth.make_workload(4)
-        n4 = w4.n if (time.time() - T_START) < a.cfg4_full_before_s else 512
         idx4 = list(range(n4))
         tk4, of4 = synth.gather_prompts(w4, idx4)
         t4, p4 = w4.target_lens[idx4], w4.pred_lens[idx4]
@@ -459,7 +481,8 @@ def main() -> int:
                            samples_per_s=(wl.n * a.steps / dt if a.steps else 0.0), prefill_ms=st["prefill_ms"], decode_ms=st["decode_ms"],
                            plan_ms=st["plan_ms"], **({"reduced_layers": a.layers} if a.layers > 0 else {}),
                            **({"gemm_mode": a.gemm_mode} if a.gemm_mode else {})),
-               roofline=roofline, cpu_baseline=cpu, paper_context=PAPER_CONTEXT, **extras)
+               roofline=roofline, cpu_baseline=cpu, paper_context=PAPER_CONTEXT,
+               **({"legs_left_out": skipped} if skipped else {}), **extras)
     print(json.dumps(out))
     return 0
 
