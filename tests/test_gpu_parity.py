@@ -257,6 +257,32 @@ def test_wide_decode_logits_each_small_batch_projection_kernel(wide2, mode):
     check_logits(got, ref, f"wide2 B=20 mode={mode}")
 
 
+@pytest.mark.parametrize("rows", [17, 33, 48, 49, 64, 100, 128])
+def test_wide_decode_logits_across_row_strips(wide2, rows):
+    """7B widths, 2-8 row strips, the kernel choice of the library itself (mode 0) and the same with the
+    two-waves-per-unit split of the sweep kernel switched off (mode 4): one strip per wave up to 48 rows, two above,
+    ragged last strips.  Three rows against the oracle in each mode; the two modes agree to rounding order."""
+    shape, W, om, gw = wide2
+    rng = np.random.default_rng(500 + rows)
+    w = synth.make_group(shape, rows, 900 + rows, ("uniform", 3, 12), ("uniform", 1, 8), None, 8, 0, ())
+    toks, offs, npr = forced_batch(w, range(rows), rng.integers(1, 3, size=rows), rng)
+    out_off = np.concatenate([[0], np.cumsum(np.diff(offs) - npr + 1)])
+    got = {}
+    for mode in (0, 4):
+        ss.ss_set_gemm_mode(mode)
+        try:
+            _say(f"7B-width x2 layers, {rows} rows, mode {mode}")
+            got[mode] = ss.ss_forward_logits(gw, toks, offs, npr)
+        finally:
+            ss.ss_set_gemm_mode(0)
+    for i in (0, rows // 2, rows - 1):
+        ref = om.teacher_forced(toks[offs[i]:offs[i + 1]], first=int(npr[i]) - 1)
+        for mode in (0, 4):
+            check_logits(got[mode][out_off[i]:out_off[i + 1]], ref, f"B={rows} row {i} mode {mode}")
+    scale = np.abs(got[0]).max()
+    assert np.abs(got[0] - got[4]).max() <= 1e-4 * scale
+
+
 def test_wide_prompt_forward_through_tiled_kernel(wide2):
     """> 64 prompt token-rows at real widths: tiled MFMA kernel incl. its ragged row and column tails."""
     shape, W, om, gw = wide2
