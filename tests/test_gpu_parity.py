@@ -105,6 +105,38 @@ def test_tiny_prompt_logits_every_position(tiny):
     check_logits(got, ref, "tiny prefill")
 
 
+def test_tiny_prompt_logits_across_attention_tiles(tiny):
+    """Prompt attention works in tiles of 64 queries and 32 keys: prompt lengths on and around every tile edge
+    (1 .. 200 tokens, head_dim 64), logits at every position against the oracle."""
+    W, om, gw = tiny
+    rng = np.random.default_rng(64)
+    lens = [1, 2, 31, 32, 33, 63, 64, 65, 96, 127, 128, 129, 200]
+    prompts = [rng.integers(0, synth.TINY.vocab, size=n).astype(np.int32) for n in lens]
+    toks = np.concatenate(prompts)
+    offs = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    _say(f"tiny prompt logits, all positions, prompt lengths {lens}")
+    got = ss.ss_forward_logits(gw, toks, offs, np.array(lens, np.int32), all_prompt_logits=True)
+    ref = np.concatenate([om.teacher_forced(p, first=0) for p in prompts], axis=0)
+    assert got.shape == ref.shape
+    check_logits(got, ref, "tiny prefill across tiles")
+
+
+def test_wide_prompt_logits_across_attention_tiles(wide2):
+    """The same at head_dim 128 (7B widths): a 150-token and a 70-token prompt next to short ones, logits at every
+    position of the two long rows."""
+    shape, W, om, gw = wide2
+    rng = np.random.default_rng(65)
+    lens = [150, 5, 70, 33]
+    prompts = [rng.integers(0, shape.vocab, size=n).astype(np.int32) for n in lens]
+    toks = np.concatenate(prompts)
+    offs = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    _say(f"7B-width prompt logits, all positions, prompt lengths {lens}")
+    got = ss.ss_forward_logits(gw, toks, offs, np.array(lens, np.int32), all_prompt_logits=True)
+    for i in (0, 2):
+        ref = om.teacher_forced(prompts[i], first=0)
+        check_logits(got[offs[i]:offs[i + 1]], ref, f"wide2 prefill row {i} ({lens[i]} tokens)")
+
+
 @pytest.mark.parametrize("rows", [1, 5, 16, 23, 40, 64, 100])
 def test_tiny_decode_logits_teacher_forced(tiny, rows):
     """Prompt forward then decode steps on forced tokens; row counts cover 1..4 strips of the skinny
