@@ -360,8 +360,8 @@ void forward(ss_weights* w, int n, int n_sel, const int32_t* d_sel, const int32_
     ss::launch_embed(st, w->embed, x, d, n, s);
     for (int l = 0; l < c.n_layers; ++l) {
         const Layer& L = w->layers[l];
-        bf16_t* kc = ws.kv.as<bf16_t>() + (size_t)l * 2 * w->kv_layer_stride;
-        bf16_t* vc = kc + w->kv_layer_stride;
+        ss::kv_t* kc = ws.kv.as<ss::kv_t>() + (size_t)l * 2 * w->kv_layer_stride;
+        ss::kv_t* vc = kc + w->kv_layer_stride;
         ss::launch_rmsnorm(st, x, l ? pd : nullptr, ks_d, st_d, L.attn_norm, c.rms_eps, nullptr, nullptr, h, h_lo, d, n, s);
         ss::launch_gemm(with_lo(mk(L.wqkv.p, h, h_lo, pqkv, nullptr, nullptr, 3 * d, d, n, 0, p_qkv), no_lo(SS_LO_QKV)),
                         ss::EPI_PARTIAL, s);

@@ -11,6 +11,7 @@
 namespace ss {
 
 typedef uint16_t bf16_t;  // bf16 bit pattern
+typedef uint16_t kv_t;    // key/value cache slot: IEEE half bit pattern (same size as bf16, three more significand bits)
 
 // Packed weight matrix: N output rows (multiple of 16), K inputs padded to Kp (multiple of 64).
 struct PackedMat {
@@ -70,15 +71,15 @@ void launch_gemm(const GemmArgs& a, int epilogue, hipStream_t s);
 void launch_swiglu_reduce(const float* part, int ksplit, size_t part_stride, int m_rows, int F, int kp_out,
                           bf16_t* out, bf16_t* out_lo, hipStream_t s);
 void launch_rope_append(const MbState& st, const float* qkv_part, int ksplit, size_t part_stride, float* qrot,
-                        bf16_t* kcache, bf16_t* vcache, const float* rope_cos, const float* rope_sin, int d, int H,
+                        kv_t* kcache, kv_t* vcache, const float* rope_cos, const float* rope_sin, int d, int H,
                         int hd, int n_max, hipStream_t s);
 // Causal attention of a prompt forward: B rows, row i holding st.row_plen[i] token-rows that start at token-row
 // st.row_j0[i]; max_len = the longest row (sizes the grid).
-void launch_attention_prompt(const MbState& st, const float* qrot, const bf16_t* kcache, const bf16_t* vcache,
+void launch_attention_prompt(const MbState& st, const float* qrot, const kv_t* kcache, const kv_t* vcache,
                              bf16_t* out_packed, bf16_t* out_packed_lo, int d, int H, int hd, int B, int max_len,
                              hipStream_t s);
 void launch_attention_decode(const MbState& st, const float* qkv_part, int ksplit, size_t part_stride,
-                             bf16_t* kcache, bf16_t* vcache, const float* rope_cos, const float* rope_sin,
+                             kv_t* kcache, kv_t* vcache, const float* rope_cos, const float* rope_sin,
                              bf16_t* out_packed, bf16_t* out_packed_lo, int d, int H, int hd, int n_max, hipStream_t s);
 void launch_argmax(const float* logits, int vocab, const int32_t* d_nsel, int32_t* am, int n_max, hipStream_t s);
 // Temperature sampling in place of the argmax: st.am[j] for the first *d_nsel selected rows.  The draw of slot j

@@ -41,12 +41,12 @@ __device__ __forceinline__ void split_bf(float v, bf16_t& hi, bf16_t& lo)
 
 // Key/value slots are stored as IEEE half: the same 2 bytes per element as bf16 with three more
 // significand bits; keys and values are projections of RMS-normalised activations, far inside its range.
-__device__ __forceinline__ float kv2f(bf16_t b) { return (float)__builtin_bit_cast(_Float16, b); }
+__device__ __forceinline__ float kv2f(kv_t b) { return (float)__builtin_bit_cast(_Float16, b); }
 // Saturating: a value beyond the half range is stored as the largest finite half, never as infinity (an infinite
 // key would turn the softmax into NaN and the token choice into an arbitrary id).
-__device__ __forceinline__ bf16_t f2kv(float f)
+__device__ __forceinline__ kv_t f2kv(float f)
 {
-    return __builtin_bit_cast(bf16_t, (_Float16)fminf(fmaxf(f, -65504.f), 65504.f));
+    return __builtin_bit_cast(kv_t, (_Float16)fminf(fmaxf(f, -65504.f), 65504.f));
 }
 
 // Element (r, k) of a packed [rows, Kp] matrix.
@@ -766,11 +766,11 @@ __global__ __launch_bounds__(256) void k_swiglu_reduce(const float* __restrict__
 
 // ------------------------------------------------------------------------------------------ RoPE + KV append
 // Token-row j: sums the k-slices of its [q | k | v] projection, rotates q and k at the row's position
-// (pairs e, e + hd/2; cos/sin from a table indexed [pos][e]), stores q as fp32 and k, v as bf16 into the
+// (pairs e, e + hd/2; cos/sin from a table indexed [pos][e]), stores q as fp32 and k, v as IEEE half (kv_t) into the
 // row's key/value slab: element (head h, slot s, e) of row i lives at so[i]*d + (h*cap[i] + s)*hd + e.
 __global__ __launch_bounds__(256) void k_rope_append(MbState st, const float* __restrict__ part, int ksplit,
                                                      size_t part_stride, float* __restrict__ qrot,
-                                                     bf16_t* __restrict__ kc, bf16_t* __restrict__ vc,
+                                                     kv_t* __restrict__ kc, kv_t* __restrict__ vc,
                                                      const float* __restrict__ rcos, const float* __restrict__ rsin,
                                                      int d, int H, int hd)
 {
@@ -813,8 +813,8 @@ constexpr int kAttnWideMaxGroups = 512;   // decode attention: (row, head) workg
 
 template <int HD, int NW>
 __device__ __forceinline__ void attend(const float* __restrict__ qs, float* __restrict__ sc, float* __restrict__ red,
-                                       float (*__restrict__ oacc)[HD], const bf16_t* __restrict__ kbase,
-                                       const bf16_t* __restrict__ vbase, int ctx, bf16_t* __restrict__ out,
+                                       float (*__restrict__ oacc)[HD], const kv_t* __restrict__ kbase,
+                                       const kv_t* __restrict__ vbase, int ctx, bf16_t* __restrict__ out,
                                        bf16_t* __restrict__ out_lo, int out_r, int out_k0, int out_kp)
 {
     constexpr int LPK = HD / 8;       // lanes per key
@@ -838,7 +838,7 @@ __device__ __forceinline__ void attend(const float* __restrict__ qs, float* __re
 #pragma unroll
         for (int u = 0; u < AU; ++u) {
             const int s = c0 + u * NW * KPW + kin;
-            const bf16_t* kv = (const bf16_t*)&raw[u];
+            const kv_t* kv = (const kv_t*)&raw[u];
             float part = 0.f;
 #pragma unroll
             for (int e = 0; e < 8; ++e) part += q[e] * kv2f(kv[e]);
@@ -893,7 +893,7 @@ __device__ __forceinline__ void attend(const float* __restrict__ qs, float* __re
         for (int u = 0; u < AU; ++u) {
             const int s = c0 + u * NW * KPW + kin;
             const float p = s < ctx ? sc[s] : 0.f;
-            const bf16_t* vv = (const bf16_t*)&raw[u];
+            const kv_t* vv = (const kv_t*)&raw[u];
 #pragma unroll
             for (int e = 0; e < 8; ++e) o[e] += p * kv2f(vv[e]);
         }
@@ -941,7 +941,7 @@ typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
 
 template <int HD>
 __global__ __launch_bounds__(256) void k_attention_prompt(MbState st, const float* __restrict__ qrot,
-                                                          const bf16_t* __restrict__ kc, const bf16_t* __restrict__ vc,
+                                                          const kv_t* __restrict__ kc, const kv_t* __restrict__ vc,
                                                           bf16_t* __restrict__ out, bf16_t* __restrict__ out_lo, int d)
 {
     constexpr int KS = HD / 32;          // steps of the score contraction
@@ -1089,8 +1089,8 @@ __global__ __launch_bounds__(256) void k_attention_prompt(MbState st, const floa
 // be resident with room to spare, 4 (128 slots) for larger batches, whose many workgroups already fill the chip.
 template <int HD, int NW>
 __global__ __launch_bounds__(64 * NW) void k_attention_decode(MbState st, const float* __restrict__ part, int ksplit,
-                                                          size_t part_stride, bf16_t* __restrict__ kc,
-                                                          bf16_t* __restrict__ vc, const float* __restrict__ rcos,
+                                                          size_t part_stride, kv_t* __restrict__ kc,
+                                                          kv_t* __restrict__ vc, const float* __restrict__ rcos,
                                                           const float* __restrict__ rsin, bf16_t* __restrict__ out,
                                                           bf16_t* __restrict__ out_lo, int d)
 {
@@ -1131,7 +1131,7 @@ __global__ __launch_bounds__(64 * NW) void k_attention_decode(MbState st, const 
             qs[e] = a;
             qs[e + HALF] = b;
         } else {
-            bf16_t* dst = (which == 1 ? kc : vc) + base + (size_t)pos * HD + e;
+            kv_t* dst = (which == 1 ? kc : vc) + base + (size_t)pos * HD + e;
             dst[0] = f2kv(a);
             dst[HALF] = f2kv(b);
         }
@@ -1523,7 +1523,7 @@ void launch_gemm(const GemmArgs& a, int epilogue, hipStream_t s)
 }
 
 void launch_rope_append(const MbState& st, const float* qkv_part, int ksplit, size_t part_stride, float* qrot,
-                        bf16_t* kcache, bf16_t* vcache, const float* rope_cos, const float* rope_sin, int d, int H,
+                        kv_t* kcache, kv_t* vcache, const float* rope_cos, const float* rope_sin, int d, int H,
                         int hd, int n_max, hipStream_t s)
 {
     hipLaunchKernelGGL(k_rope_append, dim3(n_max), dim3(256), 0, s, st, qkv_part, ksplit, part_stride, qrot, kcache,
@@ -1532,7 +1532,7 @@ void launch_rope_append(const MbState& st, const float* qkv_part, int ksplit, si
 
 template <int HD, int NW>
 static void launch_attention_decode_inst(const MbState& st, const float* qkv_part, int ksplit, size_t part_stride,
-                                         bf16_t* kcache, bf16_t* vcache, const float* rope_cos, const float* rope_sin,
+                                         kv_t* kcache, kv_t* vcache, const float* rope_cos, const float* rope_sin,
                                          bf16_t* out_packed, bf16_t* out_packed_lo, int d, int H, int n_max, hipStream_t s)
 {
     hipLaunchKernelGGL((k_attention_decode<HD, NW>), dim3(n_max, H), dim3(64 * NW), 0, s, st, qkv_part, ksplit, part_stride,
@@ -1540,7 +1540,7 @@ static void launch_attention_decode_inst(const MbState& st, const float* qkv_par
 }
 
 void launch_attention_decode(const MbState& st, const float* qkv_part, int ksplit, size_t part_stride,
-                             bf16_t* kcache, bf16_t* vcache, const float* rope_cos, const float* rope_sin,
+                             kv_t* kcache, kv_t* vcache, const float* rope_cos, const float* rope_sin,
                              bf16_t* out_packed, bf16_t* out_packed_lo, int d, int H, int hd, int n_max, hipStream_t s)
 {
     // measured at the 7B shape: 8 waves win at 16 rows (512 workgroups: 14.1 against 14.9 us per layer at context
@@ -1557,7 +1557,7 @@ void launch_attention_decode(const MbState& st, const float* qkv_part, int kspli
 #undef SS_ATTN_ARGS
 }
 
-void launch_attention_prompt(const MbState& st, const float* qrot, const bf16_t* kcache, const bf16_t* vcache,
+void launch_attention_prompt(const MbState& st, const float* qrot, const kv_t* kcache, const kv_t* vcache,
                              bf16_t* out_packed, bf16_t* out_packed_lo, int d, int H, int hd, int B, int max_len,
                              hipStream_t s)
 {
