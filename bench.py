@@ -227,6 +227,8 @@ def main() -> int:
                          "(the paper's Fig. 3a / 3b on the synthetic workload), ('sync') the group run with ends "
                          "that the host must poll for, against the poll period, greedy and sampled at T=0.5, or ('step') "
                          "the time of one decode forward against live rows and against context length (App. D)")
+    ap.add_argument("--in-flight", type=int, default=2, choices=[1, 2],
+                    help="micro-batches of a group pass generated at the same time (SS_OPT_IN_FLIGHT; reported in config)")
     ap.add_argument("--no-cfg4", action="store_true", help="skip the configuration-4 leg of the default run")
     ap.add_argument("--time-budget-s", type=float, default=590.0,
                     help="seconds the whole program should stay within: the optional legs after the timed passes (the "
@@ -257,6 +259,7 @@ def main() -> int:
     t0 = time.time()
     gw = ss.Weights(shape, W)
     log(f"uploaded + packed in {time.time() - t0:.1f}s")
+    gw.set_option(ss.SS_OPT_IN_FLIGHT, a.in_flight)
 
     pol = ss.make_policy(wl.flags, wl.base_batch, wl.l_max, wl.max_batch)
     vpol = ss.make_policy((), wl.base_batch, wl.l_max, wl.max_batch)
@@ -323,22 +326,39 @@ def main() -> int:
     def budget_left() -> float:
         return a.time_budget_s - (time.time() - T_START) - reserve_s
 
+    if a.in_flight > 1 and a.steps > 0 and not a.roofline_only:
+        # the same pass with one micro-batch at a time: what generating two at once is worth on this group
+        if 1.3 * pass_s > budget_left():
+            skipped["one_microbatch_at_a_time"] = f"left out: {budget_left():.0f} s of the {a.time_budget_s:.0f} s budget remained"
+        else:
+            gw.set_option(ss.SS_OPT_IN_FLIGHT, 1)
+            r1 = run(pol, wl.pred_lens, wl.bin_width)
+            gw.set_option(ss.SS_OPT_IN_FLIGHT, a.in_flight)
+            assert np.array_equal(r1["tokens"], r["tokens"]) and np.array_equal(r1["lens"], r["lens"])
+            assert all(r1["stats"][k] == st[k] for k in ("steps", "padded_row_steps", "computed_row_steps", "n_failed"))
+            extras["one_microbatch_at_a_time"] = dict(
+                what="the same pass with SS_OPT_IN_FLIGHT = 1: identical tokens and counters, micro-batches one after another",
+                useful_tokens_per_s=useful / (r1["stats"]["wall_ms"] / 1e3), ms=r1["stats"]["wall_ms"],
+                two_in_flight_over_it=r1["stats"]["wall_ms"] / st["wall_ms"])
+            log(f"one micro-batch at a time: {r1['stats']['wall_ms']:.0f} ms -> two in flight are "
+                f"{extras['one_microbatch_at_a_time']['two_in_flight_over_it']:.3f}x")
+
     # The configuration-4 leg: one scheduled pass over a group 4x as large with micro-batches of up to 256 rows costs
-    # about 2.05 timed passes, the vanilla pass over that group about 4.7 more.  What is left of the time budget after
+    # about 2.15 timed passes, the vanilla pass over that group about 4.85 more.  What is left of the time budget after
     # the passes asked for decides its form: both passes on the whole group; or the scheduled pass alone, compared with
-    # the vanilla rate just measured on the 256-query group (the same length laws and batch 16: 1,679 against 1,688
+    # the vanilla rate just measured on the 256-query group (the same length laws and batch 16: 1,991 against 1,996
     # tokens/s when both are measured); or that on a power-of-two prefix of the group; or nothing.  The JSON says which.
     run_cfg4 = not a.roofline_only and a.cfg == 3 and not a.no_cfg4 and a.layers <= 0 and a.steps > 0
     n4, cfg4_own_vanilla = 1024, True
     if run_cfg4:
-        if 6.75 * pass_s > budget_left():
+        if 7.0 * pass_s > budget_left():
             cfg4_own_vanilla = False
-            while n4 > 256 and 2.05 * pass_s * n4 / 1024 > budget_left():
+            while n4 > 256 and 2.15 * pass_s * n4 / 1024 > budget_left():
                 n4 //= 2
-            if 2.05 * pass_s * n4 / 1024 > budget_left() or a.no_vanilla:
+            if 2.15 * pass_s * n4 / 1024 > budget_left() or a.no_vanilla:
                 skipped["config4"] = f"left out: {budget_left():.0f} s of the {a.time_budget_s:.0f} s budget remained"
                 run_cfg4 = False
-    cfg4_cost = (6.75 if cfg4_own_vanilla else 2.05) * pass_s * n4 / 1024 if run_cfg4 else 0.0
+    cfg4_cost = (7.0 if cfg4_own_vanilla else 2.15) * pass_s * n4 / 1024 if run_cfg4 else 0.0
     if not a.roofline_only and not a.no_generate and a.steps > 0 and 1.05 * pass_s + cfg4_cost > budget_left():
         skipped["sampled_polled_generation"] = (f"left out: {budget_left():.0f} s of the {a.time_budget_s:.0f} s budget remained; "
                                                 "profiles/polled_generation_sync_sweep_7b.md has this leg's figures")
@@ -430,6 +450,9 @@ def main() -> int:
     ms_s = ss.ss_bench_decode_step(gw, ptoks, B0, ctx, a.step_iters + 3)[3:]
     sbytes = decode_step_bytes(shape, B0, ctx)
     ach = sbytes / (ms_s.mean() * 1e-3) / 1e9
+    # two such steps at once, one per lane, as a group pass runs two micro-batches: both stream the whole model
+    ms_2 = ss.ss_bench_decode_steps_in_flight(gw, ptoks, B0, ctx, a.step_iters + 6)[:, 3:-3]
+    ach_2 = 2 * sbytes / (ms_2.mean() * 1e-3) / 1e9
     step_launches = launches + 3 * shape.n_layers + 3     # + attention and two norms per layer, embedding, final norm, token choice
     traffic, traffic_source = profile_traffic(shape.name, B0, ctx, a.gemm_mode)
     roofline = dict(bound="hbm",
@@ -438,6 +461,10 @@ def main() -> int:
                     achieved=ach, peak=HBM_PEAK_GBS, unit="GB/s", frac=ach / HBM_PEAK_GBS, traffic=traffic,
                     traffic_source=traffic_source, ms=float(ms_s.mean()), ms_min=float(ms_s.min()),
                     algorithmic_bytes=sbytes, launches_per_step=step_launches,
+                    two_steps_in_flight=dict(
+                        what="two such steps running at the same time on two streams (two micro-batches of a group pass): "
+                             "bytes of both / the time one of them takes then",
+                        ms=float(ms_2.mean()), achieved=ach_2, unit="GB/s", frac=ach_2 / HBM_PEAK_GBS),
                     projection_launches=dict(
                         what="the projection kernels of that step alone (k_gemm_sweep + k_gemm_skinny), back to back",
                         ms=float(ms_w.mean()), achieved=ach_w, unit="GB/s", frac=ach_w / HBM_PEAK_GBS, launches=launches,
@@ -450,7 +477,8 @@ def main() -> int:
                                  algorithmic_bytes=sbytes, achieved_GBs=ach, frac_of_hbm_peak=ach / HBM_PEAK_GBS)
     log(f"plain read stream over the same matrices: {ms_r.mean():.3f} ms/iter -> {roofline['plain_read_stream']['achieved']:.0f} GB/s")
     log(f"weight stream: {ms_w.mean():.3f} ms/iter -> {ach_w:.0f} GB/s; decode step B={B0} ctx={ctx}: "
-        f"{ms_s.mean():.3f} ms -> {ach:.0f} GB/s = {ach / HBM_PEAK_GBS:.3f} of peak")
+        f"{ms_s.mean():.3f} ms -> {ach:.0f} GB/s = {ach / HBM_PEAK_GBS:.3f} of peak; two in flight: {ms_2.mean():.3f} ms each "
+        f"-> {ach_2:.0f} GB/s = {ach_2 / HBM_PEAK_GBS:.3f}")
     if a.roofline_only:
         # calibration for the HBM byte counters: a plain device-to-device copy of known size (1 GiB read,
         # 1 GiB written) shows up in the same trace as a copyBuffer dispatch.  It runs after the timed legs:
@@ -494,7 +522,7 @@ def main() -> int:
                            padded_row_steps=st["padded_row_steps"], computed_row_steps=st["computed_row_steps"],
                            n_failed=st["n_failed"], micro_batches=[st["n_mb_first"], st["n_mb_failure"]],
                            samples_per_s=(wl.n * a.steps / dt if a.steps else 0.0), prefill_ms=st["prefill_ms"], decode_ms=st["decode_ms"],
-                           plan_ms=st["plan_ms"], **({"reduced_layers": a.layers} if a.layers > 0 else {}),
+                           plan_ms=st["plan_ms"], microbatches_in_flight=a.in_flight, **({"reduced_layers": a.layers} if a.layers > 0 else {}),
                            **({"gemm_mode": a.gemm_mode} if a.gemm_mode else {})),
                roofline=roofline, cpu_baseline=cpu, paper_context=PAPER_CONTEXT,
                **({"legs_left_out": skipped} if skipped else {}), **extras)

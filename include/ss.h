@@ -139,7 +139,7 @@ void ss_weights_destroy(ss_weights* w);
  *   option SS_OPT_PROMPT_LO_MASK, value = OR of SS_LO_* bits of the projections that keep the lo part
  *   (SS_LO_ALL: every projection; the default SS_PROMPT_LO_DEFAULT is the cheapest set whose teacher-forced logit
  *   error stayed below 1e-2 of max|logit| at full depth, a third of the parity bar).
- * Errors: SS_EINVAL (NULL handle, unknown option, value outside the mask), SS_ESTATE (a call is in flight).
+ * Errors (both options): SS_EINVAL (NULL handle, unknown option, value out of range), SS_ESTATE (a call is in flight).
  */
 #define SS_OPT_PROMPT_LO_MASK 1
 #define SS_LO_QKV 1
@@ -149,6 +149,18 @@ void ss_weights_destroy(ss_weights* w);
 #define SS_LO_LM_HEAD 16
 #define SS_LO_ALL 31
 #define SS_PROMPT_LO_DEFAULT SS_LO_ALL
+/*
+ *   option SS_OPT_IN_FLIGHT, value = 1 or 2: how many micro-batches of a group pass (ss_run_group,
+ *   ss_run_group_generate) are generated at the same time.  The micro-batches of a pass (Sec. 4.1) are independent
+ *   of each other, and a decode step of a few rows leaves the memory system idle between its kernels; with 2 the
+ *   call hands the pass's micro-batches, longest cap first, to two host threads, each with a stream, a workspace
+ *   and a key/value cache of its own, so that one micro-batch's kernels run in the other's gaps.  Every query's
+ *   tokens are the same as with 1; only the order in which micro-batches finish changes.  The stream argument of
+ *   the call is used for one of the two; the other runs on a stream the handle owns.  The call returns when both
+ *   are done.  Device time in the statistics is summed per micro-batch and so can exceed the wall time.
+ */
+#define SS_OPT_IN_FLIGHT 2
+#define SS_IN_FLIGHT_DEFAULT 2
 int ss_set_option(ss_weights* w, int32_t option, int32_t value);
 
 /* ------------------------------------------------------------------ generation */
@@ -318,6 +330,16 @@ int ss_run_group_generate(ss_weights* w, const int32_t* prompt_tokens, const int
  */
 int ss_bench_decode_step(ss_weights* w, const int32_t* prompt_tokens, int32_t B, int32_t ctx, int32_t iters,
                          double* ms_out, void* hip_stream);
+
+/*
+ * Measurement entry point: ss_bench_decode_step on two lanes at once, as a group pass with SS_OPT_IN_FLIGHT = 2
+ * runs two micro-batches: each of two host threads prefills its own B rows of ctx tokens on its own stream, both
+ * wait for each other, then each times `iters` decode forwards.
+ *   ms_out  host, double[2*iters]: lane 0's forwards, then lane 1's (device time of each, HIP events on that
+ *           lane's stream).  Both lanes stream the whole model once per forward.
+ */
+int ss_bench_decode_steps_in_flight(ss_weights* w, const int32_t* prompt_tokens, int32_t B, int32_t ctx, int32_t iters,
+                                    double* ms_out);
 
 /*
  * Measurement entry point: the projection kernels of one decode step alone.  Launches, back to back on

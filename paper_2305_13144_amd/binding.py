@@ -19,13 +19,14 @@ SS_OK, SS_EINVAL, SS_ENOMEM, SS_EDEVICE, SS_ESTATE = 0, -1, -2, -3, -4
 SS_SORT, SS_BIN, SS_FCR, SS_VBS, SS_COMPACT = 1, 2, 4, 8, 16
 SS_VBS_CLAMP_FLOOR, SS_VBS_PAPER_POW2 = 0, 1
 SS_OPT_PROMPT_LO_MASK = 1
+SS_OPT_IN_FLIGHT, SS_IN_FLIGHT_DEFAULT = 2, 2
 SS_LO_QKV, SS_LO_O, SS_LO_GATE_UP, SS_LO_DOWN, SS_LO_LM_HEAD, SS_LO_ALL = 1, 2, 4, 8, 16, 31
 SS_BF16, SS_F32 = 0, 1
 FLAG_BITS = dict(SORT=SS_SORT, BIN=SS_BIN, FCR=SS_FCR, VBS=SS_VBS, COMPACT=SS_COMPACT)
 
 EXPORTS = ["ss_last_error", "ss_set_verbose", "ss_set_gemm_mode", "ss_schedule", "ss_schedule_failures", "ss_plan_free", "ss_weights_create",
            "ss_weights_destroy", "ss_set_option", "ss_decode_microbatch", "ss_decode_microbatch_static", "ss_forward_logits", "ss_run_group", "ss_generate_microbatch",
-           "ss_run_group_generate", "ss_bench_decode_step", "ss_bench_weight_stream", "ss_bench_read_stream"]
+           "ss_run_group_generate", "ss_bench_decode_step", "ss_bench_decode_steps_in_flight", "ss_bench_weight_stream", "ss_bench_read_stream"]
 
 
 class SsError(RuntimeError):
@@ -109,6 +110,7 @@ def lib():
         L.ss_run_group_generate.argtypes = [vp, i32p, i32p, C.c_int32, i32p, C.c_int32, C.POINTER(ss_policy),
                                             C.POINTER(ss_gen_opts), i32p, i32p, C.POINTER(ss_group_stats), vp]
         L.ss_bench_decode_step.argtypes = [vp, i32p, C.c_int32, C.c_int32, C.c_int32, vp, vp]
+        L.ss_bench_decode_steps_in_flight.argtypes = [vp, i32p, C.c_int32, C.c_int32, C.c_int32, vp]
         L.ss_bench_weight_stream.argtypes = [vp, C.c_int32, C.c_int32, vp, vp, vp]
         L.ss_bench_read_stream.argtypes = [vp, C.c_int32, vp, vp, vp]
         for name in EXPORTS:
@@ -303,6 +305,15 @@ def ss_bench_decode_step(w: Weights, prompt_tokens, B: int, ctx: int, iters: int
     ms = np.empty(iters, np.float64)
     _check(lib().ss_bench_decode_step(w.h, _ptr(pt), B, ctx, iters, _ptr(ms), stream))
     return ms
+
+
+def ss_bench_decode_steps_in_flight(w: Weights, prompt_tokens, B: int, ctx: int, iters: int) -> np.ndarray:
+    """[2, iters] device milliseconds: two lanes' decode forwards running at the same time."""
+    pt = _i32(prompt_tokens)
+    assert pt.size == B * ctx
+    ms = np.zeros(2 * iters, np.float64)
+    _check(lib().ss_bench_decode_steps_in_flight(w.h, _ptr(pt), B, ctx, iters, _ptr(ms)))
+    return ms.reshape(2, iters)
 
 
 def ss_bench_weight_stream(w: Weights, B: int, iters: int, stream: Optional[int] = None):

@@ -11,6 +11,8 @@
 #include <cstring>
 #include <mutex>
 #include <numeric>
+#include <string>
+#include <thread>
 #include <vector>
 
 #include "ss_internal.h"
@@ -118,20 +120,14 @@ struct Workspace {
 
 }  // namespace
 
-struct ss_weights {
-    ss_model_cfg cfg{};
-    int device = 0;
+// What one micro-batch in flight owns: its stream, workspace, device state and the token choice of its forwards.
+// A handle has kLanes of them; every entry point works on lane 0, and a group pass may run a second micro-batch
+// on lane 1 at the same time (the weights are shared and only read).
+namespace {
+constexpr int kLanes = 2;
+struct Lane {
     hipStream_t stream = nullptr;
-    std::vector<void*> allocs;
-    bf16_t* embed = nullptr;
-    std::vector<Layer> layers;
-    bf16_t* final_norm = nullptr;
-    PackedMat lm_head;
-    float *rope_cos = nullptr, *rope_sin = nullptr;
-    bf16_t* zero_blk = nullptr;   // 1 KiB of zeros (see GemmArgs::zero_blk)
-    int n_cu = 256;               // compute units of the device
     Workspace ws;
-    std::atomic<int> busy{0};
     int32_t* d_sel = nullptr;  // carved from ws.ints
     MbState st{};
     size_t kv_layer_stride = 0;  // elements between a layer's K and V, and 2x that between layers
@@ -143,9 +139,26 @@ struct ss_weights {
     float cur_inv_temp = 0.f;
     int32_t* h_poll = nullptr;   // pinned host copy of the 4-int device header (d_n, d_step, d_nlive, d_active)
     hipEvent_t ev[3] = {nullptr, nullptr, nullptr};   // start, end of the prompt forward, end of a micro-batch
-    void* scratch_ptr = nullptr;   // device address of this device's static scratch array
     int prompt_rows = 0, prompt_max_len = 0;   // shape of the prompt forward whose state was uploaded last
+};
+}  // namespace
+
+struct ss_weights {
+    ss_model_cfg cfg{};
+    int device = 0;
+    std::vector<void*> allocs;
+    bf16_t* embed = nullptr;
+    std::vector<Layer> layers;
+    bf16_t* final_norm = nullptr;
+    PackedMat lm_head;
+    float *rope_cos = nullptr, *rope_sin = nullptr;
+    bf16_t* zero_blk = nullptr;   // 1 KiB of zeros (see GemmArgs::zero_blk)
+    int n_cu = 256;               // compute units of the device
+    Lane lane[kLanes];
+    std::atomic<int> busy{0};
+    void* scratch_ptr = nullptr;   // device address of this device's static scratch array
     int prompt_lo_mask = SS_PROMPT_LO_DEFAULT;  // projections whose activations keep their lo part in prompt forwards
+    int in_flight = SS_IN_FLIGHT_DEFAULT;       // micro-batches a group pass keeps in flight (1 or 2)
 };
 
 namespace {
@@ -179,8 +192,8 @@ int upload_pack(ss_weights* w, Buf& staging, const void* host, int src_f32, int 
     const size_t bytes = (size_t)n_src * k * (src_f32 ? 4 : 2);
     if (int rc = staging.ensure(bytes, false)) return rc;
     HIPCHK(hipMemcpy(staging.p, host, bytes, hipMemcpyHostToDevice));
-    ss::launch_pack_weight(staging.p, src_f32, dst, n_src, k, kp, blk_stride, blk_off, w->stream);
-    HIPCHK(hipStreamSynchronize(w->stream));
+    ss::launch_pack_weight(staging.p, src_f32, dst, n_src, k, kp, blk_stride, blk_off, w->lane[0].stream);
+    HIPCHK(hipStreamSynchronize(w->lane[0].stream));
     return SS_OK;
 }
 
@@ -191,8 +204,8 @@ int upload_vec(ss_weights* w, Buf& staging, const void* host, int src_f32, size_
     const size_t bytes = count * (src_f32 ? 4 : 2);
     if (int rc = staging.ensure(bytes, false)) return rc;
     HIPCHK(hipMemcpy(staging.p, host, bytes, hipMemcpyHostToDevice));
-    ss::launch_cast_rows(staging.p, src_f32, (bf16_t*)p, count, w->stream);
-    HIPCHK(hipStreamSynchronize(w->stream));
+    ss::launch_cast_rows(staging.p, src_f32, (bf16_t*)p, count, w->lane[0].stream);
+    HIPCHK(hipStreamSynchronize(w->lane[0].stream));
     *out = (bf16_t*)p;
     return SS_OK;
 }
@@ -225,15 +238,15 @@ int check_cfg(const ss_model_cfg* c)
 // ---------------------------------------------------------------------------------------- workspace
 // n_max token-rows in a forward, B micro-batch rows, n_sel rows whose logits are wanted,
 // slots = total key/value slots of the micro-batch.
-int ensure_workspace(ss_weights* w, int n_max, int B, int n_sel, size_t slots, int max_new, hipStream_t s)
+int ensure_workspace(const ss_weights* w, Lane& ln, int n_max, int B, int n_sel, size_t slots, int max_new, hipStream_t s)
 {
     const ss_model_cfg& c = w->cfg;
     const int d = c.d_model, F = c.d_ffn, V = c.vocab;
-    Workspace& ws = w->ws;
+    Workspace& ws = ln.ws;
     const size_t nr = (size_t)ss::round_up(n_max, 128);
     const size_t Bp = ss::round_up(B, 4), np = ss::round_up(n_max, 4), sp = ss::round_up(n_sel, 4);
     const size_t n_i32 = 4 + 3 * np + 5 * Bp + 2 * sp + (size_t)B * max_new;
-    w->kv_layer_stride = slots * d;
+    ln.kv_layer_stride = slots * d;
     // Partial-sum buffers hold [ksplit][rows][N] for whatever plan a forward over 1..n_max rows gets.
     // gate|up partial sums exist only when that projection runs with k-slices (never in the sweep kernel).
     struct Item { Buf* b; size_t bytes; bool zero; };
@@ -278,7 +291,7 @@ int ensure_workspace(ss_weights* w, int n_max, int B, int n_sel, size_t slots, i
     }
     // int32 arena: d_n d_step d_nlive d_active | tr_tok tr_row tr_pos [n_max] | live_row plen j0 limit cap [B] | am sel [n_sel] | out_tok
     int32_t* q = ws.ints.as<int32_t>();
-    MbState& st = w->st;
+    MbState& st = ln.st;
     st.d_n = q; st.d_step = q + 1; st.d_nlive = q + 2; st.d_active = q + 3; q += 4;
     st.tr_tok = q; q += np;
     st.tr_row = q; q += np;
@@ -289,7 +302,7 @@ int ensure_workspace(ss_weights* w, int n_max, int B, int n_sel, size_t slots, i
     st.row_limit = q; q += Bp;
     st.row_cap = q; q += Bp;
     st.am = q; q += sp;
-    w->d_sel = q; q += sp;
+    ln.d_sel = q; q += sp;
     st.out_tok = q;
     st.max_new = max_new;
     st.row_so = ws.i64s.as<int64_t>();
@@ -328,13 +341,13 @@ GemmArgs gemm_args(const ss_weights* w, const bf16_t* W, const bf16_t* X, const 
 // Runs the decoder over the token-rows described by the device state (st.d_n of them, at most n of
 // them: n sizes the grids and picks the kernel variants).  Logits are produced for n_sel rows:
 // the rows listed in d_sel, or the first *d_nsel rows when d_sel is null.  Ends with the token choice:
-// the argmax, or a draw from the softmax when the handle carries a temperature (w->cur_inv_temp).
-void forward(ss_weights* w, int n, int n_sel, const int32_t* d_sel, const int32_t* d_nsel, bool decode, hipStream_t s)
+// the argmax, or a draw from the softmax when the lane carries a temperature (cur_inv_temp).
+void forward(const ss_weights* w, Lane& ln, int n, int n_sel, const int32_t* d_sel, const int32_t* d_nsel, bool decode, hipStream_t s)
 {
     const ss_model_cfg& c = w->cfg;
     const int d = c.d_model, H = c.n_heads, hd = c.head_dim, F = c.d_ffn, V = c.vocab;
-    Workspace& ws = w->ws;
-    const MbState& st = w->st;
+    Workspace& ws = ln.ws;
+    const MbState& st = ln.st;
     float* x = ws.x.as<float>();
     bf16_t *h = ws.h.as<bf16_t>(), *h_lo = ws.h_lo.as<bf16_t>();
     bf16_t *ao = ws.ao.as<bf16_t>(), *ao_lo = ws.ao_lo.as<bf16_t>();
@@ -360,8 +373,8 @@ void forward(ss_weights* w, int n, int n_sel, const int32_t* d_sel, const int32_
     ss::launch_embed(st, w->embed, x, d, n, s);
     for (int l = 0; l < c.n_layers; ++l) {
         const Layer& L = w->layers[l];
-        ss::kv_t* kc = ws.kv.as<ss::kv_t>() + (size_t)l * 2 * w->kv_layer_stride;
-        ss::kv_t* vc = kc + w->kv_layer_stride;
+        ss::kv_t* kc = ws.kv.as<ss::kv_t>() + (size_t)l * 2 * ln.kv_layer_stride;
+        ss::kv_t* vc = kc + ln.kv_layer_stride;
         ss::launch_rmsnorm(st, x, l ? pd : nullptr, ks_d, st_d, L.attn_norm, c.rms_eps, nullptr, nullptr, h, h_lo, d, n, s);
         ss::launch_gemm(with_lo(mk(L.wqkv.p, h, h_lo, pqkv, nullptr, nullptr, 3 * d, d, n, 0, p_qkv), no_lo(SS_LO_QKV)),
                         ss::EPI_PARTIAL, s);
@@ -370,7 +383,7 @@ void forward(ss_weights* w, int n, int n_sel, const int32_t* d_sel, const int32_
                                         s);
         } else {        // prompt: every key of a row must be in place before any of its queries attends
             ss::launch_rope_append(st, pqkv, ks_qkv, st_qkv, qrot, kc, vc, w->rope_cos, w->rope_sin, d, H, hd, n, s);
-            ss::launch_attention_prompt(st, qrot, kc, vc, ao, ao_lo, d, H, hd, w->prompt_rows, w->prompt_max_len, s);
+            ss::launch_attention_prompt(st, qrot, kc, vc, ao, ao_lo, d, H, hd, ln.prompt_rows, ln.prompt_max_len, s);
         }
         ss::launch_gemm(with_lo(mk(L.wo.p, ao, ao_lo, pd, nullptr, nullptr, d, d, n, 0, p_o), no_lo(SS_LO_O)), ss::EPI_PARTIAL, s);
         ss::launch_rmsnorm(st, x, pd, ks_o, st_d, L.mlp_norm, c.rms_eps, nullptr, nullptr, h, h_lo, d, n, s);
@@ -390,9 +403,9 @@ void forward(ss_weights* w, int n, int n_sel, const int32_t* d_sel, const int32_
     ss::launch_gemm(with_lo(mk(w->lm_head.p, hsel, hsel_lo, ws.logits.as<float>(), nullptr, nullptr, V, d, n_sel, 0, p_lm),
                             no_lo(SS_LO_LM_HEAD)),
                     ss::EPI_PARTIAL, s);
-    if (w->cur_inv_temp > 0.f)
-        ss::launch_sample(ws.logits.as<float>(), V, d_nsel ? d_nsel : st.d_n, st, w->cur_draws, w->cur_ids, w->cur_seed,
-                          w->cur_inv_temp, n_sel, s);
+    if (ln.cur_inv_temp > 0.f)
+        ss::launch_sample(ws.logits.as<float>(), V, d_nsel ? d_nsel : st.d_n, st, ln.cur_draws, ln.cur_ids, ln.cur_seed,
+                          ln.cur_inv_temp, n_sel, s);
     else
         ss::launch_argmax(ws.logits.as<float>(), V, d_nsel ? d_nsel : st.d_n, st.am, n_sel, s);
 }
@@ -424,10 +437,10 @@ struct Upload {
 // Uploads the state of a prompt forward: token-rows are the concatenated prompt positions.
 //   lens[i]   tokens of row i processed by this forward (positions 0..lens[i]-1)
 //   slab[i]   key/value slots reserved for row i
-int upload_prompt_state(ss_weights* w, const int32_t* toks, const int32_t* offs, const int32_t* lens, int B,
+int upload_prompt_state(Lane& ln, const int32_t* toks, const int32_t* offs, const int32_t* lens, int B,
                         const int32_t* slab, const int32_t* limit, const std::vector<int32_t>& sel, hipStream_t s)
 {
-    const MbState& st = w->st;
+    const MbState& st = ln.st;
     int n = 0;
     for (int i = 0; i < B; ++i) n += lens[i];
     std::vector<int32_t> tok(n), row(n), pos(n), live(B), plen(B), first(B);
@@ -454,12 +467,12 @@ int upload_prompt_state(ss_weights* w, const int32_t* toks, const int32_t* offs,
     HIPCHK(hipMemcpyAsync(st.live_row, live.data(), (size_t)B * 4, hipMemcpyHostToDevice, s));
     HIPCHK(hipMemcpyAsync(st.row_plen, plen.data(), (size_t)B * 4, hipMemcpyHostToDevice, s));
     HIPCHK(hipMemcpyAsync(st.row_j0, first.data(), (size_t)B * 4, hipMemcpyHostToDevice, s));
-    w->prompt_rows = B;
-    w->prompt_max_len = *std::max_element(plen.begin(), plen.end());
+    ln.prompt_rows = B;
+    ln.prompt_max_len = *std::max_element(plen.begin(), plen.end());
     HIPCHK(hipMemcpyAsync(st.row_limit, limit, (size_t)B * 4, hipMemcpyHostToDevice, s));
     HIPCHK(hipMemcpyAsync(st.row_cap, slab, (size_t)B * 4, hipMemcpyHostToDevice, s));
     HIPCHK(hipMemcpyAsync(st.row_so, so.data(), (size_t)B * 8, hipMemcpyHostToDevice, s));
-    if (!sel.empty()) HIPCHK(hipMemcpyAsync(w->d_sel, sel.data(), sel.size() * 4, hipMemcpyHostToDevice, s));
+    if (!sel.empty()) HIPCHK(hipMemcpyAsync(ln.d_sel, sel.data(), sel.size() * 4, hipMemcpyHostToDevice, s));
     HIPCHK(hipStreamSynchronize(s));   // the host vectors above die with this frame
     return SS_OK;
 }
@@ -507,20 +520,20 @@ struct EventList {
 
 // Clears the handle's token-choice state however the call ends.
 struct ChoiceGuard {
-    ss_weights* w;
+    Lane& ln;
     ~ChoiceGuard()
     {
-        w->cur_draws = nullptr;
-        w->cur_ids = nullptr;
-        w->cur_seed = 0;
-        w->cur_inv_temp = 0.f;
+        ln.cur_draws = nullptr;
+        ln.cur_ids = nullptr;
+        ln.cur_seed = 0;
+        ln.cur_inv_temp = 0.f;
     }
 };
 
 // One micro-batch.  gen == nullptr: greedy, rows end at target_lens (known to the host, which therefore
 // knows the number of forwards and the live rows of each).  gen != nullptr: token choice and row ends per
 // gen (checked by the caller), target_lens ignored; the host learns how many rows are left by polling.
-int decode_microbatch_impl(ss_weights* w, const int32_t* prompt_tokens, const int32_t* prompt_offsets, int32_t B,
+int decode_microbatch_impl(const ss_weights* w, Lane& ln, const int32_t* prompt_tokens, const int32_t* prompt_offsets, int32_t B,
                            int32_t max_new, const int32_t* target_lens, const ss_gen_opts* gen, uint32_t flags,
                            int32_t* out_tokens, int32_t* out_lens, uint8_t* out_failed, ss_stats* stats, hipStream_t s)
 {
@@ -546,37 +559,37 @@ int decode_microbatch_impl(ss_weights* w, const int32_t* prompt_tokens, const in
         sel[i] = prompt_offsets[i + 1] - 1;
     }
     HIPCHK(hipSetDevice(w->device));
-    if (int rc = ensure_workspace(w, std::max(n_prompt, B), B, B, slots, max_new, s)) return rc;
-    const MbState& st = w->st;
+    if (int rc = ensure_workspace(w, ln, std::max(n_prompt, B), B, B, slots, max_new, s)) return rc;
+    const MbState& st = ln.st;
     const int compact = (flags & SS_COMPACT) ? 1 : 0;
     const int eos_id = gen ? gen->eos_id : -1;
 
-    if (int rc = upload_prompt_state(w, prompt_tokens, prompt_offsets, lens.data(), B, slab.data(), limit.data(), sel, s))
+    if (int rc = upload_prompt_state(ln, prompt_tokens, prompt_offsets, lens.data(), B, slab.data(), limit.data(), sel, s))
         return rc;
-    ChoiceGuard choice{w};
+    ChoiceGuard choice{ln};
     if (gen && gen->temperature > 0.f) {
         if (gen->draws) {
-            if (int rc = w->ws.draws.ensure((size_t)B * max_new * 4, false)) return rc;
-            HIPCHK(hipMemcpy2DAsync(w->ws.draws.p, (size_t)max_new * 4, gen->draws, (size_t)gen->draws_stride * 4,
+            if (int rc = ln.ws.draws.ensure((size_t)B * max_new * 4, false)) return rc;
+            HIPCHK(hipMemcpy2DAsync(ln.ws.draws.p, (size_t)max_new * 4, gen->draws, (size_t)gen->draws_stride * 4,
                                     (size_t)max_new * 4, B, hipMemcpyHostToDevice, s));
             HIPCHK(hipStreamSynchronize(s));
-            w->cur_draws = w->ws.draws.as<float>();
+            ln.cur_draws = ln.ws.draws.as<float>();
         } else {   // generated on the device from (seed, row id, token number)
             std::vector<int32_t> ids(B);
             for (int i = 0; i < B; ++i) ids[i] = gen->draw_ids ? gen->draw_ids[i] : i;
-            if (int rc = w->ws.draws.ensure((size_t)B * 4, false)) return rc;
-            HIPCHK(hipMemcpyAsync(w->ws.draws.p, ids.data(), (size_t)B * 4, hipMemcpyHostToDevice, s));
+            if (int rc = ln.ws.draws.ensure((size_t)B * 4, false)) return rc;
+            HIPCHK(hipMemcpyAsync(ln.ws.draws.p, ids.data(), (size_t)B * 4, hipMemcpyHostToDevice, s));
             HIPCHK(hipStreamSynchronize(s));
-            w->cur_ids = w->ws.draws.as<int32_t>();
-            w->cur_seed = gen->seed;
+            ln.cur_ids = ln.ws.draws.as<int32_t>();
+            ln.cur_seed = gen->seed;
         }
-        w->cur_inv_temp = 1.f / gen->temperature;
+        ln.cur_inv_temp = 1.f / gen->temperature;
     }
     ss::launch_fill_i32(st.out_tok, -1, (size_t)B * max_new, s);
 
-    const hipEvent_t e0 = w->ev[0], e1 = w->ev[1], e2 = w->ev[2];   // created with the handle: nothing is created per call
+    const hipEvent_t e0 = ln.ev[0], e1 = ln.ev[1], e2 = ln.ev[2];   // created with the handle: nothing is created per call
     HIPCHK(hipEventRecord(e0, s));
-    forward(w, n_prompt, B, w->d_sel, st.d_nlive, false, s);
+    forward(w, ln, n_prompt, B, ln.d_sel, st.d_nlive, false, s);
     ss::launch_step_update(st, compact, eos_id, s);
     HIPCHK(hipEventRecord(e1, s));
 
@@ -590,7 +603,7 @@ int decode_microbatch_impl(ss_weights* w, const int32_t* prompt_tokens, const in
             int n_live = B;
             if (compact)
                 n_live = (int)(sorted_limit.end() - std::upper_bound(sorted_limit.begin(), sorted_limit.end(), g));
-            forward(w, n_live, n_live, nullptr, nullptr, true, s);
+            forward(w, ln, n_live, n_live, nullptr, nullptr, true, s);
             ss::launch_step_update(st, compact, eos_id, s);
             row_steps += n_live;
         }
@@ -600,17 +613,17 @@ int decode_microbatch_impl(ss_weights* w, const int32_t* prompt_tokens, const in
         // count it has read (an upper bound: the kernels take the true count from device memory) and stops
         // when a read shows no unfinished row.
         auto poll = [&](int* n_live, int* active) -> int {
-            HIPCHK(hipMemcpyAsync(w->h_poll, st.d_n, 16, hipMemcpyDeviceToHost, s));
+            HIPCHK(hipMemcpyAsync(ln.h_poll, st.d_n, 16, hipMemcpyDeviceToHost, s));
             HIPCHK(hipStreamSynchronize(s));
             ++polls;
-            if (compact) *n_live = w->h_poll[2];
-            *active = w->h_poll[3];
+            if (compact) *n_live = ln.h_poll[2];
+            *active = ln.h_poll[3];
             return SS_OK;
         };
         int n_live = B, active = B;
         if (int rc = poll(&n_live, &active)) return rc;
         for (int g = 1; g < max_new && active > 0; ++g) {
-            forward(w, n_live, n_live, nullptr, nullptr, true, s);
+            forward(w, ln, n_live, n_live, nullptr, nullptr, true, s);
             ss::launch_step_update(st, compact, eos_id, s);
             row_steps += n_live;
             ++forwards;
@@ -679,12 +692,14 @@ extern "C" int ss_weights_create(const ss_model_cfg* cfg, const void* const* ten
         return rc;
     };
     if (hipGetDevice(&w->device) != hipSuccess) return bail(ss::fail(SS_EDEVICE, "hipGetDevice failed"));
-    if (hipStreamCreate(&w->stream) != hipSuccess) return bail(ss::fail(SS_EDEVICE, "hipStreamCreate failed"));
     if (int rc_s = scratch_address(w->device, &w->scratch_ptr)) return bail(rc_s);
-    if (hipHostMalloc((void**)&w->h_poll, 16, hipHostMallocDefault) != hipSuccess)
-        return bail(ss::fail(SS_ENOMEM, "hipHostMalloc failed"));
-    for (auto& e : w->ev)
-        if (hipEventCreate(&e) != hipSuccess) return bail(ss::fail(SS_EDEVICE, "hipEventCreate failed"));
+    for (Lane& ln : w->lane) {
+        if (hipStreamCreate(&ln.stream) != hipSuccess) return bail(ss::fail(SS_EDEVICE, "hipStreamCreate failed"));
+        if (hipHostMalloc((void**)&ln.h_poll, 16, hipHostMallocDefault) != hipSuccess)
+            return bail(ss::fail(SS_ENOMEM, "hipHostMalloc failed"));
+        for (auto& e : ln.ev)
+            if (hipEventCreate(&e) != hipSuccess) return bail(ss::fail(SS_EDEVICE, "hipEventCreate failed"));
+    }
 
     const int d = cfg->d_model, F = cfg->d_ffn, V = cfg->vocab, f32 = (src_dtype == SS_F32);
     Buf staging;
@@ -756,6 +771,11 @@ extern "C" int ss_set_option(ss_weights* w, int32_t option, int32_t value)
         w->prompt_lo_mask = value;
         return SS_OK;
     }
+    if (option == SS_OPT_IN_FLIGHT) {
+        if (value < 1 || value > kLanes) return ss::fail(SS_EINVAL, "SS_OPT_IN_FLIGHT takes 1 or %d", kLanes);
+        w->in_flight = value;
+        return SS_OK;
+    }
     return ss::fail(SS_EINVAL, "unknown option %d", option);
 }
 
@@ -768,13 +788,15 @@ extern "C" void ss_weights_destroy(ss_weights* w)
 {
     if (!w) return;
     (void)hipSetDevice(w->device);
-    if (w->stream) (void)hipStreamSynchronize(w->stream);
-    w->ws.release();
+    for (Lane& ln : w->lane) {
+        if (ln.stream) (void)hipStreamSynchronize(ln.stream);
+        ln.ws.release();
+        if (ln.stream) (void)hipStreamDestroy(ln.stream);
+        if (ln.h_poll) (void)hipHostFree(ln.h_poll);
+        for (auto& e : ln.ev)
+            if (e) (void)hipEventDestroy(e);
+    }
     for (void* p : w->allocs) (void)hipFree(p);
-    if (w->stream) (void)hipStreamDestroy(w->stream);
-    if (w->h_poll) (void)hipHostFree(w->h_poll);
-    for (auto& e : w->ev)
-        if (e) (void)hipEventDestroy(e);
     delete w;
 }
 
@@ -787,8 +809,9 @@ extern "C" int ss_decode_microbatch(ss_weights* w, const int32_t* prompt_tokens,
     if (!w) return ss::fail(SS_EINVAL, "weights handle is NULL");
     BusyGuard guard(w);
     if (!guard.ok) return ss::fail(SS_ESTATE, "another call is in flight on this handle");
-    hipStream_t s = hip_stream ? (hipStream_t)hip_stream : w->stream;
-    return decode_microbatch_impl(w, prompt_tokens, prompt_offsets, B, max_new, target_lens, nullptr, flags, out_tokens,
+    Lane& ln = w->lane[0];
+    hipStream_t s = hip_stream ? (hipStream_t)hip_stream : ln.stream;
+    return decode_microbatch_impl(w, ln, prompt_tokens, prompt_offsets, B, max_new, target_lens, nullptr, flags, out_tokens,
                                   out_lens, out_failed, stats, s);
 }
 
@@ -813,18 +836,19 @@ extern "C" int ss_decode_microbatch_static(ss_weights* w, const int32_t* prompt_
         }
     } sg(g_scratch_busy[w->device]);
     if (!sg.ok) return ss::fail(SS_ESTATE, "another static call is using this GPU's scratch array");
-    hipStream_t s = hip_stream ? (hipStream_t)hip_stream : w->stream;
+    Lane& ln = w->lane[0];
+    hipStream_t s = hip_stream ? (hipStream_t)hip_stream : ln.stream;
     // The handle's own (allocated, growable) workspace steps aside for the call; every buffer is a view into the
     // scratch array instead.  decode_microbatch_impl allocates nothing else on the device: its events belong to
     // the handle, its host staging lives on the host heap.
     Workspace view;
     view.arena = (char*)w->scratch_ptr;
     view.arena_bytes = kStaticScratchBytes;
-    std::swap(w->ws, view);
-    const int rc = decode_microbatch_impl(w, prompt_tokens, prompt_offsets, B, max_new, target_lens, nullptr, flags,
+    std::swap(ln.ws, view);
+    const int rc = decode_microbatch_impl(w, ln, prompt_tokens, prompt_offsets, B, max_new, target_lens, nullptr, flags,
                                           out_tokens, out_lens, out_failed, stats, s);
-    std::swap(w->ws, view);
-    w->st = MbState{};   // pointed into the scratch array; the next call lays its own state out
+    std::swap(ln.ws, view);
+    ln.st = MbState{};   // pointed into the scratch array; the next call lays its own state out
     return rc;
 }
 
@@ -840,8 +864,9 @@ extern "C" int ss_generate_microbatch(ss_weights* w, const int32_t* prompt_token
     if (int rc = check_gen_opts(w, opts, B, max_new)) return rc;
     BusyGuard guard(w);
     if (!guard.ok) return ss::fail(SS_ESTATE, "another call is in flight on this handle");
-    hipStream_t s = hip_stream ? (hipStream_t)hip_stream : w->stream;
-    return decode_microbatch_impl(w, prompt_tokens, prompt_offsets, B, max_new, nullptr, opts, flags, out_tokens,
+    Lane& ln = w->lane[0];
+    hipStream_t s = hip_stream ? (hipStream_t)hip_stream : ln.stream;
+    return decode_microbatch_impl(w, ln, prompt_tokens, prompt_offsets, B, max_new, nullptr, opts, flags, out_tokens,
                                   out_lens, out_failed, stats, s);
 }
 
@@ -854,7 +879,8 @@ extern "C" int ss_forward_logits(ss_weights* w, const int32_t* tokens, const int
     if (!n_prompt || !logits_out) return ss::fail(SS_EINVAL, "NULL argument");
     BusyGuard guard(w);
     if (!guard.ok) return ss::fail(SS_ESTATE, "another call is in flight on this handle");
-    hipStream_t s = hip_stream ? (hipStream_t)hip_stream : w->stream;
+    Lane& ln = w->lane[0];
+    hipStream_t s = hip_stream ? (hipStream_t)hip_stream : ln.stream;
     const int V = w->cfg.vocab;
     std::vector<int32_t> len(B), slab(B), limit(B, 1), np(n_prompt, n_prompt + B), sel;
     std::vector<size_t> out_base(B);
@@ -880,21 +906,21 @@ extern "C" int ss_forward_logits(ss_weights* w, const int32_t* tokens, const int
     }
     const int n_sel = (int)sel.size();
     HIPCHK(hipSetDevice(w->device));
-    if (int rc = ensure_workspace(w, std::max(n_p, B), B, std::max(n_sel, B), slots, 1, s)) return rc;
-    const MbState& st = w->st;
+    if (int rc = ensure_workspace(w, ln, std::max(n_p, B), B, std::max(n_sel, B), slots, 1, s)) return rc;
+    const MbState& st = ln.st;
     // prompt forward over the first n_prompt[i] tokens of every row
     std::vector<int32_t> ptoks, poffs(B + 1, 0);
     for (int i = 0; i < B; ++i) {
         ptoks.insert(ptoks.end(), tokens + offsets[i], tokens + offsets[i] + np[i]);
         poffs[i + 1] = (int32_t)ptoks.size();
     }
-    if (int rc = upload_prompt_state(w, ptoks.data(), poffs.data(), np.data(), B, slab.data(), limit.data(), sel, s))
+    if (int rc = upload_prompt_state(ln, ptoks.data(), poffs.data(), np.data(), B, slab.data(), limit.data(), sel, s))
         return rc;
     const int32_t nsel32 = n_sel;
     HIPCHK(hipMemcpyAsync(st.d_nlive, &nsel32, 4, hipMemcpyHostToDevice, s));
-    forward(w, n_p, n_sel, w->d_sel, st.d_nlive, false, s);
+    forward(w, ln, n_p, n_sel, ln.d_sel, st.d_nlive, false, s);
     std::vector<float> lg((size_t)std::max(n_sel, B) * V);
-    HIPCHK(hipMemcpyAsync(lg.data(), w->ws.logits.p, (size_t)n_sel * V * 4, hipMemcpyDeviceToHost, s));
+    HIPCHK(hipMemcpyAsync(lg.data(), ln.ws.logits.p, (size_t)n_sel * V * 4, hipMemcpyDeviceToHost, s));
     HIPCHK(hipStreamSynchronize(s));
     if (all_prompt_logits) {
         std::memcpy(logits_out, lg.data(), (size_t)n_sel * V * 4);
@@ -916,8 +942,8 @@ extern "C" int ss_forward_logits(ss_weights* w, const int32_t* tokens, const int
         HIPCHK(hipMemcpyAsync(st.tr_tok, tok.data(), (size_t)n * 4, hipMemcpyHostToDevice, s));
         HIPCHK(hipMemcpyAsync(st.tr_row, row.data(), (size_t)n * 4, hipMemcpyHostToDevice, s));
         HIPCHK(hipMemcpyAsync(st.tr_pos, pos.data(), (size_t)n * 4, hipMemcpyHostToDevice, s));
-        forward(w, n, n, nullptr, nullptr, true, s);
-        HIPCHK(hipMemcpyAsync(lg.data(), w->ws.logits.p, (size_t)n * V * 4, hipMemcpyDeviceToHost, s));
+        forward(w, ln, n, n, nullptr, nullptr, true, s);
+        HIPCHK(hipMemcpyAsync(lg.data(), ln.ws.logits.p, (size_t)n * V * 4, hipMemcpyDeviceToHost, s));
         HIPCHK(hipStreamSynchronize(s));
         for (int j = 0; j < n; ++j)
             std::memcpy(logits_out + (out_base[row[j]] + g) * V, lg.data() + (size_t)j * V, (size_t)V * 4);
@@ -929,6 +955,10 @@ extern "C" int ss_forward_logits(ss_weights* w, const int32_t* tokens, const int
 namespace {
 
 // The group pipeline shared by ss_run_group (gen == nullptr, lengths known) and ss_run_group_generate.
+// A pass over a plan hands its micro-batches out one at a time, longest cap first, to the lanes at work: one
+// lane (the calling thread) or two (a second host thread on lane 1 with its own stream and workspace), so that
+// one micro-batch's kernels fill the gaps between the other's.  What a query receives does not depend on the
+// lane or the order: micro-batches are independent, failures are sorted before they are rescheduled.
 int run_group_impl(ss_weights* w, const int32_t* prompt_tokens, const int32_t* prompt_offsets, int32_t n,
                    const int32_t* target_lens, const int32_t* pred_lens, int32_t bin, const ss_policy* policy,
                    const ss_gen_opts* gen, int32_t* out_tokens, int32_t* out_lens, ss_group_stats* stats, hipStream_t s)
@@ -943,13 +973,39 @@ int run_group_impl(ss_weights* w, const int32_t* prompt_tokens, const int32_t* p
     const int L = policy->base_len;
     const uint32_t eflags = policy->flags & SS_COMPACT;
     std::vector<int32_t> failed;
-    std::vector<int32_t> mb_toks, mb_offs, mb_tl, mb_out, mb_lens, mb_ids;
-    std::vector<float> mb_draws;
-    std::vector<uint8_t> mb_failed;
     for (size_t i = 0; i < (size_t)n * L; ++i) out_tokens[i] = -1;
 
-    auto run_plan = [&](const ss_plan* pl, bool first) -> int {
-        for (int k = 0; k < pl->n_mb; ++k) {
+    // state shared by the lanes of one pass
+    struct Pass {
+        const ss_plan* pl = nullptr;
+        bool first = true;
+        std::vector<int> order;        // micro-batch indices in the order they are handed out
+        std::atomic<int> next{0};
+        std::atomic<int> stop{0};
+        std::mutex mu;                 // guards gs, failed, rc/err and the progress lines
+        int rc = SS_OK;
+        std::string err;
+    };
+
+    // One lane's share of a pass.  Runs on the calling thread (lane 0) or on a thread of its own (lane 1).
+    auto work = [&](Pass& ps, Lane& ln, hipStream_t ls) {
+        std::vector<int32_t> mb_toks, mb_offs, mb_tl, mb_out, mb_lens, mb_ids;
+        std::vector<float> mb_draws;
+        std::vector<uint8_t> mb_failed;
+        const ss_plan* pl = ps.pl;
+        auto give_up = [&](int rc) {
+            std::lock_guard<std::mutex> lock(ps.mu);
+            if (ps.rc == SS_OK) {
+                ps.rc = rc;
+                ps.err = ss_last_error();
+            }
+            ps.stop.store(1);
+        };
+        if (hipSetDevice(w->device) != hipSuccess) return give_up(ss::fail(SS_EDEVICE, "hipSetDevice failed"));
+        while (!ps.stop.load()) {
+            const int at = ps.next.fetch_add(1);
+            if (at >= pl->n_mb) break;
+            const int k = ps.order[at];
             const int b0 = pl->mb_offsets[k], B = pl->mb_offsets[k + 1] - b0, cap = pl->mb_cap[k];
             const int32_t* src_tl = gen ? gen->target_lens : target_lens;
             mb_toks.clear();
@@ -980,10 +1036,11 @@ int run_group_impl(ss_weights* w, const int32_t* prompt_tokens, const int32_t* p
                 mbg.draw_ids = mb_ids.data();
                 mbg.target_lens = src_tl ? mb_tl.data() : nullptr;
             }
-            if (int rc = decode_microbatch_impl(w, mb_toks.data(), mb_offs.data(), B, cap, mb_tl.data(),
+            if (int rc = decode_microbatch_impl(w, ln, mb_toks.data(), mb_offs.data(), B, cap, mb_tl.data(),
                                                 gen ? &mbg : nullptr, eflags, mb_out.data(), mb_lens.data(),
-                                                mb_failed.data(), &st, s))
-                return rc;
+                                                mb_failed.data(), &st, ls))
+                return give_up(rc);
+            std::lock_guard<std::mutex> lock(ps.mu);
             for (int r = 0; r < B; ++r) {
                 const int qi = pl->query_idx[b0 + r];
                 // unfinished below the global limit: partial output and key/value state are dropped, the
@@ -1003,14 +1060,52 @@ int run_group_impl(ss_weights* w, const int32_t* prompt_tokens, const int32_t* p
             gs.decode_ms += st.decode_ms;
             gs.polls += st.polls;
             gs.idle_steps += st.idle_steps;
-            (first ? gs.n_mb_first : gs.n_mb_failure) += 1;
+            (ps.first ? gs.n_mb_first : gs.n_mb_failure) += 1;
             if (ss::verbose() > 0) {
                 std::fprintf(stderr, "[ss] %s micro-batch %d/%d: %d rows, cap %d, %d steps, %.0f ms\n",
-                             first ? "first-pass" : "recompute", k + 1, pl->n_mb, B, cap, st.steps,
+                             ps.first ? "first-pass" : "recompute", k + 1, pl->n_mb, B, cap, st.steps,
                              st.prefill_ms + st.decode_ms);
                 std::fflush(stderr);
             }
         }
+    };
+    // A lane's share with nothing escaping the thread it runs on.
+    auto work_noexcept = [&](Pass& ps, Lane& ln, hipStream_t ls) {
+        try {
+            work(ps, ln, ls);
+        } catch (...) {
+            std::lock_guard<std::mutex> lock(ps.mu);
+            if (ps.rc == SS_OK) {
+                ps.rc = SS_ENOMEM;
+                ps.err = "host allocation failed in a micro-batch";
+            }
+            ps.stop.store(1);
+        }
+    };
+
+    auto run_plan = [&](const ss_plan* pl, bool first) -> int {
+        Pass ps;
+        ps.pl = pl;
+        ps.first = first;
+        ps.order.resize((size_t)pl->n_mb);
+        std::iota(ps.order.begin(), ps.order.end(), 0);
+        const int lanes = std::min({w->in_flight, kLanes, (int)pl->n_mb});
+        if (lanes > 1)   // longest first, so that the pass does not end with one lane idle behind a long micro-batch
+            std::stable_sort(ps.order.begin(), ps.order.end(), [&](int a, int b) {
+                const int64_t ca = (int64_t)pl->mb_cap[a] * (64 + pl->mb_offsets[a + 1] - pl->mb_offsets[a]);
+                const int64_t cb = (int64_t)pl->mb_cap[b] * (64 + pl->mb_offsets[b + 1] - pl->mb_offsets[b]);
+                return ca > cb;
+            });
+        std::thread second;
+        if (lanes > 1) {
+            try {
+                second = std::thread([&] { work_noexcept(ps, w->lane[1], w->lane[1].stream); });
+            } catch (...) {   // no second thread to be had: the pass runs on this one alone
+            }
+        }
+        work_noexcept(ps, w->lane[0], s);
+        if (second.joinable()) second.join();
+        if (ps.rc != SS_OK) return ss::fail(ps.rc, "%s", ps.err.c_str());
         return SS_OK;
     };
 
@@ -1051,7 +1146,8 @@ extern "C" int ss_run_group(ss_weights* w, const int32_t* prompt_tokens, const i
         return ss::fail(SS_EINVAL, "NULL or empty argument");
     BusyGuard guard(w);
     if (!guard.ok) return ss::fail(SS_ESTATE, "another call is in flight on this handle");
-    hipStream_t s = hip_stream ? (hipStream_t)hip_stream : w->stream;
+    Lane& ln = w->lane[0];
+    hipStream_t s = hip_stream ? (hipStream_t)hip_stream : ln.stream;
     for (int i = 0; i < n; ++i)
         if (target_lens[i] < 1 || target_lens[i] > policy->base_len)
             return ss::fail(SS_EINVAL, "target_lens[%d] outside [1, base_len]", i);
@@ -1072,39 +1168,51 @@ extern "C" int ss_run_group_generate(ss_weights* w, const int32_t* prompt_tokens
     if (int rc = check_gen_opts(w, opts, n, policy->base_len)) return rc;
     BusyGuard guard(w);
     if (!guard.ok) return ss::fail(SS_ESTATE, "another call is in flight on this handle");
-    hipStream_t s = hip_stream ? (hipStream_t)hip_stream : w->stream;
+    Lane& ln = w->lane[0];
+    hipStream_t s = hip_stream ? (hipStream_t)hip_stream : ln.stream;
     return run_group_impl(w, prompt_tokens, prompt_offsets, n, nullptr, pred_lens, bin, policy, opts, out_tokens,
                           out_lens, stats, s);
 }
 
-extern "C" int ss_bench_decode_step(ss_weights* w, const int32_t* prompt_tokens, int32_t B, int32_t ctx,
-                                    int32_t iters, double* ms_out, void* hip_stream)
+namespace {
+
+// Prefills B rows of ctx tokens on a lane, then times iters decode forwards on it.  `gate`, when given, is
+// counted up after the prefill has finished and waited on until it reaches `parties`, so that several lanes
+// start their timed forwards together.
+int bench_decode_step_lane(const ss_weights* w, Lane& ln, hipStream_t s, const int32_t* prompt_tokens, int32_t B,
+                           int32_t ctx, int32_t iters, double* ms_out, std::atomic<int>* gate, int parties)
 {
-    ss::clear_error();
-    if (!w || !prompt_tokens || !ms_out) return ss::fail(SS_EINVAL, "NULL argument");
-    if (B <= 0 || B > ss::kMaxBatch || ctx < 1 || ctx + 1 > ss::kMaxPos || iters < 1)
-        return ss::fail(SS_EINVAL, "bad B / ctx / iters");
-    for (size_t t = 0; t < (size_t)B * ctx; ++t)
-        if (prompt_tokens[t] < 0 || prompt_tokens[t] >= w->cfg.vocab) return ss::fail(SS_EINVAL, "token id out of range");
-    BusyGuard guard(w);
-    if (!guard.ok) return ss::fail(SS_ESTATE, "another call is in flight on this handle");
-    hipStream_t s = hip_stream ? (hipStream_t)hip_stream : w->stream;
+    struct Arrive {   // a lane that fails before the gate must not leave the others waiting
+        std::atomic<int>* g;
+        bool done = false;
+        void now()
+        {
+            if (g && !done) g->fetch_add(1);
+            done = true;
+        }
+        ~Arrive() { now(); }
+    } arrive{gate};
     std::vector<int32_t> offs(B + 1), lens(B, ctx), slab(B, ctx + 1), limit(B, 2), sel(B);
     for (int i = 0; i <= B; ++i) offs[i] = i * ctx;
     for (int i = 0; i < B; ++i) sel[i] = (i + 1) * ctx - 1;
     HIPCHK(hipSetDevice(w->device));
-    if (int rc = ensure_workspace(w, B * ctx, B, B, (size_t)B * (ctx + 1), 2, s)) return rc;
-    const MbState& st = w->st;
-    if (int rc = upload_prompt_state(w, prompt_tokens, offs.data(), lens.data(), B, slab.data(), limit.data(), sel, s))
+    if (int rc = ensure_workspace(w, ln, B * ctx, B, B, (size_t)B * (ctx + 1), 2, s)) return rc;
+    const MbState& st = ln.st;
+    if (int rc = upload_prompt_state(ln, prompt_tokens, offs.data(), lens.data(), B, slab.data(), limit.data(), sel, s))
         return rc;
-    forward(w, B * ctx, B, w->d_sel, st.d_nlive, false, s);
+    forward(w, ln, B * ctx, B, ln.d_sel, st.d_nlive, false, s);
     ss::launch_step_update(st, 0, -1, s);   // token-rows of the decode step: every row at position ctx
     EventList evl;
     if (int rc = evl.create(iters + 1)) return rc;
     const std::vector<hipEvent_t>& ev = evl.e;
+    if (gate) {
+        HIPCHK(hipStreamSynchronize(s));
+        arrive.now();
+        while (gate->load() < parties) std::this_thread::yield();
+    }
     HIPCHK(hipEventRecord(ev[0], s));
     for (int it = 0; it < iters; ++it) {
-        forward(w, B, B, nullptr, nullptr, true, s);
+        forward(w, ln, B, B, nullptr, nullptr, true, s);
         HIPCHK(hipEventRecord(ev[it + 1], s));
     }
     HIPCHK(hipStreamSynchronize(s));
@@ -1117,6 +1225,59 @@ extern "C" int ss_bench_decode_step(ss_weights* w, const int32_t* prompt_tokens,
     return SS_OK;
 }
 
+int check_bench_decode_step(const ss_weights* w, const int32_t* prompt_tokens, int32_t B, int32_t ctx, int32_t iters,
+                            const double* ms_out)
+{
+    if (!w || !prompt_tokens || !ms_out) return ss::fail(SS_EINVAL, "NULL argument");
+    if (B <= 0 || B > ss::kMaxBatch || ctx < 1 || ctx + 1 > ss::kMaxPos || iters < 1)
+        return ss::fail(SS_EINVAL, "bad B / ctx / iters");
+    for (size_t t = 0; t < (size_t)B * ctx; ++t)
+        if (prompt_tokens[t] < 0 || prompt_tokens[t] >= w->cfg.vocab) return ss::fail(SS_EINVAL, "token id out of range");
+    return SS_OK;
+}
+
+}  // namespace
+
+extern "C" int ss_bench_decode_step(ss_weights* w, const int32_t* prompt_tokens, int32_t B, int32_t ctx,
+                                    int32_t iters, double* ms_out, void* hip_stream)
+{
+    ss::clear_error();
+    if (int rc = check_bench_decode_step(w, prompt_tokens, B, ctx, iters, ms_out)) return rc;
+    BusyGuard guard(w);
+    if (!guard.ok) return ss::fail(SS_ESTATE, "another call is in flight on this handle");
+    Lane& ln = w->lane[0];
+    hipStream_t s = hip_stream ? (hipStream_t)hip_stream : ln.stream;
+    return bench_decode_step_lane(w, ln, s, prompt_tokens, B, ctx, iters, ms_out, nullptr, 0);
+}
+
+extern "C" int ss_bench_decode_steps_in_flight(ss_weights* w, const int32_t* prompt_tokens, int32_t B, int32_t ctx,
+                                               int32_t iters, double* ms_out)
+{
+    ss::clear_error();
+    if (int rc = check_bench_decode_step(w, prompt_tokens, B, ctx, iters, ms_out)) return rc;
+    BusyGuard guard(w);
+    if (!guard.ok) return ss::fail(SS_ESTATE, "another call is in flight on this handle");
+    std::atomic<int> gate{0};
+    int rc1 = SS_OK;
+    std::string err1;
+    std::thread second;
+    try {
+        second = std::thread([&] {
+            rc1 = bench_decode_step_lane(w, w->lane[1], w->lane[1].stream, prompt_tokens, B, ctx, iters, ms_out + iters,
+                                         &gate, kLanes);
+            if (rc1) err1 = ss_last_error();
+        });
+    } catch (...) {
+        return ss::fail(SS_ESTATE, "could not start a second host thread");
+    }
+    const int rc0 = bench_decode_step_lane(w, w->lane[0], w->lane[0].stream, prompt_tokens, B, ctx, iters, ms_out, &gate,
+                                           kLanes);
+    second.join();
+    if (rc0) return rc0;
+    if (rc1) return ss::fail(rc1, "%s", err1.c_str());
+    return SS_OK;
+}
+
 extern "C" int ss_bench_weight_stream(ss_weights* w, int32_t B, int32_t iters, double* ms_out, int32_t* launches_out,
                                       void* hip_stream)
 {
@@ -1125,12 +1286,13 @@ extern "C" int ss_bench_weight_stream(ss_weights* w, int32_t B, int32_t iters, d
     if (B <= 0 || B > ss::kMaxBatch || iters < 1) return ss::fail(SS_EINVAL, "bad B / iters");
     BusyGuard guard(w);
     if (!guard.ok) return ss::fail(SS_ESTATE, "another call is in flight on this handle");
-    hipStream_t s = hip_stream ? (hipStream_t)hip_stream : w->stream;
+    Lane& ln = w->lane[0];
+    hipStream_t s = hip_stream ? (hipStream_t)hip_stream : ln.stream;
     HIPCHK(hipSetDevice(w->device));
-    if (int rc = ensure_workspace(w, B, B, B, (size_t)B, 1, s)) return rc;
+    if (int rc = ensure_workspace(w, ln, B, B, B, (size_t)B, 1, s)) return rc;
     const ss_model_cfg& c = w->cfg;
     const int d = c.d_model, F = c.d_ffn, V = c.vocab, Fp = ss::padded_k(F), n = B;
-    Workspace& ws = w->ws;
+    Workspace& ws = ln.ws;
     const Plans pl = make_plans(w, n, n);
     const ss::GemmPlan &p_qkv = pl.qkv, &p_o = pl.o, &p_gu = pl.gu, &p_d = pl.down, &p_lm = pl.lm;
     auto mk = [w](const bf16_t* W, const bf16_t* X, const bf16_t* Xlo, float* out, bf16_t* outp, bf16_t* outp_lo, int N,
@@ -1183,10 +1345,11 @@ extern "C" int ss_bench_read_stream(ss_weights* w, int32_t iters, double* ms_out
     if (iters < 1) return ss::fail(SS_EINVAL, "bad iters");
     BusyGuard guard(w);
     if (!guard.ok) return ss::fail(SS_ESTATE, "another call is in flight on this handle");
-    hipStream_t s = hip_stream ? (hipStream_t)hip_stream : w->stream;
+    Lane& ln = w->lane[0];
+    hipStream_t s = hip_stream ? (hipStream_t)hip_stream : ln.stream;
     HIPCHK(hipSetDevice(w->device));
-    if (int rc = w->ws.ints.ensure(64, false)) return rc;
-    uint32_t* sink = w->ws.ints.as<uint32_t>();
+    if (int rc = ln.ws.ints.ensure(64, false)) return rc;
+    uint32_t* sink = ln.ws.ints.as<uint32_t>();
     auto mat_bytes = [](const PackedMat& m) { return ((size_t)m.N * m.Kp * 2) & ~(size_t)0xffff; };
     EventList evl;
     if (int rc = evl.create(iters + 1)) return rc;

@@ -464,6 +464,45 @@ def test_tiny_group_every_policy_same_answers(tiny, flags):
         check_tokens_teacher_forced(om, w.prompt(i), r["tokens"][i, :t], what=f"query {i}")
 
 
+def test_group_results_do_not_depend_on_microbatches_in_flight(tiny):
+    """Two micro-batches in flight (two host threads, two streams, two workspaces) against one at a time: every
+    query's tokens and every counter of the group are the same, for known lengths and for sampled rows that end
+    by themselves, with failures and a recomputation pass in both."""
+    W, om, gw = tiny
+    flags = ("SORT", "BIN", "FCR", "VBS", "COMPACT")
+    w = synth.make_group(synth.TINY, 128, 777, ("uniform", 4, 30), ("lognormal", 14.0, 0.7, 1, 48), 0.3, 48, 8,
+                         flags, base_batch=4, max_batch=32)
+    pol = ss.make_policy(flags, 4, 48, 32)
+    draws = synth.make_draws(w.n, w.l_max, seed=11)
+    counters = ("steps", "padded_row_steps", "computed_row_steps", "n_failed", "useful_tokens", "n_mb_first",
+                "n_mb_failure", "prompt_tokens", "polls", "idle_steps")
+    got = {}
+    try:
+        for lanes in (1, 2, 2):
+            gw.set_option(ss.SS_OPT_IN_FLIGHT, lanes)
+            _say(f"tiny group of {w.n}, {lanes} in flight")
+            a = ss.ss_run_group(gw, w.prompt_tokens, w.prompt_offsets, w.target_lens, w.pred_lens, 8, pol)
+            b = ss.ss_run_group_generate(gw, w.prompt_tokens, w.prompt_offsets, w.pred_lens, 8, pol, eos_id=-1,
+                                         temperature=0.7, draws=draws, target_lens=w.target_lens, sync_every=1)
+            c = ss.ss_run_group(gw, w.prompt_tokens, w.prompt_offsets, w.target_lens, None, 0,
+                                ss.make_policy((), 4, 48, 32))
+            if not got:
+                got = dict(a=a, b=b, c=c)
+                assert a["stats"]["n_failed"] >= 1 and a["stats"]["n_mb_first"] >= 8
+                continue
+            for k, r in (("a", a), ("b", b), ("c", c)):
+                assert np.array_equal(r["tokens"], got[k]["tokens"]), k
+                assert np.array_equal(r["lens"], got[k]["lens"]), k
+                for name in counters:
+                    assert r["stats"][name] == got[k]["stats"][name], (k, name)
+    finally:
+        gw.set_option(ss.SS_OPT_IN_FLIGHT, ss.SS_IN_FLIGHT_DEFAULT)
+    with pytest.raises(ss.SsError):
+        gw.set_option(ss.SS_OPT_IN_FLIGHT, 3)
+    with pytest.raises(ss.SsError):
+        gw.set_option(ss.SS_OPT_IN_FLIGHT, 0)
+
+
 def test_runs_are_bit_repeatable(tiny, wide2):
     """Race canary: every reduction is ordered (no float atomics), so two runs of the same call must agree
     bit for bit - logits and tokens, skinny and tiled kernels, padded and compacted."""
