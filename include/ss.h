@@ -121,35 +121,19 @@ typedef struct ss_weights ss_weights; /* opaque; owns packed bf16 weights and a 
  *            The caller keeps ownership; the data is copied.
  * Requires n_heads*head_dim == d_model, head_dim in {64, 128}, d_model % 64 == 0 and <= 8192, d_ffn % 16 == 0,
  * vocab % 16 == 0.
- * Precision: weights are bf16; accumulation, softmax and normalisation are fp32; an activation that feeds a
- * projection is carried as the sum of two bf16 values; key/value cache slots are IEEE half (2 bytes per element,
- * 11 significand bits), saturating at +-65504.  Source values must be finite: they are not checked.  A row whose
- * logits are all NaN or -inf yields token id 0, never an id outside the vocabulary.
+ * Precision: weights are bf16 values (fp32 sources are rounded to bf16, nearest-even), held on the device as
+ * IEEE half: the same number for 2^-17 <= |w| <= 65504, rounded to a multiple of 2^-24 below that, saturated
+ * above.  An activation that feeds a projection is rounded to IEEE half once (11 significand bits); accumulation,
+ * softmax, normalisation and the residual stream are fp32; key/value cache slots are IEEE half (2 bytes per
+ * element).  Everything stored as half saturates at +-65504.  Source values must be finite: they are not checked.
+ * A row whose logits are all NaN or -inf yields token id 0, never an id outside the vocabulary.
  * Errors: SS_EINVAL (shape), SS_EDEVICE (no usable GPU / HIP error), SS_ENOMEM.
  */
 int  ss_weights_create(const ss_model_cfg* cfg, const void* const* tensors, int32_t src_dtype, ss_weights** out);
 void ss_weights_destroy(ss_weights* w);
 
 /*
- * Per-handle precision switch of the prompt forward ("instruction processing", Sec. 4.1, Overhead of Length
- * Prediction: it should cost no more than a few generated tokens).  An activation that feeds a projection is
- * carried as hi + lo (two bf16 values); in prompt forwards of more than 128 token-rows, where the projections are
- * bound by the matrix cores, a projection whose bit is clear in the mask contracts the hi part only (half the
- * matrix-core work, bf16 precision of that activation).  Decode forwards always use both parts.
- *   option SS_OPT_PROMPT_LO_MASK, value = OR of SS_LO_* bits of the projections that keep the lo part
- *   (SS_LO_ALL: every projection; the default SS_PROMPT_LO_DEFAULT is the cheapest set whose teacher-forced logit
- *   error stayed below 1e-2 of max|logit| at full depth, a third of the parity bar).
- * Errors (both options): SS_EINVAL (NULL handle, unknown option, value out of range), SS_ESTATE (a call is in flight).
- */
-#define SS_OPT_PROMPT_LO_MASK 1
-#define SS_LO_QKV 1
-#define SS_LO_O 2
-#define SS_LO_GATE_UP 4
-#define SS_LO_DOWN 8
-#define SS_LO_LM_HEAD 16
-#define SS_LO_ALL 31
-#define SS_PROMPT_LO_DEFAULT SS_LO_ALL
-/*
+ * Per-handle options.
  *   option SS_OPT_IN_FLIGHT, value = 1 or 2: how many micro-batches of a group pass (ss_run_group,
  *   ss_run_group_generate) are generated at the same time.  The micro-batches of a pass (Sec. 4.1) are independent
  *   of each other, and a decode step of a few rows leaves the memory system idle between its kernels; with 2 the
@@ -158,6 +142,7 @@ void ss_weights_destroy(ss_weights* w);
  *   tokens are the same as with 1; only the order in which micro-batches finish changes.  The stream argument of
  *   the call is used for one of the two; the other runs on a stream the handle owns.  The call returns when both
  *   are done.  Device time in the statistics is summed per micro-batch and so can exceed the wall time.
+ * Errors: SS_EINVAL (NULL handle, unknown option, value out of range), SS_ESTATE (a call is in flight).
  */
 #define SS_OPT_IN_FLIGHT 2
 #define SS_IN_FLIGHT_DEFAULT 2
@@ -298,8 +283,10 @@ typedef struct {
  * ss_decode_microbatch for rows that end by themselves: token choice per `opts`, a row ends when it emits
  * opts->eos_id, reaches its optional target length, or has emitted max_new tokens.  End detection, the
  * shrinking of the live batch and the sampling all run on the device; the host only polls a counter.
- * Given the same weights, prompts and draws the output of a row does not depend on B, on flags, on
- * sync_every or on the other rows.
+ * Given the same weights, prompts and draws the output of a row does not depend on flags, on sync_every or on
+ * what the other rows hold; across batch compositions that change the launch shapes (the total prompt length,
+ * the number of 16-row strips) logits agree to about 1e-3 of the largest, and a sampled token can differ where its
+ * draw lies within that of an interval edge.
  *   out_lens    host, int32[B]: tokens emitted (the end-of-sequence token included)
  *   out_failed  host, uint8[B]: the row was still unfinished after max_new tokens (Sec. 4.1 failure)
  * Other arguments, ownership and errors as ss_decode_microbatch; additionally SS_EINVAL for a NULL opts,
@@ -313,7 +300,9 @@ int ss_generate_microbatch(ss_weights* w, const int32_t* prompt_tokens, const in
 /*
  * ss_run_group for rows that end by themselves.  opts->draws, opts->draw_ids and opts->target_lens are indexed
  * by query (n rows, stride draws_stride >= policy->base_len), so a recomputed query sees the same draws and
- * repeats its first attempt token for token before going on.  A query that is unfinished at a cap below
+ * repeats its first attempt before going on, except where a draw lies so close to an edge of its token's
+ * probability interval that the rounding differences between two batch compositions (logits agree to about 1e-3 of
+ * the largest) decide it the other way.  A query that is unfinished at a cap below
  * policy->base_len is collected and recomputed with cap = base_len; one that is unfinished at base_len is
  * complete (truncated there).  stats->useful_tokens = sum of out_lens.
  */

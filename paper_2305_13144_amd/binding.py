@@ -18,9 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libss.so")
 SS_OK, SS_EINVAL, SS_ENOMEM, SS_EDEVICE, SS_ESTATE = 0, -1, -2, -3, -4
 SS_SORT, SS_BIN, SS_FCR, SS_VBS, SS_COMPACT = 1, 2, 4, 8, 16
 SS_VBS_CLAMP_FLOOR, SS_VBS_PAPER_POW2 = 0, 1
-SS_OPT_PROMPT_LO_MASK = 1
 SS_OPT_IN_FLIGHT, SS_IN_FLIGHT_DEFAULT = 2, 2
-SS_LO_QKV, SS_LO_O, SS_LO_GATE_UP, SS_LO_DOWN, SS_LO_LM_HEAD, SS_LO_ALL = 1, 2, 4, 8, 16, 31
 SS_BF16, SS_F32 = 0, 1
 FLAG_BITS = dict(SORT=SS_SORT, BIN=SS_BIN, FCR=SS_FCR, VBS=SS_VBS, COMPACT=SS_COMPACT)
 

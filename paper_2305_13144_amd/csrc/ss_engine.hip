@@ -19,6 +19,7 @@
 #include "ss_kernels.h"
 
 using ss::bf16_t;
+using ss::f16_t;
 using ss::GemmArgs;
 using ss::MbState;
 using ss::PackedMat;
@@ -106,14 +107,13 @@ struct Buf {
 };
 
 struct Workspace {
-    Buf x, h, h_lo, ao, ao_lo, act, act_lo, qrot, pqkv, pd, pgu, hsel, hsel_lo, logits, kv, ints, i64s, draws;
+    Buf x, h, ao, act, qrot, pqkv, pd, pgu, hsel, logits, kv, ints, i64s, draws;
     // Non-null: every buffer is carved out of [arena, arena + arena_bytes) instead of being allocated.
     char* arena = nullptr;
     size_t arena_bytes = 0;
     void release()
     {
-        for (Buf* b : {&x, &h, &h_lo, &ao, &ao_lo, &act, &act_lo, &qrot, &pqkv, &pd, &pgu, &hsel, &hsel_lo, &logits, &kv,
-                       &ints, &i64s, &draws})
+        for (Buf* b : {&x, &h, &ao, &act, &qrot, &pqkv, &pd, &pgu, &hsel, &logits, &kv, &ints, &i64s, &draws})
             b->release();
     }
 };
@@ -152,12 +152,11 @@ struct ss_weights {
     bf16_t* final_norm = nullptr;
     PackedMat lm_head;
     float *rope_cos = nullptr, *rope_sin = nullptr;
-    bf16_t* zero_blk = nullptr;   // 1 KiB of zeros (see GemmArgs::zero_blk)
+    f16_t* zero_blk = nullptr;    // 1 KiB of zeros (see GemmArgs::zero_blk)
     int n_cu = 256;               // compute units of the device
     Lane lane[kLanes];
     std::atomic<int> busy{0};
     void* scratch_ptr = nullptr;   // device address of this device's static scratch array
-    int prompt_lo_mask = SS_PROMPT_LO_DEFAULT;  // projections whose activations keep their lo part in prompt forwards
     int in_flight = SS_IN_FLIGHT_DEFAULT;       // micro-batches a group pass keeps in flight (1 or 2)
 };
 
@@ -186,7 +185,7 @@ int dev_alloc(ss_weights* w, void** out, size_t bytes, bool zero)
 
 // Uploads a row-major host matrix through a staging buffer and packs it into dst (Sec. of ss_internal.h
 // on the operand layout).  Source row r -> packed row (r/16*blk_stride + blk_off)*16 + r%16.
-int upload_pack(ss_weights* w, Buf& staging, const void* host, int src_f32, int n_src, int k, bf16_t* dst, int kp,
+int upload_pack(ss_weights* w, Buf& staging, const void* host, int src_f32, int n_src, int k, f16_t* dst, int kp,
                 int blk_stride, int blk_off)
 {
     const size_t bytes = (size_t)n_src * k * (src_f32 ? 4 : 2);
@@ -217,7 +216,7 @@ int alloc_packed(ss_weights* w, PackedMat* m, int n, int k)
     m->Kp = ss::padded_k(k);
     void* p = nullptr;
     if (int rc = dev_alloc(w, &p, (size_t)n * m->Kp * 2, m->Kp != k)) return rc;
-    m->p = (bf16_t*)p;
+    m->p = (f16_t*)p;
     return SS_OK;
 }
 
@@ -253,17 +252,13 @@ int ensure_workspace(const ss_weights* w, Lane& ln, int n_max, int B, int n_sel,
     const Item items[] = {
         {&ws.x, nr * d * 4, false},
         {&ws.h, nr * d * 2, true},
-        {&ws.h_lo, nr * d * 2, true},
         {&ws.ao, nr * d * 2, true},
-        {&ws.ao_lo, nr * d * 2, true},
         {&ws.act, nr * ss::padded_k(F) * 2, true},
-        {&ws.act_lo, nr * ss::padded_k(F) * 2, true},
         {&ws.qrot, nr * d * 4, false},
         {&ws.pqkv, ss::gemm_partial_rows_bound(3 * d, n_max) * 3 * d * 4, false},
         {&ws.pd, ss::gemm_partial_rows_bound(d, n_max) * d * 4, false},
         {&ws.pgu, ss::gemm_partial_rows_bound(2 * F, n_max, true) * 2 * F * 4, false},
         {&ws.hsel, (size_t)ss::round_up(n_sel, 128) * d * 2, true},
-        {&ws.hsel_lo, (size_t)ss::round_up(n_sel, 128) * d * 2, true},
         {&ws.logits, (size_t)ss::round_up(n_sel, 16) * V * 4, false},
         {&ws.kv, (size_t)c.n_layers * 2 * slots * d * 2, false},
         {&ws.ints, n_i32 * 4, false},
@@ -327,11 +322,11 @@ Plans make_plans(const ss_weights* w, int n, int n_sel)
     return p;
 }
 
-GemmArgs gemm_args(const ss_weights* w, const bf16_t* W, const bf16_t* X, const bf16_t* Xlo, float* out, bf16_t* outp,
-                   bf16_t* outp_lo, int N, int Kp, int rows, int kp_out, const ss::GemmPlan& p)
+GemmArgs gemm_args(const ss_weights* w, const f16_t* W, const f16_t* X, float* out, f16_t* outp, int N, int Kp, int rows,
+                   int kp_out, const ss::GemmPlan& p)
 {
     GemmArgs g{};
-    g.W = W; g.X = X; g.X_lo = Xlo; g.out = out; g.out_packed = outp; g.out_packed_lo = outp_lo; g.N = N; g.Kp = Kp;
+    g.W = W; g.X = X; g.out = out; g.out_packed = outp; g.N = N; g.Kp = Kp;
     g.m_rows = rows; g.m_stride = rows; g.kp_out = kp_out; g.ksplit = p.ksplit; g.nb = p.nb; g.kd = p.kd;
     g.kp = p.kp; g.sweep_p = p.sweep_p; g.sweep_gn = p.sweep_gn; g.sweep_kh = p.sweep_kh; g.zero_blk = w->zero_blk;
     return g;
@@ -349,9 +344,7 @@ void forward(const ss_weights* w, Lane& ln, int n, int n_sel, const int32_t* d_s
     Workspace& ws = ln.ws;
     const MbState& st = ln.st;
     float* x = ws.x.as<float>();
-    bf16_t *h = ws.h.as<bf16_t>(), *h_lo = ws.h_lo.as<bf16_t>();
-    bf16_t *ao = ws.ao.as<bf16_t>(), *ao_lo = ws.ao_lo.as<bf16_t>();
-    bf16_t *act = ws.act.as<bf16_t>(), *act_lo = ws.act_lo.as<bf16_t>();
+    f16_t *h = ws.h.as<f16_t>(), *ao = ws.ao.as<f16_t>(), *act = ws.act.as<f16_t>();
     float* qrot = ws.qrot.as<float>();
     float* pqkv = ws.pqkv.as<float>();
     float* pd = ws.pd.as<float>();
@@ -361,48 +354,35 @@ void forward(const ss_weights* w, Lane& ln, int n, int n_sel, const int32_t* d_s
     const ss::GemmPlan &p_qkv = pl.qkv, &p_o = pl.o, &p_gu = pl.gu, &p_d = pl.down, &p_lm = pl.lm;
     const int ks_qkv = p_qkv.ksplit, ks_o = p_o.ksplit, ks_d = p_d.ksplit;
     const size_t st_qkv = (size_t)n * 3 * d, st_d = (size_t)n * d;
-    auto mk = [w](const bf16_t* W, const bf16_t* X, const bf16_t* Xlo, float* out, bf16_t* outp, bf16_t* outp_lo, int N,
-                  int Kp, int rows, int kp_out, const ss::GemmPlan& p) {
-        return gemm_args(w, W, X, Xlo, out, outp, outp_lo, N, Kp, rows, kp_out, p);
-    };
-
-    // prompt forwards: which projections run without the activations' lo part in the tiled kernel
-    auto no_lo = [&](int bit) { return (!decode && !(w->prompt_lo_mask & bit)) ? 1 : 0; };
-    auto with_lo = [](GemmArgs g, int no) { g.tiled_no_lo = no; return g; };
+    auto mk = [w](const f16_t* W, const f16_t* X, float* out, f16_t* outp, int N, int Kp, int rows, int kp_out,
+                  const ss::GemmPlan& p) { return gemm_args(w, W, X, out, outp, N, Kp, rows, kp_out, p); };
 
     ss::launch_embed(st, w->embed, x, d, n, s);
     for (int l = 0; l < c.n_layers; ++l) {
         const Layer& L = w->layers[l];
         ss::kv_t* kc = ws.kv.as<ss::kv_t>() + (size_t)l * 2 * ln.kv_layer_stride;
         ss::kv_t* vc = kc + ln.kv_layer_stride;
-        ss::launch_rmsnorm(st, x, l ? pd : nullptr, ks_d, st_d, L.attn_norm, c.rms_eps, nullptr, nullptr, h, h_lo, d, n, s);
-        ss::launch_gemm(with_lo(mk(L.wqkv.p, h, h_lo, pqkv, nullptr, nullptr, 3 * d, d, n, 0, p_qkv), no_lo(SS_LO_QKV)),
-                        ss::EPI_PARTIAL, s);
+        ss::launch_rmsnorm(st, x, l ? pd : nullptr, ks_d, st_d, L.attn_norm, c.rms_eps, nullptr, nullptr, h, d, n, s);
+        ss::launch_gemm(mk(L.wqkv.p, h, pqkv, nullptr, 3 * d, d, n, 0, p_qkv), ss::EPI_PARTIAL, s);
         if (decode) {   // one token-row per row: rotation and append are fused into the attention kernel
-            ss::launch_attention_decode(st, pqkv, ks_qkv, st_qkv, kc, vc, w->rope_cos, w->rope_sin, ao, ao_lo, d, H, hd, n,
-                                        s);
+            ss::launch_attention_decode(st, pqkv, ks_qkv, st_qkv, kc, vc, w->rope_cos, w->rope_sin, ao, d, H, hd, n, s);
         } else {        // prompt: every key of a row must be in place before any of its queries attends
             ss::launch_rope_append(st, pqkv, ks_qkv, st_qkv, qrot, kc, vc, w->rope_cos, w->rope_sin, d, H, hd, n, s);
-            ss::launch_attention_prompt(st, qrot, kc, vc, ao, ao_lo, d, H, hd, ln.prompt_rows, ln.prompt_max_len, s);
+            ss::launch_attention_prompt(st, qrot, kc, vc, ao, d, H, hd, ln.prompt_rows, ln.prompt_max_len, s);
         }
-        ss::launch_gemm(with_lo(mk(L.wo.p, ao, ao_lo, pd, nullptr, nullptr, d, d, n, 0, p_o), no_lo(SS_LO_O)), ss::EPI_PARTIAL, s);
-        ss::launch_rmsnorm(st, x, pd, ks_o, st_d, L.mlp_norm, c.rms_eps, nullptr, nullptr, h, h_lo, d, n, s);
+        ss::launch_gemm(mk(L.wo.p, ao, pd, nullptr, d, d, n, 0, p_o), ss::EPI_PARTIAL, s);
+        ss::launch_rmsnorm(st, x, pd, ks_o, st_d, L.mlp_norm, c.rms_eps, nullptr, nullptr, h, d, n, s);
         if (p_gu.ksplit == 1) {
-            ss::launch_gemm(with_lo(mk(L.wgu.p, h, h_lo, nullptr, act, act_lo, 2 * F, d, n, Fp, p_gu), no_lo(SS_LO_GATE_UP)),
-                            ss::EPI_SWIGLU, s);
+            ss::launch_gemm(mk(L.wgu.p, h, nullptr, act, 2 * F, d, n, Fp, p_gu), ss::EPI_SWIGLU, s);
         } else {   // k-sliced: partial sums, then one small kernel adds them and applies SwiGLU
-            ss::launch_gemm(with_lo(mk(L.wgu.p, h, h_lo, ws.pgu.as<float>(), nullptr, nullptr, 2 * F, d, n, 0, p_gu),
-                                    no_lo(SS_LO_GATE_UP)),
-                            ss::EPI_PARTIAL, s);
-            ss::launch_swiglu_reduce(ws.pgu.as<float>(), p_gu.ksplit, (size_t)n * 2 * F, n, F, Fp, act, act_lo, s);
+            ss::launch_gemm(mk(L.wgu.p, h, ws.pgu.as<float>(), nullptr, 2 * F, d, n, 0, p_gu), ss::EPI_PARTIAL, s);
+            ss::launch_swiglu_reduce(ws.pgu.as<float>(), p_gu.ksplit, (size_t)n * 2 * F, n, F, Fp, act, s);
         }
-        ss::launch_gemm(with_lo(mk(L.wd.p, act, act_lo, pd, nullptr, nullptr, d, Fp, n, 0, p_d), no_lo(SS_LO_DOWN)), ss::EPI_PARTIAL, s);
+        ss::launch_gemm(mk(L.wd.p, act, pd, nullptr, d, Fp, n, 0, p_d), ss::EPI_PARTIAL, s);
     }
-    bf16_t *hsel = ws.hsel.as<bf16_t>(), *hsel_lo = ws.hsel_lo.as<bf16_t>();
-    ss::launch_rmsnorm(st, x, pd, ks_d, st_d, w->final_norm, c.rms_eps, d_sel, d_nsel, hsel, hsel_lo, d, n_sel, s);
-    ss::launch_gemm(with_lo(mk(w->lm_head.p, hsel, hsel_lo, ws.logits.as<float>(), nullptr, nullptr, V, d, n_sel, 0, p_lm),
-                            no_lo(SS_LO_LM_HEAD)),
-                    ss::EPI_PARTIAL, s);
+    f16_t* hsel = ws.hsel.as<f16_t>();
+    ss::launch_rmsnorm(st, x, pd, ks_d, st_d, w->final_norm, c.rms_eps, d_sel, d_nsel, hsel, d, n_sel, s);
+    ss::launch_gemm(mk(w->lm_head.p, hsel, ws.logits.as<float>(), nullptr, V, d, n_sel, 0, p_lm), ss::EPI_PARTIAL, s);
     if (ln.cur_inv_temp > 0.f)
         ss::launch_sample(ws.logits.as<float>(), V, d_nsel ? d_nsel : st.d_n, st, ln.cur_draws, ln.cur_ids, ln.cur_seed,
                           ln.cur_inv_temp, n_sel, s);
@@ -743,7 +723,7 @@ extern "C" int ss_weights_create(const ss_model_cfg* cfg, const void* const* ten
     }
     void* p = nullptr;
     if ((rc = dev_alloc(w, &p, 1024, true))) return done(rc);
-    w->zero_blk = (bf16_t*)p;
+    w->zero_blk = (f16_t*)p;
     hipDeviceProp_t prop;
     if (hipGetDeviceProperties(&prop, w->device) != hipSuccess || prop.multiProcessorCount <= 0)
         return done(ss::fail(SS_EDEVICE, "cannot read the device's compute unit count"));
@@ -766,11 +746,6 @@ extern "C" int ss_set_option(ss_weights* w, int32_t option, int32_t value)
     if (!w) return ss::fail(SS_EINVAL, "weights handle is NULL");
     BusyGuard guard(w);
     if (!guard.ok) return ss::fail(SS_ESTATE, "another call is in flight on this handle");
-    if (option == SS_OPT_PROMPT_LO_MASK) {
-        if (value < 0 || value > SS_LO_ALL) return ss::fail(SS_EINVAL, "SS_OPT_PROMPT_LO_MASK takes a mask of SS_LO_* bits");
-        w->prompt_lo_mask = value;
-        return SS_OK;
-    }
     if (option == SS_OPT_IN_FLIGHT) {
         if (value < 1 || value > kLanes) return ss::fail(SS_EINVAL, "SS_OPT_IN_FLIGHT takes 1 or %d", kLanes);
         w->in_flight = value;
@@ -1295,12 +1270,9 @@ extern "C" int ss_bench_weight_stream(ss_weights* w, int32_t B, int32_t iters, d
     Workspace& ws = ln.ws;
     const Plans pl = make_plans(w, n, n);
     const ss::GemmPlan &p_qkv = pl.qkv, &p_o = pl.o, &p_gu = pl.gu, &p_d = pl.down, &p_lm = pl.lm;
-    auto mk = [w](const bf16_t* W, const bf16_t* X, const bf16_t* Xlo, float* out, bf16_t* outp, bf16_t* outp_lo, int N,
-                  int Kp, int rows, int kp_out, const ss::GemmPlan& p) {
-        return gemm_args(w, W, X, Xlo, out, outp, outp_lo, N, Kp, rows, kp_out, p);
-    };
-    bf16_t *h = ws.h.as<bf16_t>(), *ao = ws.ao.as<bf16_t>(), *act = ws.act.as<bf16_t>();
-    bf16_t *h_lo = ws.h_lo.as<bf16_t>(), *ao_lo = ws.ao_lo.as<bf16_t>(), *act_lo = ws.act_lo.as<bf16_t>();
+    auto mk = [w](const f16_t* W, const f16_t* X, float* out, f16_t* outp, int N, int Kp, int rows, int kp_out,
+                  const ss::GemmPlan& p) { return gemm_args(w, W, X, out, outp, N, Kp, rows, kp_out, p); };
+    f16_t *h = ws.h.as<f16_t>(), *ao = ws.ao.as<f16_t>(), *act = ws.act.as<f16_t>();
     float *pqkv = ws.pqkv.as<float>(), *pd = ws.pd.as<float>();
     EventList evl;
     if (int rc = evl.create(iters + 1)) return rc;
@@ -1311,18 +1283,16 @@ extern "C" int ss_bench_weight_stream(ss_weights* w, int32_t B, int32_t iters, d
         launches = 0;
         for (int l = 0; l < c.n_layers; ++l) {
             const Layer& L = w->layers[l];
-            ss::launch_gemm(mk(L.wqkv.p, h, h_lo, pqkv, nullptr, nullptr, 3 * d, d, n, 0, p_qkv), ss::EPI_PARTIAL, s);
-            ss::launch_gemm(mk(L.wo.p, ao, ao_lo, pd, nullptr, nullptr, d, d, n, 0, p_o), ss::EPI_PARTIAL, s);
+            ss::launch_gemm(mk(L.wqkv.p, h, pqkv, nullptr, 3 * d, d, n, 0, p_qkv), ss::EPI_PARTIAL, s);
+            ss::launch_gemm(mk(L.wo.p, ao, pd, nullptr, d, d, n, 0, p_o), ss::EPI_PARTIAL, s);
             if (p_gu.ksplit == 1)
-                ss::launch_gemm(mk(L.wgu.p, h, h_lo, nullptr, act, act_lo, 2 * F, d, n, Fp, p_gu), ss::EPI_SWIGLU, s);
+                ss::launch_gemm(mk(L.wgu.p, h, nullptr, act, 2 * F, d, n, Fp, p_gu), ss::EPI_SWIGLU, s);
             else
-                ss::launch_gemm(mk(L.wgu.p, h, h_lo, ws.pgu.as<float>(), nullptr, nullptr, 2 * F, d, n, 0, p_gu),
-                                ss::EPI_PARTIAL, s);
-            ss::launch_gemm(mk(L.wd.p, act, act_lo, pd, nullptr, nullptr, d, Fp, n, 0, p_d), ss::EPI_PARTIAL, s);
+                ss::launch_gemm(mk(L.wgu.p, h, ws.pgu.as<float>(), nullptr, 2 * F, d, n, 0, p_gu), ss::EPI_PARTIAL, s);
+            ss::launch_gemm(mk(L.wd.p, act, pd, nullptr, d, Fp, n, 0, p_d), ss::EPI_PARTIAL, s);
             launches += 4;
         }
-        ss::launch_gemm(mk(w->lm_head.p, ws.hsel.as<bf16_t>(), ws.hsel_lo.as<bf16_t>(), ws.logits.as<float>(), nullptr,
-                           nullptr, V, d, n, 0, p_lm),
+        ss::launch_gemm(mk(w->lm_head.p, ws.hsel.as<f16_t>(), ws.logits.as<float>(), nullptr, V, d, n, 0, p_lm),
                         ss::EPI_PARTIAL, s);
         launches += 1;
         HIPCHK(hipEventRecord(ev[it + 1], s));

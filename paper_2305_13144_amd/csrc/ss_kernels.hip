@@ -1,5 +1,5 @@
 // gfx950 kernels of the decode path.  One wavefront = 64 lanes; matrix work uses
-// v_mfma_f32_16x16x32_bf16 (A: 16 rows x 32 k, B: 32 k x 16 cols, 8 bf16 per lane;
+// v_mfma_f32_16x16x32_f16 (A: 16 rows x 32 k, B: 32 k x 16 cols, 8 halves per lane;
 // D: lane holds rows 4*(lane/16)..+3 of column lane%16).
 //
 // Convention for every contraction here: the weight strip is the A operand (its 16 output
@@ -15,7 +15,8 @@
 
 namespace ss {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));  // one 16-byte operand fragment
 
@@ -29,14 +30,15 @@ __device__ __forceinline__ bf16_t f2bf(float f)
     return (bf16_t)(u >> 16);
 }
 
-// Activations that feed an MFMA are stored as the sum of two bf16 values, hi = bf16(v) and
-// lo = bf16(v - hi): the contraction runs once per part, so products carry ~16 significand bits of the
-// activation while the weights stay plain bf16.  One bf16 rounding per projection input, six per layer
-// over 32+ layers, is otherwise the dominant term of the logit error.
-__device__ __forceinline__ void split_bf(float v, bf16_t& hi, bf16_t& lo)
+// Both operands of every projection are IEEE half.  A bf16 weight keeps its exact value in that format (8
+// significand bits fit in 11; see k_pack_weight for the two ends of the range).  An activation that feeds a
+// projection is rounded to half once: 11 significand bits, where a bf16 operand would keep 8 - one such rounding
+// per projection input, six per layer over 32+ layers, is the dominant term of the logit error, and at 8 bits it
+// is as large as the whole tolerance.  Finite values saturate, like the key/value slots below; a NaN stays a NaN.
+__device__ __forceinline__ f16_t f2h(float f)
 {
-    hi = f2bf(v);
-    lo = f2bf(v - bf2f(hi));
+    const float c = fminf(fmaxf(f, -65504.f), 65504.f);   // of a NaN and a number these return the number
+    return __builtin_bit_cast(f16_t, (_Float16)(f != f ? f : c));
 }
 
 // Key/value slots are stored as IEEE half: the same 2 bytes per element as bf16 with three more
@@ -71,9 +73,11 @@ __device__ __forceinline__ float wave_max(float v)
 }
 
 // ------------------------------------------------------------------------------------------ weight packing
-// src is row-major [n_src, k] (bf16 bits or fp32); source row r lands in packed row
-// (r/16 * blk_stride + blk_off) * 16 + r%16.  One thread moves 8 consecutive k.
-__global__ void k_pack_weight(const void* __restrict__ src, int src_f32, bf16_t* __restrict__ dst, int n_src, int k,
+// src is row-major [n_src, k] (bf16 bits or fp32, rounded to bf16 first); source row r lands in packed row
+// (r/16 * blk_stride + blk_off) * 16 + r%16.  One thread moves 8 consecutive k.  The packed element is the bf16
+// value written as IEEE half: the same number for 2^-17 <= |w| <= 65504 (half subnormals included); smaller
+// magnitudes are rounded to a multiple of 2^-24 (an absolute error below 3e-8 per weight), larger ones saturate.
+__global__ void k_pack_weight(const void* __restrict__ src, int src_f32, f16_t* __restrict__ dst, int n_src, int k,
                               int kp, int blk_stride, int blk_off)
 {
     const int groups = k >> 3;
@@ -89,8 +93,11 @@ __global__ void k_pack_weight(const void* __restrict__ src, int src_f32, bf16_t*
             const uint4 raw = *(const uint4*)((const bf16_t*)src + (size_t)r * k + kg * 8);
             *(uint4*)v = raw;
         }
+        f16_t o[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o[e] = f2h(bf2f(v[e]));
         const int rd = ((r >> 4) * blk_stride + blk_off) * 16 + (r & 15);
-        *(uint4*)(dst + pk_index(rd, kg * 8, kp)) = *(const uint4*)v;
+        *(uint4*)(dst + pk_index(rd, kg * 8, kp)) = *(const uint4*)o;
     }
 }
 
@@ -125,7 +132,7 @@ __global__ __launch_bounds__(256) void k_embed(MbState st, const bf16_t* __restr
 
 // ------------------------------------------------------------------------------------------ RMSNorm
 // Row j (or sel[j]) of the residual stream: x += sum over k-slices of the previous projection's
-// partial sums (written back when sel is null), then h = x * rsqrt(mean x^2 + eps) * w as packed bf16.
+// partial sums (written back when sel is null), then h = x * rsqrt(mean x^2 + eps) * w as packed halves.
 // 1024 threads per row, at most two float4 chunks per thread (d <= 8192); the loads of all k-slices of a
 // chunk are issued together (the slice loop is unrolled with a predicate), so a row costs about one
 // memory round trip instead of one per slice.
@@ -134,8 +141,7 @@ constexpr int kNormMaxSplit = 8;
 __global__ __launch_bounds__(1024) void k_rmsnorm(const int32_t* __restrict__ d_count, float* __restrict__ x,
                                                   const float* __restrict__ part, int ksplit, size_t part_stride,
                                                   const bf16_t* __restrict__ w, float eps,
-                                                  const int32_t* __restrict__ sel, bf16_t* __restrict__ h,
-                                                  bf16_t* __restrict__ h_lo, int d)
+                                                  const int32_t* __restrict__ sel, f16_t* __restrict__ h, int d)
 {
     const int j = blockIdx.x;
     // The row count, the row, its partial sums and the norm weights are all requested before anything waits:
@@ -189,14 +195,10 @@ __global__ __launch_bounds__(1024) void k_rmsnorm(const int32_t* __restrict__ d_
         const int c = threadIdx.x * 4 + it * 4096;
         if (c < d) {
             const bf16_t* wv = (const bf16_t*)&wr[it];
-            bf16_t o[4], ol[4];
-            split_bf(v[it].x * r * bf2f(wv[0]), o[0], ol[0]);
-            split_bf(v[it].y * r * bf2f(wv[1]), o[1], ol[1]);
-            split_bf(v[it].z * r * bf2f(wv[2]), o[2], ol[2]);
-            split_bf(v[it].w * r * bf2f(wv[3]), o[3], ol[3]);
+            const f16_t o[4] = {f2h(v[it].x * r * bf2f(wv[0])), f2h(v[it].y * r * bf2f(wv[1])),
+                                f2h(v[it].z * r * bf2f(wv[2])), f2h(v[it].w * r * bf2f(wv[3]))};
             const size_t at = pk_index(j, c, d);   // d is a multiple of 64: Kp == d
             *(uint2*)(h + at) = *(const uint2*)o;
-            *(uint2*)(h_lo + at) = *(const uint2*)ol;
         }
     }
 }
@@ -215,15 +217,14 @@ template <int MT, int NB, int KD>
 struct SkinnyFrags {
     u32x4 w[NB][KD];
     u32x4 x[MT][KD];
-    u32x4 xl[MT][KD];
 };
 
 // Loads for k-blocks kb..kb+KD-1; k-blocks at or beyond kend are clamped re-reads whose activation
 // operands are zeroed in skinny_mma, so they add 0.
 template <int MT, int NB, int KD>
 __device__ __forceinline__ void skinny_load(SkinnyFrags<MT, NB, KD>& f, const u32x4* __restrict__ Wl,
-                                            const u32x4* __restrict__ Xl, const u32x4* __restrict__ Xlo, int KB,
-                                            int nb0, int nvalid, int kb, int kend)
+                                            const u32x4* __restrict__ Xl, int KB, int nb0, int nvalid, int kb,
+                                            int kend)
 {
 #pragma unroll
     for (int q = 0; q < KD; ++q) {
@@ -234,10 +235,7 @@ __device__ __forceinline__ void skinny_load(SkinnyFrags<MT, NB, KD>& f, const u3
             f.w[i][q] = __builtin_nontemporal_load(Wl + ((size_t)nb * KB + kk) * 64);
         }
 #pragma unroll
-        for (int m = 0; m < MT; ++m) {
-            f.x[m][q] = Xl[((size_t)m * KB + kk) * 64];
-            f.xl[m][q] = Xlo[((size_t)m * KB + kk) * 64];
-        }
+        for (int m = 0; m < MT; ++m) f.x[m][q] = Xl[((size_t)m * KB + kk) * 64];
     }
 }
 
@@ -250,14 +248,11 @@ __device__ __forceinline__ void skinny_mma(const SkinnyFrags<MT, NB, KD>& f, f32
         const bool live = kb + q < kend;
 #pragma unroll
         for (int m = 0; m < MT; ++m) {
-            const u32x4 xh = live ? f.x[m][q] : zero, xl = live ? f.xl[m][q] : zero;
+            const u32x4 xv = live ? f.x[m][q] : zero;
 #pragma unroll
-            for (int i = 0; i < NB; ++i) {
-                acc[i][m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, f.w[i][q]),
-                                                                    __builtin_bit_cast(bf16x8, xl), acc[i][m], 0, 0, 0);
-                acc[i][m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, f.w[i][q]),
-                                                                    __builtin_bit_cast(bf16x8, xh), acc[i][m], 0, 0, 0);
-            }
+            for (int i = 0; i < NB; ++i)
+                acc[i][m] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, f.w[i][q]),
+                                                                   __builtin_bit_cast(f16x8, xv), acc[i][m], 0, 0, 0);
         }
     }
 }
@@ -283,17 +278,16 @@ __global__ __launch_bounds__(256) void k_gemm_skinny(GemmArgs a, int n_groups, i
 
     const u32x4* Wl = (const u32x4*)a.W + lane;
     const u32x4* Xl = (const u32x4*)a.X + lane;
-    const u32x4* Xlo = (const u32x4*)a.X_lo + lane;
     if (kbeg < kend) {
         SkinnyFrags<MT, NB, KD> fa, fb;
-        skinny_load(fa, Wl, Xl, Xlo, KB, nb0, nvalid, kbeg, kend);
+        skinny_load(fa, Wl, Xl, KB, nb0, nvalid, kbeg, kend);
         // Loads past the wave's k-range are skipped rather than clamped: measured, the wasted re-reads of an
         // unconditional tail cost more (k-ranges are only 4-40 blocks) than the conservative load-counter waits
         // the branches cause; latency is hidden by the 12-20 resident waves per CU, not inside a wave.
         for (int kb = kbeg; kb < kend; kb += 2 * KD) {
-            if (kb + KD < kend) skinny_load(fb, Wl, Xl, Xlo, KB, nb0, nvalid, kb + KD, kend);
+            if (kb + KD < kend) skinny_load(fb, Wl, Xl, KB, nb0, nvalid, kb + KD, kend);
             skinny_mma(fa, acc, kb, kend);
-            if (kb + 2 * KD < kend) skinny_load(fa, Wl, Xl, Xlo, KB, nb0, nvalid, kb + 2 * KD, kend);
+            if (kb + 2 * KD < kend) skinny_load(fa, Wl, Xl, KB, nb0, nvalid, kb + 2 * KD, kend);
             if (kb + KD < kend) skinny_mma(fb, acc, kb + KD, kend);
         }
     }
@@ -330,12 +324,11 @@ __global__ __launch_bounds__(256) void k_gemm_skinny(GemmArgs a, int n_groups, i
             for (int i = 0; i + 1 < NB; i += 2)
                 if (i + 1 < nvalid) {
                     const int f = ((nb0 + i) >> 1) * 16 + col4;
-                    bf16_t o[4], ol[4];
+                    f16_t o[4];
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) split_bf(silu_f(acc[i][m][e]) * acc[i + 1][m][e], o[e], ol[e]);
+                    for (int e = 0; e < 4; ++e) o[e] = f2h(silu_f(acc[i][m][e]) * acc[i + 1][m][e]);
                     const size_t at = pk_index(row, f, a.kp_out);
                     *(uint2*)(a.out_packed + at) = *(const uint2*)o;
-                    *(uint2*)(a.out_packed_lo + at) = *(const uint2*)ol;
                 }
         }
     }
@@ -347,7 +340,7 @@ __global__ __launch_bounds__(256) void k_gemm_skinny(GemmArgs a, int n_groups, i
 // flight towards L2/HBM, and every byte requested through the vector memory path counts, also an activation
 // operand that hits in L2: in the kernel above, where each wave fetches its own activation operands, those
 // take a quarter of that budget (2 strips) or an eighth (4 strips).  Here the waves of a workgroup own
-// different output strips and sweep the same k-range together, so an activation chunk (KC k-blocks, hi + lo,
+// different output strips and sweep the same k-range together, so an activation chunk (KC k-blocks,
 // all row strips) is fetched once per workgroup, staged in LDS (double-buffered, one barrier per chunk) and
 // read from there by every wave; one workgroup per compute unit means once per unit.  No wave shares an
 // output with another: no reduction at the end, and the SwiGLU epilogue stays inside the wave that owns a
@@ -383,27 +376,27 @@ __device__ __forceinline__ void sweep_load_w(SweepSlot<NBW, KQ>& f, const u32x4*
     }
 }
 
-// An activation chunk is 2*KC*MT operand blocks of 64 x 16 bytes, block (m*2 + part)*KC + q = row strip m,
-// part (0 hi, 1 lo), k-block q of the chunk.  Thread t of the workgroup moves pieces t, t + 64P, ...;
+// An activation chunk is KC*MT operand blocks of 64 x 16 bytes, block m*KC + q = row strip m, k-block q of
+// the chunk.  Thread t of the workgroup moves pieces t, t + 64P, ...;
 // indices past the end are clamped to the last piece (the same bytes written twice).
 template <int P, int MT, int KC>
 struct SweepStage {
-    static constexpr int PIECES = 2 * KC * MT * 64;
+    static constexpr int PIECES = KC * MT * 64;
     static constexpr int XI = (PIECES + 64 * P - 1) / (64 * P);
     u32x4 v[XI];
 };
 
 template <int P, int MT, int KC>
-__device__ __forceinline__ void sweep_load_x(SweepStage<P, MT, KC>& xs, const u32x4* __restrict__ X,
-                                             const u32x4* __restrict__ Xlo, int KB, int kb, int kend)
+__device__ __forceinline__ void sweep_load_x(SweepStage<P, MT, KC>& xs, const u32x4* __restrict__ X, int KB, int kb,
+                                             int kend)
 {
 #pragma unroll
     for (int i = 0; i < SweepStage<P, MT, KC>::XI; ++i) {
         const int piece = min((int)threadIdx.x + i * 64 * P, SweepStage<P, MT, KC>::PIECES - 1);
         const int b = piece >> 6, l = piece & 63;
-        const int m = b / (2 * KC), part = (b / KC) & 1, q = b % KC;
+        const int m = b / KC, q = b % KC;
         const int kk = min(kb + q, kend - 1);
-        xs.v[i] = (part ? Xlo : X)[((size_t)m * KB + kk) * 64 + l];
+        xs.v[i] = X[((size_t)m * KB + kk) * 64 + l];
     }
 }
 
@@ -422,21 +415,15 @@ __device__ __forceinline__ void sweep_mma(const SweepSlot<NBW, KQ>& f, const u32
 {
 #pragma unroll
     for (int q = 0; q < KQ; ++q) {
-        u32x4 xh[MT], xl[MT];
+        u32x4 xv[MT];
 #pragma unroll
-        for (int m = 0; m < MT; ++m) {
-            xh[m] = buf[((m * 2 + 0) * KC + q0 + q) * 64 + lane];
-            xl[m] = buf[((m * 2 + 1) * KC + q0 + q) * 64 + lane];
-        }
+        for (int m = 0; m < MT; ++m) xv[m] = buf[(m * KC + q0 + q) * 64 + lane];
 #pragma unroll
         for (int m = 0; m < MT; ++m)
 #pragma unroll
-            for (int i = 0; i < NBW; ++i) {
-                acc[i][m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, f.w[i][q]),
-                                                                    __builtin_bit_cast(bf16x8, xl[m]), acc[i][m], 0, 0, 0);
-                acc[i][m] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, f.w[i][q]),
-                                                                    __builtin_bit_cast(bf16x8, xh[m]), acc[i][m], 0, 0, 0);
-            }
+            for (int i = 0; i < NBW; ++i)
+                acc[i][m] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, f.w[i][q]),
+                                                                   __builtin_bit_cast(f16x8, xv[m]), acc[i][m], 0, 0, 0);
     }
 }
 
@@ -448,18 +435,18 @@ __device__ __forceinline__ void sweep_mma(const SweepSlot<NBW, KQ>& f, const u32
 template <bool ACTIVE, int P, int MT, int NBW, int KC, int KH>
 __device__ __forceinline__ void sweep_run(u32x4* xl0, u32x4* xl1, f32x4 (&acc)[NBW][MT],
                                           const u32x4* __restrict__ Wl, const u32x4* __restrict__ Zl,
-                                          const u32x4* __restrict__ X, const u32x4* __restrict__ Xlo, int KB, int nb0,
-                                          int nvalid, int s0, int s1, int C, int lane, int q0)
+                                          const u32x4* __restrict__ X, int KB, int nb0, int nvalid, int s0, int s1,
+                                          int C, int lane, int q0)
 {
     constexpr int KQ = KC / KH;
     SweepSlot<NBW, KQ> fa, fb;
     SweepStage<P, MT, KC> xs;
-    sweep_load_x<P, MT, KC>(xs, X, Xlo, KB, s0, s1);
+    sweep_load_x<P, MT, KC>(xs, X, KB, s0, s1);
     if (ACTIVE) sweep_load_w<NBW, KQ>(fa, Wl, Zl, KB, nb0, nvalid, s0 + q0, s1);
     __builtin_amdgcn_sched_barrier(0);
     sweep_store_x<P, MT, KC>(xs, xl0);
     __builtin_amdgcn_sched_barrier(0);
-    sweep_load_x<P, MT, KC>(xs, X, Xlo, KB, s0 + KC, s1);
+    sweep_load_x<P, MT, KC>(xs, X, KB, s0 + KC, s1);
     if (ACTIVE) sweep_load_w<NBW, KQ>(fb, Wl, Zl, KB, nb0, nvalid, s0 + KC + q0, s1);
     __builtin_amdgcn_sched_barrier(0);
     __syncthreads();
@@ -472,7 +459,7 @@ __device__ __forceinline__ void sweep_run(u32x4* xl0, u32x4* xl1, f32x4 (&acc)[N
         __builtin_amdgcn_sched_barrier(0);
         sweep_store_x<P, MT, KC>(xs, xl1);
         __builtin_amdgcn_sched_barrier(0);
-        sweep_load_x<P, MT, KC>(xs, X, Xlo, KB, k2, s1);
+        sweep_load_x<P, MT, KC>(xs, X, KB, k2, s1);
         if (ACTIVE) sweep_load_w<NBW, KQ>(fa, Wl, Zl, KB, nb0, nvalid, k2 + q0, s1);
         __builtin_amdgcn_sched_barrier(0);
         __syncthreads();
@@ -480,7 +467,7 @@ __device__ __forceinline__ void sweep_run(u32x4* xl0, u32x4* xl1, f32x4 (&acc)[N
         __builtin_amdgcn_sched_barrier(0);
         sweep_store_x<P, MT, KC>(xs, xl0);
         __builtin_amdgcn_sched_barrier(0);
-        sweep_load_x<P, MT, KC>(xs, X, Xlo, KB, k3, s1);
+        sweep_load_x<P, MT, KC>(xs, X, KB, k3, s1);
         if (ACTIVE) sweep_load_w<NBW, KQ>(fb, Wl, Zl, KB, nb0, nvalid, k3 + q0, s1);
         __builtin_amdgcn_sched_barrier(0);
         __syncthreads();
@@ -493,11 +480,14 @@ __device__ __forceinline__ void sweep_run(u32x4* xl0, u32x4* xl1, f32x4 (&acc)[N
 template <int P, int MT, int NBW, int EPI, int KH>
 __global__ __launch_bounds__(64 * P) void k_gemm_sweep(GemmArgs a, int n_units, int n_gn, int kb_per_slice)
 {
-    constexpr int KC = MT > 4 ? 2 : 4;   // k-blocks per chunk: both LDS buffers together stay within 64 KiB
+    constexpr int KC = MT > 4 ? 2 : 4;   // k-blocks per chunk
     static_assert(KC % KH == 0, "a chunk's k-blocks split evenly between the waves of a unit");
-    __shared__ u32x4 xlds[2][SweepStage<P, MT, KC>::PIECES];
-    static_assert(KH == 1 || (P / 2) * NBW * MT * 64 <= 2 * SweepStage<P, MT, KC>::PIECES,
-                  "the accumulators of the odd waves fit the staging buffers");
+    constexpr int STAGE = SweepStage<P, MT, KC>::PIECES;
+    // two staging buffers; after the sweep the same memory carries the odd waves' accumulators (KH = 2)
+    constexpr int RED = KH == 2 ? (P / 2) * NBW * MT * 64 : 0;
+    __shared__ u32x4 xlds[2 * STAGE > RED ? 2 * STAGE : RED];
+    u32x4* const xl0 = xlds;
+    u32x4* const xl1 = xlds + STAGE;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int gn = blockIdx.x % n_gn, ks = blockIdx.x / n_gn;
     const int KB = a.Kp >> 5, NBT = a.N >> 4;
@@ -519,18 +509,17 @@ __global__ __launch_bounds__(64 * P) void k_gemm_sweep(GemmArgs a, int n_units, 
     const u32x4* Wl = (const u32x4*)a.W + lane;
     const u32x4* Zl = (const u32x4*)a.zero_blk + lane;
     const u32x4* X = (const u32x4*)a.X;
-    const u32x4* Xlo = (const u32x4*)a.X_lo;
     const int C = (s1 - s0 + KC - 1) / KC;   // chunks of this slice: the same for every wave of the workgroup
     if (C > 0) {
         if (active)
-            sweep_run<true, P, MT, NBW, KC, KH>(xlds[0], xlds[1], acc, Wl, Zl, X, Xlo, KB, nb0, nvalid, s0, s1, C, lane, q0);
+            sweep_run<true, P, MT, NBW, KC, KH>(xl0, xl1, acc, Wl, Zl, X, KB, nb0, nvalid, s0, s1, C, lane, q0);
         else
-            sweep_run<false, P, MT, NBW, KC, KH>(xlds[0], xlds[1], acc, Wl, Zl, X, Xlo, KB, nb0, nvalid, s0, s1, C, lane, q0);
+            sweep_run<false, P, MT, NBW, KC, KH>(xl0, xl1, acc, Wl, Zl, X, KB, nb0, nvalid, s0, s1, C, lane, q0);
     }
     if (KH == 2) {
         // the odd wave of a pair hands its sums to the even one (the staging buffers are free after the last barrier
         // of the sweep; with no chunk at all nobody has touched them)
-        f32x4* red = (f32x4*)&xlds[0][0];
+        f32x4* red = (f32x4*)xlds;
         if (active && (wave & 1)) {
 #pragma unroll
             for (int i = 0; i < NBW; ++i)
@@ -565,12 +554,11 @@ __global__ __launch_bounds__(64 * P) void k_gemm_sweep(GemmArgs a, int n_units, 
             for (int i = 0; i + 1 < NBW; i += 2)
                 if (i + 1 < nvalid) {
                     const int f = ((nb0 + i) >> 1) * 16 + col4;
-                    bf16_t o[4], ol[4];
+                    f16_t o[4];
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) split_bf(silu_f(acc[i][m][e]) * acc[i + 1][m][e], o[e], ol[e]);
+                    for (int e = 0; e < 4; ++e) o[e] = f2h(silu_f(acc[i][m][e]) * acc[i + 1][m][e]);
                     const size_t at = pk_index(row, f, a.kp_out);
                     *(uint2*)(a.out_packed + at) = *(const uint2*)o;
-                    *(uint2*)(a.out_packed_lo + at) = *(const uint2*)ol;
                 }
         }
     }
@@ -581,7 +569,7 @@ __global__ __launch_bounds__(64 * P) void k_gemm_sweep(GemmArgs a, int n_units, 
 // TMS*16 token rows x 256 output columns; wave w owns 4 strips of 16 columns and every row strip.
 // Weights never touch LDS: they are stored in operand order, so each wave loads its own 4 operand
 // blocks per k-block straight into registers (1 KiB coalesced each) and is the only wave of the
-// workgroup that needs them.  The activation tile (hi and lo parts) is shared by the 4 waves and staged
+// workgroup that needs them.  The activation tile is shared by the 4 waves and staged
 // through LDS in operand order (conflict-free 1 KiB reads).  One k-block per trip; both streams run
 // D k-blocks ahead of the MFMAs in a register ring, so with two workgroups per CU about 100 KiB are in
 // flight per CU, enough to keep HBM busy when the weights are streamed once for a decode batch.
@@ -592,18 +580,15 @@ __global__ __launch_bounds__(64 * P) void k_gemm_sweep(GemmArgs a, int n_units, 
 // own LDS stages) and the second group hands its accumulators to the first through LDS at the end.  Used
 // when there are too few tiles to give every CU two workgroups: it doubles the waves per CU and halves
 // the serial k loop without sending partial sums through HBM.
-// LO = false: the activations' lo part is left out (one product per operand pair instead of two): half the
-// matrix-core work and half the staged bytes, at bf16 precision of the activations.
-template <int TMS, int KP, int EPI, bool LO>
+template <int TMS, int KP, int EPI>
 __global__ __launch_bounds__(256 * KP, 2) void k_gemm_tiled(GemmArgs a, int kb_per_slice, int n_ntiles, int n_mtiles)
 {
     constexpr int D = 4;                        // k-blocks in flight
-    constexpr int NP = LO ? 2 : 1;              // activation parts: hi, lo
-    constexpr int XV = TMS * NP * 64 / 256;     // 16-byte vectors per thread: one k-block of the activation tile
-    __shared__ u32x4 lds_all[KP][2][TMS * NP * 64];           // [k-part][stage][row strip][hi, lo][lane]
+    constexpr int XV = TMS * 64 / 256;          // 16-byte vectors per thread: one k-block of the activation tile
+    __shared__ u32x4 lds_all[KP][2][TMS * 64];                // [k-part][stage][row strip][lane]
     __shared__ f32x4 red[KP > 1 ? 4 * TMS : 1][KP > 1 ? 256 : 1];
     const int part = threadIdx.x >> 8, tid = threadIdx.x & 255, lane = tid & 63, wave = tid >> 6;
-    u32x4 (*lds)[TMS * NP * 64] = lds_all[part];
+    u32x4 (*lds)[TMS * 64] = lds_all[part];
     const int KB = a.Kp >> 5, NBT = a.N >> 4;
     const int MBT = (a.m_rows + 15) >> 4;
     const int per_slice = ((n_ntiles + 7) >> 3) * 8 * n_mtiles;
@@ -624,7 +609,6 @@ __global__ __launch_bounds__(256 * KP, 2) void k_gemm_tiled(GemmArgs a, int kb_p
 
     const u32x4* W4 = (const u32x4*)a.W + lane;
     const u32x4* Xh = (const u32x4*)a.X;
-    const u32x4* Xl = (const u32x4*)a.X_lo;
     // Ring slots are separately named arrays of native vectors indexed only by unrolled constants, so
     // that they stay in registers (a ring that ends up in scratch memory makes every access wait for all
     // outstanding loads).
@@ -636,27 +620,22 @@ __global__ __launch_bounds__(256 * KP, 2) void k_gemm_tiled(GemmArgs a, int kb_p
 #define SS_XLOAD(X_, KB_)                                                                       \
     _Pragma("unroll") for (int i_ = 0; i_ < XV; ++i_) {                                         \
         const int c_ = tid + i_ * 256;                                                          \
-        const int ln_ = c_ & 63, hl_ = LO ? (c_ >> 6) & 1 : 0, ms_ = LO ? c_ >> 7 : c_ >> 6;    \
-        X_[i_] = (hl_ ? Xl : Xh)[((size_t)min(mb0 + ms_, MBT - 1) * KB + (KB_)) * 64 + ln_];    \
+        const int ln_ = c_ & 63, ms_ = c_ >> 6;                                                 \
+        X_[i_] = Xh[((size_t)min(mb0 + ms_, MBT - 1) * KB + (KB_)) * 64 + ln_];                 \
     }
 #define SS_XSTORE(STAGE_, X_, LIVE_)                                                            \
     _Pragma("unroll") for (int i_ = 0; i_ < XV; ++i_) lds[STAGE_][tid + i_ * 256] = (LIVE_) ? X_[i_] : zero4;
 #define SS_COMPUTE(W_, STAGE_)                                                                  \
     {                                                                                           \
         /* every operand read of the trip is issued before the first MFMA (the reads return in  \
-           order, so each MFMA group waits only for its own pair): LDS latency overlaps MFMAs */ \
-        u32x4 xh_[TMS], xl_[TMS];                                                               \
-        _Pragma("unroll") for (int m_ = 0; m_ < TMS; ++m_) {                                    \
-            if (LO) xl_[m_] = lds[STAGE_][(m_ * 2 + 1) * 64 + lane];                            \
-            xh_[m_] = lds[STAGE_][(m_ * NP + 0) * 64 + lane];                                   \
-        }                                                                                       \
+           order, so each MFMA group waits only for its own operand): LDS latency overlaps MFMAs */ \
+        u32x4 xh_[TMS];                                                                         \
+        _Pragma("unroll") for (int m_ = 0; m_ < TMS; ++m_) xh_[m_] = lds[STAGE_][m_ * 64 + lane]; \
         __builtin_amdgcn_sched_barrier(0x16);   /* only VALU, SALU and global loads may cross */ \
         _Pragma("unroll") for (int m_ = 0; m_ < TMS; ++m_) {                                    \
             _Pragma("unroll") for (int i_ = 0; i_ < 4; ++i_) {                                  \
-                if (LO) acc[i_][m_] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(                  \
-                    __builtin_bit_cast(bf16x8, W_[i_]), __builtin_bit_cast(bf16x8, xl_[m_]), acc[i_][m_], 0, 0, 0); \
-                acc[i_][m_] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(                          \
-                    __builtin_bit_cast(bf16x8, W_[i_]), __builtin_bit_cast(bf16x8, xh_[m_]), acc[i_][m_], 0, 0, 0); \
+                acc[i_][m_] = __builtin_amdgcn_mfma_f32_16x16x32_f16(                           \
+                    __builtin_bit_cast(f16x8, W_[i_]), __builtin_bit_cast(f16x8, xh_[m_]), acc[i_][m_], 0, 0, 0); \
             }                                                                                   \
         }                                                                                       \
     }
@@ -725,12 +704,11 @@ __global__ __launch_bounds__(256 * KP, 2) void k_gemm_tiled(GemmArgs a, int kb_p
             for (int i = 0; i < 4; i += 2)
                 if (nb0 + i + 1 < NBT) {
                     const int f = ((nb0 + i) >> 1) * 16 + col4;
-                    bf16_t o[4], ol[4];
+                    f16_t o[4];
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) split_bf(silu_f(acc[i][m][e]) * acc[i + 1][m][e], o[e], ol[e]);
+                    for (int e = 0; e < 4; ++e) o[e] = f2h(silu_f(acc[i][m][e]) * acc[i + 1][m][e]);
                     const size_t at = pk_index(row, f, a.kp_out);
                     *(uint2*)(a.out_packed + at) = *(const uint2*)o;
-                    *(uint2*)(a.out_packed_lo + at) = *(const uint2*)ol;
                 }
         }
     }
@@ -738,10 +716,9 @@ __global__ __launch_bounds__(256 * KP, 2) void k_gemm_tiled(GemmArgs a, int kb_p
 
 // SwiGLU over k-sliced partial sums: the gate|up projection was run with k-slices (its output columns are
 // in strip order: strip 2j = gate columns 16j.., strip 2j+1 = the matching up columns); this adds the
-// slices and writes silu(gate)*up as hi/lo packed activations.  One thread per 4 MLP columns of a row.
+// slices and writes silu(gate)*up as packed activations.  One thread per 4 MLP columns of a row.
 __global__ __launch_bounds__(256) void k_swiglu_reduce(const float* __restrict__ part, int ksplit, size_t part_stride,
-                                                       int m_rows, int F, int kp_out, bf16_t* __restrict__ out,
-                                                       bf16_t* __restrict__ out_lo)
+                                                       int m_rows, int F, int kp_out, f16_t* __restrict__ out)
 {
     const int row = blockIdx.y;
     const int f = (blockIdx.x * 256 + threadIdx.x) * 4;
@@ -754,14 +731,9 @@ __global__ __launch_bounds__(256) void k_swiglu_reduce(const float* __restrict__
         g.x += a.x; g.y += a.y; g.z += a.z; g.w += a.w;
         u.x += b.x; u.y += b.y; u.z += b.z; u.w += b.w;
     }
-    bf16_t o[4], ol[4];
-    split_bf(silu_f(g.x) * u.x, o[0], ol[0]);
-    split_bf(silu_f(g.y) * u.y, o[1], ol[1]);
-    split_bf(silu_f(g.z) * u.z, o[2], ol[2]);
-    split_bf(silu_f(g.w) * u.w, o[3], ol[3]);
+    const f16_t o[4] = {f2h(silu_f(g.x) * u.x), f2h(silu_f(g.y) * u.y), f2h(silu_f(g.z) * u.z), f2h(silu_f(g.w) * u.w)};
     const size_t at = pk_index(row, f, kp_out);
     *(uint2*)(out + at) = *(const uint2*)o;
-    *(uint2*)(out_lo + at) = *(const uint2*)ol;
 }
 
 // ------------------------------------------------------------------------------------------ RoPE + KV append
@@ -814,8 +786,8 @@ constexpr int kAttnWideMaxGroups = 512;   // decode attention: (row, head) workg
 template <int HD, int NW>
 __device__ __forceinline__ void attend(const float* __restrict__ qs, float* __restrict__ sc, float* __restrict__ red,
                                        float (*__restrict__ oacc)[HD], const kv_t* __restrict__ kbase,
-                                       const kv_t* __restrict__ vbase, int ctx, bf16_t* __restrict__ out,
-                                       bf16_t* __restrict__ out_lo, int out_r, int out_k0, int out_kp)
+                                       const kv_t* __restrict__ vbase, int ctx, f16_t* __restrict__ out, int out_r,
+                                       int out_k0, int out_kp)
 {
     constexpr int LPK = HD / 8;       // lanes per key
     constexpr int KPW = 64 / LPK;     // keys per wave load
@@ -907,18 +879,17 @@ __device__ __forceinline__ void attend(const float* __restrict__ qs, float* __re
         for (int e = 0; e < 8; ++e) oacc[wave][sub * 8 + e] = o[e];
     __syncthreads();
     if (tid < HD / 4) {
-        bf16_t r[4], rl[4];
+        f16_t r[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             const int c = tid * 4 + e;
             float t = 0.f;
 #pragma unroll
             for (int w = 0; w < NW; ++w) t += oacc[w][c];
-            split_bf(t * inv, r[e], rl[e]);
+            r[e] = f2h(t * inv);
         }
         const size_t at = pk_index(out_r, out_k0 + tid * 4, out_kp);
         *(uint2*)(out + at) = *(const uint2*)r;
-        *(uint2*)(out_lo + at) = *(const uint2*)rl;
     }
 }
 
@@ -936,13 +907,10 @@ __device__ __forceinline__ void attend(const float* __restrict__ qs, float* __re
 //                 D: lane holds, for query lane%16, output elements 16t + 4*(lane/16)..+3.
 // So a query's running maximum, sum and rescale factor stay in its own lanes: fp32 online softmax with no
 // transposition of the probabilities.  Slots above a query's position are masked before the exponential.
-typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
-typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
-
 template <int HD>
 __global__ __launch_bounds__(256) void k_attention_prompt(MbState st, const float* __restrict__ qrot,
                                                           const kv_t* __restrict__ kc, const kv_t* __restrict__ vc,
-                                                          bf16_t* __restrict__ out, bf16_t* __restrict__ out_lo, int d)
+                                                          f16_t* __restrict__ out, int d)
 {
     constexpr int KS = HD / 32;          // steps of the score contraction
     constexpr int ET = HD / 16;          // 16-element tiles of the output
@@ -1073,12 +1041,11 @@ __global__ __launch_bounds__(256) void k_attention_prompt(MbState st, const floa
     const int j = j0 + qpos;
 #pragma unroll
     for (int tt = 0; tt < ET; ++tt) {
-        bf16_t r[4], rl[4];
+        f16_t r[4];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) split_bf(o[tt][e] * inv, r[e], rl[e]);
+        for (int e = 0; e < 4; ++e) r[e] = f2h(o[tt][e] * inv);
         const size_t at = pk_index(j, h * HD + tt * 16 + 4 * g, d);
         *(uint2*)(out + at) = *(const uint2*)r;
-        *(uint2*)(out_lo + at) = *(const uint2*)rl;
     }
 }
 
@@ -1091,8 +1058,8 @@ template <int HD, int NW>
 __global__ __launch_bounds__(64 * NW) void k_attention_decode(MbState st, const float* __restrict__ part, int ksplit,
                                                           size_t part_stride, kv_t* __restrict__ kc,
                                                           kv_t* __restrict__ vc, const float* __restrict__ rcos,
-                                                          const float* __restrict__ rsin, bf16_t* __restrict__ out,
-                                                          bf16_t* __restrict__ out_lo, int d)
+                                                          const float* __restrict__ rsin, f16_t* __restrict__ out,
+                                                          int d)
 {
     __shared__ float sc[kMaxPos];
     __shared__ float red[2 * NW];
@@ -1137,7 +1104,7 @@ __global__ __launch_bounds__(64 * NW) void k_attention_decode(MbState st, const 
         }
     }
     __syncthreads();   // the new key/value slot and q are visible to the whole workgroup
-    attend<HD, NW>(qs, sc, red, oacc, kc + base, vc + base, pos + 1, out, out_lo, j, h * HD, d);
+    attend<HD, NW>(qs, sc, red, oacc, kc + base, vc + base, pos + 1, out, j, h * HD, d);
 }
 
 // ------------------------------------------------------------------------------------------ argmax
@@ -1380,7 +1347,7 @@ static inline int grid_for(size_t n, int block)
     return (int)(g > (1u << 20) ? (1u << 20) : (g < 1 ? 1 : g));
 }
 
-void launch_pack_weight(const void* src, int src_f32, bf16_t* dst, int n_src, int k, int kp, int blk_stride,
+void launch_pack_weight(const void* src, int src_f32, f16_t* dst, int n_src, int k, int kp, int blk_stride,
                         int blk_off, hipStream_t s)
 {
     const size_t total = (size_t)n_src * (k / 8);
@@ -1405,18 +1372,18 @@ void launch_embed(const MbState& st, const bf16_t* embed, float* x, int d, int n
 }
 
 void launch_rmsnorm(const MbState& st, float* x, const float* part, int ksplit, size_t part_stride,
-                    const bf16_t* w, float eps, const int32_t* sel, const int32_t* d_nsel, bf16_t* h_packed,
-                    bf16_t* h_packed_lo, int d, int n_max, hipStream_t s)
+                    const bf16_t* w, float eps, const int32_t* sel, const int32_t* d_nsel, f16_t* h_packed, int d,
+                    int n_max, hipStream_t s)
 {
     hipLaunchKernelGGL(k_rmsnorm, dim3(n_max), dim3(1024), 0, s, d_nsel ? d_nsel : st.d_n, x, part,
-                       part ? ksplit : 0, part_stride, w, eps, sel, h_packed, h_packed_lo, d);
+                       part ? ksplit : 0, part_stride, w, eps, sel, h_packed, d);
 }
 
 void launch_swiglu_reduce(const float* part, int ksplit, size_t part_stride, int m_rows, int F, int kp_out,
-                          bf16_t* out, bf16_t* out_lo, hipStream_t s)
+                          f16_t* out, hipStream_t s)
 {
     hipLaunchKernelGGL(k_swiglu_reduce, dim3((F / 4 + 255) / 256, m_rows), dim3(256), 0, s, part, ksplit, part_stride,
-                       m_rows, F, kp_out, out, out_lo);
+                       m_rows, F, kp_out, out);
 }
 
 template <int MT, int NB, int KD, int EPI>
@@ -1504,14 +1471,10 @@ static void launch_gemm_epi(const GemmArgs& a, hipStream_t s)
     constexpr int TMS = 4;
     const int n_ntiles = (a.N + 255) / 256, n_mtiles = (a.m_rows + TMS * 16 - 1) / (TMS * 16);
     const int grid = (n_ntiles + 7) / 8 * 8 * n_mtiles * a.ksplit;
-    const bool lo = a.X_lo != nullptr && !a.tiled_no_lo;
-    if (a.kp == 2) {
-        if (lo) hipLaunchKernelGGL((k_gemm_tiled<TMS, 2, EPI, true>), dim3(grid), dim3(512), 0, s, a, kbs, n_ntiles, n_mtiles);
-        else hipLaunchKernelGGL((k_gemm_tiled<TMS, 2, EPI, false>), dim3(grid), dim3(512), 0, s, a, kbs, n_ntiles, n_mtiles);
-    } else {
-        if (lo) hipLaunchKernelGGL((k_gemm_tiled<TMS, 1, EPI, true>), dim3(grid), dim3(256), 0, s, a, kbs, n_ntiles, n_mtiles);
-        else hipLaunchKernelGGL((k_gemm_tiled<TMS, 1, EPI, false>), dim3(grid), dim3(256), 0, s, a, kbs, n_ntiles, n_mtiles);
-    }
+    if (a.kp == 2)
+        hipLaunchKernelGGL((k_gemm_tiled<TMS, 2, EPI>), dim3(grid), dim3(512), 0, s, a, kbs, n_ntiles, n_mtiles);
+    else
+        hipLaunchKernelGGL((k_gemm_tiled<TMS, 1, EPI>), dim3(grid), dim3(256), 0, s, a, kbs, n_ntiles, n_mtiles);
 }
 
 void launch_gemm(const GemmArgs& a, int epilogue, hipStream_t s)
@@ -1533,20 +1496,20 @@ void launch_rope_append(const MbState& st, const float* qkv_part, int ksplit, si
 template <int HD, int NW>
 static void launch_attention_decode_inst(const MbState& st, const float* qkv_part, int ksplit, size_t part_stride,
                                          kv_t* kcache, kv_t* vcache, const float* rope_cos, const float* rope_sin,
-                                         bf16_t* out_packed, bf16_t* out_packed_lo, int d, int H, int n_max, hipStream_t s)
+                                         f16_t* out_packed, int d, int H, int n_max, hipStream_t s)
 {
     hipLaunchKernelGGL((k_attention_decode<HD, NW>), dim3(n_max, H), dim3(64 * NW), 0, s, st, qkv_part, ksplit, part_stride,
-                       kcache, vcache, rope_cos, rope_sin, out_packed, out_packed_lo, d);
+                       kcache, vcache, rope_cos, rope_sin, out_packed, d);
 }
 
 void launch_attention_decode(const MbState& st, const float* qkv_part, int ksplit, size_t part_stride,
                              kv_t* kcache, kv_t* vcache, const float* rope_cos, const float* rope_sin,
-                             bf16_t* out_packed, bf16_t* out_packed_lo, int d, int H, int hd, int n_max, hipStream_t s)
+                             f16_t* out_packed, int d, int H, int hd, int n_max, hipStream_t s)
 {
     // measured at the 7B shape: 8 waves win at 16 rows (512 workgroups: 14.1 against 14.9 us per layer at context
     // 200), 4 waves win at 64 rows (2048 workgroups: 25.7 against 36.1 us at context 100)
     const bool wide = n_max * H <= kAttnWideMaxGroups;
-#define SS_ATTN_ARGS st, qkv_part, ksplit, part_stride, kcache, vcache, rope_cos, rope_sin, out_packed, out_packed_lo, d, H, n_max, s
+#define SS_ATTN_ARGS st, qkv_part, ksplit, part_stride, kcache, vcache, rope_cos, rope_sin, out_packed, d, H, n_max, s
     if (hd == 128) {
         if (wide) launch_attention_decode_inst<128, 8>(SS_ATTN_ARGS);
         else launch_attention_decode_inst<128, 4>(SS_ATTN_ARGS);
@@ -1558,16 +1521,13 @@ void launch_attention_decode(const MbState& st, const float* qkv_part, int kspli
 }
 
 void launch_attention_prompt(const MbState& st, const float* qrot, const kv_t* kcache, const kv_t* vcache,
-                             bf16_t* out_packed, bf16_t* out_packed_lo, int d, int H, int hd, int B, int max_len,
-                             hipStream_t s)
+                             f16_t* out_packed, int d, int H, int hd, int B, int max_len, hipStream_t s)
 {
     const dim3 grid((max_len + 63) / 64, H, B);
     if (hd == 128)
-        hipLaunchKernelGGL((k_attention_prompt<128>), grid, dim3(256), 0, s, st, qrot, kcache, vcache, out_packed,
-                           out_packed_lo, d);
+        hipLaunchKernelGGL((k_attention_prompt<128>), grid, dim3(256), 0, s, st, qrot, kcache, vcache, out_packed, d);
     else
-        hipLaunchKernelGGL((k_attention_prompt<64>), grid, dim3(256), 0, s, st, qrot, kcache, vcache, out_packed,
-                           out_packed_lo, d);
+        hipLaunchKernelGGL((k_attention_prompt<64>), grid, dim3(256), 0, s, st, qrot, kcache, vcache, out_packed, d);
 }
 
 void launch_argmax(const float* logits, int vocab, const int32_t* d_nsel, int32_t* am, int n_max, hipStream_t s)
@@ -1575,7 +1535,7 @@ void launch_argmax(const float* logits, int vocab, const int32_t* d_nsel, int32_
     hipLaunchKernelGGL(k_argmax, dim3(n_max), dim3(1024), 0, s, logits, vocab, d_nsel, am);
 }
 
-void launch_read_stream(const bf16_t* p, size_t bytes, uint32_t* sink, hipStream_t s)
+void launch_read_stream(const f16_t* p, size_t bytes, uint32_t* sink, hipStream_t s)
 {
     const int n_chunks = (int)(bytes >> 16);
     if (n_chunks < 1) return;

@@ -281,7 +281,7 @@ def test_7b_full_depth_sampled_rows_that_end_by_themselves(full7b):
     """Full depth, vocabulary 32000, the launch configuration the benchmark's sampled leg runs: 16 rows sampled at
     T = 0.5 with device-side ends; every emitted token is the oracle's inverse-CDF choice on the GPU's own logits
     and prefix, lengths and flags are exact, and the logits themselves meet the bar."""
-    from test_gpu_generate import check_row_on_own_prefix
+    from test_gpu_generate import check_row_on_own_prefix, microbatch_logits
     shape, W, om, gw = full7b
     w = synth.make_workload(3)
     idx = list(range(16))
@@ -297,10 +297,12 @@ def test_7b_full_depth_sampled_rows_that_end_by_themselves(full7b):
         assert np.array_equal(r["failed"].astype(bool), t > cap)
         assert r["stats"]["steps"] == cap + 0 and r["stats"]["idle_steps"] == 0
         dec = tot = 0
+        got = microbatch_logits(gw, [w.prompt(i) for i in idx], [r["tokens"][j, :int(r["lens"][j])] for j in range(16)])
         for j in (5, 14):
             L = int(r["lens"][j])
             assert (r["tokens"][j, :L] >= 0).all() and (r["tokens"][j, L:] == -1).all()
-            g, e, L = check_row_on_own_prefix(om, gw, w.prompt(idx[j]), r["tokens"][j, :L], T, draws[j], f"7B T={T} row {j}")
+            g, e, L = check_row_on_own_prefix(om, gw, w.prompt(idx[j]), r["tokens"][j, :L], T, draws[j], f"7B T={T} row {j}",
+                                              got[j])
             dec, tot = dec + g, tot + L
         _say(f"  T={T}: {dec}/{tot} positions decided given the logits and equal")
         if T < 0.1:

@@ -293,7 +293,8 @@ def test_wide_decode_logits_each_small_batch_projection_kernel(wide2, mode):
 def test_wide_decode_logits_across_row_strips(wide2, rows):
     """7B widths, 2-8 row strips, the kernel choice of the library itself (mode 0) and the same with the
     two-waves-per-unit split of the sweep kernel switched off (mode 4): one strip per wave up to 48 rows, two above,
-    ragged last strips.  Three rows against the oracle in each mode; the two modes agree to rounding order."""
+    ragged last strips.  Three rows against the oracle in each mode; the two modes differ only in the order of fp32
+    sums, which can move an activation by one unit of its half-precision rounding (2^-11) and a logit by that order."""
     shape, W, om, gw = wide2
     rng = np.random.default_rng(500 + rows)
     w = synth.make_group(shape, rows, 900 + rows, ("uniform", 3, 12), ("uniform", 1, 8), None, 8, 0, ())
@@ -312,7 +313,7 @@ def test_wide_decode_logits_across_row_strips(wide2, rows):
         for mode in (0, 4):
             check_logits(got[mode][out_off[i]:out_off[i + 1]], ref, f"B={rows} row {i} mode {mode}")
     scale = np.abs(got[0]).max()
-    assert np.abs(got[0] - got[4]).max() <= 1e-4 * scale
+    assert np.abs(got[0] - got[4]).max() <= 2e-3 * scale
 
 
 def test_wide_prompt_forward_through_tiled_kernel(wide2):
@@ -579,30 +580,38 @@ def test_invalid_generation_arguments(tiny):
     assert r["lens"].tolist() == [2, 3]
 
 
-def test_prompt_forward_lo_mask_option(wide2):
-    """The per-handle precision switch of the prompt forward: dropping the lo part of the activations that feed
-    projections (here: every projection) moves the logits by far more than rounding order yet stays inside the
-    bar at this depth; the default (every lo part kept) is restored and reproduces the first result bit for bit;
-    bad arguments are refused."""
-    shape, W, om, gw = wide2
-    rng = np.random.default_rng(77)
-    w = synth.make_group(shape, 8, 4711, ("uniform", 20, 40), ("uniform", 1, 4), None, 4, 0, ())
-    toks, offs, npr = forced_batch(w, range(8), [2] * 8, rng)          # > 128 prompt token-rows: the tiled kernel
-    assert int(npr.sum()) > 128
-    full = ss.ss_forward_logits(gw, toks, offs, npr)
-    try:
-        gw.set_option(ss.SS_OPT_PROMPT_LO_MASK, 0)
-        hi_only = ss.ss_forward_logits(gw, toks, offs, npr)
-    finally:
-        gw.set_option(ss.SS_OPT_PROMPT_LO_MASK, ss.SS_LO_ALL)
-    again = ss.ss_forward_logits(gw, toks, offs, npr)
-    assert np.array_equal(full, again)
-    ref = oracle_forced_logits(om, toks[offs[0]:offs[2]], offs[:3] - offs[0], npr[:2])
-    n_out = int((np.diff(offs)[:2] - npr[:2] + 1).sum())
-    e_full = check_logits(full[:n_out], ref, "every lo part kept")
-    e_hi = check_logits(hi_only[:n_out], ref, "no lo part in the prompt forward")
-    assert e_hi > 2 * e_full
-    for opt, val in ((ss.SS_OPT_PROMPT_LO_MASK, 32), (ss.SS_OPT_PROMPT_LO_MASK, -1), (99, 0)):
+def test_small_weights_keep_their_value_on_the_device(tiny):
+    """Weights live on the device as IEEE half.  A projection whose bf16 weights are all of magnitude ~1e-5 (half's
+    subnormal range starts at 6.1e-5; bf16 values down to 2^-17 = 7.6e-6 are exact in it, smaller ones are off by
+    less than 3e-8) must still give the oracle's logits: nothing is flushed to zero on the way through the matrix
+    cores.  The LM head is scaled by 2^-11, so every logit comes from such weights; a down projection scaled the
+    same way checks a matrix in the middle of the network."""
+    W, om, gw = tiny
+    specs = synth.TINY.tensor_specs()
+    names = [n for n, _ in specs]
+    w = synth.make_workload(1)
+    for which in ([len(W) - 1], [i for i, n in enumerate(names) if n.endswith("wd")][:1]):
+        W2 = list(W)
+        for i in which:
+            f = (W[i].astype(np.uint32) << 16).view(np.float32) * np.float32(2.0 ** -11)
+            W2[i] = synth.f32_to_bf16_bits(f)       # a power of two: exact
+            mag = np.abs((W2[i].astype(np.uint32) << 16).view(np.float32))
+            assert np.median(mag) < 2e-5 and (mag < 6.1e-5).mean() > 0.95
+        om2 = OracleModel(synth.TINY, W2, "f64")
+        gw2 = ss.Weights(synth.TINY, W2)
+        try:
+            _say(f"tiny, tensor {names[which[0]]} scaled into half's subnormal range")
+            got = ss.ss_forward_logits(gw2, w.prompt_tokens, w.prompt_offsets, w.prompt_lens)
+            ref = np.stack([om2.teacher_forced(w.prompt(i), first=len(w.prompt(i)) - 1)[0] for i in range(w.n)])
+            assert np.abs(ref).max() > 0
+            check_logits(got, ref, f"{names[which[0]]} x 2^-11")
+        finally:
+            gw2.close()
+
+
+def test_unknown_option_is_refused(tiny):
+    W, om, gw = tiny
+    for opt, val in ((1, 0), (99, 0), (ss.SS_OPT_IN_FLIGHT, -1)):
         with pytest.raises(ss.SsError) as e:
             gw.set_option(opt, val)
         assert e.value.code == ss.SS_EINVAL
