@@ -214,7 +214,7 @@ def main() -> int:
     ap.add_argument("--step-iters", type=int, default=20, help="decode-step timing iterations")
     ap.add_argument("--step-rows", type=int, default=16, help="rows of the timed decode step (roofline legs)")
     ap.add_argument("--step-ctx", type=int, default=200, help="context length of the timed decode step")
-    ap.add_argument("--gemm-mode", type=int, default=0, choices=[0, 1, 2, 4, 5, 6],
+    ap.add_argument("--gemm-mode", type=int, default=0, choices=[0, 1, 2, 4, 5, 6, 8],
                     help="small-batch projection kernel: 0 chosen per shape, 1 always k_gemm_skinny, 2 always k_gemm_sweep "
                          "(for A/B profiles; anything but 0 is reported in config)")
     ap.add_argument("--ablation", action="store_true",

@@ -328,7 +328,7 @@ GemmArgs gemm_args(const ss_weights* w, const f16_t* W, const f16_t* X, float* o
     GemmArgs g{};
     g.W = W; g.X = X; g.out = out; g.out_packed = outp; g.N = N; g.Kp = Kp;
     g.m_rows = rows; g.m_stride = rows; g.kp_out = kp_out; g.ksplit = p.ksplit; g.nb = p.nb; g.kd = p.kd;
-    g.kp = p.kp; g.sweep_p = p.sweep_p; g.sweep_gn = p.sweep_gn; g.sweep_kh = p.sweep_kh; g.zero_blk = w->zero_blk;
+    g.kp = p.kp; g.tms = p.tms; g.sweep_p = p.sweep_p; g.sweep_gn = p.sweep_gn; g.sweep_kh = p.sweep_kh; g.zero_blk = w->zero_blk;
     return g;
 }
 
@@ -756,7 +756,7 @@ extern "C" int ss_set_option(ss_weights* w, int32_t option, int32_t value)
 
 extern "C" void ss_set_gemm_mode(int32_t mode)
 {
-    if (mode >= 0 && mode <= 6 && (mode & 3) != 3) ss::set_gemm_mode(mode);
+    if (mode >= 0 && mode <= 14 && (mode & 3) != 3) ss::set_gemm_mode(mode);
 }
 
 extern "C" void ss_weights_destroy(ss_weights* w)

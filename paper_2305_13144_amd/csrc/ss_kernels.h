@@ -52,6 +52,7 @@ struct GemmArgs {
     int ksplit;          // outer k-slices (gemm_plan)
     int nb, kd;          // skinny kernel shape (gemm_plan)
     int kp;              // tiled kernel: k-parts inside the workgroup (gemm_plan)
+    int tms;             //      row strips per tile, 4 or 8 (gemm_plan)
     int sweep_p;         // > 0: sweep kernel with this many waves per workgroup (gemm_plan)
     int sweep_gn;        //      its workgroups per k-slice
     int sweep_kh;        //      2: two waves per unit, each half of every chunk's k-blocks (gemm_plan)

@@ -9,15 +9,18 @@ namespace ss {
 namespace {
 std::atomic<int> g_gemm_mode{0};
 std::atomic<int> g_sweep_split{1};
+std::atomic<int> g_tall_tiles{1};
 constexpr int kSmallMaxKsplit = 8;   // sweep and skinny kernels: at most 8 k-slices
 constexpr int kTiledMaxKsplit = 4;   // tiled kernel: at most 4
-constexpr int kTiledFullTiles = 512; // from this many 64x256 tiles on the tiled kernel runs unsliced
+constexpr int kTiledFullTiles = 512; // from this many tiles on the tiled kernel runs unsliced
 }
 
 void set_gemm_mode(int mode)
 {
     // bit 2 (value 4) added to a mode: the sweep kernel never splits a unit between two waves (A/B measurements)
     g_sweep_split.store((mode & 4) ? 0 : 1, std::memory_order_relaxed);
+    // bit 3 (value 8): the tiled kernel never uses 128-row tiles (A/B measurements)
+    g_tall_tiles.store((mode & 8) ? 0 : 1, std::memory_order_relaxed);
     g_gemm_mode.store(mode & 3, std::memory_order_relaxed);
 }
 int gemm_mode() { return g_gemm_mode.load(std::memory_order_relaxed); }
@@ -45,7 +48,7 @@ int sweep_nbw(int epilogue, int m_rows) { return (epilogue == EPI_SWIGLU || m_ro
 
 GemmPlan gemm_plan(int N, int Kp, int m_rows, int epilogue, int n_cu, int max_ksplit)
 {
-    GemmPlan p{1, 2, 4, 1, 0, 0, 1};
+    GemmPlan p{1, 2, 4, 1, 0, 0, 1, 4};
     const int KB = Kp / 32;
     const int mode = gemm_mode();
     if (m_rows <= kSweepMaxRows) {
@@ -85,7 +88,11 @@ GemmPlan gemm_plan(int N, int Kp, int m_rows, int epilogue, int n_cu, int max_ks
     // (decode batches of 65-256 rows): measured on the 7B shapes, outer k-slices up to 4 (partial sums
     // through HBM are small while rows are few) beat everything else; where slicing is impossible an
     // 8-wave workgroup halves the k range inside the workgroup instead.
-    const int tiles = ((N + 255) / 256) * ((m_rows + 63) / 64);
+    // Tile height: 64 token-rows, or 128 from kTiledTallFrom rows on.  A 64 x 256 tile asks L2 for 20 KiB per 16
+    // matrix-core instructions of every wave, which is more than a compute unit can take in while its matrix cores
+    // run; a 128 x 256 tile asks for 24 KiB per 32.  Below that row count tall tiles leave too many rows idle.
+    p.tms = (m_rows >= kTiledTallFrom && g_tall_tiles.load(std::memory_order_relaxed)) ? 8 : 4;
+    const int tiles = ((N + 255) / 256) * ((m_rows + p.tms * 16 - 1) / (p.tms * 16));
     if (tiles >= kTiledFullTiles) return p;
     while (tiles * p.ksplit < kTiledFullTiles && p.ksplit * 2 <= max_ksplit && p.ksplit < kTiledMaxKsplit &&
            KB / (p.ksplit * 2) >= 16)
@@ -97,10 +104,11 @@ GemmPlan gemm_plan(int N, int Kp, int m_rows, int epilogue, int n_cu, int max_ks
 size_t gemm_partial_rows_bound(int N, int n_max, bool sliced_only)
 {
     // up to kSweepMaxRows rows: at most kSmallMaxKsplit slices; above: the tiled kernel slices only while it
-    // has fewer than kTiledFullTiles tiles, i.e. up to 64 * floor((kTiledFullTiles - 1) / column tiles) rows
+    // has fewer than kTiledFullTiles tiles, i.e. up to 128 * floor((kTiledFullTiles - 1) / column tiles) rows
+    // (its tallest tile)
     const size_t n = (size_t)std::max(n_max, 1);
     const size_t col_tiles = (size_t)(N + 255) / 256;
-    const size_t tiled_rows = 64 * ((size_t)(kTiledFullTiles - 1) / std::max<size_t>(col_tiles, 1));
+    const size_t tiled_rows = 128 * ((size_t)(kTiledFullTiles - 1) / std::max<size_t>(col_tiles, 1));
     size_t need = sliced_only ? 1 : n;
     need = std::max(need, (size_t)kSmallMaxKsplit * std::min<size_t>(n, (size_t)kSweepMaxRows));
     need = std::max(need, (size_t)kTiledMaxKsplit * std::min(n, tiled_rows));

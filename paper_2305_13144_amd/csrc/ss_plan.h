@@ -15,7 +15,10 @@ struct GemmPlan {
     int ksplit, nb, kd, kp;
     int sweep_p, sweep_gn;
     int sweep_kh;   // sweep kernel: waves per unit (1 or 2)
+    int tms;        // tiled kernel: row strips per tile (4 = 64 rows, 8 = 128 rows)
 };
+
+constexpr int kTiledTallFrom = 896;   // token-rows from which the tiled kernel uses 128-row tiles
 
 // n_cu: compute units of the device (the sweep kernel runs one workgroup per unit).
 // max_ksplit: 1 when the consumer reads the output directly (logits).
