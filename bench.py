@@ -451,8 +451,14 @@ def main() -> int:
     sbytes = decode_step_bytes(shape, B0, ctx)
     ach = sbytes / (ms_s.mean() * 1e-3) / 1e9
     # two such steps at once, one per lane, as a group pass runs two micro-batches: both stream the whole model
-    ms_2 = ss.ss_bench_decode_steps_in_flight(gw, ptoks, B0, ctx, a.step_iters + 6)[:, 3:-3]
-    ach_2 = 2 * sbytes / (ms_2.mean() * 1e-3) / 1e9
+    # (not under --roofline-only: the profiles taken from that command keep every kernel's launches undisturbed)
+    two = None
+    if not a.roofline_only:
+        ms_2 = ss.ss_bench_decode_steps_in_flight(gw, ptoks, B0, ctx, a.step_iters + 6)[:, 3:-3]
+        ach_2 = 2 * sbytes / (ms_2.mean() * 1e-3) / 1e9
+        two = dict(what="two such steps running at the same time on two streams (two micro-batches of a group pass): "
+                        "bytes of both / the time one of them takes then",
+                   ms=float(ms_2.mean()), achieved=ach_2, unit="GB/s", frac=ach_2 / HBM_PEAK_GBS)
     step_launches = launches + 3 * shape.n_layers + 3     # + attention and two norms per layer, embedding, final norm, token choice
     traffic, traffic_source = profile_traffic(shape.name, B0, ctx, a.gemm_mode)
     roofline = dict(bound="hbm",
@@ -461,10 +467,7 @@ def main() -> int:
                     achieved=ach, peak=HBM_PEAK_GBS, unit="GB/s", frac=ach / HBM_PEAK_GBS, traffic=traffic,
                     traffic_source=traffic_source, ms=float(ms_s.mean()), ms_min=float(ms_s.min()),
                     algorithmic_bytes=sbytes, launches_per_step=step_launches,
-                    two_steps_in_flight=dict(
-                        what="two such steps running at the same time on two streams (two micro-batches of a group pass): "
-                             "bytes of both / the time one of them takes then",
-                        ms=float(ms_2.mean()), achieved=ach_2, unit="GB/s", frac=ach_2 / HBM_PEAK_GBS),
+                    two_steps_in_flight=two,
                     projection_launches=dict(
                         what="the projection kernels of that step alone (k_gemm_sweep + k_gemm_skinny), back to back",
                         ms=float(ms_w.mean()), achieved=ach_w, unit="GB/s", frac=ach_w / HBM_PEAK_GBS, launches=launches,
@@ -477,8 +480,8 @@ def main() -> int:
                                  algorithmic_bytes=sbytes, achieved_GBs=ach, frac_of_hbm_peak=ach / HBM_PEAK_GBS)
     log(f"plain read stream over the same matrices: {ms_r.mean():.3f} ms/iter -> {roofline['plain_read_stream']['achieved']:.0f} GB/s")
     log(f"weight stream: {ms_w.mean():.3f} ms/iter -> {ach_w:.0f} GB/s; decode step B={B0} ctx={ctx}: "
-        f"{ms_s.mean():.3f} ms -> {ach:.0f} GB/s = {ach / HBM_PEAK_GBS:.3f} of peak; two in flight: {ms_2.mean():.3f} ms each "
-        f"-> {ach_2:.0f} GB/s = {ach_2 / HBM_PEAK_GBS:.3f}")
+        f"{ms_s.mean():.3f} ms -> {ach:.0f} GB/s = {ach / HBM_PEAK_GBS:.3f} of peak"
+        + (f"; two in flight: {two['ms']:.3f} ms each -> {two['achieved']:.0f} GB/s = {two['frac']:.3f}" if two else ""))
     if a.roofline_only:
         # calibration for the HBM byte counters: a plain device-to-device copy of known size (1 GiB read,
         # 1 GiB written) shows up in the same trace as a copyBuffer dispatch.  It runs after the timed legs:

@@ -18,9 +18,9 @@ constexpr int kMaxPos = 4096;     // positions per row (prompt + generated) the 
 constexpr int kMaxBatch = 1024;   // rows per micro-batch the bookkeeping kernel supports
 
 // ---- packed operand layout ---------------------------------------------------------------
-// Every bf16 matrix that feeds an MFMA contraction (weights [N, K] and activations [rows, K]) is
+// Every IEEE-half matrix that feeds an MFMA contraction (weights [N, K] and activations [rows, K]) is
 // stored as 16-row strips of 16x32 blocks; a block is 64 lanes x 8 consecutive-k values, i.e. the
-// register image of one mfma_f32_16x16x32_bf16 operand, 1 KiB contiguous.  K is padded to 64.
+// register image of one mfma_f32_16x16x32_f16 operand, 1 KiB contiguous.  K is padded to 64.
 inline int round_up(int v, int m) { return (v + m - 1) / m * m; }
 inline int padded_k(int k) { return round_up(k, 64); }
 inline size_t packed_elems(int rows, int k) { return (size_t)round_up(rows, 16) * (size_t)padded_k(k); }
