@@ -133,13 +133,14 @@ __global__ __launch_bounds__(256) void k_embed(MbState st, const bf16_t* __restr
 // ------------------------------------------------------------------------------------------ RMSNorm
 // Row j (or sel[j]) of the residual stream: x += sum over k-slices of the previous projection's
 // partial sums (written back when sel is null), then h = x * rsqrt(mean x^2 + eps) * w as packed halves.
-// 1024 threads per row, at most two float4 chunks per thread (d <= 8192); the loads of all k-slices of a
+// T threads per row, at most ITER float4 chunks per thread (T * ITER * 4 >= d, d <= 8192); the loads of all k-slices of a
 // chunk are issued together (the slice loop is unrolled with a predicate), so a row costs about one
 // memory round trip instead of one per slice.
 constexpr int kNormMaxSplit = 8;
-constexpr int kNormRowsFrom = 512;  // token-rows from which k_rmsnorm_rows runs instead of k_rmsnorm
+constexpr int kNormNarrowFrom = 384;   // token-rows from which a row gets 256 threads instead of 1024
 
-__global__ __launch_bounds__(1024) void k_rmsnorm(const int32_t* __restrict__ d_count, float* __restrict__ x,
+template <int T, int ITER>
+__global__ __launch_bounds__(T) void k_rmsnorm(const int32_t* __restrict__ d_count, float* __restrict__ x,
                                                   const float* __restrict__ part, int ksplit, size_t part_stride,
                                                   const bf16_t* __restrict__ w, float eps,
                                                   const int32_t* __restrict__ sel, f16_t* __restrict__ h, int d)
@@ -155,12 +156,12 @@ __global__ __launch_bounds__(1024) void k_rmsnorm(const int32_t* __restrict__ d_
         if (j >= count) return;
         src = sel[j];
     }
-    float4 v[2];
-    uint2 wr[2];
+    float4 v[ITER];
+    uint2 wr[ITER];
     float ss = 0.f;
 #pragma unroll
-    for (int it = 0; it < 2; ++it) {
-        const int c = threadIdx.x * 4 + it * 4096;
+    for (int it = 0; it < ITER; ++it) {
+        const int c = threadIdx.x * 4 + it * T * 4;
         if (c < d) {
             float4 a = *(const float4*)(x + (size_t)src * d + c);
             float4 p[kNormMaxSplit];
@@ -178,22 +179,22 @@ __global__ __launch_bounds__(1024) void k_rmsnorm(const int32_t* __restrict__ d_
     if (j >= count) return;   // block-uniform
     if (ksplit > 0 && !sel) {
 #pragma unroll
-        for (int it = 0; it < 2; ++it) {
-            const int c = threadIdx.x * 4 + it * 4096;
+        for (int it = 0; it < ITER; ++it) {
+            const int c = threadIdx.x * 4 + it * T * 4;
             if (c < d) *(float4*)(x + (size_t)src * d + c) = v[it];
         }
     }
-    __shared__ float red[16];
+    __shared__ float red[T / 64];
     ss = wave_sum(ss);
     if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
     __syncthreads();
     float tot = 0.f;
 #pragma unroll
-    for (int i = 0; i < 16; ++i) tot += red[i];
+    for (int i = 0; i < T / 64; ++i) tot += red[i];
     const float r = rsqrtf(tot / (float)d + eps);
 #pragma unroll
-    for (int it = 0; it < 2; ++it) {
-        const int c = threadIdx.x * 4 + it * 4096;
+    for (int it = 0; it < ITER; ++it) {
+        const int c = threadIdx.x * 4 + it * T * 4;
         if (c < d) {
             const bf16_t* wv = (const bf16_t*)&wr[it];
             const f16_t o[4] = {f2h(v[it].x * r * bf2f(wv[0])), f2h(v[it].y * r * bf2f(wv[1])),
@@ -201,46 +202,6 @@ __global__ __launch_bounds__(1024) void k_rmsnorm(const int32_t* __restrict__ d_
             const size_t at = pk_index(j, c, d);   // d is a multiple of 64: Kp == d
             *(uint2*)(h + at) = *(const uint2*)o;
         }
-    }
-}
-
-// The same operation for forwards of many token-rows (prompt forwards, large decode batches), where the kernel
-// above, a 1024-thread workgroup and a barrier per row, is bound by its own start-up: here a wave owns a row and a
-// workgroup is four independent waves.  Two passes over the row: the first adds the partial sums into the residual
-// stream and accumulates the squares, the second re-reads the row (just written by the same lane, or untouched
-// when there are no partial sums) and writes the normalised halves.  No selection list: all rows below the count.
-__global__ __launch_bounds__(256) void k_rmsnorm_rows(const int32_t* __restrict__ d_count, float* __restrict__ x,
-                                                      const float* __restrict__ part, int ksplit, size_t part_stride,
-                                                      const bf16_t* __restrict__ w, float eps, f16_t* __restrict__ h,
-                                                      int d)
-{
-    const int lane = threadIdx.x & 63;
-    const int j = blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (j >= *d_count) return;   // wave-uniform; the kernel has no barrier
-    float* xr = x + (size_t)j * d;
-    float ss = 0.f;
-    for (int c = lane * 4; c < d; c += 256) {
-        float4 a = *(const float4*)(xr + c);
-        if (ksplit > 0) {
-            float4 p[kNormMaxSplit];
-#pragma unroll
-            for (int s = 0; s < kNormMaxSplit; ++s)
-                p[s] = s < ksplit ? *(const float4*)(part + (size_t)s * part_stride + (size_t)j * d + c)
-                                  : make_float4(0.f, 0.f, 0.f, 0.f);
-#pragma unroll
-            for (int s = 0; s < kNormMaxSplit; ++s) { a.x += p[s].x; a.y += p[s].y; a.z += p[s].z; a.w += p[s].w; }
-            *(float4*)(xr + c) = a;
-        }
-        ss += a.x * a.x + a.y * a.y + a.z * a.z + a.w * a.w;
-    }
-    const float r = rsqrtf(wave_sum(ss) / (float)d + eps);
-    for (int c = lane * 4; c < d; c += 256) {
-        const float4 a = *(const float4*)(xr + c);
-        const uint2 wr = *(const uint2*)(w + c);
-        const bf16_t* wv = (const bf16_t*)&wr;
-        const f16_t o[4] = {f2h(a.x * r * bf2f(wv[0])), f2h(a.y * r * bf2f(wv[1])), f2h(a.z * r * bf2f(wv[2])),
-                            f2h(a.w * r * bf2f(wv[3]))};
-        *(uint2*)(h + pk_index(j, c, d)) = *(const uint2*)o;
     }
 }
 
@@ -1425,12 +1386,16 @@ void launch_rmsnorm(const MbState& st, float* x, const float* part, int ksplit, 
                     const bf16_t* w, float eps, const int32_t* sel, const int32_t* d_nsel, f16_t* h_packed, int d,
                     int n_max, hipStream_t s)
 {
-    // many rows and no selection list: a wave per row (measured at the 7B width: 640 rows 27 instead of 47 us, 15360 rows 0.36 instead of 0.53 ms; at 256 rows the kernel above is the faster one)
-    if (!sel && n_max >= kNormRowsFrom)
-        hipLaunchKernelGGL(k_rmsnorm_rows, dim3((n_max + 3) / 4), dim3(256), 0, s, d_nsel ? d_nsel : st.d_n, x, part,
-                           part ? ksplit : 0, part_stride, w, eps, h_packed, d);
+    // Few rows: 1024 threads per row, the whole row in one round trip.  Many rows (prompt forwards): 256 threads per
+    // row, so that eight rows share a compute unit and the launch is bound by bytes rather than by workgroup
+    // start-up (measured at the 7B width: a prompt forward of 640 token-rows takes 13.8 ms, against 15.8 with 1024
+    // threads per row, whose norm launches took 47 us each there; up to 256 rows the wide form is the faster one:
+    // 24 rows 3.29 against 3.37 ms per decode step, 256 rows equal).
+    if (n_max >= kNormNarrowFrom)
+        hipLaunchKernelGGL((k_rmsnorm<256, 8>), dim3(n_max), dim3(256), 0, s, d_nsel ? d_nsel : st.d_n, x, part,
+                           part ? ksplit : 0, part_stride, w, eps, sel, h_packed, d);
     else
-        hipLaunchKernelGGL(k_rmsnorm, dim3(n_max), dim3(1024), 0, s, d_nsel ? d_nsel : st.d_n, x, part,
+        hipLaunchKernelGGL((k_rmsnorm<1024, 2>), dim3(n_max), dim3(1024), 0, s, d_nsel ? d_nsel : st.d_n, x, part,
                            part ? ksplit : 0, part_stride, w, eps, sel, h_packed, d);
 }
 
