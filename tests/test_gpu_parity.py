@@ -504,6 +504,33 @@ def test_group_results_do_not_depend_on_microbatches_in_flight(tiny):
         gw.set_option(ss.SS_OPT_IN_FLIGHT, 0)
 
 
+def test_an_error_in_one_microbatch_ends_the_group_call_cleanly(tiny):
+    """One query's prompt leaves no room for its cap (prompt + cap > 4096 positions): whichever lane meets its
+    micro-batch reports the error, the other lane stops after the micro-batch it is on, the call returns the error
+    with its message, and the handle works afterwards - with one and with two micro-batches in flight."""
+    W, om, gw = tiny
+    w = synth.make_group(synth.TINY, 40, 4321, ("uniform", 4, 20), ("uniform", 1, 12), 0.3, 12, 4, ("SORT", "BIN", "FCR"),
+                         base_batch=4, max_batch=4)
+    pol = ss.make_policy(("SORT", "BIN", "FCR"), 4, 12, 4)
+    good = ss.ss_run_group(gw, w.prompt_tokens, w.prompt_offsets, w.target_lens, w.pred_lens, 4, pol)
+    rng = np.random.default_rng(1)
+    prompts = [w.prompt(i) for i in range(w.n)]
+    prompts[17] = rng.integers(0, synth.TINY.vocab, size=4095).astype(np.int32)      # 4095 + any cap >= 4 > 4096
+    toks = np.concatenate(prompts).astype(np.int32)
+    offs = np.concatenate([[0], np.cumsum([len(p) for p in prompts])]).astype(np.int32)
+    try:
+        for lanes in (2, 1):
+            gw.set_option(ss.SS_OPT_IN_FLIGHT, lanes)
+            _say(f"group with one impossible query, {lanes} in flight")
+            with pytest.raises(ss.SsError) as e:
+                ss.ss_run_group(gw, toks, offs, w.target_lens, w.pred_lens, 4, pol)
+            assert e.value.code == ss.SS_EINVAL and "positions" in str(e.value)
+            again = ss.ss_run_group(gw, w.prompt_tokens, w.prompt_offsets, w.target_lens, w.pred_lens, 4, pol)
+            assert np.array_equal(again["tokens"], good["tokens"]) and again["stats"]["steps"] == good["stats"]["steps"]
+    finally:
+        gw.set_option(ss.SS_OPT_IN_FLIGHT, ss.SS_IN_FLIGHT_DEFAULT)
+
+
 def test_runs_are_bit_repeatable(tiny, wide2):
     """Race canary: every reduction is ordered (no float atomics), so two runs of the same call must agree
     bit for bit - logits and tokens, skinny and tiled kernels, padded and compacted."""
