@@ -573,8 +573,9 @@ __global__ __launch_bounds__(64 * P) void k_gemm_sweep(GemmArgs a, int n_units, 
 // blocks per k-block straight into registers (1 KiB coalesced each) and is the only wave of the
 // workgroup that needs them.  The activation tile is shared by the 4 waves and staged
 // through LDS in operand order (conflict-free 1 KiB reads).  One k-block per trip; both streams run
-// D k-blocks ahead of the MFMAs in a register ring, so with two workgroups per CU about 100 KiB are in
-// flight per CU, enough to keep HBM busy when the weights are streamed once for a decode batch.
+// D k-blocks ahead of the MFMAs in a register ring (6 for a 64-row tile: 150 KiB in flight per CU with two
+// workgroups, enough to keep HBM busy when the weights are streamed once for a decode batch; 2 for a 128-row
+// tile, whose doubled accumulators leave no registers for more).
 // Workgroup ids are mapped so that the row tiles of one column tile follow each other at a stride of 8:
 // they land on the same XCD (ids are dealt round-robin over the 8 XCDs) at about the same time and share
 // that column tile's weights through its L2.
@@ -585,7 +586,7 @@ __global__ __launch_bounds__(64 * P) void k_gemm_sweep(GemmArgs a, int n_units, 
 template <int TMS, int KP, int EPI>
 __global__ __launch_bounds__(256 * KP, 2) void k_gemm_tiled(GemmArgs a, int kb_per_slice, int n_ntiles, int n_mtiles)
 {
-    constexpr int D = TMS > 4 ? 2 : 4;          // k-blocks in flight (a 128-row tile leaves registers for 2)
+    constexpr int D = TMS > 4 ? 2 : (KP == 1 ? 6 : 4);   // k-blocks in flight
     constexpr int XV = TMS * 64 / 256;          // 16-byte vectors per thread: one k-block of the activation tile
     __shared__ u32x4 lds_all[KP][2][TMS * 64];                // [k-part][stage][row strip][lane]
     __shared__ f32x4 red[KP > 1 ? 4 * TMS : 1][KP > 1 ? 256 : 1];
@@ -614,8 +615,8 @@ __global__ __launch_bounds__(256 * KP, 2) void k_gemm_tiled(GemmArgs a, int kb_p
     // Ring slots are separately named arrays of native vectors indexed only by unrolled constants, so
     // that they stay in registers (a ring that ends up in scratch memory makes every access wait for all
     // outstanding loads).
-    u32x4 w0[4], w1[4], w2[4], w3[4], x0[XV], x1[XV], x2[XV], x3[XV];
-    static_assert(D == 4 || D == 2, "the ring below is written out for 4 slots and for 2");
+    u32x4 w0[4], w1[4], w2[4], w3[4], w4[4], w5[4], x0[XV], x1[XV], x2[XV], x3[XV], x4[XV], x5[XV];
+    static_assert(D == 6 || D == 4 || D == 2, "the ring below is written out for 6, 4 and 2 slots");
 #define SS_WLOAD(W_, KB_)                                                                       \
     _Pragma("unroll") for (int i_ = 0; i_ < 4; ++i_)                                            \
         W_[i_] = W4[((size_t)min(nb0 + i_, NBT - 1) * KB + (KB_)) * 64];
@@ -659,13 +660,26 @@ __global__ __launch_bounds__(256 * KP, 2) void k_gemm_tiled(GemmArgs a, int kb_p
     const int last = max(min(kb1, KB) - 1, 0);   // beyond the range: a harmless in-bounds re-read
     SS_WLOAD(w0, min(kb0, last)) SS_XLOAD(x0, min(kb0, last))
     SS_WLOAD(w1, min(kb0 + 1, last)) SS_XLOAD(x1, min(kb0 + 1, last))
-    if (D == 4) {
+    if (D >= 4) {
         SS_WLOAD(w2, min(kb0 + 2, last)) SS_XLOAD(x2, min(kb0 + 2, last))
         SS_WLOAD(w3, min(kb0 + 3, last)) SS_XLOAD(x3, min(kb0 + 3, last))
     }
+    if (D == 6) {
+        SS_WLOAD(w4, min(kb0 + 4, last)) SS_XLOAD(x4, min(kb0 + 4, last))
+        SS_WLOAD(w5, min(kb0 + 5, last)) SS_XLOAD(x5, min(kb0 + 5, last))
+    }
     SS_XSTORE(0, x0, kb0 < kb1)
     __syncthreads();
-    if (D == 4) {
+    if (D == 6) {
+        for (int it = 0; it < part_len; it += 6) {
+            SS_TRIP(0, w0, x0, x1)
+            SS_TRIP(1, w1, x1, x2)
+            SS_TRIP(2, w2, x2, x3)
+            SS_TRIP(3, w3, x3, x4)
+            SS_TRIP(4, w4, x4, x5)
+            SS_TRIP(5, w5, x5, x0)
+        }
+    } else if (D == 4) {
         for (int it = 0; it < part_len; it += 4) {
             SS_TRIP(0, w0, x0, x1)
             SS_TRIP(1, w1, x1, x2)
