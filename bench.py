@@ -230,7 +230,7 @@ def main() -> int:
     ap.add_argument("--in-flight", type=int, default=2, choices=[1, 2],
                     help="micro-batches of a group pass generated at the same time (SS_OPT_IN_FLIGHT; reported in config)")
     ap.add_argument("--no-cfg4", action="store_true", help="skip the configuration-4 leg of the default run")
-    ap.add_argument("--time-budget-s", type=float, default=590.0,
+    ap.add_argument("--time-budget-s", type=float, default=560.0,
                     help="seconds the whole program should stay within: the optional legs after the timed passes (the "
                          "configuration-4 comparison, then the sampled rerun) shrink or are left out, and say so in the JSON, "
                          "when the passes asked for have already used most of it")
