@@ -174,7 +174,10 @@ typedef struct {
  *   target_lens     host, int32[B], >= 1
  *   flags           0 or SS_COMPACT.  Without it a finished row keeps being computed on its own last
  *                   token until the micro-batch ends (the padding that vanilla batching pays for);
- *                   with it the live batch shrinks.  Outputs are identical either way.
+ *                   with it the live batch shrinks.  Lengths and flags are identical either way; tokens
+ *                   are too, except where a row's two largest logits lie within the rounding difference
+ *                   between two launch shapes (about 1e-3 of the largest logit) once the live batch has
+ *                   shrunk past a multiple of 16 rows.
  *   out_tokens      host, int32[B*max_new] row-major; -1 after the emitted length
  *   out_lens        host, int32[B]   = min(target, max_new)
  *   out_failed      host, uint8[B]   = target > max_new  (an FCR failure: to be recomputed later)
