@@ -520,7 +520,8 @@ def main() -> int:
                warmup=a.warmup, ms_per_step=(dt / a.steps * 1e3 if a.steps else 0.0), higher_is_better=True, scaling="weak",
                vs_baseline=None, dtype="bf16", data="synthetic",
                config=dict(workload=f"config {a.cfg}: {shape.name}, group {wl.n}, policy {'+'.join(wl.flags) or 'vanilla'}"
-                                    f" bin {wl.bin_width} base batch {wl.base_batch} L_max {wl.l_max}",
+                                    f" bin {wl.bin_width} base batch {wl.base_batch} L_max {wl.l_max}"
+                                    + (f", {a.in_flight} micro-batches in flight" if a.in_flight > 1 else ""),
                            group=wl.n, useful_tokens=useful, steps_per_pass=st["steps"],
                            padded_row_steps=st["padded_row_steps"], computed_row_steps=st["computed_row_steps"],
                            n_failed=st["n_failed"], micro_batches=[st["n_mb_first"], st["n_mb_failure"]],
