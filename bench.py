@@ -227,7 +227,7 @@ def main() -> int:
                          "(the paper's Fig. 3a / 3b on the synthetic workload), ('sync') the group run with ends "
                          "that the host must poll for, against the poll period, greedy and sampled at T=0.5, or ('step') "
                          "the time of one decode forward against live rows and against context length (App. D)")
-    ap.add_argument("--in-flight", type=int, default=2, choices=[1, 2],
+    ap.add_argument("--in-flight", type=int, default=4, choices=[1, 2, 3, 4],
                     help="micro-batches of a group pass generated at the same time (SS_OPT_IN_FLIGHT; reported in config)")
     ap.add_argument("--no-cfg4", action="store_true", help="skip the configuration-4 leg of the default run")
     ap.add_argument("--time-budget-s", type=float, default=560.0,
@@ -327,7 +327,7 @@ def main() -> int:
         return a.time_budget_s - (time.time() - T_START) - reserve_s
 
     if a.in_flight > 1 and a.steps > 0 and not a.roofline_only:
-        # the same pass with one micro-batch at a time: what generating two at once is worth on this group
+        # the same pass with one micro-batch at a time: what generating several at once is worth on this group
         if 1.3 * pass_s > budget_left():
             skipped["one_microbatch_at_a_time"] = f"left out: {budget_left():.0f} s of the {a.time_budget_s:.0f} s budget remained"
         else:
@@ -338,10 +338,11 @@ def main() -> int:
             assert all(r1["stats"][k] == st[k] for k in ("steps", "padded_row_steps", "computed_row_steps", "n_failed"))
             extras["one_microbatch_at_a_time"] = dict(
                 what="the same pass with SS_OPT_IN_FLIGHT = 1: identical tokens and counters, micro-batches one after another",
+                in_flight=a.in_flight,
                 useful_tokens_per_s=useful / (r1["stats"]["wall_ms"] / 1e3), ms=r1["stats"]["wall_ms"],
-                two_in_flight_over_it=r1["stats"]["wall_ms"] / st["wall_ms"])
-            log(f"one micro-batch at a time: {r1['stats']['wall_ms']:.0f} ms -> two in flight are "
-                f"{extras['one_microbatch_at_a_time']['two_in_flight_over_it']:.3f}x")
+                in_flight_over_it=r1["stats"]["wall_ms"] / st["wall_ms"])
+            log(f"one micro-batch at a time: {r1['stats']['wall_ms']:.0f} ms -> {a.in_flight} in flight are "
+                f"{extras['one_microbatch_at_a_time']['in_flight_over_it']:.3f}x")
 
     # The configuration-4 leg: one scheduled pass over a group 4x as large with micro-batches of up to 256 rows costs
     # about 2.15 timed passes, the vanilla pass over that group about 4.85 more.  What is left of the time budget after
@@ -450,15 +451,19 @@ def main() -> int:
     ms_s = ss.ss_bench_decode_step(gw, ptoks, B0, ctx, a.step_iters + 3)[3:]
     sbytes = decode_step_bytes(shape, B0, ctx)
     ach = sbytes / (ms_s.mean() * 1e-3) / 1e9
-    # two such steps at once, one per lane, as a group pass runs two micro-batches: both stream the whole model
+    # several such steps at once, one per lane, as a group pass runs its micro-batches: each streams the whole model
     # (not under --roofline-only: the profiles taken from that command keep every kernel's launches undisturbed)
     two = None
-    if not a.roofline_only:
-        ms_2 = ss.ss_bench_decode_steps_in_flight(gw, ptoks, B0, ctx, a.step_iters + 6)[:, 3:-3]
-        ach_2 = 2 * sbytes / (ms_2.mean() * 1e-3) / 1e9
-        two = dict(what="two such steps running at the same time on two streams (two micro-batches of a group pass): "
-                        "bytes of both / the time one of them takes then",
-                   ms=float(ms_2.mean()), achieved=ach_2, unit="GB/s", frac=ach_2 / HBM_PEAK_GBS)
+    if not a.roofline_only and a.in_flight > 1:
+        per_lanes = {}
+        for lanes in sorted({2, a.in_flight}):
+            ms_l = ss.ss_bench_decode_steps_in_flight(gw, ptoks, B0, ctx, a.step_iters + 6, lanes)[:, 3:-3]
+            ach_l = lanes * sbytes / (ms_l.mean() * 1e-3) / 1e9
+            per_lanes[lanes] = dict(ms=float(ms_l.mean()), achieved=ach_l, frac=ach_l / HBM_PEAK_GBS)
+        two = dict(what=f"{a.in_flight} such steps running at the same time on {a.in_flight} streams (as many micro-batches of a "
+                        "group pass): bytes of all / the time one of them takes then",
+                   lanes=a.in_flight, unit="GB/s", **per_lanes[a.in_flight],
+                   **({"with_two_lanes": per_lanes[2]} if a.in_flight != 2 else {}))
     step_launches = launches + 3 * shape.n_layers + 3     # + attention and two norms per layer, embedding, final norm, token choice
     traffic, traffic_source = profile_traffic(shape.name, B0, ctx, a.gemm_mode)
     roofline = dict(bound="hbm",
@@ -467,7 +472,7 @@ def main() -> int:
                     achieved=ach, peak=HBM_PEAK_GBS, unit="GB/s", frac=ach / HBM_PEAK_GBS, traffic=traffic,
                     traffic_source=traffic_source, ms=float(ms_s.mean()), ms_min=float(ms_s.min()),
                     algorithmic_bytes=sbytes, launches_per_step=step_launches,
-                    two_steps_in_flight=two,
+                    steps_in_flight=two,
                     projection_launches=dict(
                         what="the projection kernels of that step alone (k_gemm_sweep + k_gemm_skinny), back to back",
                         ms=float(ms_w.mean()), achieved=ach_w, unit="GB/s", frac=ach_w / HBM_PEAK_GBS, launches=launches,
@@ -481,7 +486,7 @@ def main() -> int:
     log(f"plain read stream over the same matrices: {ms_r.mean():.3f} ms/iter -> {roofline['plain_read_stream']['achieved']:.0f} GB/s")
     log(f"weight stream: {ms_w.mean():.3f} ms/iter -> {ach_w:.0f} GB/s; decode step B={B0} ctx={ctx}: "
         f"{ms_s.mean():.3f} ms -> {ach:.0f} GB/s = {ach / HBM_PEAK_GBS:.3f} of peak"
-        + (f"; two in flight: {two['ms']:.3f} ms each -> {two['achieved']:.0f} GB/s = {two['frac']:.3f}" if two else ""))
+        + (f"; {two['lanes']} in flight: {two['ms']:.3f} ms each -> {two['achieved']:.0f} GB/s = {two['frac']:.3f}" if two else ""))
     if a.roofline_only:
         # calibration for the HBM byte counters: a plain device-to-device copy of known size (1 GiB read,
         # 1 GiB written) shows up in the same trace as a copyBuffer dispatch.  It runs after the timed legs:

@@ -135,18 +135,22 @@ void ss_weights_destroy(ss_weights* w);
 
 /*
  * Per-handle options.
- *   option SS_OPT_IN_FLIGHT, value = 1 or 2: how many micro-batches of a group pass (ss_run_group,
+ *   option SS_OPT_IN_FLIGHT, value = 1 .. SS_IN_FLIGHT_MAX: how many micro-batches of a group pass (ss_run_group,
  *   ss_run_group_generate) are generated at the same time.  The micro-batches of a pass (Sec. 4.1) are independent
- *   of each other, and a decode step of a few rows leaves the memory system idle between its kernels; with 2 the
- *   call hands the pass's micro-batches, longest cap first, to two host threads, each with a stream, a workspace
- *   and a key/value cache of its own, so that one micro-batch's kernels run in the other's gaps.  Every query's
- *   tokens are the same as with 1; only the order in which micro-batches finish changes.  The stream argument of
- *   the call is used for one of the two; the other runs on a stream the handle owns.  The call returns when both
- *   are done.  Device time in the statistics is summed per micro-batch and so can exceed the wall time.
+ *   of each other, and a decode step of a few rows leaves the memory system idle between its kernels; with more than
+ *   one the call hands the pass's micro-batches, longest cap first, to that many host threads, each with a stream, a
+ *   workspace and a key/value cache of its own, so that one micro-batch's kernels run in the others' gaps (measured
+ *   at the 7B shape, 16-row steps: 58 % of the HBM peak with one in flight, 69 % with two, 70 % with three; the
+ *   further gain of three and four on a whole group is a shorter tail at the end of a pass).  Every query's tokens
+ *   are the same as with 1; only the order in which micro-batches finish changes.  The stream argument of the call
+ *   is used for one of them; the others run on streams the handle owns.  The call returns when all are done.  Device
+ *   time in the statistics is summed per micro-batch and so can exceed the wall time.  Device memory: one workspace
+ *   and key/value cache per lane in use, each as large as the largest micro-batch that lane has run.
  * Errors: SS_EINVAL (NULL handle, unknown option, value out of range), SS_ESTATE (a call is in flight).
  */
 #define SS_OPT_IN_FLIGHT 2
-#define SS_IN_FLIGHT_DEFAULT 2
+#define SS_IN_FLIGHT_MAX 4
+#define SS_IN_FLIGHT_DEFAULT 4
 int ss_set_option(ss_weights* w, int32_t option, int32_t value);
 
 /* ------------------------------------------------------------------ generation */
@@ -325,14 +329,14 @@ int ss_bench_decode_step(ss_weights* w, const int32_t* prompt_tokens, int32_t B,
                          double* ms_out, void* hip_stream);
 
 /*
- * Measurement entry point: ss_bench_decode_step on two lanes at once, as a group pass with SS_OPT_IN_FLIGHT = 2
- * runs two micro-batches: each of two host threads prefills its own B rows of ctx tokens on its own stream, both
- * wait for each other, then each times `iters` decode forwards.
- *   ms_out  host, double[2*iters]: lane 0's forwards, then lane 1's (device time of each, HIP events on that
- *           lane's stream).  Both lanes stream the whole model once per forward.
+ * Measurement entry point: ss_bench_decode_step on `lanes` lanes at once (1 .. SS_IN_FLIGHT_MAX), as a group pass
+ * with SS_OPT_IN_FLIGHT = lanes runs that many micro-batches: each of `lanes` host threads prefills its own B rows of
+ * ctx tokens on its own stream, all wait for each other, then each times `iters` decode forwards.
+ *   ms_out  host, double[lanes*iters]: lane 0's forwards, then lane 1's, ... (device time of each, HIP events on
+ *           that lane's stream).  Every lane streams the whole model once per forward.
  */
 int ss_bench_decode_steps_in_flight(ss_weights* w, const int32_t* prompt_tokens, int32_t B, int32_t ctx, int32_t iters,
-                                    double* ms_out);
+                                    int32_t lanes, double* ms_out);
 
 /*
  * Measurement entry point: the projection kernels of one decode step alone.  Launches, back to back on

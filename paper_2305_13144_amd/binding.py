@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libss.so")
 SS_OK, SS_EINVAL, SS_ENOMEM, SS_EDEVICE, SS_ESTATE = 0, -1, -2, -3, -4
 SS_SORT, SS_BIN, SS_FCR, SS_VBS, SS_COMPACT = 1, 2, 4, 8, 16
 SS_VBS_CLAMP_FLOOR, SS_VBS_PAPER_POW2 = 0, 1
-SS_OPT_IN_FLIGHT, SS_IN_FLIGHT_DEFAULT = 2, 2
+SS_OPT_IN_FLIGHT, SS_IN_FLIGHT_MAX, SS_IN_FLIGHT_DEFAULT = 2, 4, 4
 SS_BF16, SS_F32 = 0, 1
 FLAG_BITS = dict(SORT=SS_SORT, BIN=SS_BIN, FCR=SS_FCR, VBS=SS_VBS, COMPACT=SS_COMPACT)
 
@@ -108,7 +108,7 @@ def lib():
         L.ss_run_group_generate.argtypes = [vp, i32p, i32p, C.c_int32, i32p, C.c_int32, C.POINTER(ss_policy),
                                             C.POINTER(ss_gen_opts), i32p, i32p, C.POINTER(ss_group_stats), vp]
         L.ss_bench_decode_step.argtypes = [vp, i32p, C.c_int32, C.c_int32, C.c_int32, vp, vp]
-        L.ss_bench_decode_steps_in_flight.argtypes = [vp, i32p, C.c_int32, C.c_int32, C.c_int32, vp]
+        L.ss_bench_decode_steps_in_flight.argtypes = [vp, i32p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, vp]
         L.ss_bench_weight_stream.argtypes = [vp, C.c_int32, C.c_int32, vp, vp, vp]
         L.ss_bench_read_stream.argtypes = [vp, C.c_int32, vp, vp, vp]
         for name in EXPORTS:
@@ -305,13 +305,13 @@ def ss_bench_decode_step(w: Weights, prompt_tokens, B: int, ctx: int, iters: int
     return ms
 
 
-def ss_bench_decode_steps_in_flight(w: Weights, prompt_tokens, B: int, ctx: int, iters: int) -> np.ndarray:
-    """[2, iters] device milliseconds: two lanes' decode forwards running at the same time."""
+def ss_bench_decode_steps_in_flight(w: Weights, prompt_tokens, B: int, ctx: int, iters: int, lanes: int = 2) -> np.ndarray:
+    """[lanes, iters] device milliseconds: the lanes' decode forwards running at the same time."""
     pt = _i32(prompt_tokens)
     assert pt.size == B * ctx
-    ms = np.zeros(2 * iters, np.float64)
-    _check(lib().ss_bench_decode_steps_in_flight(w.h, _ptr(pt), B, ctx, iters, _ptr(ms)))
-    return ms.reshape(2, iters)
+    ms = np.zeros(lanes * iters, np.float64)
+    _check(lib().ss_bench_decode_steps_in_flight(w.h, _ptr(pt), B, ctx, iters, lanes, _ptr(ms)))
+    return ms.reshape(lanes, iters)
 
 
 def ss_bench_weight_stream(w: Weights, B: int, iters: int, stream: Optional[int] = None):

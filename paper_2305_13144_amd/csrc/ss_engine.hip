@@ -121,10 +121,10 @@ struct Workspace {
 }  // namespace
 
 // What one micro-batch in flight owns: its stream, workspace, device state and the token choice of its forwards.
-// A handle has kLanes of them; every entry point works on lane 0, and a group pass may run a second micro-batch
-// on lane 1 at the same time (the weights are shared and only read).
+// A handle has kLanes of them; every entry point works on lane 0, and a group pass may run further micro-batches
+// on the other lanes at the same time (the weights are shared and only read).
 namespace {
-constexpr int kLanes = 2;
+constexpr int kLanes = SS_IN_FLIGHT_MAX;
 struct Lane {
     hipStream_t stream = nullptr;
     Workspace ws;
@@ -157,7 +157,7 @@ struct ss_weights {
     Lane lane[kLanes];
     std::atomic<int> busy{0};
     void* scratch_ptr = nullptr;   // device address of this device's static scratch array
-    int in_flight = SS_IN_FLIGHT_DEFAULT;       // micro-batches a group pass keeps in flight (1 or 2)
+    int in_flight = SS_IN_FLIGHT_DEFAULT;       // micro-batches a group pass keeps in flight (1 to kLanes)
 };
 
 namespace {
@@ -747,7 +747,7 @@ extern "C" int ss_set_option(ss_weights* w, int32_t option, int32_t value)
     BusyGuard guard(w);
     if (!guard.ok) return ss::fail(SS_ESTATE, "another call is in flight on this handle");
     if (option == SS_OPT_IN_FLIGHT) {
-        if (value < 1 || value > kLanes) return ss::fail(SS_EINVAL, "SS_OPT_IN_FLIGHT takes 1 or %d", kLanes);
+        if (value < 1 || value > kLanes) return ss::fail(SS_EINVAL, "SS_OPT_IN_FLIGHT takes 1 to %d", kLanes);
         w->in_flight = value;
         return SS_OK;
     }
@@ -930,9 +930,9 @@ extern "C" int ss_forward_logits(ss_weights* w, const int32_t* tokens, const int
 namespace {
 
 // The group pipeline shared by ss_run_group (gen == nullptr, lengths known) and ss_run_group_generate.
-// A pass over a plan hands its micro-batches out one at a time, longest cap first, to the lanes at work: one
-// lane (the calling thread) or two (a second host thread on lane 1 with its own stream and workspace), so that
-// one micro-batch's kernels fill the gaps between the other's.  What a query receives does not depend on the
+// A pass over a plan hands its micro-batches out one at a time, longest cap first, to the lanes at work: the
+// calling thread on lane 0 and up to kLanes - 1 further host threads, each on a lane with its own stream and
+// workspace, so that one micro-batch's kernels fill the gaps between the others'.  What a query receives does not depend on the
 // lane or the order: micro-batches are independent, failures are sorted before they are rescheduled.
 int run_group_impl(ss_weights* w, const int32_t* prompt_tokens, const int32_t* prompt_offsets, int32_t n,
                    const int32_t* target_lens, const int32_t* pred_lens, int32_t bin, const ss_policy* policy,
@@ -1071,15 +1071,16 @@ int run_group_impl(ss_weights* w, const int32_t* prompt_tokens, const int32_t* p
                 const int64_t cb = (int64_t)pl->mb_cap[b] * (64 + pl->mb_offsets[b + 1] - pl->mb_offsets[b]);
                 return ca > cb;
             });
-        std::thread second;
-        if (lanes > 1) {
+        std::vector<std::thread> others;
+        for (int l = 1; l < lanes; ++l) {
             try {
-                second = std::thread([&] { work_noexcept(ps, w->lane[1], w->lane[1].stream); });
-            } catch (...) {   // no second thread to be had: the pass runs on this one alone
+                others.emplace_back([&, l] { work_noexcept(ps, w->lane[l], w->lane[l].stream); });
+            } catch (...) {   // no further thread to be had: the pass runs on those it has
+                break;
             }
         }
         work_noexcept(ps, w->lane[0], s);
-        if (second.joinable()) second.join();
+        for (std::thread& t : others) t.join();
         if (ps.rc != SS_OK) return ss::fail(ps.rc, "%s", ps.err.c_str());
         return SS_OK;
     };
@@ -1226,30 +1227,36 @@ extern "C" int ss_bench_decode_step(ss_weights* w, const int32_t* prompt_tokens,
 }
 
 extern "C" int ss_bench_decode_steps_in_flight(ss_weights* w, const int32_t* prompt_tokens, int32_t B, int32_t ctx,
-                                               int32_t iters, double* ms_out)
+                                               int32_t iters, int32_t lanes, double* ms_out)
 {
     ss::clear_error();
     if (int rc = check_bench_decode_step(w, prompt_tokens, B, ctx, iters, ms_out)) return rc;
+    if (lanes < 1 || lanes > kLanes) return ss::fail(SS_EINVAL, "lanes outside [1, %d]", kLanes);
     BusyGuard guard(w);
     if (!guard.ok) return ss::fail(SS_ESTATE, "another call is in flight on this handle");
     std::atomic<int> gate{0};
-    int rc1 = SS_OK;
-    std::string err1;
-    std::thread second;
-    try {
-        second = std::thread([&] {
-            rc1 = bench_decode_step_lane(w, w->lane[1], w->lane[1].stream, prompt_tokens, B, ctx, iters, ms_out + iters,
-                                         &gate, kLanes);
-            if (rc1) err1 = ss_last_error();
-        });
-    } catch (...) {
-        return ss::fail(SS_ESTATE, "could not start a second host thread");
+    std::vector<int> rc((size_t)lanes, SS_OK);
+    std::vector<std::string> err((size_t)lanes);
+    auto run = [&](int l) {
+        rc[l] = bench_decode_step_lane(w, w->lane[l], w->lane[l].stream, prompt_tokens, B, ctx, iters,
+                                       ms_out + (size_t)l * iters, &gate, lanes);
+        if (rc[l]) err[l] = ss_last_error();
+    };
+    std::vector<std::thread> others;
+    for (int l = 1; l < lanes; ++l) {
+        try {
+            others.emplace_back(run, l);
+        } catch (...) {
+            // the lanes already started wait at the gate for `lanes` arrivals: stand in for the missing ones
+            gate.fetch_add(lanes - l);
+            for (std::thread& t : others) t.join();
+            return ss::fail(SS_ESTATE, "could not start host thread %d", l);
+        }
     }
-    const int rc0 = bench_decode_step_lane(w, w->lane[0], w->lane[0].stream, prompt_tokens, B, ctx, iters, ms_out, &gate,
-                                           kLanes);
-    second.join();
-    if (rc0) return rc0;
-    if (rc1) return ss::fail(rc1, "%s", err1.c_str());
+    run(0);
+    for (std::thread& t : others) t.join();
+    for (int l = 0; l < lanes; ++l)
+        if (rc[l]) return ss::fail(rc[l], "%s", err[l].c_str());
     return SS_OK;
 }
 

@@ -466,7 +466,7 @@ def test_tiny_group_every_policy_same_answers(tiny, flags):
 
 
 def test_group_results_do_not_depend_on_microbatches_in_flight(tiny):
-    """Two micro-batches in flight (two host threads, two streams, two workspaces) against one at a time: every
+    """Two to four micro-batches in flight (as many host threads, streams and workspaces) against one at a time: every
     query's tokens and every counter of the group are the same, for known lengths and for sampled rows that end
     by themselves, with failures and a recomputation pass in both."""
     W, om, gw = tiny
@@ -479,7 +479,7 @@ def test_group_results_do_not_depend_on_microbatches_in_flight(tiny):
                 "n_mb_failure", "prompt_tokens", "polls", "idle_steps")
     got = {}
     try:
-        for lanes in (1, 2, 2):
+        for lanes in (1, 2, 4, 3):
             gw.set_option(ss.SS_OPT_IN_FLIGHT, lanes)
             _say(f"tiny group of {w.n}, {lanes} in flight")
             a = ss.ss_run_group(gw, w.prompt_tokens, w.prompt_offsets, w.target_lens, w.pred_lens, 8, pol)
@@ -499,7 +499,7 @@ def test_group_results_do_not_depend_on_microbatches_in_flight(tiny):
     finally:
         gw.set_option(ss.SS_OPT_IN_FLIGHT, ss.SS_IN_FLIGHT_DEFAULT)
     with pytest.raises(ss.SsError):
-        gw.set_option(ss.SS_OPT_IN_FLIGHT, 3)
+        gw.set_option(ss.SS_OPT_IN_FLIGHT, ss.SS_IN_FLIGHT_MAX + 1)
     with pytest.raises(ss.SsError):
         gw.set_option(ss.SS_OPT_IN_FLIGHT, 0)
 
@@ -507,7 +507,7 @@ def test_group_results_do_not_depend_on_microbatches_in_flight(tiny):
 def test_an_error_in_one_microbatch_ends_the_group_call_cleanly(tiny):
     """One query's prompt leaves no room for its cap (prompt + cap > 4096 positions): whichever lane meets its
     micro-batch reports the error, the other lane stops after the micro-batch it is on, the call returns the error
-    with its message, and the handle works afterwards - with one and with two micro-batches in flight."""
+    with its message, and the handle works afterwards - with one, two and four micro-batches in flight."""
     W, om, gw = tiny
     w = synth.make_group(synth.TINY, 40, 4321, ("uniform", 4, 20), ("uniform", 1, 12), 0.3, 12, 4, ("SORT", "BIN", "FCR"),
                          base_batch=4, max_batch=4)
@@ -519,7 +519,7 @@ def test_an_error_in_one_microbatch_ends_the_group_call_cleanly(tiny):
     toks = np.concatenate(prompts).astype(np.int32)
     offs = np.concatenate([[0], np.cumsum([len(p) for p in prompts])]).astype(np.int32)
     try:
-        for lanes in (2, 1):
+        for lanes in (4, 2, 1):
             gw.set_option(ss.SS_OPT_IN_FLIGHT, lanes)
             _say(f"group with one impossible query, {lanes} in flight")
             with pytest.raises(ss.SsError) as e:

@@ -116,7 +116,7 @@ def test_generation_entry_points_reject_null_without_touching_a_gpu(lib):
     assert lib.ss_forward_logits(None, None, None, 1, None, 0, None, None) == ss.SS_EINVAL
     assert lib.ss_run_group(None, None, None, 1, None, None, 0, None, None, None, None, None) == ss.SS_EINVAL
     assert lib.ss_bench_decode_step(None, None, 1, 1, 1, None, None) == ss.SS_EINVAL
-    assert lib.ss_bench_decode_steps_in_flight(None, None, 1, 1, 1, None) == ss.SS_EINVAL
+    assert lib.ss_bench_decode_steps_in_flight(None, None, 1, 1, 1, 2, None) == ss.SS_EINVAL
     assert lib.ss_bench_weight_stream(None, 1, 1, None, None, None) == ss.SS_EINVAL
     assert lib.ss_bench_read_stream(None, 1, None, None, None) == ss.SS_EINVAL
     assert lib.ss_generate_microbatch(None, None, None, 1, 1, None, 0, None, None, None, None, None) == ss.SS_EINVAL
