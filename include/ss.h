@@ -140,8 +140,8 @@ void ss_weights_destroy(ss_weights* w);
  *   of each other, and a decode step of a few rows leaves the memory system idle between its kernels; with more than
  *   one the call hands the pass's micro-batches, longest cap first, to that many host threads, each with a stream, a
  *   workspace and a key/value cache of its own, so that one micro-batch's kernels run in the others' gaps (measured
- *   at the 7B shape, 16-row steps: 58 % of the HBM peak with one in flight, 69 % with two, 70 % with three; the
- *   further gain of three and four on a whole group is a shorter tail at the end of a pass).  Every query's tokens
+ *   at the 7B shape, 16-row steps: 58 % of the HBM peak with one in flight, 69 % with two, 70 % with three, 72 %
+ *   with four; on a whole group the third and fourth also shorten the tail at the end of a pass).  Every query's tokens
  *   are the same as with 1; only the order in which micro-batches finish changes.  The stream argument of the call
  *   is used for one of them; the others run on streams the handle owns.  The call returns when all are done.  Device
  *   time in the statistics is summed per micro-batch and so can exceed the wall time.  Device memory: one workspace
