@@ -523,7 +523,7 @@ def main() -> int:
 
     out = dict(metric="useful_generated_tokens_per_s", value=value, unit="tokens/s", n_gpus=1, steps=a.steps,
                warmup=a.warmup, ms_per_step=(dt / a.steps * 1e3 if a.steps else 0.0), higher_is_better=True, scaling="weak",
-               vs_baseline=None, dtype="bf16", data="synthetic",
+               vs_baseline=None, dtype="f16", data="synthetic",
                config=dict(workload=f"config {a.cfg}: {shape.name}, group {wl.n}, policy {'+'.join(wl.flags) or 'vanilla'}"
                                     f" bin {wl.bin_width} base batch {wl.base_batch} L_max {wl.l_max}"
                                     + (f", {a.in_flight} micro-batches in flight" if a.in_flight > 1 else ""),
@@ -531,7 +531,9 @@ def main() -> int:
                            padded_row_steps=st["padded_row_steps"], computed_row_steps=st["computed_row_steps"],
                            n_failed=st["n_failed"], micro_batches=[st["n_mb_first"], st["n_mb_failure"]],
                            samples_per_s=(wl.n * a.steps / dt if a.steps else 0.0), prefill_ms=st["prefill_ms"], decode_ms=st["decode_ms"],
-                           plan_ms=st["plan_ms"], microbatches_in_flight=a.in_flight, **({"reduced_layers": a.layers} if a.layers > 0 else {}),
+                           plan_ms=st["plan_ms"], microbatches_in_flight=a.in_flight,
+                           precision="weights: bf16 values, held as IEEE half (exact); projection inputs and key/value slots: "
+                                     "IEEE half; MFMA f16 x f16 with fp32 accumulation; softmax, norms, residual stream fp32", **({"reduced_layers": a.layers} if a.layers > 0 else {}),
                            **({"gemm_mode": a.gemm_mode} if a.gemm_mode else {})),
                roofline=roofline, cpu_baseline=cpu, paper_context=PAPER_CONTEXT,
                **({"legs_left_out": skipped} if skipped else {}), **extras)
