@@ -287,6 +287,8 @@ def main() -> int:
     t0 = time.perf_counter()
     for i in range(a.steps):
         r = run(pol, wl.pred_lens, wl.bin_width)
+        if a.steps > 1:
+            log(f"pass {i + 1}/{a.steps}: {r['stats']['wall_ms']:.0f} ms")     # a long run must not look hung
     assert hip.hipDeviceSynchronize() == 0
     dt = time.perf_counter() - t0
     useful = int(wl.target_lens.sum())
