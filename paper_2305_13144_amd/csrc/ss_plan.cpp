@@ -12,7 +12,8 @@ std::atomic<int> g_sweep_split{1};
 std::atomic<int> g_tall_tiles{1};
 constexpr int kSmallMaxKsplit = 8;   // sweep and skinny kernels: at most 8 k-slices
 constexpr int kTiledMaxKsplit = 4;   // tiled kernel: at most 4
-constexpr int kTiledFullTiles = 512; // from this many tiles on the tiled kernel runs unsliced
+constexpr int kTiledNoSliceTiles = 256;  // from this many tiles on (one per compute unit) the tiled kernel runs unsliced
+constexpr int kTiledFullGroups = 320;    // below that, k-slices double until it has this many workgroups
 }
 
 void set_gemm_mode(int mode)
@@ -93,8 +94,12 @@ GemmPlan gemm_plan(int N, int Kp, int m_rows, int epilogue, int n_cu, int max_ks
     // run; a 128 x 256 tile asks for 24 KiB per 32.  Below that row count tall tiles leave too many rows idle.
     p.tms = (m_rows >= kTiledTallFrom && g_tall_tiles.load(std::memory_order_relaxed)) ? 8 : 4;
     const int tiles = ((N + 255) / 256) * ((m_rows + p.tms * 16 - 1) / (p.tms * 16));
-    if (tiles >= kTiledFullTiles) return p;
-    while (tiles * p.ksplit < kTiledFullTiles && p.ksplit * 2 <= max_ksplit && p.ksplit < kTiledMaxKsplit &&
+    // Measured at the 7B shape, same GPU, against slicing up to 512 workgroups whenever there are fewer than 512 tiles:
+    // prompt forward of 640 token-rows 12.6 against 13.8 ms (q|k|v, 480 tiles, now unsliced; o and down, 160 tiles, two
+    // slices instead of four), 1280 token-rows 19.6 against 21.9, decode steps of 129-256 rows 3-4 % shorter; stopping at
+    // 256 workgroups instead of 320 costs 4 % at 1024 token-rows, going on to 384 costs 5 % at 640 and 1280.
+    if (tiles >= kTiledNoSliceTiles) return p;
+    while (tiles * p.ksplit < kTiledFullGroups && p.ksplit * 2 <= max_ksplit && p.ksplit < kTiledMaxKsplit &&
            KB / (p.ksplit * 2) >= 16)
         p.ksplit *= 2;
     if (p.ksplit == 1) p.kp = 2;
@@ -104,11 +109,11 @@ GemmPlan gemm_plan(int N, int Kp, int m_rows, int epilogue, int n_cu, int max_ks
 size_t gemm_partial_rows_bound(int N, int n_max, bool sliced_only)
 {
     // up to kSweepMaxRows rows: at most kSmallMaxKsplit slices; above: the tiled kernel slices only while it
-    // has fewer than kTiledFullTiles tiles, i.e. up to 128 * floor((kTiledFullTiles - 1) / column tiles) rows
+    // has fewer than kTiledNoSliceTiles tiles, i.e. up to 128 * floor((kTiledNoSliceTiles - 1) / column tiles) rows
     // (its tallest tile)
     const size_t n = (size_t)std::max(n_max, 1);
     const size_t col_tiles = (size_t)(N + 255) / 256;
-    const size_t tiled_rows = 128 * ((size_t)(kTiledFullTiles - 1) / std::max<size_t>(col_tiles, 1));
+    const size_t tiled_rows = 128 * ((size_t)(kTiledNoSliceTiles - 1) / std::max<size_t>(col_tiles, 1));
     size_t need = sliced_only ? 1 : n;
     need = std::max(need, (size_t)kSmallMaxKsplit * std::min<size_t>(n, (size_t)kSweepMaxRows));
     need = std::max(need, (size_t)kTiledMaxKsplit * std::min(n, tiled_rows));
