@@ -37,7 +37,7 @@ void ss_set_verbose(int32_t level);
  * count; 1: never the kernel that stages activations once per workgroup (then: the k-splitting kernel up to 64
  * token-rows, the tiled kernel above); 2: that kernel for every projection of at most 128 token-rows.
  * Adding 4 to a mode (4, 5, 6) keeps that kernel from sharing a strip's k-blocks between two wavefronts (what it
- * does from 17 token-rows on when a workgroup has few strips); adding 8 keeps the tiled kernel at 64-row tiles where
+ * does above 96 token-rows when a workgroup has few strips); adding 8 keeps the tiled kernel at 64-row tiles where
  * it would use 128-row tiles (prompt forwards of 896 token-rows and more); both for A/B measurements.
  * Results agree to the rounding differences between launch shapes (about 1e-3 of the largest logit).  Process-wide (atomic integers, read when a forward is planned: set it
  * between calls, not during one); other values are ignored. */

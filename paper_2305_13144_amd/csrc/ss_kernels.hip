@@ -351,7 +351,7 @@ __global__ __launch_bounds__(256) void k_gemm_skinny(GemmArgs a, int n_groups, i
 // beyond the matrix read a block of zeros instead of weights (an L2 hit) and add 0.
 // With KH = 2 two waves share a unit: wave 2u takes the first half of every chunk's k-blocks, wave 2u + 1 the second
 // (each loads only its own weight blocks and reads only its own operands from LDS); the odd wave hands its
-// accumulators to the even one through LDS at the end.  Used from 17 rows on when a workgroup owns at most 4 units:
+// accumulators to the even one through LDS at the end.  Used above 96 rows when a workgroup owns at most 4 units:
 // there the matrix-core and LDS work per weight byte grows with the row strips, and 3 or 4 waves (one per SIMD,
 // nothing to overlap their waits with) no longer keep up with the weight stream.
 template <int NBW, int KQ>
@@ -482,7 +482,8 @@ __device__ __forceinline__ void sweep_run(u32x4* xl0, u32x4* xl1, f32x4 (&acc)[N
 template <int P, int MT, int NBW, int EPI, int KH>
 __global__ __launch_bounds__(64 * P) void k_gemm_sweep(GemmArgs a, int n_units, int n_gn, int kb_per_slice)
 {
-    constexpr int KC = MT > 4 ? 2 : 4;   // k-blocks per chunk
+    constexpr int KC = 4;   // k-blocks per chunk: both staging buffers take at most 64 KiB (8 row strips); measured against 2
+                            // (5-8 row strips) and against 2 and 8 (one strip): 4 is the fastest everywhere
     static_assert(KC % KH == 0, "a chunk's k-blocks split evenly between the waves of a unit");
     constexpr int STAGE = SweepStage<P, MT, KC>::PIECES;
     // two staging buffers; after the sweep the same memory carries the odd waves' accumulators (KH = 2)
@@ -1453,11 +1454,11 @@ static void launch_sweep_inst(const GemmArgs& a, int units, hipStream_t s)
 template <int P, int MT, int EPI, int KH>
 static void launch_sweep_mt(const GemmArgs& a, int units, int nbw, hipStream_t s)
 {
-    // strips per wave (sweep_nbw): always 2 with the SwiGLU epilogue and above 3 row strips
-    if (EPI == EPI_SWIGLU || nbw == 2 || MT > 3)
+    // strips per wave (sweep_nbw): always 2 with the SwiGLU epilogue and above 4 row strips
+    if (EPI == EPI_SWIGLU || nbw == 2 || MT > 4)
         launch_sweep_inst<P, MT, 2, EPI, KH>(a, units, s);
     else
-        launch_sweep_inst<P, MT, (EPI == EPI_SWIGLU || MT > 3) ? 2 : 1, EPI, KH>(a, units, s);
+        launch_sweep_inst<P, MT, (EPI == EPI_SWIGLU || MT > 4) ? 2 : 1, EPI, KH>(a, units, s);
 }
 
 template <int P, int EPI, int KH>
@@ -1493,7 +1494,7 @@ static void launch_gemm_epi(const GemmArgs& a, hipStream_t s)
         const int units = (a.N / 16 + nbw - 1) / nbw;
         const int per = (units + a.sweep_gn - 1) / a.sweep_gn;   // most units any workgroup owns
         if (a.sweep_p == 4 && per <= 4) {
-            // from 17 rows on: 8 waves, two per unit (see SweepSlot)
+            // where the plan asks for it (above 96 rows): 8 waves, two per unit (see SweepSlot)
             if (a.m_rows > 16 && a.sweep_kh == 2) return launch_sweep_p<8, EPI, 2>(a, units, nbw, s);
             return launch_sweep_p<4, EPI, 1>(a, units, nbw, s);
         }
