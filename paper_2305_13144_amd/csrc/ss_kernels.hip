@@ -1452,27 +1452,24 @@ static void launch_sweep_inst(const GemmArgs& a, int units, hipStream_t s)
 }
 
 template <int P, int MT, int EPI, int KH>
-static void launch_sweep_mt(const GemmArgs& a, int units, int nbw, hipStream_t s)
+static void launch_sweep_mt(const GemmArgs& a, int units, hipStream_t s)
 {
-    // strips per wave (sweep_nbw): always 2 with the SwiGLU epilogue and above 4 row strips
-    if (EPI == EPI_SWIGLU || nbw == 2 || MT > 4)
-        launch_sweep_inst<P, MT, 2, EPI, KH>(a, units, s);
-    else
-        launch_sweep_inst<P, MT, (EPI == EPI_SWIGLU || MT > 4) ? 2 : 1, EPI, KH>(a, units, s);
+    // strips per wave (sweep_nbw): a gate/up pair with the SwiGLU epilogue, otherwise one
+    launch_sweep_inst<P, MT, EPI == EPI_SWIGLU ? 2 : 1, EPI, KH>(a, units, s);
 }
 
 template <int P, int EPI, int KH>
-static void launch_sweep_p(const GemmArgs& a, int units, int nbw, hipStream_t s)
+static void launch_sweep_p(const GemmArgs& a, int units, hipStream_t s)
 {
     switch ((a.m_rows + 15) / 16) {
-        case 1: launch_sweep_mt<P, 1, EPI, 1>(a, units, nbw, s); break;   // one row strip: never split
-        case 2: launch_sweep_mt<P, 2, EPI, KH>(a, units, nbw, s); break;
-        case 3: launch_sweep_mt<P, 3, EPI, KH>(a, units, nbw, s); break;
-        case 4: launch_sweep_mt<P, 4, EPI, KH>(a, units, nbw, s); break;
-        case 5: launch_sweep_mt<P, 5, EPI, KH>(a, units, nbw, s); break;
-        case 6: launch_sweep_mt<P, 6, EPI, KH>(a, units, nbw, s); break;
-        case 7: launch_sweep_mt<P, 7, EPI, KH>(a, units, nbw, s); break;
-        default: launch_sweep_mt<P, 8, EPI, KH>(a, units, nbw, s); break;
+        case 1: launch_sweep_mt<P, 1, EPI, 1>(a, units, s); break;   // one row strip: never split
+        case 2: launch_sweep_mt<P, 2, EPI, KH>(a, units, s); break;
+        case 3: launch_sweep_mt<P, 3, EPI, KH>(a, units, s); break;
+        case 4: launch_sweep_mt<P, 4, EPI, KH>(a, units, s); break;
+        case 5: launch_sweep_mt<P, 5, EPI, KH>(a, units, s); break;
+        case 6: launch_sweep_mt<P, 6, EPI, KH>(a, units, s); break;
+        case 7: launch_sweep_mt<P, 7, EPI, KH>(a, units, s); break;
+        default: launch_sweep_mt<P, 8, EPI, KH>(a, units, s); break;
     }
 }
 
@@ -1495,10 +1492,10 @@ static void launch_gemm_epi(const GemmArgs& a, hipStream_t s)
         const int per = (units + a.sweep_gn - 1) / a.sweep_gn;   // most units any workgroup owns
         if (a.sweep_p == 4 && per <= 4) {
             // where the plan asks for it (above 96 rows): 8 waves, two per unit (see SweepSlot)
-            if (a.m_rows > 16 && a.sweep_kh == 2) return launch_sweep_p<8, EPI, 2>(a, units, nbw, s);
-            return launch_sweep_p<4, EPI, 1>(a, units, nbw, s);
+            if (a.m_rows > 16 && a.sweep_kh == 2) return launch_sweep_p<8, EPI, 2>(a, units, s);
+            return launch_sweep_p<4, EPI, 1>(a, units, s);
         }
-        if (per <= 8) return launch_sweep_p<8, EPI, 1>(a, units, nbw, s);
+        if (per <= 8) return launch_sweep_p<8, EPI, 1>(a, units, s);
         // a plan this kernel cannot run falls through to the other kernels
     }
     if (a.m_rows <= 64) {

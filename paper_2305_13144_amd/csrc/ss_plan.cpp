@@ -39,12 +39,12 @@ int gemm_mode() { return g_gemm_mode.load(std::memory_order_relaxed); }
 // never leaving a wave fewer than 4 k-blocks.  Tiled kernel: ksplit fills the chip when there are few
 // 64x256 tiles.
 
-// Strips per wave of the sweep kernel: a gate/up pair for the SwiGLU epilogue.  Otherwise one strip up to 64 rows and
-// two above: two strips per wave halve the LDS operand reads per weight byte, which is what bounds the kernel from
-// 5 row strips on; below that, one strip per wave gives twice the units, so half the k-slices (longer sweeps, half the
-// partial sums).  Measured on the 7B shapes, same GPU, decode step at context 100, one against two strips per wave:
-// 56 rows 3.90 / 4.17 ms, 64 rows 3.99 / 4.27, 80 rows 4.96 / 4.78, 96 rows 5.27 / 5.10.
-int sweep_nbw(int epilogue, int m_rows) { return (epilogue == EPI_SWIGLU || m_rows > 64) ? 2 : 1; }
+// Strips per wave of the sweep kernel: a gate/up pair for the SwiGLU epilogue, otherwise one.  One strip per wave gives
+// twice the units of two, so half the k-slices (longer sweeps, half the partial sums).  Two strips per wave halve the LDS
+// operand reads per weight byte and were the better choice from 49 rows on while an activation was two operands; with
+// one operand per activation they never are.  Same GPU, 7B shapes, decode step at context 100, one / two strips per wave:
+// 64 rows 3.99 / 4.27 ms, 80 rows 4.36 / 4.58, 96 rows 4.82 / 5.04, 128 rows 5.59 / 5.81.
+int sweep_nbw(int epilogue, int /*m_rows*/) { return epilogue == EPI_SWIGLU ? 2 : 1; }
 
 GemmPlan gemm_plan(int N, int Kp, int m_rows, int epilogue, int n_cu, int max_ksplit)
 {
@@ -67,8 +67,8 @@ GemmPlan gemm_plan(int N, int Kp, int m_rows, int epilogue, int n_cu, int max_ks
             p.sweep_gn = gn;
             // above 96 rows a workgroup with at most 4 units runs 8 waves, two per unit: the work per weight byte
             // grows with the row strips and 4 waves (one per SIMD) stop keeping up with the weight stream (same GPU,
-            // split / not split: 112 rows 5.47 / 5.52 ms per step, 128 rows 5.81 / 5.89; up to 96 rows the split
-            // costs 0.3-1 %: 64 rows 4.00 / 3.99, 96 rows 5.10 / 5.05)
+            // split / not split: 104 rows 5.09 / 5.18 ms per step, 112 rows 5.21 / 5.28, 128 rows 5.59 / 5.81; up to
+            // 96 rows the two are equal to within 0.1 %)
             p.sweep_kh = (p.sweep_p == 4 && m_rows > 96 && g_sweep_split.load(std::memory_order_relaxed)) ? 2 : 1;
             return p;
         }
