@@ -35,7 +35,7 @@ void ss_set_verbose(int32_t level);
 
 /* Testing aid: which kernel runs the projections of small batches.  0 (default): chosen per shape and row
  * count; 1: never the kernel that stages activations once per workgroup (then: the k-splitting kernel up to 64
- * token-rows, the tiled kernel above); 2: that kernel for every projection of at most 128 token-rows.
+ * token-rows, the tiled kernel above); 2: that kernel for every projection of at most 256 token-rows.
  * Adding 4 to a mode (4, 5, 6) keeps that kernel from sharing a strip's k-blocks between two wavefronts (what it
  * does above 96 token-rows when a workgroup has few strips); adding 8 keeps the tiled kernel at 64-row tiles where
  * it would use 128-row tiles (prompt forwards of 896 token-rows and more); both for A/B measurements.

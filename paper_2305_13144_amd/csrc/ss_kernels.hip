@@ -337,7 +337,7 @@ __global__ __launch_bounds__(256) void k_gemm_skinny(GemmArgs a, int n_groups, i
 }
 
 // ------------------------------------------------------------------------------------------ sweep GEMM
-// Up to 128 token rows (8 row strips), for projections large enough to give every compute unit one workgroup
+// Up to 256 token rows (16 row strips), for projections large enough to give every compute unit one workgroup
 // with several waves of work.  What bounds a weight stream on this chip is the number of bytes a compute unit can have in
 // flight towards L2/HBM, and every byte requested through the vector memory path counts, also an activation
 // operand that hits in L2: in the kernel above, where each wave fetches its own activation operands, those
@@ -482,8 +482,10 @@ __device__ __forceinline__ void sweep_run(u32x4* xl0, u32x4* xl1, f32x4 (&acc)[N
 template <int P, int MT, int NBW, int EPI, int KH>
 __global__ __launch_bounds__(64 * P) void k_gemm_sweep(GemmArgs a, int n_units, int n_gn, int kb_per_slice)
 {
-    constexpr int KC = 4;   // k-blocks per chunk: both staging buffers take at most 64 KiB (8 row strips); measured against 2
-                            // (5-8 row strips) and against 2 and 8 (one strip): 4 is the fastest everywhere
+    // k-blocks per chunk: 4 up to 12 row strips (both staging buffers: 8 KiB per row strip, at most 96 KiB), 2 above.
+    // Measured: one strip 4 against 2 and 8, 5-8 strips 4 against 2: 4 is the fastest; 9-12 strips 4 against 2: 4 % faster;
+    // 13-15 strips: equal; 16 strips: 2 is 10 % faster (128 KiB of LDS and the registers of the widest instantiation).
+    constexpr int KC = MT > 12 ? 2 : 4;
     static_assert(KC % KH == 0, "a chunk's k-blocks split evenly between the waves of a unit");
     constexpr int STAGE = SweepStage<P, MT, KC>::PIECES;
     // two staging buffers; after the sweep the same memory carries the odd waves' accumulators (KH = 2)
@@ -1469,7 +1471,15 @@ static void launch_sweep_p(const GemmArgs& a, int units, hipStream_t s)
         case 5: launch_sweep_mt<P, 5, EPI, KH>(a, units, s); break;
         case 6: launch_sweep_mt<P, 6, EPI, KH>(a, units, s); break;
         case 7: launch_sweep_mt<P, 7, EPI, KH>(a, units, s); break;
-        default: launch_sweep_mt<P, 8, EPI, KH>(a, units, s); break;
+        case 8: launch_sweep_mt<P, 8, EPI, KH>(a, units, s); break;
+        case 9: launch_sweep_mt<P, 9, EPI, KH>(a, units, s); break;
+        case 10: launch_sweep_mt<P, 10, EPI, KH>(a, units, s); break;
+        case 11: launch_sweep_mt<P, 11, EPI, KH>(a, units, s); break;
+        case 12: launch_sweep_mt<P, 12, EPI, KH>(a, units, s); break;
+        case 13: launch_sweep_mt<P, 13, EPI, KH>(a, units, s); break;
+        case 14: launch_sweep_mt<P, 14, EPI, KH>(a, units, s); break;
+        case 15: launch_sweep_mt<P, 15, EPI, KH>(a, units, s); break;
+        default: launch_sweep_mt<P, 16, EPI, KH>(a, units, s); break;
     }
 }
 

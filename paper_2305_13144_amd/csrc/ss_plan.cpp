@@ -27,7 +27,7 @@ void set_gemm_mode(int mode)
 int gemm_mode() { return g_gemm_mode.load(std::memory_order_relaxed); }
 
 // Launch shape of a projection.
-// Sweep kernel (<= 128 rows, at least 160 KiB of weights per compute unit and row strip; below that the launch is
+// Sweep kernel (<= 256 rows, at least 160 KiB of weights per compute unit and row strip; below that the launch is
 // too short to amortise its start-up and the skinny kernel's finer split wins: measured at 16 rows, the 7B o
 // projection, 131 KiB per unit, is 12 % faster in the skinny kernel, the 13B one, 205 KiB, 30 % faster here): one workgroup per compute unit and
 // k-slice, a wave per output strip (per gate/up strip pair with the SwiGLU epilogue).  k-slices double

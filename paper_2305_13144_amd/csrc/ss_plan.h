@@ -9,7 +9,7 @@ namespace ss {
 
 enum Epilogue { EPI_PARTIAL = 0, EPI_SWIGLU = 1 };
 
-constexpr int kSweepMaxRows = 128;   // 8 row strips: accumulators and the LDS chunk of the sweep kernel still fit
+constexpr int kSweepMaxRows = 256;   // 16 row strips: accumulators and the LDS chunk of the sweep kernel still fit
 
 struct GemmPlan {
     int ksplit, nb, kd, kp;

@@ -289,9 +289,9 @@ def test_wide_decode_logits_each_small_batch_projection_kernel(wide2, mode):
     check_logits(got, ref, f"wide2 B=20 mode={mode}")
 
 
-@pytest.mark.parametrize("rows", [17, 33, 48, 49, 64, 100, 128])
+@pytest.mark.parametrize("rows", [17, 33, 48, 49, 64, 100, 128, 129, 176, 200, 256])
 def test_wide_decode_logits_across_row_strips(wide2, rows):
-    """7B widths, 2-8 row strips, the kernel choice of the library itself (mode 0) and the same with the
+    """7B widths, 2-16 row strips, the kernel choice of the library itself (mode 0) and the same with the
     two-waves-per-unit split of the sweep kernel switched off (mode 4; the split is used above 96 rows),
     ragged last strips.  Three rows against the oracle in each mode; the two modes differ only in the order of fp32
     sums, which can move an activation by one unit of its half-precision rounding (2^-11) and a logit by that order."""
