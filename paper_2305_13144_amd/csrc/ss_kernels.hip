@@ -570,14 +570,15 @@ __global__ __launch_bounds__(64 * P) void k_gemm_sweep(GemmArgs a, int n_units, 
 }
 
 // ------------------------------------------------------------------------------------------ tiled GEMM
-// More than 64 token rows (prompt forwards, large variable batches).  A workgroup computes
+// More than 64 token rows where the sweep kernel does not apply: prompt forwards (more than 256 token-rows) and
+// matrices too small for it.  A workgroup computes
 // TMS*16 token rows x 256 output columns; wave w owns 4 strips of 16 columns and every row strip.
 // Weights never touch LDS: they are stored in operand order, so each wave loads its own 4 operand
 // blocks per k-block straight into registers (1 KiB coalesced each) and is the only wave of the
 // workgroup that needs them.  The activation tile is shared by the 4 waves and staged
 // through LDS in operand order (conflict-free 1 KiB reads).  One k-block per trip; both streams run
 // D k-blocks ahead of the MFMAs in a register ring (6 for a 64-row tile: 150 KiB in flight per CU with two
-// workgroups, enough to keep HBM busy when the weights are streamed once for a decode batch; 2 for a 128-row
+// workgroups, enough to keep HBM busy when there are few row tiles; 2 for a 128-row
 // tile, whose doubled accumulators leave no registers for more).
 // Workgroup ids are mapped so that the row tiles of one column tile follow each other at a stride of 8:
 // they land on the same XCD (ids are dealt round-robin over the 8 XCDs) at about the same time and share

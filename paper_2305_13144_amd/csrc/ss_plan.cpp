@@ -87,7 +87,7 @@ GemmPlan gemm_plan(int N, int Kp, int m_rows, int epilogue, int n_cu, int max_ks
         return p;
     }
     // Tiled kernel.  Many tiles (prompt forwards): 4-wave workgroups, two per CU, no slicing.  Few tiles
-    // (decode batches of 65-256 rows): measured on the 7B shapes, outer k-slices up to 4 (partial sums
+    // (short prompt forwards; decode batches of 65-256 rows on matrices too small for the sweep kernel): measured on the 7B shapes, outer k-slices up to 4 (partial sums
     // through HBM are small while rows are few) beat everything else; where slicing is impossible an
     // 8-wave workgroup halves the k range inside the workgroup instead.
     // Tile height: 64 token-rows, or 128 from kTiledTallFrom rows on.  A 64 x 256 tile asks L2 for 20 KiB per 16
