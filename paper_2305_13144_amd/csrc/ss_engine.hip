@@ -1247,8 +1247,9 @@ extern "C" int ss_bench_decode_steps_in_flight(ss_weights* w, const int32_t* pro
         try {
             others.emplace_back(run, l);
         } catch (...) {
-            // the lanes already started wait at the gate for `lanes` arrivals: stand in for the missing ones
-            gate.fetch_add(lanes - l);
+            // the lanes already started (1 .. l-1) wait at the gate for `lanes` arrivals: stand in for the ones
+            // that will not come (l .. lanes-1, and lane 0, which this thread would have run)
+            gate.fetch_add(lanes - l + 1);
             for (std::thread& t : others) t.join();
             return ss::fail(SS_ESTATE, "could not start host thread %d", l);
         }
