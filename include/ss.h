@@ -86,7 +86,8 @@ typedef struct {
  * the batch size allowed for their largest prediction.  cap = min(largest scheduled length in the
  * micro-batch, base_len) with SS_FCR, else base_len.
  * Errors: SS_EINVAL for n <= 0, NULL out/policy, pred < 1, bin < 0, SS_BIN without SS_SORT or with bin 0,
- * SS_VBS without SS_SORT, base_batch < 1, max_batch < base_batch, base_len < 1, unknown vbs_rule.
+ * SS_VBS without SS_SORT, base_batch < 1, max_batch < base_batch, base_len < 1, unknown vbs_rule; SS_ENOMEM when
+ * the host cannot hold the plan.  *out is written only on success.
  */
 int ss_schedule(const int32_t* pred_lens, int32_t n, int32_t bin, const ss_policy* policy, ss_plan** out);
 

@@ -11,7 +11,6 @@
 #include <cstring>
 #include <mutex>
 #include <numeric>
-#include <string>
 #include <thread>
 #include <vector>
 
@@ -648,9 +647,82 @@ int decode_microbatch_impl(const ss_weights* w, Lane& ln, const int32_t* prompt_
     return SS_OK;
 }
 
+// Fills a fresh handle: streams and events of every lane, the packed weights, the rotary tables.  Whatever it
+// has created when it fails (or throws) is released by the caller through ss_weights_destroy.
+int weights_create_impl(ss_weights* w, const void* const* tensors, int32_t src_dtype)
+{
+    const ss_model_cfg* cfg = &w->cfg;
+    if (hipGetDevice(&w->device) != hipSuccess) return ss::fail(SS_EDEVICE, "hipGetDevice failed");
+    if (int rc_s = scratch_address(w->device, &w->scratch_ptr)) return rc_s;
+    for (Lane& ln : w->lane) {
+        if (hipStreamCreate(&ln.stream) != hipSuccess) return ss::fail(SS_EDEVICE, "hipStreamCreate failed");
+        if (hipHostMalloc((void**)&ln.h_poll, 16, hipHostMallocDefault) != hipSuccess)
+            return ss::fail(SS_ENOMEM, "hipHostMalloc failed");
+        for (auto& e : ln.ev)
+            if (hipEventCreate(&e) != hipSuccess) return ss::fail(SS_EDEVICE, "hipEventCreate failed");
+    }
+
+    const int d = cfg->d_model, F = cfg->d_ffn, V = cfg->vocab, f32 = (src_dtype == SS_F32);
+    struct Staging {   // the upload buffer goes however the function ends
+        Buf b;
+        ~Staging() { b.release(); }
+    } staging_owner;
+    Buf& staging = staging_owner.b;
+    int rc = SS_OK;
+    int ti = 0;
+    if ((rc = upload_vec(w, staging, tensors[ti++], f32, (size_t)V * d, &w->embed))) return rc;
+    w->layers.resize(cfg->n_layers);
+    for (int l = 0; l < cfg->n_layers; ++l) {
+        Layer& L = w->layers[l];
+        if ((rc = upload_vec(w, staging, tensors[ti++], f32, d, &L.attn_norm))) return rc;
+        if ((rc = alloc_packed(w, &L.wqkv, 3 * d, d))) return rc;
+        for (int part = 0; part < 3; ++part)   // q, k, v stacked along the output dimension
+            if ((rc = upload_pack(w, staging, tensors[ti++], f32, d, d, L.wqkv.p, L.wqkv.Kp, 1, part * d / 16)))
+                return rc;
+        if ((rc = alloc_packed(w, &L.wo, d, d))) return rc;
+        if ((rc = upload_pack(w, staging, tensors[ti++], f32, d, d, L.wo.p, L.wo.Kp, 1, 0))) return rc;
+        if ((rc = upload_vec(w, staging, tensors[ti++], f32, d, &L.mlp_norm))) return rc;
+        if ((rc = alloc_packed(w, &L.wgu, 2 * F, d))) return rc;
+        for (int part = 0; part < 2; ++part)   // gate and up strips interleaved: strip 2j = gate, 2j+1 = up
+            if ((rc = upload_pack(w, staging, tensors[ti++], f32, F, d, L.wgu.p, L.wgu.Kp, 2, part))) return rc;
+        if ((rc = alloc_packed(w, &L.wd, d, F))) return rc;
+        if ((rc = upload_pack(w, staging, tensors[ti++], f32, d, F, L.wd.p, L.wd.Kp, 1, 0))) return rc;
+    }
+    if ((rc = upload_vec(w, staging, tensors[ti++], f32, d, &w->final_norm))) return rc;
+    if ((rc = alloc_packed(w, &w->lm_head, V, d))) return rc;
+    if ((rc = upload_pack(w, staging, tensors[ti++], f32, V, d, w->lm_head.p, w->lm_head.Kp, 1, 0))) return rc;
+
+    // rotary tables: cos/sin(pos * base^(-2e/hd)) evaluated in double, stored as fp32 [pos][e]
+    const int half = cfg->head_dim / 2;
+    std::vector<float> tc((size_t)ss::kMaxPos * half), tsn((size_t)ss::kMaxPos * half);
+    for (int e = 0; e < half; ++e) {
+        const double inv = std::pow((double)cfg->rope_base, -2.0 * e / (double)cfg->head_dim);
+        for (int p = 0; p < ss::kMaxPos; ++p) {
+            tc[(size_t)p * half + e] = (float)std::cos(p * inv);
+            tsn[(size_t)p * half + e] = (float)std::sin(p * inv);
+        }
+    }
+    void* p = nullptr;
+    if ((rc = dev_alloc(w, &p, 1024, true))) return rc;
+    w->zero_blk = (f16_t*)p;
+    hipDeviceProp_t prop;
+    if (hipGetDeviceProperties(&prop, w->device) != hipSuccess || prop.multiProcessorCount <= 0)
+        return ss::fail(SS_EDEVICE, "cannot read the device's compute unit count");
+    w->n_cu = prop.multiProcessorCount;
+    if ((rc = dev_alloc(w, &p, tc.size() * 4, false))) return rc;
+    w->rope_cos = (float*)p;
+    if ((rc = dev_alloc(w, &p, tsn.size() * 4, false))) return rc;
+    w->rope_sin = (float*)p;
+    if (hipMemcpy(w->rope_cos, tc.data(), tc.size() * 4, hipMemcpyHostToDevice) != hipSuccess ||
+        hipMemcpy(w->rope_sin, tsn.data(), tsn.size() * 4, hipMemcpyHostToDevice) != hipSuccess)
+        return ss::fail(SS_EDEVICE, "rotary table upload failed");
+    return SS_OK;
+}
+
 }  // namespace
 
 // ============================================================================================ C ABI
+// No entry point lets a C++ exception out: host allocations that fail are reported as SS_ENOMEM (ss::no_throw).
 extern "C" int ss_weights_create(const ss_model_cfg* cfg, const void* const* tensors, int32_t src_dtype,
                                  ss_weights** out)
 {
@@ -667,75 +739,11 @@ extern "C" int ss_weights_create(const ss_model_cfg* cfg, const void* const* ten
     ss_weights* w = new (std::nothrow) ss_weights();
     if (!w) return ss::fail(SS_ENOMEM, "host allocation failed");
     w->cfg = *cfg;
-    auto bail = [&](int rc) {
+    const int rc = ss::no_throw([&] { return weights_create_impl(w, tensors, src_dtype); });
+    if (rc != SS_OK) {
         ss_weights_destroy(w);
         return rc;
-    };
-    if (hipGetDevice(&w->device) != hipSuccess) return bail(ss::fail(SS_EDEVICE, "hipGetDevice failed"));
-    if (int rc_s = scratch_address(w->device, &w->scratch_ptr)) return bail(rc_s);
-    for (Lane& ln : w->lane) {
-        if (hipStreamCreate(&ln.stream) != hipSuccess) return bail(ss::fail(SS_EDEVICE, "hipStreamCreate failed"));
-        if (hipHostMalloc((void**)&ln.h_poll, 16, hipHostMallocDefault) != hipSuccess)
-            return bail(ss::fail(SS_ENOMEM, "hipHostMalloc failed"));
-        for (auto& e : ln.ev)
-            if (hipEventCreate(&e) != hipSuccess) return bail(ss::fail(SS_EDEVICE, "hipEventCreate failed"));
     }
-
-    const int d = cfg->d_model, F = cfg->d_ffn, V = cfg->vocab, f32 = (src_dtype == SS_F32);
-    Buf staging;
-    int rc = SS_OK;
-    int ti = 0;
-    auto done = [&](int r) {
-        staging.release();
-        return r == SS_OK ? SS_OK : bail(r);
-    };
-    if ((rc = upload_vec(w, staging, tensors[ti++], f32, (size_t)V * d, &w->embed))) return done(rc);
-    w->layers.resize(cfg->n_layers);
-    for (int l = 0; l < cfg->n_layers; ++l) {
-        Layer& L = w->layers[l];
-        if ((rc = upload_vec(w, staging, tensors[ti++], f32, d, &L.attn_norm))) return done(rc);
-        if ((rc = alloc_packed(w, &L.wqkv, 3 * d, d))) return done(rc);
-        for (int part = 0; part < 3; ++part)   // q, k, v stacked along the output dimension
-            if ((rc = upload_pack(w, staging, tensors[ti++], f32, d, d, L.wqkv.p, L.wqkv.Kp, 1, part * d / 16)))
-                return done(rc);
-        if ((rc = alloc_packed(w, &L.wo, d, d))) return done(rc);
-        if ((rc = upload_pack(w, staging, tensors[ti++], f32, d, d, L.wo.p, L.wo.Kp, 1, 0))) return done(rc);
-        if ((rc = upload_vec(w, staging, tensors[ti++], f32, d, &L.mlp_norm))) return done(rc);
-        if ((rc = alloc_packed(w, &L.wgu, 2 * F, d))) return done(rc);
-        for (int part = 0; part < 2; ++part)   // gate and up strips interleaved: strip 2j = gate, 2j+1 = up
-            if ((rc = upload_pack(w, staging, tensors[ti++], f32, F, d, L.wgu.p, L.wgu.Kp, 2, part))) return done(rc);
-        if ((rc = alloc_packed(w, &L.wd, d, F))) return done(rc);
-        if ((rc = upload_pack(w, staging, tensors[ti++], f32, d, F, L.wd.p, L.wd.Kp, 1, 0))) return done(rc);
-    }
-    if ((rc = upload_vec(w, staging, tensors[ti++], f32, d, &w->final_norm))) return done(rc);
-    if ((rc = alloc_packed(w, &w->lm_head, V, d))) return done(rc);
-    if ((rc = upload_pack(w, staging, tensors[ti++], f32, V, d, w->lm_head.p, w->lm_head.Kp, 1, 0))) return done(rc);
-
-    // rotary tables: cos/sin(pos * base^(-2e/hd)) evaluated in double, stored as fp32 [pos][e]
-    const int half = cfg->head_dim / 2;
-    std::vector<float> tc((size_t)ss::kMaxPos * half), tsn((size_t)ss::kMaxPos * half);
-    for (int e = 0; e < half; ++e) {
-        const double inv = std::pow((double)cfg->rope_base, -2.0 * e / (double)cfg->head_dim);
-        for (int p = 0; p < ss::kMaxPos; ++p) {
-            tc[(size_t)p * half + e] = (float)std::cos(p * inv);
-            tsn[(size_t)p * half + e] = (float)std::sin(p * inv);
-        }
-    }
-    void* p = nullptr;
-    if ((rc = dev_alloc(w, &p, 1024, true))) return done(rc);
-    w->zero_blk = (f16_t*)p;
-    hipDeviceProp_t prop;
-    if (hipGetDeviceProperties(&prop, w->device) != hipSuccess || prop.multiProcessorCount <= 0)
-        return done(ss::fail(SS_EDEVICE, "cannot read the device's compute unit count"));
-    w->n_cu = prop.multiProcessorCount;
-    if ((rc = dev_alloc(w, &p, tc.size() * 4, false))) return done(rc);
-    w->rope_cos = (float*)p;
-    if ((rc = dev_alloc(w, &p, tsn.size() * 4, false))) return done(rc);
-    w->rope_sin = (float*)p;
-    if (hipMemcpy(w->rope_cos, tc.data(), tc.size() * 4, hipMemcpyHostToDevice) != hipSuccess ||
-        hipMemcpy(w->rope_sin, tsn.data(), tsn.size() * 4, hipMemcpyHostToDevice) != hipSuccess)
-        return done(ss::fail(SS_EDEVICE, "rotary table upload failed"));
-    staging.release();
     *out = w;
     return SS_OK;
 }
@@ -786,8 +794,10 @@ extern "C" int ss_decode_microbatch(ss_weights* w, const int32_t* prompt_tokens,
     if (!guard.ok) return ss::fail(SS_ESTATE, "another call is in flight on this handle");
     Lane& ln = w->lane[0];
     hipStream_t s = hip_stream ? (hipStream_t)hip_stream : ln.stream;
-    return decode_microbatch_impl(w, ln, prompt_tokens, prompt_offsets, B, max_new, target_lens, nullptr, flags, out_tokens,
-                                  out_lens, out_failed, stats, s);
+    return ss::no_throw([&] {
+        return decode_microbatch_impl(w, ln, prompt_tokens, prompt_offsets, B, max_new, target_lens, nullptr, flags,
+                                      out_tokens, out_lens, out_failed, stats, s);
+    });
 }
 
 extern "C" int ss_decode_microbatch_static(ss_weights* w, const int32_t* prompt_tokens, const int32_t* prompt_offsets,
@@ -816,15 +826,24 @@ extern "C" int ss_decode_microbatch_static(ss_weights* w, const int32_t* prompt_
     // The handle's own (allocated, growable) workspace steps aside for the call; every buffer is a view into the
     // scratch array instead.  decode_microbatch_impl allocates nothing else on the device: its events belong to
     // the handle, its host staging lives on the host heap.
-    Workspace view;
-    view.arena = (char*)w->scratch_ptr;
-    view.arena_bytes = kStaticScratchBytes;
-    std::swap(ln.ws, view);
-    const int rc = decode_microbatch_impl(w, ln, prompt_tokens, prompt_offsets, B, max_new, target_lens, nullptr, flags,
-                                          out_tokens, out_lens, out_failed, stats, s);
-    std::swap(ln.ws, view);
-    ln.st = MbState{};   // pointed into the scratch array; the next call lays its own state out
-    return rc;
+    struct View {   // swaps the lane's workspace for the view, and back however the call ends
+        Lane& ln;
+        Workspace ws;
+        explicit View(Lane& l) : ln(l) {}
+        void in() { std::swap(ln.ws, ws); }
+        ~View()
+        {
+            std::swap(ln.ws, ws);
+            ln.st = MbState{};   // pointed into the scratch array; the next call lays its own state out
+        }
+    } view(ln);
+    view.ws.arena = (char*)w->scratch_ptr;
+    view.ws.arena_bytes = kStaticScratchBytes;
+    view.in();
+    return ss::no_throw([&] {
+        return decode_microbatch_impl(w, ln, prompt_tokens, prompt_offsets, B, max_new, target_lens, nullptr, flags,
+                                      out_tokens, out_lens, out_failed, stats, s);
+    });
 }
 
 extern "C" int ss_generate_microbatch(ss_weights* w, const int32_t* prompt_tokens, const int32_t* prompt_offsets,
@@ -841,21 +860,17 @@ extern "C" int ss_generate_microbatch(ss_weights* w, const int32_t* prompt_token
     if (!guard.ok) return ss::fail(SS_ESTATE, "another call is in flight on this handle");
     Lane& ln = w->lane[0];
     hipStream_t s = hip_stream ? (hipStream_t)hip_stream : ln.stream;
-    return decode_microbatch_impl(w, ln, prompt_tokens, prompt_offsets, B, max_new, nullptr, opts, flags, out_tokens,
-                                  out_lens, out_failed, stats, s);
+    return ss::no_throw([&] {
+        return decode_microbatch_impl(w, ln, prompt_tokens, prompt_offsets, B, max_new, nullptr, opts, flags, out_tokens,
+                                      out_lens, out_failed, stats, s);
+    });
 }
 
-extern "C" int ss_forward_logits(ss_weights* w, const int32_t* tokens, const int32_t* offsets, int32_t B,
-                                 const int32_t* n_prompt, int32_t all_prompt_logits, float* logits_out,
-                                 void* hip_stream)
+namespace {
+
+int forward_logits_impl(const ss_weights* w, Lane& ln, hipStream_t s, const int32_t* tokens, const int32_t* offsets,
+                        int32_t B, const int32_t* n_prompt, int32_t all_prompt_logits, float* logits_out)
 {
-    ss::clear_error();
-    if (int rc = check_prompts(w, tokens, offsets, B)) return rc;
-    if (!n_prompt || !logits_out) return ss::fail(SS_EINVAL, "NULL argument");
-    BusyGuard guard(w);
-    if (!guard.ok) return ss::fail(SS_ESTATE, "another call is in flight on this handle");
-    Lane& ln = w->lane[0];
-    hipStream_t s = hip_stream ? (hipStream_t)hip_stream : ln.stream;
     const int V = w->cfg.vocab;
     std::vector<int32_t> len(B), slab(B), limit(B, 1), np(n_prompt, n_prompt + B), sel;
     std::vector<size_t> out_base(B);
@@ -927,6 +942,23 @@ extern "C" int ss_forward_logits(ss_weights* w, const int32_t* tokens, const int
     return SS_OK;
 }
 
+}  // namespace
+
+extern "C" int ss_forward_logits(ss_weights* w, const int32_t* tokens, const int32_t* offsets, int32_t B,
+                                 const int32_t* n_prompt, int32_t all_prompt_logits, float* logits_out,
+                                 void* hip_stream)
+{
+    ss::clear_error();
+    if (int rc = check_prompts(w, tokens, offsets, B)) return rc;
+    if (!n_prompt || !logits_out) return ss::fail(SS_EINVAL, "NULL argument");
+    BusyGuard guard(w);
+    if (!guard.ok) return ss::fail(SS_ESTATE, "another call is in flight on this handle");
+    Lane& ln = w->lane[0];
+    hipStream_t s = hip_stream ? (hipStream_t)hip_stream : ln.stream;
+    return ss::no_throw(
+        [&] { return forward_logits_impl(w, ln, s, tokens, offsets, B, n_prompt, all_prompt_logits, logits_out); });
+}
+
 namespace {
 
 // The group pipeline shared by ss_run_group (gen == nullptr, lengths known) and ss_run_group_generate.
@@ -940,8 +972,13 @@ int run_group_impl(ss_weights* w, const int32_t* prompt_tokens, const int32_t* p
 {
     using clk = std::chrono::steady_clock;
     const auto t_plan0 = clk::now();
-    ss_plan* plan = nullptr;
-    if (int rc = ss_schedule(pred_lens, n, bin, policy, &plan)) return rc;
+    struct PlanOwner {   // frees the plan however the call ends
+        ss_plan* p = nullptr;
+        ~PlanOwner() { ss_plan_free(p); }
+    };
+    PlanOwner first_plan;
+    if (int rc = ss_schedule(pred_lens, n, bin, policy, &first_plan.p)) return rc;
+    const ss_plan* plan = first_plan.p;
     double plan_ms = std::chrono::duration<double, std::milli>(clk::now() - t_plan0).count();
 
     ss_group_stats gs{};
@@ -959,10 +996,10 @@ int run_group_impl(ss_weights* w, const int32_t* prompt_tokens, const int32_t* p
         std::atomic<int> stop{0};
         std::mutex mu;                 // guards gs, failed, rc/err and the progress lines
         int rc = SS_OK;
-        std::string err;
+        char err[512] = "";            // fixed storage: recording an error allocates nothing
     };
 
-    // One lane's share of a pass.  Runs on the calling thread (lane 0) or on a thread of its own (lane 1).
+    // One lane's share of a pass.  Runs on the calling thread (lane 0) or on a thread of its own (the other lanes).
     auto work = [&](Pass& ps, Lane& ln, hipStream_t ls) {
         std::vector<int32_t> mb_toks, mb_offs, mb_tl, mb_out, mb_lens, mb_ids;
         std::vector<float> mb_draws;
@@ -972,7 +1009,7 @@ int run_group_impl(ss_weights* w, const int32_t* prompt_tokens, const int32_t* p
             std::lock_guard<std::mutex> lock(ps.mu);
             if (ps.rc == SS_OK) {
                 ps.rc = rc;
-                ps.err = ss_last_error();
+                std::snprintf(ps.err, sizeof(ps.err), "%s", ss_last_error());
             }
             ps.stop.store(1);
         };
@@ -1052,7 +1089,7 @@ int run_group_impl(ss_weights* w, const int32_t* prompt_tokens, const int32_t* p
             std::lock_guard<std::mutex> lock(ps.mu);
             if (ps.rc == SS_OK) {
                 ps.rc = SS_ENOMEM;
-                ps.err = "host allocation failed in a micro-batch";
+                std::snprintf(ps.err, sizeof(ps.err), "host allocation failed in a micro-batch");
             }
             ps.stop.store(1);
         }
@@ -1071,35 +1108,35 @@ int run_group_impl(ss_weights* w, const int32_t* prompt_tokens, const int32_t* p
                 const int64_t cb = (int64_t)pl->mb_cap[b] * (64 + pl->mb_offsets[b + 1] - pl->mb_offsets[b]);
                 return ca > cb;
             });
-        std::vector<std::thread> others;
+        std::thread others[kLanes];   // fixed storage: from here on nothing can throw past the joins
+        int n_others = 0;
         for (int l = 1; l < lanes; ++l) {
             try {
-                others.emplace_back([&, l] { work_noexcept(ps, w->lane[l], w->lane[l].stream); });
+                others[n_others] = std::thread([&, l] { work_noexcept(ps, w->lane[l], w->lane[l].stream); });
+                ++n_others;
             } catch (...) {   // no further thread to be had: the pass runs on those it has
                 break;
             }
         }
         work_noexcept(ps, w->lane[0], s);
-        for (std::thread& t : others) t.join();
-        if (ps.rc != SS_OK) return ss::fail(ps.rc, "%s", ps.err.c_str());
+        for (int i = 0; i < n_others; ++i) others[i].join();
+        if (ps.rc != SS_OK) return ss::fail(ps.rc, "%s", ps.err);
         return SS_OK;
     };
 
     const auto t0 = clk::now();
     int rc = run_plan(plan, true);
-    ss_plan_free(plan);
     if (rc) return rc;
     gs.n_failed = (int32_t)failed.size();
     if (!failed.empty()) {
         std::sort(failed.begin(), failed.end());
         const auto tp = clk::now();
-        ss_plan* fplan = nullptr;
-        if ((rc = ss_schedule_failures(pred_lens, n, failed.data(), (int32_t)failed.size(), bin, policy, &fplan)))
+        PlanOwner fplan;
+        if ((rc = ss_schedule_failures(pred_lens, n, failed.data(), (int32_t)failed.size(), bin, policy, &fplan.p)))
             return rc;
         plan_ms += std::chrono::duration<double, std::milli>(clk::now() - tp).count();
         failed.clear();
-        rc = run_plan(fplan, false);
-        ss_plan_free(fplan);
+        rc = run_plan(fplan.p, false);
         if (rc) return rc;
         if (!failed.empty()) return ss::fail(SS_ESTATE, "a query failed in the recomputation pass");
     }
@@ -1127,8 +1164,10 @@ extern "C" int ss_run_group(ss_weights* w, const int32_t* prompt_tokens, const i
     for (int i = 0; i < n; ++i)
         if (target_lens[i] < 1 || target_lens[i] > policy->base_len)
             return ss::fail(SS_EINVAL, "target_lens[%d] outside [1, base_len]", i);
-    return run_group_impl(w, prompt_tokens, prompt_offsets, n, target_lens, pred_lens, bin, policy, nullptr, out_tokens,
-                          out_lens, stats, s);
+    return ss::no_throw([&] {
+        return run_group_impl(w, prompt_tokens, prompt_offsets, n, target_lens, pred_lens, bin, policy, nullptr,
+                              out_tokens, out_lens, stats, s);
+    });
 }
 
 extern "C" int ss_run_group_generate(ss_weights* w, const int32_t* prompt_tokens, const int32_t* prompt_offsets,
@@ -1146,8 +1185,10 @@ extern "C" int ss_run_group_generate(ss_weights* w, const int32_t* prompt_tokens
     if (!guard.ok) return ss::fail(SS_ESTATE, "another call is in flight on this handle");
     Lane& ln = w->lane[0];
     hipStream_t s = hip_stream ? (hipStream_t)hip_stream : ln.stream;
-    return run_group_impl(w, prompt_tokens, prompt_offsets, n, nullptr, pred_lens, bin, policy, opts, out_tokens,
-                          out_lens, stats, s);
+    return ss::no_throw([&] {
+        return run_group_impl(w, prompt_tokens, prompt_offsets, n, nullptr, pred_lens, bin, policy, opts, out_tokens,
+                              out_lens, stats, s);
+    });
 }
 
 namespace {
@@ -1223,7 +1264,8 @@ extern "C" int ss_bench_decode_step(ss_weights* w, const int32_t* prompt_tokens,
     if (!guard.ok) return ss::fail(SS_ESTATE, "another call is in flight on this handle");
     Lane& ln = w->lane[0];
     hipStream_t s = hip_stream ? (hipStream_t)hip_stream : ln.stream;
-    return bench_decode_step_lane(w, ln, s, prompt_tokens, B, ctx, iters, ms_out, nullptr, 0);
+    return ss::no_throw(
+        [&] { return bench_decode_step_lane(w, ln, s, prompt_tokens, B, ctx, iters, ms_out, nullptr, 0); });
 }
 
 extern "C" int ss_bench_decode_steps_in_flight(ss_weights* w, const int32_t* prompt_tokens, int32_t B, int32_t ctx,
@@ -1235,42 +1277,44 @@ extern "C" int ss_bench_decode_steps_in_flight(ss_weights* w, const int32_t* pro
     BusyGuard guard(w);
     if (!guard.ok) return ss::fail(SS_ESTATE, "another call is in flight on this handle");
     std::atomic<int> gate{0};
-    std::vector<int> rc((size_t)lanes, SS_OK);
-    std::vector<std::string> err((size_t)lanes);
-    auto run = [&](int l) {
-        rc[l] = bench_decode_step_lane(w, w->lane[l], w->lane[l].stream, prompt_tokens, B, ctx, iters,
-                                       ms_out + (size_t)l * iters, &gate, lanes);
-        if (rc[l]) err[l] = ss_last_error();
+    int rc[kLanes] = {};
+    char err[kLanes][256] = {};
+    auto run = [&](int l) {   // a lane's thread lets no exception out; its error text is copied for the caller
+        rc[l] = ss::no_throw([&] {
+            return bench_decode_step_lane(w, w->lane[l], w->lane[l].stream, prompt_tokens, B, ctx, iters,
+                                          ms_out + (size_t)l * iters, &gate, lanes);
+        });
+        if (rc[l]) std::snprintf(err[l], sizeof(err[l]), "%s", ss_last_error());
     };
-    std::vector<std::thread> others;
+    std::thread others[kLanes];   // fixed storage: only starting a thread can fail below
+    int n_others = 0;
+    auto join_all = [&] {
+        for (int i = 0; i < n_others; ++i) others[i].join();
+    };
     for (int l = 1; l < lanes; ++l) {
         try {
-            others.emplace_back(run, l);
+            others[n_others] = std::thread(run, l);
+            ++n_others;
         } catch (...) {
             // the lanes already started (1 .. l-1) wait at the gate for `lanes` arrivals: stand in for the ones
             // that will not come (l .. lanes-1, and lane 0, which this thread would have run)
             gate.fetch_add(lanes - l + 1);
-            for (std::thread& t : others) t.join();
+            join_all();
             return ss::fail(SS_ESTATE, "could not start host thread %d", l);
         }
     }
     run(0);
-    for (std::thread& t : others) t.join();
+    join_all();
     for (int l = 0; l < lanes; ++l)
-        if (rc[l]) return ss::fail(rc[l], "%s", err[l].c_str());
+        if (rc[l]) return ss::fail(rc[l], "%s", err[l]);
     return SS_OK;
 }
 
-extern "C" int ss_bench_weight_stream(ss_weights* w, int32_t B, int32_t iters, double* ms_out, int32_t* launches_out,
-                                      void* hip_stream)
+namespace {
+
+int bench_weight_stream_impl(const ss_weights* w, Lane& ln, hipStream_t s, int32_t B, int32_t iters, double* ms_out,
+                             int32_t* launches_out)
 {
-    ss::clear_error();
-    if (!w || !ms_out) return ss::fail(SS_EINVAL, "NULL argument");
-    if (B <= 0 || B > ss::kMaxBatch || iters < 1) return ss::fail(SS_EINVAL, "bad B / iters");
-    BusyGuard guard(w);
-    if (!guard.ok) return ss::fail(SS_ESTATE, "another call is in flight on this handle");
-    Lane& ln = w->lane[0];
-    hipStream_t s = hip_stream ? (hipStream_t)hip_stream : ln.stream;
     HIPCHK(hipSetDevice(w->device));
     if (int rc = ensure_workspace(w, ln, B, B, B, (size_t)B, 1, s)) return rc;
     const ss_model_cfg& c = w->cfg;
@@ -1316,15 +1360,9 @@ extern "C" int ss_bench_weight_stream(ss_weights* w, int32_t B, int32_t iters, d
     return SS_OK;
 }
 
-extern "C" int ss_bench_read_stream(ss_weights* w, int32_t iters, double* ms_out, int64_t* bytes_out, void* hip_stream)
+int bench_read_stream_impl(const ss_weights* w, Lane& ln, hipStream_t s, int32_t iters, double* ms_out,
+                           int64_t* bytes_out)
 {
-    ss::clear_error();
-    if (!w || !ms_out) return ss::fail(SS_EINVAL, "NULL argument");
-    if (iters < 1) return ss::fail(SS_EINVAL, "bad iters");
-    BusyGuard guard(w);
-    if (!guard.ok) return ss::fail(SS_ESTATE, "another call is in flight on this handle");
-    Lane& ln = w->lane[0];
-    hipStream_t s = hip_stream ? (hipStream_t)hip_stream : ln.stream;
     HIPCHK(hipSetDevice(w->device));
     if (int rc = ln.ws.ints.ensure(64, false)) return rc;
     uint32_t* sink = ln.ws.ints.as<uint32_t>();
@@ -1354,4 +1392,31 @@ extern "C" int ss_bench_read_stream(ss_weights* w, int32_t iters, double* ms_out
     }
     if (bytes_out) *bytes_out = (int64_t)bytes;
     return SS_OK;
+}
+
+}  // namespace
+
+extern "C" int ss_bench_weight_stream(ss_weights* w, int32_t B, int32_t iters, double* ms_out, int32_t* launches_out,
+                                      void* hip_stream)
+{
+    ss::clear_error();
+    if (!w || !ms_out) return ss::fail(SS_EINVAL, "NULL argument");
+    if (B <= 0 || B > ss::kMaxBatch || iters < 1) return ss::fail(SS_EINVAL, "bad B / iters");
+    BusyGuard guard(w);
+    if (!guard.ok) return ss::fail(SS_ESTATE, "another call is in flight on this handle");
+    Lane& ln = w->lane[0];
+    hipStream_t s = hip_stream ? (hipStream_t)hip_stream : ln.stream;
+    return ss::no_throw([&] { return bench_weight_stream_impl(w, ln, s, B, iters, ms_out, launches_out); });
+}
+
+extern "C" int ss_bench_read_stream(ss_weights* w, int32_t iters, double* ms_out, int64_t* bytes_out, void* hip_stream)
+{
+    ss::clear_error();
+    if (!w || !ms_out) return ss::fail(SS_EINVAL, "NULL argument");
+    if (iters < 1) return ss::fail(SS_EINVAL, "bad iters");
+    BusyGuard guard(w);
+    if (!guard.ok) return ss::fail(SS_ESTATE, "another call is in flight on this handle");
+    Lane& ln = w->lane[0];
+    hipStream_t s = hip_stream ? (hipStream_t)hip_stream : ln.stream;
+    return ss::no_throw([&] { return bench_read_stream_impl(w, ln, s, iters, ms_out, bytes_out); });
 }

@@ -4,6 +4,8 @@
 
 #include <cstddef>
 #include <cstdint>
+#include <exception>
+#include <new>
 
 #include "../../include/ss.h"
 
@@ -13,6 +15,22 @@ namespace ss {
 int fail(int code, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
 void clear_error();
 int verbose();   // ss_set_verbose level
+
+// Runs the body of an entry point (a callable returning an SS_* code) so that no C++ exception crosses the C ABI:
+// a failed host allocation becomes SS_ENOMEM, anything else SS_ESTATE, each with a message.
+template <class Body>
+int no_throw(Body&& body) noexcept
+{
+    try {
+        return body();
+    } catch (const std::bad_alloc&) {
+        return fail(SS_ENOMEM, "host allocation failed");
+    } catch (const std::exception& e) {
+        return fail(SS_ESTATE, "unexpected host error: %s", e.what());
+    } catch (...) {
+        return fail(SS_ESTATE, "unexpected host error");
+    }
+}
 
 constexpr int kMaxPos = 4096;     // positions per row (prompt + generated) the attention kernel supports
 constexpr int kMaxBatch = 1024;   // rows per micro-batch the bookkeeping kernel supports

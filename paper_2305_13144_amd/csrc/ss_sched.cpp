@@ -10,6 +10,7 @@
 
 #include <algorithm>
 #include <cstring>
+#include <memory>
 #include <numeric>
 #include <vector>
 
@@ -64,14 +65,14 @@ inline int32_t batch_size(int64_t L, const ss_policy& p)
     return static_cast<int32_t>(std::max<int64_t>(p.base_batch, std::min<int64_t>(p.max_batch, b)));
 }
 
-PlanStorage* finish(PlanStorage* s)
+ss_plan* finish(std::unique_ptr<PlanStorage> s)
 {
     s->pub.n = static_cast<int32_t>(s->idx.size());
     s->pub.n_mb = static_cast<int32_t>(s->cap.size());
     s->pub.mb_offsets = s->offsets.data();
     s->pub.query_idx = s->idx.data();
     s->pub.mb_cap = s->cap.data();
-    return s;
+    return &s.release()->pub;   // the caller owns it from here: ss_plan_free
 }
 
 void emit(PlanStorage* s, const int32_t* rows, int32_t count, int32_t cap)
@@ -81,9 +82,7 @@ void emit(PlanStorage* s, const int32_t* rows, int32_t count, int32_t cap)
     s->cap.push_back(cap);
 }
 
-}  // namespace
-
-extern "C" int ss_schedule(const int32_t* pred_lens, int32_t n, int32_t bin, const ss_policy* policy, ss_plan** out)
+int schedule_impl(const int32_t* pred_lens, int32_t n, int32_t bin, const ss_policy* policy, ss_plan** out)
 {
     if (!out) return ss::fail(SS_EINVAL, "out is NULL");
     if (n <= 0) return ss::fail(SS_EINVAL, "n must be > 0");
@@ -95,15 +94,15 @@ extern "C" int ss_schedule(const int32_t* pred_lens, int32_t n, int32_t bin, con
         for (int32_t i = 0; i < n; ++i)
             if (pred_lens[i] < 1) return ss::fail(SS_EINVAL, "pred_lens[%d] = %d < 1", i, pred_lens[i]);
 
-    PlanStorage* s = new (std::nothrow) PlanStorage();
-    if (!s) return ss::fail(SS_ENOMEM, "plan allocation failed");
+    std::unique_ptr<PlanStorage> plan(new PlanStorage());
+    PlanStorage* s = plan.get();
     s->offsets.push_back(0);
     std::vector<int32_t> order(n);
     std::iota(order.begin(), order.end(), 0);
 
     if (!sorted) {  // vanilla: arrival order, fixed batch, global cap
         for (int32_t b = 0; b < n; b += p.base_batch) emit(s, &order[b], std::min(p.base_batch, n - b), p.base_len);
-        *out = &finish(s)->pub;
+        *out = finish(std::move(plan));
         return SS_OK;
     }
 
@@ -138,12 +137,12 @@ extern "C" int ss_schedule(const int32_t* pred_lens, int32_t n, int32_t bin, con
             at = end;
         }
     }
-    *out = &finish(s)->pub;
+    *out = finish(std::move(plan));
     return SS_OK;
 }
 
-extern "C" int ss_schedule_failures(const int32_t* pred_lens, int32_t n, const int32_t* failed_idx, int32_t n_failed,
-                                    int32_t bin, const ss_policy* policy, ss_plan** out)
+int schedule_failures_impl(const int32_t* pred_lens, int32_t n, const int32_t* failed_idx, int32_t n_failed,
+                           int32_t bin, const ss_policy* policy, ss_plan** out)
 {
     if (!out) return ss::fail(SS_EINVAL, "out is NULL");
     if (n <= 0 || n_failed < 0 || n_failed > n) return ss::fail(SS_EINVAL, "bad n / n_failed");
@@ -161,13 +160,27 @@ extern "C" int ss_schedule_failures(const int32_t* pred_lens, int32_t n, const i
             return la != lb ? la < lb : a < b;
         });
     }
-    PlanStorage* s = new (std::nothrow) PlanStorage();
-    if (!s) return ss::fail(SS_ENOMEM, "plan allocation failed");
+    std::unique_ptr<PlanStorage> plan(new PlanStorage());
+    PlanStorage* s = plan.get();
     s->offsets.push_back(0);
     for (int32_t b = 0; b < n_failed; b += p.base_batch)
         emit(s, &order[b], std::min(p.base_batch, n_failed - b), p.base_len);
-    *out = &finish(s)->pub;
+    *out = finish(std::move(plan));
     return SS_OK;
+}
+
+}  // namespace
+
+// The entry points hand no C++ exception to the caller: a plan that does not fit the host's memory is SS_ENOMEM.
+extern "C" int ss_schedule(const int32_t* pred_lens, int32_t n, int32_t bin, const ss_policy* policy, ss_plan** out)
+{
+    return ss::no_throw([&] { return schedule_impl(pred_lens, n, bin, policy, out); });
+}
+
+extern "C" int ss_schedule_failures(const int32_t* pred_lens, int32_t n, const int32_t* failed_idx, int32_t n_failed,
+                                    int32_t bin, const ss_policy* policy, ss_plan** out)
+{
+    return ss::no_throw([&] { return schedule_failures_impl(pred_lens, n, failed_idx, n_failed, bin, policy, out); });
 }
 
 extern "C" void ss_plan_free(ss_plan* plan)

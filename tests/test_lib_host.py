@@ -128,3 +128,37 @@ def test_generation_entry_points_reject_null_without_touching_a_gpu(lib):
     assert lib.ss_weights_create(C.byref(cfg), arr, ss.SS_BF16, C.byref(h)) == ss.SS_EINVAL
     lib.ss_weights_destroy(None)
     lib.ss_plan_free(None)
+
+
+_NO_MEMORY_CHILD = r"""
+import ctypes as C, resource, sys
+from paper_2305_13144_amd import binding as ss
+L = ss.lib()
+pol = ss.make_policy((), 16, 512, 256)            # vanilla batching: the predictions are not read
+plan = C.POINTER(ss.ss_plan)()
+assert L.ss_schedule(None, 1000, 0, C.byref(pol), C.byref(plan)) == ss.SS_OK and plan.contents.n_mb == 63
+L.ss_plan_free(plan)
+# cap the address space a little above what the process holds now: a plan over 2^31 - 1 queries needs three arrays
+# of that many int32, which cannot be had
+with open("/proc/self/statm") as f:
+    held = int(f.read().split()[0]) * resource.getpagesize()
+resource.setrlimit(resource.RLIMIT_AS, (held + (1 << 30), held + (1 << 30)))
+plan = C.POINTER(ss.ss_plan)()
+rc = L.ss_schedule(None, 2**31 - 1, 0, C.byref(pol), C.byref(plan))
+print("rc", rc, "plan", bool(plan), "msg", L.ss_last_error().decode())
+failed = (C.c_int32 * 1)(0)
+rc2 = L.ss_schedule(None, 100, 0, C.byref(pol), C.byref(plan))    # and the library goes on working
+print("rc2", rc2, "n_mb", plan.contents.n_mb)
+"""
+
+
+def test_a_plan_that_does_not_fit_host_memory_is_an_error_code(lib):
+    """No C++ exception crosses the C ABI: the scheduler answers SS_ENOMEM when its arrays cannot be allocated, sets no
+    plan, and the next call works.  Runs in a child process because it lowers the process's address-space limit."""
+    import subprocess
+    import sys
+    out = subprocess.run([sys.executable, "-c", _NO_MEMORY_CHILD], cwd=ROOT, capture_output=True, text=True, timeout=120)
+    assert out.returncode == 0, out.stderr[-2000:]
+    lines = out.stdout.strip().splitlines()
+    assert lines[0].startswith(f"rc {ss.SS_ENOMEM} plan False msg host allocation failed"), lines
+    assert lines[1] == "rc2 0 n_mb 7", lines
