@@ -199,6 +199,35 @@ def test_sampler_distribution_peaked_and_flat_draws(tiny):
     assert (r["tokens"][::2] >= synth.TINY.vocab - 4).all()
 
 
+def test_draws_on_the_edges_of_the_cdf_with_bit_equal_logits(tiny):
+    """Every LM-head row identical -> all logits of a position are bit-equal -> every token has mass exactly 1/V, and
+    with V a power of two the edges k/V of the CDF are exact in both precisions.  A draw equal to an edge must pick the
+    token above it, the largest float below the edge the token under it (token v owns [c_{v-1}, c_v)); every token is
+    compared with the oracle's rule on the same (all-equal) logits, with no undecided band."""
+    W, om, gw = tiny
+    V = synth.TINY.vocab
+    assert V & (V - 1) == 0
+    W2 = [t.copy() for t in W]
+    W2[-1][:] = W2[-1][5]
+    gw2 = ss.Weights(synth.TINY, W2)
+    try:
+        w = synth.make_workload(1)
+        cap = 8
+        rng = np.random.default_rng(77)
+        ks = rng.integers(1, V, size=(w.n, cap))
+        ks[0, :4] = [1, V - 1, V // 2, 3]
+        draws = (ks / V).astype(np.float32)
+        draws[:, 1::2] = np.nextafter(draws[:, 1::2], np.float32(0))       # odd token numbers: just under the edge
+        draws[1, 0], draws[1, 2] = 0.0, np.nextafter(np.float32(1), np.float32(0))
+        r = ss.ss_generate_microbatch(gw2, w.prompt_tokens, w.prompt_offsets, cap, temperature=0.5, draws=draws)
+        want = np.array([[sm.sample_token(np.zeros(V), 0.5, float(draws[i, s]))[0] for s in range(cap)]
+                         for i in range(w.n)], np.int32)
+        assert want[0, :4].tolist() == [1, V - 2, V // 2, 2] and want[1, 0] == 0 and want[1, 2] == V - 1
+        assert np.array_equal(r["lens"], np.full(w.n, cap)) and np.array_equal(r["tokens"], want)
+    finally:
+        gw2.close()
+
+
 def test_generated_draws_equal_the_oracles_table(tiny):
     """Draws generated on the device from (seed, row id, token number) give exactly the tokens that the same call
     gives when it is handed the oracle's table of those draws: the two generators agree bit for bit."""

@@ -83,6 +83,21 @@ def test_schedule_bit_exact_random_groups(lib, flags, rule):
             assert gotf == _as_pairs(wantf)
 
 
+def test_library_batch_size_rules_for_every_length(lib):
+    """The batch size the library allows for a scheduled length L, read off a group of equal predictions (the first
+    chunk is as large as allowed), against the oracle's rule for every L; and predictions without SS_SORT change nothing."""
+    n = 300
+    for L in range(43, 360):        # from 43 up the power-of-two rule allows at most 256 rows: the group can show it
+        pred = np.full(n, L, np.int32)
+        got = ss.ss_schedule(pred, n, 0, ss.make_policy(("SORT", "VBS"), 16, 512, 256, ss.SS_VBS_PAPER_POW2))
+        assert len(got[0][0]) == so.vbs_paper_pow2(L), L
+        got = ss.ss_schedule(pred, n, 0, ss.make_policy(("SORT", "VBS"), 16, 512, 256))
+        assert len(got[0][0]) == so.vbs_clamp_floor(L, 16, 512, 256), L
+    pred = np.array([30, 120, 55, 49, 260, 51, 100, 7], np.int32)
+    got = ss.ss_schedule(pred, 8, 50, ss.make_policy((), 3, 64))
+    assert got == [([0, 1, 2], 64), ([3, 4, 5], 64), ([6, 7], 64)]
+
+
 def test_schedule_rejects_bad_arguments(lib):
     pol = ss.make_policy(("SORT", "BIN", "FCR"))
     pred = np.array([10, 20, 30], np.int32)

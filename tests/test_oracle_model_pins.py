@@ -222,6 +222,19 @@ def test_greedy_microbatch_semantics(tiny):
             assert math.isclose(top2[1] - top2[0], r["margins"][i, g], rel_tol=1e-3, abs_tol=2e-6)
 
 
+def test_a_row_that_ends_exactly_at_the_cap_has_not_failed(tiny):
+    """Sec. 4.1, FCR: a row fails when it is still unfinished at the cap.  A response of exactly `cap` tokens is complete;
+    one token more is a failure whose first `cap` tokens are the same."""
+    W, om, hf = tiny
+    w = synth.make_workload(1)
+    toks, offs = w.prompt_tokens[:w.prompt_offsets[3]], w.prompt_offsets[:4]
+    r = om.greedy_microbatch(toks, offs, 6, [6, 7, 5])
+    assert r["failed"].tolist() == [0, 1, 0] and r["lens"].tolist() == [6, 6, 5] and r["steps"] == 6
+    r1 = om.greedy_microbatch(toks, offs, 7, [6, 7, 5])
+    assert r1["failed"].tolist() == [0, 0, 0] and r1["lens"].tolist() == [6, 7, 5] and r1["steps"] == 7
+    assert np.array_equal(r["tokens"][1, :6], r1["tokens"][1, :6])
+
+
 def test_query_output_independent_of_batch(tiny):
     """A query's tokens are the same alone, in a micro-batch, and after a capped (failed) first try."""
     W, om, _ = tiny

@@ -71,6 +71,30 @@ def test_vocabulary_order_of_the_cdf():
     assert sm.sample_token(l, T, 0.0)[0] == 0
 
 
+def test_a_draw_on_an_interval_edge_belongs_to_the_next_token():
+    """Token v owns the half-open interval [c_{v-1}, c_v) of the CDF, so that a uniform u in [0,1) picks it with
+    probability p_v exactly: u equal to an edge picks the token above it.  Equal logits with a power-of-two count make
+    every edge exact in binary."""
+    for V in (2, 4, 8):
+        l = np.full(V, -0.75)
+        for k in range(1, V):
+            assert sm.sample_token(l, 0.5, k / V)[0] == k
+            assert sm.sample_token(l, 0.5, float(np.nextafter(k / V, 0.0)))[0] == k - 1
+        assert sm.sample_token(l, 0.5, 0.0)[0] == 0
+
+
+def test_a_cdf_that_rounding_leaves_below_the_draw_ends_on_the_last_token():
+    """Ten equal masses of 0.1 add up to 1 - 2^-53 in double precision; the largest draw below 1 is not exceeded by any
+    partial sum, and the definition's answer (the last interval reaches up to 1) is the last token."""
+    acc = 0.0
+    for _ in range(10):
+        acc += 0.1
+    u = float(np.nextafter(1.0, 0.0))
+    assert acc == u                                   # the premise: no partial sum is > u
+    tok, mg = sm.sample_token(np.zeros(10), 1.0, u)
+    assert tok == 9 and mg == 0.0
+
+
 def test_softmax_invariances():
     rng = np.random.default_rng(3)
     l = rng.normal(size=100)

@@ -45,6 +45,22 @@ def test_paper_vbs_pow2_rule():
     assert all(a >= b for a, b in zip(outs, outs[1:]))     # larger batches for shorter responses
 
 
+def test_paper_vbs_pow2_rule_is_the_nearest_power_of_two_by_brute_force():
+    """Sec. 4.2: below 300 the batch size is 256*50/L rounded to the nearest power of two.  For every L the result
+    must be the power of two closest to 12800/L among all of them, found here by trying each one in exact rational
+    arithmetic (no L makes two of them equally close: 12800/L = 1.5 * 2^k has no integer solution)."""
+    from fractions import Fraction
+    powers = [2 ** k for k in range(0, 15)]
+    for L in range(1, 300):
+        x = Fraction(256 * 50, L)
+        dist = sorted((abs(x - b), b) for b in powers)
+        assert dist[0][0] != dist[1][0]
+        assert so.vbs_paper_pow2(L) == dist[0][1], L
+    # the places where the constant shows: 12800/260 = 49.2 is nearer 64 (a numerator of 12288 would say 32)
+    assert so.vbs_paper_pow2(260) == 64 and so.vbs_paper_pow2(270) == 32
+    assert so.vbs_paper_pow2(130) == 128 and so.vbs_paper_pow2(134) == 64
+
+
 # ------------------------------------------------------------------ closed forms of the configured rule
 def test_vbs_clamp_floor_tables():
     got = [so.vbs_clamp_floor(ub, 16, 512, 256) for ub in range(50, 600, 50)]
@@ -88,6 +104,13 @@ def test_hand_enumerated_vanilla_group():
     assert r["redundancy"] == pytest.approx(1 - 733 / 1160)
 
 
+def test_predictions_without_the_sort_flag_are_ignored():
+    """The vanilla baseline of Sec. 4.2 batches in arrival order even when predictions are at hand."""
+    pol = so.Policy(flags=(), base_batch=3, l_max=64)
+    plan = so.schedule(PRED, len(PRED), 50, pol)
+    assert [(m.idx, m.cap) for m in plan] == [([0, 1, 2], 64), ([3, 4, 5], 64), ([6, 7], 64)]
+
+
 def test_hand_enumerated_sorted_fcr_without_bins():
     pol = so.Policy(flags=("SORT", "FCR"), base_batch=3, l_max=512)
     plan = so.schedule(PRED, 8, 0, pol)
@@ -127,6 +150,13 @@ def test_hand_enumerated_failure_pass_order_with_bins():
     assert [m["steps"] for m in r["second"].per_mb] == [180, 400]
     assert r["second"].steps == 580 and r["second"].padded_row_steps == 1160      # index order would cost 400 + 300
     assert r["steps"] == 1395 and r["useful_tokens"] == 1305 and r["n_failed"] == 4
+    # Sec. 4.2's metrics, by hand: 4 of the 8 queries failed; every row-step of both passes is paid for
+    # (1015 + 1160 = 2175), of which 1305 produced a token that is kept (the failed rows' first attempts, 50 + 100 +
+    # 150 + 300 row-steps, are thrown away, so they count as waste although they were "live")
+    assert r["failure_ratio"] == 4 / 8
+    assert r["padded_row_steps"] == 2175 and r["live_row_steps"] == 965 + 940
+    assert r["redundancy"] == 1.0 - 1305 / 2175
+    assert r["avg_len_weighted"] == 2175 / 12 and r["avg_len_unweighted"] == 1395 / 8
     # the order does not depend on the order the failures are handed over in
     for given in ([0, 1, 3, 5], [5, 3, 1, 0], [3, 0, 5, 1]):
         assert [m.idx for m in so.schedule_failures(PRED_F, given, 50, pol)] == [[1, 3], [5, 0]]
