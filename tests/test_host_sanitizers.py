@@ -97,7 +97,8 @@ PLAN_DRIVER = textwrap.dedent(r"""
                                 32704, 32705, 100000, 1048576};
         const int cus[] = {64, 256, 304};
         long checked = 0;
-        for (int mode = 0; mode <= 2; ++mode) {
+        const int modes[] = {0, 1, 2, 4, 5, 6, 8, 9, 10, 12, 13, 14};   // every mode the library accepts
+        for (int mode : modes) {
             ss::set_gemm_mode(mode);
             for (int cu : cus)
                 for (int d : dims)
@@ -113,6 +114,31 @@ PLAN_DRIVER = textwrap.dedent(r"""
                                     if (n > n_max) break;
                                     const ss::GemmPlan p = ss::gemm_plan(m.N, m.Kp, n, m.epi, cu);
                                     if (p.ksplit < 1 || p.ksplit > 8) { std::printf("bad ksplit\n"); return 2; }
+                                    // what the launchers assume of a plan
+                                    const int KB = m.Kp / 32;
+                                    bool ok = KB / p.ksplit >= 1 && (p.ksplit & (p.ksplit - 1)) == 0;
+                                    if (p.sweep_gn > 0) {        // sweep kernel: at most 8 units per workgroup, 4 with 4 waves
+                                        const int nbw = ss::sweep_nbw(m.epi, n);
+                                        const int units = (m.N / 16 + nbw - 1) / nbw;
+                                        const int per = (units + p.sweep_gn - 1) / p.sweep_gn;
+                                        ok = ok && n <= ss::kSweepMaxRows && per >= 1 && per <= 8;
+                                        ok = ok && (p.sweep_p == 8 || (p.sweep_p == 4 && per <= 4));
+                                        ok = ok && (p.sweep_kh == 1 || (p.sweep_kh == 2 && p.sweep_p == 4 && n > 96));
+                                        ok = ok && (m.epi != ss::EPI_SWIGLU || p.ksplit == 1);
+                                    } else if (n <= 64) {        // skinny kernel
+                                        ok = ok && (p.nb == 2 || p.nb == 4) && (p.kd == 2 || p.kd == 4);
+                                        ok = ok && (m.epi != ss::EPI_SWIGLU || p.ksplit == 1);
+                                    } else {                     // tiled kernel
+                                        ok = ok && (p.kp == 1 || (p.kp == 2 && p.ksplit == 1)) && (p.tms == 4 || p.tms == 8);
+                                        ok = ok && p.ksplit <= 4 && (p.tms == 4 || n >= ss::kTiledTallFrom);
+                                        ok = ok && ((mode & 8) == 0 || p.tms == 4);
+                                    }
+                                    if (!ok) {
+                                        std::printf("plan breaks a launcher's assumption: mode %d N %d Kp %d rows %d cu %d: "
+                                                    "ksplit %d nb %d kd %d kp %d sweep %d/%d/%d tms %d\n", mode, m.N, m.Kp, n,
+                                                    cu, p.ksplit, p.nb, p.kd, p.kp, p.sweep_p, p.sweep_gn, p.sweep_kh, p.tms);
+                                        return 7;
+                                    }
                                     if (m.sliced_only && p.ksplit == 1) continue;
                                     if ((size_t)p.ksplit * (size_t)n > cap) {
                                         std::printf("overflow: N %d Kp %d rows %d (n_max %d) ksplit %d > %zu rows\n", m.N,
