@@ -239,6 +239,9 @@ def main() -> int:
     ap.add_argument("--roofline-only", action="store_true",
                     help="only the roofline legs (weight-stream kernels and one decode step); the command profiled "
                          "under rocprofv3 for profiles/")
+    ap.add_argument("--in-flight-only", action="store_true",
+                    help="only the leg that runs --in-flight decode steps at the same time, one per lane (the command "
+                         "profiled under rocprofv3 for profiles/decode_steps_in_flight_7b_kernel_trace.txt)")
     a = ap.parse_args()
     if a.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus must be 1 (micro-batches would be dealt to GPUs "
@@ -267,6 +270,17 @@ def main() -> int:
     def run(policy, pred, binw):
         return ss.ss_run_group(gw, wl.prompt_tokens, wl.prompt_offsets, wl.target_lens, pred, binw, policy)
 
+    if a.in_flight_only:
+        B0, ctx = a.step_rows, a.step_ctx
+        ptoks = np.random.default_rng(7).integers(0, shape.vocab, size=B0 * ctx).astype(np.int32)
+        ms_l = ss.ss_bench_decode_steps_in_flight(gw, ptoks, B0, ctx, a.step_iters + 6, a.in_flight)[:, 3:-3]
+        ach_l = a.in_flight * decode_step_bytes(shape, B0, ctx) / (ms_l.mean() * 1e-3) / 1e9
+        log(f"{a.in_flight} decode steps in flight, B={B0} ctx={ctx}: {ms_l.mean():.3f} ms each -> {ach_l:.0f} GB/s = "
+            f"{ach_l / HBM_PEAK_GBS:.3f} of peak for the bytes of all")
+        print(json.dumps(dict(lanes=a.in_flight, rows=B0, ctx=ctx, iters_per_lane=int(ms_l.shape[1]), ms=float(ms_l.mean()),
+                              achieved=ach_l, unit="GB/s", frac=ach_l / HBM_PEAK_GBS)), flush=True)
+        gw.close()
+        return 0
     if a.ablation:
         return ablation(a, ss, gw, wl, shape)
     if a.sweep:
