@@ -33,3 +33,25 @@ def test_decode_step_bytes_is_weights_plus_history_plus_new_slot_plus_embedding(
     assert abs(b / 8e12 * 1e3 - 1.864) < 1e-3
     # one more live row costs its history, its new slot and its embedding row
     assert bench.decode_step_bytes(synth.LLAMA7B, 17, 200) - b == 201 * 524_288 + 524_288 + 8_192
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """This build runs on one GPU: asking for more must end with a message and a non-zero status before anything
+    touches a device."""
+    import subprocess
+    import sys
+    root = pathlib.Path(__file__).resolve().parent.parent
+    r = subprocess.run([sys.executable, str(root / "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 2 and "ONE GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_roofline_traffic_comes_from_the_committed_counter_summary_or_is_null():
+    """`roofline.traffic` is read from the committed rocprofv3 counter summary for exactly the shape and launch
+    configuration it was taken at; for any other it is null with the reason, never a stale constant."""
+    got, source = bench.profile_traffic("llama7b", 16, 200, 0)
+    assert got is not None and source.startswith("profiles/decode_step_7b_hbm_traffic.txt")
+    alg = bench.decode_step_bytes(synth.LLAMA7B, 16, 200)
+    assert 1.0 <= got / alg < 1.10          # measured traffic: a few per cent above the algorithmic bytes, no re-reads
+    for other in (("llama13b", 16, 200, 0), ("llama7b", 32, 200, 0), ("llama7b", 16, 100, 0), ("llama7b", 16, 200, 2)):
+        got, why = bench.profile_traffic(*other)
+        assert got is None and "another shape" in why
