@@ -97,7 +97,7 @@ GemmPlan gemm_plan(int N, int Kp, int m_rows, int epilogue, int n_cu, int max_ks
     const int tiles = ((N + 255) / 256) * ((m_rows + p.tms * 16 - 1) / (p.tms * 16));
     // Measured at the 7B shape, same GPU, against slicing up to 512 workgroups whenever there are fewer than 512 tiles:
     // prompt forward of 640 token-rows 12.6 against 13.8 ms (q|k|v, 480 tiles, now unsliced; o and down, 160 tiles, two
-    // slices instead of four), 1280 token-rows 19.6 against 21.9, decode steps of 129-256 rows 3-4 % shorter; stopping at
+    // slices instead of four), 1280 token-rows 19.6 against 21.9, decode steps of 129-256 rows (run by this kernel at the time) 3-4 % shorter; stopping at
     // 256 workgroups instead of 320 costs 4 % at 1024 token-rows, going on to 384 costs 5 % at 640 and 1280.
     if (tiles >= kTiledNoSliceTiles) return p;
     while (tiles * p.ksplit < kTiledFullGroups && p.ksplit * 2 <= max_ksplit && p.ksplit < kTiledMaxKsplit &&
