@@ -66,7 +66,7 @@ def test_schedule_bit_exact_random_groups(lib, flags, rule):
     for trial in range(25):
         n = int(rng.integers(1, 300))
         lmax = int(rng.choice([48, 100, 512, 1024]))
-        w = int(rng.choice([7, 50, 64, lmax]))
+        w = int(rng.choice([1, 7, 50, 64, lmax]))      # cell 1: neighbouring lengths are neighbouring bins
         b0 = int(rng.choice([1, 2, 16]))
         maxb = int(rng.choice([b0, 64, 256]))
         pred = rng.integers(1, int(lmax * 1.3) + 2, size=n).astype(np.int32)
@@ -121,8 +121,13 @@ def test_schedule_rejects_bad_arguments(lib):
     out = C.POINTER(ss.ss_plan)()
     assert lib.ss_schedule(None, 3, 0, None, C.byref(out)) == ss.SS_EINVAL
     assert lib.ss_schedule(None, 3, 0, C.byref(ss.make_policy(())), None) == ss.SS_EINVAL
-    with pytest.raises(ss.SsError):
-        ss.ss_schedule_failures(pred, 3, [5], 50, pol)
+    for bad in ([5], [3], [-1], [0, 3]):                      # indices are 0 .. n-1
+        with pytest.raises(ss.SsError) as e:
+            ss.ss_schedule_failures(pred, 3, bad, 50, pol)
+        assert e.value.code == ss.SS_EINVAL
+    assert ss.ss_schedule_failures(pred, 3, [2], 50, pol) == [([2], 512)]
+    with pytest.raises(ss.SsError):                           # index n is refused as such, not for what lies behind the array
+        ss.ss_schedule_failures(np.array([10, 20, 30, 40], np.int32), 3, [3], 50, pol)
 
 
 def test_generation_entry_points_reject_null_without_touching_a_gpu(lib):
