@@ -250,6 +250,58 @@ def test_philox_known_answer_vectors():
     assert n == 3
 
 
+_TRITON_CHILD = r"""
+import os, sys
+os.environ["TRITON_INTERPRET"] = "1"          # the library's CPU interpreter: no GPU, no compilation
+import numpy as np, torch, triton, triton.language as tl
+
+@triton.jit
+def k(seed_ptr, c_ptr, out_ptr, N: tl.constexpr):
+    i = tl.arange(0, N)
+    o0, o1, o2, o3 = tl.philox(tl.load(seed_ptr + i), tl.load(c_ptr + i), tl.load(c_ptr + N + i),
+                               tl.load(c_ptr + 2 * N + i), tl.load(c_ptr + 3 * N + i))
+    tl.store(out_ptr + i, o0)
+    tl.store(out_ptr + N + i, o1)
+    tl.store(out_ptr + 2 * N + i, o2)
+    tl.store(out_ptr + 3 * N + i, o3)
+
+N = 256
+rng = np.random.default_rng(int(sys.argv[1]))
+seed = rng.integers(-2**63, 2**63, size=N, dtype=np.int64)
+ctr = rng.integers(0, 2**32, size=(4, N), dtype=np.uint64).astype(np.uint32)
+ctr[0, :8] = [0, 1, 2, 3, 0xffffffff, 0, 7, 511]          # the sampler's counters: (token number, row id, 0, 0)
+ctr[1, :8] = [0, 5, 1, 77, 3, 0xffffffff, 2, 9]
+ctr[2:, :8] = 0
+out = torch.zeros(4, N, dtype=torch.uint32)
+k[(1,)](torch.from_numpy(seed), torch.from_numpy(ctr.copy()), out, N=N)
+o = out.numpy()
+for j in range(N):
+    print(int(seed[j]) & (2**64 - 1), *[int(x) for x in ctr[:, j]], *[int(x) for x in o[:, j]])
+"""
+
+
+def test_philox_matches_an_independent_library_implementation():
+    """The oracle's Philox4x32-10 against the one a tensor-compiler library ships for its random numbers, run in
+    that library's CPU interpreter on 256 seeded (counter, key) pairs (the library takes the key as one 64-bit seed:
+    low word first).  This pins the round function, its constants, the key schedule and the word order to code that
+    shares nothing with this repository; the three published vectors above pin the same things to the paper's table."""
+    import subprocess
+    import sys
+    pytest.importorskip("triton")
+    r = subprocess.run([sys.executable, "-c", _TRITON_CHILD, "2024"], capture_output=True, text=True, timeout=600)
+    if r.returncode != 0 and "philox" not in r.stderr:
+        pytest.skip("the library's CPU interpreter does not run here: " + r.stderr.strip().splitlines()[-1][:200])
+    assert r.returncode == 0, r.stderr[-2000:]
+    rows = [[int(x) for x in line.split()] for line in r.stdout.strip().splitlines()]
+    assert len(rows) == 256
+    for seed, c0, c1, c2, c3, *out in rows:
+        assert sm.philox4x32_10((c0, c1, c2, c3), (seed & 0xFFFFFFFF, seed >> 32)) == tuple(out)
+    # the draw the sampler uses: counter (token number, row id, 0, 0), top 24 bits of the first word
+    for seed, c0, c1, c2, c3, *out in rows[:8]:
+        assert c2 == 0 and c3 == 0
+        assert sm.generated_draw(seed, c1, c0) == np.float32((out[0] >> 8) * 2.0 ** -24)
+
+
 def test_generated_draw_is_top_24_bits_of_the_first_word():
     # counter (0,0,0,0), key 0: first word 0x6627e8d5 -> 0x6627e8 * 2^-24
     assert sm.generated_draw(0, 0, 0) == np.float32(0x6627E8 / 2.0 ** 24)
