@@ -272,6 +272,11 @@ ctr = rng.integers(0, 2**32, size=(4, N), dtype=np.uint64).astype(np.uint32)
 ctr[0, :8] = [0, 1, 2, 3, 0xffffffff, 0, 7, 511]          # the sampler's counters: (token number, row id, 0, 0)
 ctr[1, :8] = [0, 5, 1, 77, 3, 0xffffffff, 2, 9]
 ctr[2:, :8] = 0
+kat = [l.split("|") for l in open(sys.argv[2]) if l.strip() and not l.startswith("#")]     # inputs of the published vectors
+for j, (c, key, _) in enumerate(kat):
+    ctr[:, 8 + j] = [int(x, 16) for x in c.split()]
+    k0, k1 = [int(x, 16) for x in key.split()]
+    seed[8 + j] = np.array([(k1 << 32) | k0], np.uint64).astype(np.int64)[0]
 out = torch.zeros(4, N, dtype=torch.uint32)
 k[(1,)](torch.from_numpy(seed), torch.from_numpy(ctr.copy()), out, N=N)
 o = out.numpy()
@@ -288,7 +293,9 @@ def test_philox_matches_an_independent_library_implementation():
     import subprocess
     import sys
     pytest.importorskip("triton")
-    r = subprocess.run([sys.executable, "-c", _TRITON_CHILD, "2024"], capture_output=True, text=True, timeout=600)
+    import os
+    kat_path = os.path.join(os.path.dirname(__file__), "golden", "philox4x32_10_kat.txt")
+    r = subprocess.run([sys.executable, "-c", _TRITON_CHILD, "2024", kat_path], capture_output=True, text=True, timeout=600)
     if r.returncode != 0 and "philox" not in r.stderr:
         pytest.skip("the library's CPU interpreter does not run here: " + r.stderr.strip().splitlines()[-1][:200])
     assert r.returncode == 0, r.stderr[-2000:]
@@ -296,6 +303,9 @@ def test_philox_matches_an_independent_library_implementation():
     assert len(rows) == 256
     for seed, c0, c1, c2, c3, *out in rows:
         assert sm.philox4x32_10((c0, c1, c2, c3), (seed & 0xFFFFFFFF, seed >> 32)) == tuple(out)
+    # rows 8-10 are the inputs of the stored known-answer vectors: the library gives the stored outputs
+    stored = [[int(x, 16) for x in l.split("|")[2].split()] for l in open(kat_path) if l.strip() and not l.startswith("#")]
+    assert [row[5:] for row in rows[8:8 + len(stored)]] == stored and len(stored) == 3
     # the draw the sampler uses: counter (token number, row id, 0, 0), top 24 bits of the first word
     for seed, c0, c1, c2, c3, *out in rows[:8]:
         assert c2 == 0 and c3 == 0
