@@ -1,0 +1,22 @@
+"""The library's host code under AddressSanitizer / UndefinedBehaviorSanitizer on a GPU: a C++ driver (no Python, so
+nothing has to be preloaded) calls every entry point of the C ABI on the tiny model, with one to four micro-batches in
+flight, through both group pipelines, the static-scratch entry point, the measurement entry points and the error paths.
+Any report of either sanitizer ends the program with a non-zero status."""
+import os
+import subprocess
+
+import pytest
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+EXE = os.path.join(HERE, "host_sanitizer_driver")
+
+
+@pytest.mark.gpu
+def test_every_entry_point_runs_clean_under_host_sanitizers():
+    if not os.path.exists(EXE):
+        pytest.skip("tests/host_sanitizer_driver is not built: run `python -c 'import __graft_entry__ as g; g.build()'` first")
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=0:protect_shadow_gap=0", UBSAN_OPTIONS="print_stacktrace=1")
+    r = subprocess.run([EXE], capture_output=True, text=True, timeout=110, env=env)
+    tail = (r.stdout + r.stderr)[-3000:]
+    assert r.returncode == 0, tail
+    assert "[host-sanitizer-driver] done" in r.stdout and "ERROR: AddressSanitizer" not in tail and "runtime error" not in tail, tail
