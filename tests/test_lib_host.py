@@ -182,3 +182,47 @@ def test_a_plan_that_does_not_fit_host_memory_is_an_error_code(lib):
     lines = out.stdout.strip().splitlines()
     assert lines[0].startswith(f"rc {ss.SS_ENOMEM} plan False msg host allocation failed"), lines
     assert lines[1] == "rc2 0 n_mb 7", lines
+
+
+def test_library_plans_have_the_properties_the_method_states(lib):
+    """Properties that Sec. 4.1 states of a plan, checked on the library's output for generated groups and policies
+    without going through the scheduler oracle: a plan is a partition of the group; with sorting the scheduled lengths
+    never decrease along it; the cap is the largest scheduled length of the micro-batch under FCR (at most the global
+    limit) and the global limit otherwise; a micro-batch never holds more rows than its longest scheduled length allows;
+    with bins every micro-batch lies inside one bin."""
+    from hypothesis import given, settings, strategies as st
+
+    flag_sets = [f for f in FLAG_SETS if "COMPACT" not in f]
+
+    @settings(max_examples=300, deadline=None)
+    @given(pred=st.lists(st.integers(1, 700), min_size=1, max_size=120), flags=st.sampled_from(flag_sets),
+           b0=st.sampled_from([1, 2, 3, 16]), lmax=st.sampled_from([32, 100, 512]), w=st.sampled_from([1, 7, 50, 64]),
+           maxb=st.sampled_from([16, 64, 256]), pow2=st.booleans())
+    def check(pred, flags, b0, lmax, w, maxb, pow2):
+        n = len(pred)
+        binw = w if "BIN" in flags else 0
+        rule = ss.SS_VBS_PAPER_POW2 if pow2 else ss.SS_VBS_CLAMP_FLOOR
+        plan = ss.ss_schedule(np.array(pred, np.int32), n, binw, ss.make_policy(flags, b0, lmax, max(maxb, b0), rule))
+        order = [i for idx, _ in plan for i in idx]
+        assert sorted(order) == list(range(n))
+        if "SORT" not in flags:
+            assert order == list(range(n)) and all(cap == lmax and len(idx) <= b0 for idx, cap in plan)
+            return
+        top = -(-lmax // binw) * binw if binw else None
+        key = [min(-(-p // binw) * binw, top) if binw else p for p in pred]
+        assert all(key[a] <= key[b] for a, b in zip(order, order[1:]))
+        for idx, cap in plan:
+            longest = max(key[i] for i in idx)
+            assert cap == (min(longest, lmax) if "FCR" in flags else lmax)
+            if "VBS" in flags:
+                if pow2:
+                    allowed = 16 if longest >= 300 else min((2 ** k for k in range(15)), key=lambda b: abs(b - 12800 / longest))
+                else:
+                    allowed = max(b0, min(max(maxb, b0), b0 * lmax // longest))
+            else:
+                allowed = b0
+            assert len(idx) <= allowed
+            if binw:
+                assert len({key[i] for i in idx}) == 1
+
+    check()
